@@ -1,0 +1,302 @@
+"""Slow, plain CPU implementation of the MaxScore routing path (TEST INFRASTRUCTURE).
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may call this package; the
+product library never does, and this package imports nothing from the product.
+
+Everything is fp64 / int64 and written to be checked against the paper by eye:
+
+  router_logits      Eq. 2 / Algorithm 1 step 2:  L = x . W_g (+ optional per-expert bias)
+  softmax_rows       Table 2 row 1
+  soft_topk          Eq. 6 (reading stated in the function)
+  quantise           integer rewards round(A * 2^shift)
+  max_score_assignment   Eq. 7-8 / Table 1, successive cheapest augmenting paths (mcmf.c)
+  gates              Eq. 2: the affinity of each selected (token, expert) pair, not renormalised
+  dispatch           per-expert buffers (Section 2.3 capacity layout): stable sort by expert
+  verify_optimal     independent optimality proof for any assignment (no negative residual cycle)
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmcmf_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile mcmf.c with gcc into libmcmf_oracle.so next to this file."""
+    src = os.path.join(_HERE, "mcmf.c")
+    if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(src):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-o", _LIB_PATH, src])
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB_PATH)
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        u8p = ctypes.POINTER(ctypes.c_uint8)
+        _lib.mcmf_literal.argtypes = [i64p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                      u8p, i64p, i64p, i64p]
+        _lib.mcmf_literal.restype = ctypes.c_int
+        _lib.mcmf_contracted.argtypes = [i64p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                         u8p, i64p, i64p, i64p, i64p, i64p]
+        _lib.mcmf_contracted.restype = ctypes.c_int
+    return _lib
+
+
+# ------------------------------------------------------------------------------------------------
+# a1  router projection
+
+def router_logits(x: np.ndarray, W: np.ndarray, bias: Optional[np.ndarray] = None) -> np.ndarray:
+    """Eq. 2 / Algorithm 1 step 2: logits = x . W_g in fp64 over the given stored values.
+    `bias` (per expert) is a workload device of the synthetic configs, added to the logits."""
+    L = np.asarray(x, dtype=np.float64) @ np.asarray(W, dtype=np.float64)
+    if bias is not None:
+        L = L + np.asarray(bias, dtype=np.float64)[None, :]
+    return L
+
+
+# ------------------------------------------------------------------------------------------------
+# a2  SoftTopk
+
+def softmax_rows(L: np.ndarray) -> np.ndarray:
+    """Table 2, row 1: y = e^x / sum_j e^x_j per token row (max-subtracted, fp64)."""
+    L = np.asarray(L, dtype=np.float64)
+    z = np.exp(L - L.max(axis=1, keepdims=True))
+    return z / z.sum(axis=1, keepdims=True)
+
+
+def descending_rank(L: np.ndarray) -> np.ndarray:
+    """1-based rank of each entry within its row, largest first, ties to the lower index."""
+    L = np.asarray(L)
+    order = np.argsort(-L, axis=1, kind="stable")
+    rank = np.empty_like(order)
+    rows = np.arange(L.shape[0])[:, None]
+    rank[rows, order] = np.arange(1, L.shape[1] + 1)[None, :]
+    return rank
+
+
+def soft_topk(L: np.ndarray, k: int, t: float) -> np.ndarray:
+    """Eq. 6, taken level by level.
+
+    Reading: level 1 is Softmax(a); level m (2..k) adds SE^(m), which is t*Softmax(a)_i on the
+    entries not among the m-1 largest of a and 0 on those m-1 entries.  The loop below is that
+    recursion written out; its closed form is p_i * (1 + t*(min(rank_i, k) - 1)).
+    """
+    L = np.asarray(L, dtype=np.float64)
+    p = softmax_rows(L)
+    rank = descending_rank(L)
+    A = p.copy()                                   # SoftTopk^(1)
+    for m in range(2, k + 1):
+        SE = np.where(rank <= m - 1, 0.0, t * p)   # entries already in Top(m-1) get nothing
+        A = A + SE                                 # SoftTopk^(m) = SoftTopk^(m-1) + SE
+    return A
+
+
+# ------------------------------------------------------------------------------------------------
+# a3  integer rewards
+
+def quantise(A: np.ndarray, shift: int = 20) -> np.ndarray:
+    """q = round-half-even(A * 2^shift) as int64."""
+    return np.rint(np.asarray(A, dtype=np.float64) * float(1 << shift)).astype(np.int64)
+
+
+# ------------------------------------------------------------------------------------------------
+# a4  assignment
+
+def _as_q(q) -> np.ndarray:
+    q = np.ascontiguousarray(q, dtype=np.int64)
+    assert q.ndim == 2
+    return q
+
+
+def assign_literal_graph(q, k: int, C: int) -> dict:
+    """Successive cheapest paths on the literal graph of Table 1.  Any sizes; small inputs only."""
+    q = _as_q(q)
+    T, E = q.shape
+    P = np.zeros((T, E), dtype=np.uint8)
+    flow, total, arcs = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    rc = _load().mcmf_literal(q.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), T, E, k, C,
+                              P.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
+                              ctypes.byref(flow), ctypes.byref(total), ctypes.byref(arcs))
+    if rc:
+        raise ValueError(f"mcmf_literal failed rc={rc}")
+    return dict(P=P, flow=flow.value, total=total.value, arcs=arcs.value)
+
+
+def assign_contracted(q, k: int, C: int) -> dict:
+    """Same optimum with the token layer contracted (needs T*k <= E*min(C,T))."""
+    q = _as_q(q)
+    T, E = q.shape
+    P = np.zeros((T, E), dtype=np.uint8)
+    prices = np.zeros(E, dtype=np.int64)
+    flow, total, paths, hops = (ctypes.c_int64() for _ in range(4))
+    rc = _load().mcmf_contracted(q.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), T, E, k, C,
+                                 P.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
+                                 prices.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                 ctypes.byref(flow), ctypes.byref(total), ctypes.byref(paths),
+                                 ctypes.byref(hops))
+    if rc:
+        raise ValueError(f"mcmf_contracted failed rc={rc}")
+    return dict(P=P, prices=prices, flow=flow.value, total=total.value, paths=paths.value,
+                hops=hops.value)
+
+
+def max_score_assignment(q, k: int, C: int) -> dict:
+    """Exact maximum-flow-then-maximum-score assignment; picks the solver by the precondition."""
+    q = _as_q(q)
+    T, E = q.shape
+    if T * k <= E * min(C, T):
+        return assign_contracted(q, k, C)
+    return assign_literal_graph(q, k, C)
+
+
+def max_flow_value(T: int, E: int, k: int, C: int) -> int:
+    """Flow value of the complete bipartite network of Table 1 when k <= E."""
+    return min(T * k, E * min(C, T))
+
+
+def assignment_matrix(assign: np.ndarray, E: int) -> np.ndarray:
+    """[T, k] expert ids (-1 = empty slot) -> P in {0,1}^{T x E}; rejects repeated experts."""
+    assign = np.asarray(assign)
+    T = assign.shape[0]
+    P = np.zeros((T, E), dtype=np.int64)
+    rows, cols = np.nonzero(assign >= 0)
+    np.add.at(P, (rows, assign[rows, cols]), 1)
+    if P.max(initial=0) > 1:
+        raise ValueError("a token holds the same expert twice")
+    return P.astype(np.uint8)
+
+
+def check_feasible(P: np.ndarray, k: int, C: int) -> Tuple[bool, str]:
+    """Row sums <= k, column sums <= C, flow value = min(T*k, E*min(C,T)) (Eq. 7 read as <=)."""
+    P = np.asarray(P).astype(np.int64)
+    T, E = P.shape
+    if P.min(initial=0) < 0 or P.max(initial=0) > 1:
+        return False, "P not binary"
+    if P.sum(axis=1).max(initial=0) > k:
+        return False, "a token exceeds k experts"
+    if P.sum(axis=0).max(initial=0) > C:
+        return False, "an expert exceeds capacity"
+    if int(P.sum()) != max_flow_value(T, E, k, C):
+        return False, f"flow {int(P.sum())} != {max_flow_value(T, E, k, C)}"
+    return True, ""
+
+
+def verify_optimal(q, P, k: int, C: int) -> dict:
+    """Proof of optimality for a feasible maximum-flow P when T*k <= E*min(C,T), independent of
+    how P was found: the residual network, with tokens contracted, has experts and the sink as
+    nodes; arc j->j' costs min over tokens on j and not on j' of q_uj - q_uj'; j->sink costs 0
+    if j has spare capacity; sink->j costs 0 if j holds a token.  P is optimal iff no negative
+    cycle exists (Bellman-Ford from a virtual root).  The resulting potentials give expert
+    prices p >= 0 (0 on unfilled experts) under which every token holds its k best q_ij - p_j:
+    complementary slackness of the LP dual of Eq. 7-8."""
+    q = _as_q(q)
+    P = np.asarray(P).astype(bool)
+    T, E = q.shape
+    Ce = min(C, T)
+    assert T * k <= E * Ce
+    load = P.sum(axis=0)
+    INF = np.int64(1) << 60
+    Lm = np.full((E + 1, E + 1), INF, dtype=np.int64)      # node E = sink
+    for j in range(E):
+        rows = np.nonzero(P[:, j])[0]
+        if rows.size:
+            diff = q[rows, j][:, None] - q[rows, :]          # cost of moving u from j to j'
+            diff = np.where(P[rows, :], INF, diff)
+            Lm[j, :E] = diff.min(axis=0)
+            Lm[E, j] = 0
+        Lm[j, j] = INF
+        if load[j] < Ce:
+            Lm[j, E] = 0
+    dist = np.zeros(E + 1, dtype=np.int64)
+    changed = True
+    for _ in range(E + 2):
+        cand = (dist[:, None] + np.minimum(Lm, INF // 2)).min(axis=0)
+        new = np.minimum(dist, cand)
+        changed = bool((new != dist).any())
+        dist = new
+        if not changed:
+            break
+    optimal = not changed
+    prices = dist[E] - dist[:E]                               # p_j = phi_sink - phi_j
+    prices = np.where(load == 0, np.maximum(prices, 0), prices)  # nobody holds j: any p_j >= 0 above it works
+    ok_cs = False
+    if optimal:
+        net = q - prices[None, :]
+        held_min = np.where(P, net, INF).min(axis=1)
+        unheld_max = np.where(P, -INF, net).max(axis=1)
+        ok_cs = bool((held_min >= unheld_max).all() and (prices >= 0).all()
+                     and (prices[load < Ce] == 0).all() and (P.sum(axis=1) == k).all())
+    return dict(optimal=optimal and ok_cs, prices=prices, total=int(q[P].sum()))
+
+
+# ------------------------------------------------------------------------------------------------
+# a5  gates
+
+def gates(A: np.ndarray, assign: np.ndarray) -> np.ndarray:
+    """Eq. 2: R(x) keeps the affinity A_ij of every selected pair (no renormalisation);
+    empty slots (-1) get 0."""
+    A = np.asarray(A, dtype=np.float64)
+    assign = np.asarray(assign)
+    rows = np.arange(A.shape[0])[:, None]
+    g = A[rows, np.maximum(assign, 0)]
+    return np.where(assign >= 0, g, 0.0)
+
+
+# ------------------------------------------------------------------------------------------------
+# a6  dispatch
+
+def dispatch(assign: np.ndarray, gate: np.ndarray, E: int) -> dict:
+    """Per-expert buffers in compact form: all (expert, token) pairs sorted by expert, then by
+    token id (stable sort); offsets = exclusive prefix sum of the per-expert counts.
+    token_pos[i, s] is the position of pair (i, assign[i, s]) inside its expert's buffer."""
+    assign = np.asarray(assign)
+    gate = np.asarray(gate)
+    T, k = assign.shape
+    tok, slot = np.nonzero(assign >= 0)                  # row-major: token ascending
+    exp = assign[tok, slot]
+    order = np.argsort(exp, kind="stable")
+    tok_s, slot_s, exp_s = tok[order], slot[order], exp[order]
+    counts = np.bincount(exp, minlength=E).astype(np.int64)
+    offsets = np.zeros(E + 1, dtype=np.int64)
+    offsets[1:] = np.cumsum(counts)
+    token_pos = np.full((T, k), -1, dtype=np.int64)
+    token_pos[tok_s, slot_s] = np.arange(exp_s.size) - offsets[exp_s]
+    return dict(expert_offsets=offsets, disp_token=tok_s.astype(np.int64),
+                disp_gate=gate[tok_s, slot_s], token_pos=token_pos)
+
+
+# ------------------------------------------------------------------------------------------------
+# whole path
+
+def route(x, W, bias, k: int, C: int, t: float, shift: int = 20) -> dict:
+    """x, W -> logits -> SoftTopk -> integer rewards -> exact assignment -> gates -> dispatch."""
+    L = router_logits(x, W, bias)
+    return route_from_logits(L, k, C, t, shift)
+
+
+def route_from_logits(L, k: int, C: int, t: float, shift: int = 20) -> dict:
+    L = np.asarray(L, dtype=np.float64)
+    A = soft_topk(L, k, t)
+    q = quantise(A, shift)
+    sol = max_score_assignment(q, k, C)
+    P = sol["P"].astype(bool)
+    T, E = P.shape
+    assign = np.full((T, k), -1, dtype=np.int64)
+    for i in range(T):
+        js = np.nonzero(P[i])[0]
+        assign[i, : js.size] = js
+    g = gates(A, assign)
+    out = dict(logits=L, scores=A, q=q, P=sol["P"], assign=assign, gates=g, total=sol["total"],
+               flow=sol["flow"], prices=sol.get("prices"))
+    out.update(dispatch(assign, g, E))
+    return out
