@@ -1,0 +1,151 @@
+/*
+ * maxscore.h - C ABI of the MaxScore routing hot path on one AMD MI355X (gfx950).
+ *
+ * Method: "Maximum Score Routing For Mixture-of-Experts" (arXiv 2508.12801), Section 3.2.
+ * Notation follows the paper: T = n tokens, E = e experts, k experts per token, C = c capacity
+ * per expert, d = model width, t = SoftTopk temperature.
+ *
+ * Path (each step is one or more HIP kernels; nothing runs on the host except launches,
+ * argument checks and the convergence poll of the solver):
+ *
+ *   a1  logits  L = x . W_g (+ bias)                Eq. 2, Algorithm 1 step 2
+ *   a2  scores  A = SoftTopk_t^(k)(L) per token row  Eq. 6 (Table 2 row 1 for the softmax inside)
+ *   a3  rewards q = round_half_even(A * 2^shift)     integer form of the affinities A_ij
+ *   a4  assignment P: binary, <= k distinct experts per token, <= C tokens per expert,
+ *       maximum number of ones first, then maximum sum P_ij q_ij
+ *                                                    Eq. 7-8, Table 1 (min-cost max-flow)
+ *   a5  gates   g[i,s] = A[i, assign[i,s]]           Eq. 2 (affinity of the selected experts)
+ *   a6  dispatch into per-expert buffers             Section 2.3 (capacity c = k*n/e buffers)
+ *
+ * Conventions common to every entry point
+ *   - Every data pointer is DEVICE memory owned by the caller, row-major, densely packed, and
+ *     must stay valid until the stream has executed the call.  Outputs are fully overwritten.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - `workspace` is device scratch of at least maxscore_workspace_bytes(...) bytes, 256-byte
+ *     aligned.  Two calls may overlap only if they use different workspaces.
+ *   - Return value: MAXSCORE_OK or a negative MAXSCORE_ERR_* code.  Argument errors are found on
+ *     the host before anything is launched.  No entry point throws or allocates device memory.
+ *   - Entry points that contain the assignment step (a4) poll a device flag for convergence and
+ *     therefore SYNCHRONISE `stream` before returning; the others only enqueue work.
+ *   - Supported sizes: 1 <= k <= E <= 1024, k <= 64, 1 <= T <= 2^21, C >= 1 (C > T acts as T),
+ *     and T*k <= E*min(C,T) (true for every capacity c' = c_f*k*n/e with c_f >= 1, Section 2.3).
+ */
+#ifndef MAXSCORE_H
+#define MAXSCORE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MAXSCORE_OK = 0,
+    MAXSCORE_ERR_NULL = -1,           /* a required pointer is NULL */
+    MAXSCORE_ERR_SHAPE = -2,          /* T, E, k, C, d outside the supported sizes, or k > E */
+    MAXSCORE_ERR_WORKSPACE = -3,      /* workspace NULL, misaligned or too small */
+    MAXSCORE_ERR_DTYPE = -4,          /* unknown input dtype code */
+    MAXSCORE_ERR_HIP = -5,            /* a HIP call or kernel launch failed */
+    MAXSCORE_ERR_OVERSUBSCRIBED = -6, /* T*k > E*min(C,T): not every token can get k experts */
+    MAXSCORE_ERR_RANGE = -7,          /* reward range too wide for the solver's 64-bit bids */
+    MAXSCORE_ERR_NOT_CONVERGED = -8   /* max_rounds reached; outputs hold the last state */
+};
+
+enum { MAXSCORE_DTYPE_BF16 = 0, MAXSCORE_DTYPE_FP32 = 1 };
+
+/* Options.  Pass NULL for the defaults {t = 1, quant_shift = 20, max_rounds = 200000,
+ * eps_div = 8}. */
+typedef struct {
+    float t;              /* SoftTopk temperature of Eq. 6 */
+    int32_t quant_shift;  /* rewards are round(A * 2^quant_shift); 1..24 */
+    int32_t max_rounds;   /* cap on solver rounds (bid pass + select pass) */
+    int32_t eps_div;      /* eps-scaling ratio between solver phases, >= 2 */
+} maxscore_opts;
+
+/* Filled on the HOST when the call returns (may be NULL). */
+typedef struct {
+    int64_t total_score_q; /* sum of q over the chosen pairs */
+    int32_t flow_value;    /* number of chosen pairs */
+    int32_t rounds;        /* solver rounds executed */
+    int32_t phases;        /* eps-scaling phases executed (restarts included) */
+    int32_t status;        /* MAXSCORE_OK, MAXSCORE_ERR_RANGE or MAXSCORE_ERR_NOT_CONVERGED */
+    float solver_ms;       /* device time of a4 between two events on `stream` */
+    float bid_ms;          /* summed device time of the bid-pass launches inside a4 (0 unless
+                              timing was switched on with maxscore_set_kernel_timing) */
+    int32_t bid_launches;  /* bid-pass launches that did work (0 unless timing is on) */
+    int32_t reserved;
+} maxscore_stats;
+
+/* Bytes of device scratch the calls below need for these sizes (0 on invalid sizes). */
+size_t maxscore_workspace_bytes(int32_t T, int32_t d, int32_t E, int32_t k, int32_t C);
+
+/* a1.  logits[T,E] (fp32) = x[T,d] . W[d,E] + bias[E].  x and W are bf16 (16-bit patterns,
+ * fp32 accumulation on the matrix cores) or fp32 according to in_dtype; bias may be NULL. */
+int32_t maxscore_router_logits(const void *x, const void *W, const float *bias, int32_t in_dtype,
+                               int32_t T, int32_t d, int32_t E, float *logits, void *stream);
+
+/* a2 + a3.  Per row: p = softmax(logits); rank r (1 = largest, ties to the lower index);
+ * scores = p * (1 + t*(min(r,k) - 1)), the level-by-level reading of Eq. 6;
+ * q = round_half_even(scores * 2^shift).  scores and/or q may be NULL. */
+int32_t maxscore_softtopk(const float *logits, int32_t T, int32_t E, int32_t k, float t,
+                          int32_t quant_shift, float *scores, int32_t *q, void *stream);
+
+/* a4.  Exact assignment on integer rewards q[T,E].
+ *   assign[T,k] : expert ids per token, distinct, ascending slot order is arbitrary.
+ *   prices[E]   : (may be NULL) int64 expert prices in units of 1/price_scale of a q unit;
+ *                 every token holds k experts whose price_scale*q_ij - price_j is within 1 of
+ *                 its best alternatives, and unfilled experts have price 0 (the dual side of
+ *                 Eq. 7-8 that certifies the optimum).  price_scale[1] (may be NULL) receives
+ *                 the scale, a power of two > E.
+ * Synchronises `stream`. */
+int32_t maxscore_assign_i32(const int32_t *q, int32_t T, int32_t E, int32_t k, int32_t C,
+                            const maxscore_opts *opts, int32_t *assign, int64_t *prices,
+                            int64_t *price_scale, maxscore_stats *stats, void *workspace,
+                            size_t workspace_bytes, void *stream);
+
+/* a5.  gates[T,k] = scores[i, assign[i,s]] (0 where assign < 0). */
+int32_t maxscore_gates(const float *scores, const int32_t *assign, int32_t T, int32_t E, int32_t k,
+                       float *gates, void *stream);
+
+/* a6.  Dispatch.  expert_offsets[E+1] = exclusive prefix sum of tokens per expert; inside expert j
+ * tokens appear in ascending token id; disp_token[T*k], disp_gate[T*k] list the pairs in that
+ * order; token_pos[T,k] is the position of pair (i, assign[i,s]) inside its expert's buffer, so
+ * its address in a padded [E, C] capacity buffer is assign[i,s]*C + token_pos[i,s].
+ * disp_gate / gates may both be NULL. */
+int32_t maxscore_dispatch(const int32_t *assign, const float *gates, int32_t T, int32_t E, int32_t k,
+                          int32_t *expert_offsets, int32_t *disp_token, float *disp_gate,
+                          int32_t *token_pos, void *workspace, size_t workspace_bytes, void *stream);
+
+/* a2..a6 from given logits.  scores_out[T,E] and q_out[T,E] are required (they are the working
+ * storage of a2/a3).  Synchronises `stream`. */
+int32_t maxscore_route_logits(const float *logits, int32_t T, int32_t E, int32_t k, int32_t C,
+                              const maxscore_opts *opts, float *scores_out, int32_t *q_out,
+                              int32_t *assign, float *gates, int32_t *expert_offsets,
+                              int32_t *disp_token, float *disp_gate, int32_t *token_pos,
+                              int64_t *prices, maxscore_stats *stats, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+/* a1..a6 from x and W_g.  logits_out[T,E] is required.  Synchronises `stream`. */
+int32_t maxscore_route_xw(const void *x, const void *W, const float *bias, int32_t in_dtype,
+                          int32_t T, int32_t d, int32_t E, int32_t k, int32_t C,
+                          const maxscore_opts *opts, float *logits_out, float *scores_out,
+                          int32_t *q_out, int32_t *assign, float *gates, int32_t *expert_offsets,
+                          int32_t *disp_token, float *disp_gate, int32_t *token_pos,
+                          int64_t *prices, maxscore_stats *stats, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
+/* Switch per-launch HIP-event timing of the solver's bid pass on (1) or off (0, default).
+ * Timing adds two event records per round; it is meant for benchmarks. */
+void maxscore_set_kernel_timing(int32_t on);
+
+/* Plain device-to-device copy kernel of `bytes` bytes (multiple of 16), used by the benchmark to
+ * calibrate memory counters and to measure achievable bandwidth. */
+int32_t maxscore_copy_bytes(const void *src, void *dst, size_t bytes, void *stream);
+
+const char *maxscore_status_string(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MAXSCORE_H */

@@ -1,0 +1,13 @@
+"""MaxScore routing hot path on one MI355X: thin Python binding over libmaxscore.so.
+
+Every step runs in the HIP kernels of the shared library; this package only marshals arguments
+(torch supplies device memory and the current stream).  Importing works without a GPU; calling
+any compute function without the built library or without a GPU raises.
+"""
+from .binding import (MaxScoreError, Stats, lib_path, load_library, exported_symbols, workspace_bytes,
+                      router_logits, softtopk, assign_i32, gates, dispatch, route_logits, route_xw,
+                      set_kernel_timing, copy_bytes, status_string)
+
+__all__ = ["MaxScoreError", "Stats", "lib_path", "load_library", "exported_symbols", "workspace_bytes",
+           "router_logits", "softtopk", "assign_i32", "gates", "dispatch", "route_logits", "route_xw",
+           "set_kernel_timing", "copy_bytes", "status_string"]

@@ -1,0 +1,284 @@
+"""ctypes binding with the same names as include/maxscore.h (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+OK = 0
+ERR_NOT_CONVERGED = -8
+DTYPE_BF16, DTYPE_FP32 = 0, 1
+
+
+class MaxScoreError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} ({code})")
+
+
+class _Opts(ctypes.Structure):
+    _fields_ = [("t", ctypes.c_float), ("quant_shift", ctypes.c_int32), ("max_rounds", ctypes.c_int32),
+                ("eps_div", ctypes.c_int32)]
+
+
+class Stats(ctypes.Structure):
+    _fields_ = [("total_score_q", ctypes.c_int64), ("flow_value", ctypes.c_int32), ("rounds", ctypes.c_int32),
+                ("phases", ctypes.c_int32), ("status", ctypes.c_int32), ("solver_ms", ctypes.c_float),
+                ("bid_ms", ctypes.c_float), ("bid_launches", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libmaxscore.so")
+
+
+_SIGS = {
+    "maxscore_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int32] * 5),
+    "maxscore_router_logits": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                                ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                                ctypes.c_void_p]),
+    "maxscore_softtopk": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                           ctypes.c_float, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.c_void_p]),
+    "maxscore_assign_i32": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                             ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                             ctypes.c_void_p]),
+    "maxscore_gates": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                        ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]),
+    "maxscore_dispatch": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                           ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "maxscore_route_logits": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                               ctypes.c_int32, ctypes.c_void_p] + [ctypes.c_void_p] * 11 +
+                              [ctypes.c_size_t, ctypes.c_void_p]),
+    "maxscore_route_xw": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                           ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                           ctypes.c_int32, ctypes.c_void_p] + [ctypes.c_void_p] * 12 +
+                          [ctypes.c_size_t, ctypes.c_void_p]),
+    "maxscore_set_kernel_timing": (None, [ctypes.c_int32]),
+    "maxscore_copy_bytes": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "maxscore_status_string": (ctypes.c_char_p, [ctypes.c_int32]),
+}
+
+
+def exported_symbols():
+    return sorted(_SIGS)
+
+
+def load_library():
+    """Load libmaxscore.so built in-tree; raises if it has not been built."""
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise MaxScoreError(-5, f"{path} is missing: run `python -m paper_2508_12801_amd.build` first")
+        lib = ctypes.CDLL(path)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _LIB = lib
+    return _LIB
+
+
+def status_string(code: int) -> str:
+    try:
+        return load_library().maxscore_status_string(code).decode()
+    except Exception:
+        return "status %d" % code
+
+
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        raise MaxScoreError(-5, "no GPU visible: the MaxScore kernels have no CPU fallback")
+    return torch
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int, where: str, allow=()):
+    if rc != OK and rc not in allow:
+        raise MaxScoreError(rc, where)
+
+
+_WS = {}
+
+
+def workspace_bytes(T: int, d: int, E: int, k: int, C: int) -> int:
+    return int(load_library().maxscore_workspace_bytes(T, d, E, k, C))
+
+
+def _workspace(T, E, k, C, device):
+    torch = _torch()
+    need = workspace_bytes(T, 1, E, k, C)
+    if need == 0:
+        raise MaxScoreError(-2, "workspace_bytes")
+    key = (str(device),)
+    buf = _WS.get(key)
+    if buf is None or buf.numel() < need:
+        buf = torch.empty(need, dtype=torch.uint8, device=device)
+        _WS[key] = buf
+    return buf, need
+
+
+def _opts(t=1.0, quant_shift=20, max_rounds=200000, eps_div=8):
+    return _Opts(float(t), int(quant_shift), int(max_rounds), int(eps_div))
+
+
+def set_kernel_timing(on: bool) -> None:
+    load_library().maxscore_set_kernel_timing(1 if on else 0)
+
+
+def copy_bytes(src, dst) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().maxscore_copy_bytes(_ptr(src), _ptr(dst), nbytes, _stream()), "maxscore_copy_bytes")
+
+
+def _in_dtype(x):
+    torch = _torch()
+    if x.dtype == torch.float32:
+        return DTYPE_FP32
+    if x.dtype in (torch.bfloat16, torch.int16, torch.uint16):
+        return DTYPE_BF16
+    raise MaxScoreError(-4, "input dtype")
+
+
+def router_logits(x, W, bias=None):
+    """a1: logits[T,E] fp32 = x[T,d] . W[d,E] + bias.  x, W: bf16 (or int16 bit patterns) or fp32."""
+    torch = _torch()
+    T, d = x.shape
+    E = W.shape[1]
+    assert W.shape[0] == d and x.is_contiguous() and W.is_contiguous() and x.dtype == W.dtype
+    out = torch.empty((T, E), dtype=torch.float32, device=x.device)
+    rc = load_library().maxscore_router_logits(_ptr(x), _ptr(W), _ptr(bias), _in_dtype(x), T, d, E, _ptr(out),
+                                               _stream())
+    _check(rc, "maxscore_router_logits")
+    return out
+
+
+def softtopk(logits, k: int, t: float, quant_shift: int = 20):
+    """a2 + a3: (scores fp32 [T,E], q int32 [T,E])."""
+    torch = _torch()
+    T, E = logits.shape
+    assert logits.dtype == torch.float32 and logits.is_contiguous()
+    scores = torch.empty_like(logits)
+    q = torch.empty((T, E), dtype=torch.int32, device=logits.device)
+    rc = load_library().maxscore_softtopk(_ptr(logits), T, E, k, float(t), quant_shift, _ptr(scores), _ptr(q),
+                                          _stream())
+    _check(rc, "maxscore_softtopk")
+    return scores, q
+
+
+def assign_i32(q, k: int, C: int, max_rounds: int = 200000, eps_div: int = 8, allow_not_converged=False):
+    """a4: exact assignment on int32 rewards.  Returns dict(assign, prices, price_scale, stats)."""
+    torch = _torch()
+    T, E = q.shape
+    assert q.dtype == torch.int32 and q.is_contiguous()
+    assign = torch.empty((T, k), dtype=torch.int32, device=q.device)
+    prices = torch.empty(E, dtype=torch.int64, device=q.device)
+    scale = torch.empty(1, dtype=torch.int64, device=q.device)
+    stats = Stats()
+    ws, need = _workspace(T, E, k, C, q.device)
+    o = _opts(max_rounds=max_rounds, eps_div=eps_div)
+    rc = load_library().maxscore_assign_i32(_ptr(q), T, E, k, C, ctypes.byref(o), _ptr(assign), _ptr(prices),
+                                            _ptr(scale), ctypes.byref(stats), _ptr(ws), need, _stream())
+    _check(rc, "maxscore_assign_i32", allow=(ERR_NOT_CONVERGED,) if allow_not_converged else ())
+    return dict(assign=assign, prices=prices, price_scale=int(scale.item()), stats=stats.as_dict(), rc=rc)
+
+
+def gates(scores, assign):
+    """a5: gates[T,k] = scores[i, assign[i,s]]."""
+    torch = _torch()
+    T, E = scores.shape
+    k = assign.shape[1]
+    out = torch.empty((T, k), dtype=torch.float32, device=scores.device)
+    _check(load_library().maxscore_gates(_ptr(scores), _ptr(assign), T, E, k, _ptr(out), _stream()),
+           "maxscore_gates")
+    return out
+
+
+def dispatch(assign, gate, E: int, C: int = 1):
+    """a6: dict(expert_offsets[E+1], disp_token[T*k], disp_gate[T*k], token_pos[T,k])."""
+    torch = _torch()
+    T, k = assign.shape
+    dev = assign.device
+    offsets = torch.empty(E + 1, dtype=torch.int32, device=dev)
+    disp_token = torch.full((T * k,), -1, dtype=torch.int32, device=dev)
+    disp_gate = torch.zeros(T * k, dtype=torch.float32, device=dev) if gate is not None else None
+    token_pos = torch.empty((T, k), dtype=torch.int32, device=dev)
+    ws, need = _workspace(T, E, k, max(C, 1), dev)
+    rc = load_library().maxscore_dispatch(_ptr(assign), _ptr(gate), T, E, k, _ptr(offsets), _ptr(disp_token),
+                                          _ptr(disp_gate), _ptr(token_pos), _ptr(ws), need, _stream())
+    _check(rc, "maxscore_dispatch")
+    return dict(expert_offsets=offsets, disp_token=disp_token, disp_gate=disp_gate, token_pos=token_pos)
+
+
+def _route_outputs(T, E, k, dev):
+    torch = _torch()
+    return dict(scores=torch.empty((T, E), dtype=torch.float32, device=dev),
+                q=torch.empty((T, E), dtype=torch.int32, device=dev),
+                assign=torch.empty((T, k), dtype=torch.int32, device=dev),
+                gates=torch.empty((T, k), dtype=torch.float32, device=dev),
+                expert_offsets=torch.empty(E + 1, dtype=torch.int32, device=dev),
+                disp_token=torch.empty(T * k, dtype=torch.int32, device=dev),
+                disp_gate=torch.empty(T * k, dtype=torch.float32, device=dev),
+                token_pos=torch.empty((T, k), dtype=torch.int32, device=dev),
+                prices=torch.empty(E, dtype=torch.int64, device=dev))
+
+
+def route_logits(logits, k: int, C: int, t: float = 1.0, quant_shift: int = 20, max_rounds: int = 200000,
+                 eps_div: int = 8, out: Optional[dict] = None):
+    """a2..a6 from logits."""
+    torch = _torch()
+    T, E = logits.shape
+    assert logits.dtype == torch.float32 and logits.is_contiguous()
+    o = out if out is not None else _route_outputs(T, E, k, logits.device)
+    ws, need = _workspace(T, E, k, C, logits.device)
+    stats = Stats()
+    opts = _opts(t, quant_shift, max_rounds, eps_div)
+    rc = load_library().maxscore_route_logits(
+        _ptr(logits), T, E, k, C, ctypes.byref(opts), _ptr(o["scores"]), _ptr(o["q"]), _ptr(o["assign"]),
+        _ptr(o["gates"]), _ptr(o["expert_offsets"]), _ptr(o["disp_token"]), _ptr(o["disp_gate"]),
+        _ptr(o["token_pos"]), _ptr(o["prices"]), ctypes.byref(stats), _ptr(ws), need, _stream())
+    _check(rc, "maxscore_route_logits")
+    o = dict(o)
+    o["stats"] = stats.as_dict()
+    return o
+
+
+def route_xw(x, W, bias, k: int, C: int, t: float = 1.0, quant_shift: int = 20, max_rounds: int = 200000,
+             eps_div: int = 8, out: Optional[dict] = None):
+    """a1..a6 from x and W_g."""
+    torch = _torch()
+    T, d = x.shape
+    E = W.shape[1]
+    assert W.shape[0] == d and x.is_contiguous() and W.is_contiguous() and x.dtype == W.dtype
+    o = out if out is not None else _route_outputs(T, E, k, x.device)
+    if "logits" not in o:
+        o["logits"] = torch.empty((T, E), dtype=torch.float32, device=x.device)
+    ws, need = _workspace(T, E, k, C, x.device)
+    stats = Stats()
+    opts = _opts(t, quant_shift, max_rounds, eps_div)
+    rc = load_library().maxscore_route_xw(
+        _ptr(x), _ptr(W), _ptr(bias), _in_dtype(x), T, d, E, k, C, ctypes.byref(opts), _ptr(o["logits"]),
+        _ptr(o["scores"]), _ptr(o["q"]), _ptr(o["assign"]), _ptr(o["gates"]), _ptr(o["expert_offsets"]),
+        _ptr(o["disp_token"]), _ptr(o["disp_gate"]), _ptr(o["token_pos"]), _ptr(o["prices"]),
+        ctypes.byref(stats), _ptr(ws), need, _stream())
+    _check(rc, "maxscore_route_xw")
+    o = dict(o)
+    o["stats"] = stats.as_dict()
+    return o

@@ -1,0 +1,196 @@
+// Host side of the C ABI: argument validation, workspace carving, stream enqueue.
+#include <cstring>
+
+#include "common.h"
+
+namespace maxscore {
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+WorkspaceLayout workspace_layout(int T, int E, int k)
+{
+    WorkspaceLayout L;
+    size_t off = 0;
+    L.state_off = off; off = align_up(off + sizeof(SolverState), 256);
+    L.theta_off = off; off = align_up(off + sizeof(long long) * kMaxE, 256);
+    L.gcount_off = off; off = align_up(off + sizeof(int) * (kMaxE + 2), 256);
+    L.klist_off = off; off = align_up(off + sizeof(long long) * (size_t)E * T, 256);
+    L.n_tiles = (int)(((size_t)T * k + 1023) / 1024);
+    L.tiles_off = off; off = align_up(off + sizeof(int) * (size_t)L.n_tiles * E, 256);
+    L.total = off;
+    return L;
+}
+
+static bool shape_ok(int T, int E, int k, int C)
+{
+    return T >= 1 && T <= (1 << kMaxTBits) && E >= 1 && E <= kMaxE && k >= 1 && k <= E && k <= kMaxK && C >= 1;
+}
+
+static maxscore_opts resolve(const maxscore_opts *o)
+{
+    maxscore_opts r = {1.0f, 20, 200000, 8};
+    if (o) {
+        r = *o;
+        if (r.quant_shift == 0) r.quant_shift = 20;
+        if (r.max_rounds <= 0) r.max_rounds = 200000;
+        if (r.eps_div < 2) r.eps_div = 8;
+    }
+    return r;
+}
+
+static int32_t check_ws(const void *ws, size_t bytes, int T, int E, int k)
+{
+    if (!ws || ((uintptr_t)ws % 256) != 0) return MAXSCORE_ERR_WORKSPACE;
+    if (bytes < workspace_layout(T, E, k).total) return MAXSCORE_ERR_WORKSPACE;
+    return MAXSCORE_OK;
+}
+
+}  // namespace maxscore
+
+using namespace maxscore;
+
+extern "C" {
+
+size_t maxscore_workspace_bytes(int32_t T, int32_t d, int32_t E, int32_t k, int32_t C)
+{
+    (void)d;
+    if (!shape_ok(T, E, k, C)) return 0;
+    return workspace_layout(T, E, k).total;
+}
+
+int32_t maxscore_router_logits(const void *x, const void *W, const float *bias, int32_t in_dtype, int32_t T,
+                               int32_t d, int32_t E, float *logits, void *stream)
+{
+    if (!x || !W || !logits) return MAXSCORE_ERR_NULL;
+    if (T < 1 || d < 1 || E < 1 || E > kMaxE || T > (1 << kMaxTBits)) return MAXSCORE_ERR_SHAPE;
+    if (in_dtype != MAXSCORE_DTYPE_BF16 && in_dtype != MAXSCORE_DTYPE_FP32) return MAXSCORE_ERR_DTYPE;
+    return gemm_run(x, W, bias, in_dtype, T, d, E, logits, (hipStream_t)stream);
+}
+
+int32_t maxscore_softtopk(const float *logits, int32_t T, int32_t E, int32_t k, float t, int32_t quant_shift,
+                          float *scores, int32_t *q, void *stream)
+{
+    if (!logits || (!scores && !q)) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, k, 1) || quant_shift < 1 || quant_shift > 24 || !(t >= 0.f) || t > 64.f)
+        return MAXSCORE_ERR_SHAPE;
+    return softtopk_run(logits, T, E, k, t, quant_shift, scores, q, (hipStream_t)stream);
+}
+
+int32_t maxscore_assign_i32(const int32_t *q, int32_t T, int32_t E, int32_t k, int32_t C,
+                            const maxscore_opts *opts, int32_t *assign, int64_t *prices, int64_t *price_scale,
+                            maxscore_stats *stats, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!q || !assign) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, k, C)) return MAXSCORE_ERR_SHAPE;
+    const int Ce = C < T ? C : T;
+    if ((long long)T * k > (long long)E * Ce) return MAXSCORE_ERR_OVERSUBSCRIBED;
+    int32_t rc = check_ws(workspace, workspace_bytes, T, E, k);
+    if (rc) return rc;
+    maxscore_opts o = resolve(opts);
+    if (stats) std::memset(stats, 0, sizeof(*stats));
+    return solver_run(q, T, E, k, Ce, o, assign, prices, price_scale, stats, (char *)workspace,
+                      (hipStream_t)stream);
+}
+
+int32_t maxscore_gates(const float *scores, const int32_t *assign, int32_t T, int32_t E, int32_t k, float *gates,
+                       void *stream)
+{
+    if (!scores || !assign || !gates) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, k, 1)) return MAXSCORE_ERR_SHAPE;
+    return gates_run(scores, assign, T, E, k, gates, (hipStream_t)stream);
+}
+
+int32_t maxscore_dispatch(const int32_t *assign, const float *gates, int32_t T, int32_t E, int32_t k,
+                          int32_t *expert_offsets, int32_t *disp_token, float *disp_gate, int32_t *token_pos,
+                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!assign || !expert_offsets || !disp_token || !token_pos) return MAXSCORE_ERR_NULL;
+    if ((disp_gate != nullptr) != (gates != nullptr)) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, k, 1)) return MAXSCORE_ERR_SHAPE;
+    int32_t rc = check_ws(workspace, workspace_bytes, T, E, k);
+    if (rc) return rc;
+    return dispatch_run(assign, gates, T, E, k, expert_offsets, disp_token, disp_gate, token_pos,
+                        (char *)workspace, (hipStream_t)stream);
+}
+
+int32_t maxscore_route_logits(const float *logits, int32_t T, int32_t E, int32_t k, int32_t C,
+                              const maxscore_opts *opts, float *scores_out, int32_t *q_out, int32_t *assign,
+                              float *gates, int32_t *expert_offsets, int32_t *disp_token, float *disp_gate,
+                              int32_t *token_pos, int64_t *prices, maxscore_stats *stats, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    if (!logits || !scores_out || !q_out || !assign || !gates || !expert_offsets || !disp_token || !disp_gate ||
+        !token_pos)
+        return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, k, C)) return MAXSCORE_ERR_SHAPE;
+    const int Ce = C < T ? C : T;
+    if ((long long)T * k > (long long)E * Ce) return MAXSCORE_ERR_OVERSUBSCRIBED;
+    int32_t rc = check_ws(workspace, workspace_bytes, T, E, k);
+    if (rc) return rc;
+    maxscore_opts o = resolve(opts);
+    if (o.quant_shift < 1 || o.quant_shift > 24 || !(o.t >= 0.f) || o.t > 64.f) return MAXSCORE_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    if (stats) std::memset(stats, 0, sizeof(*stats));
+    rc = softtopk_run(logits, T, E, k, o.t, o.quant_shift, scores_out, q_out, s);
+    if (rc) return rc;
+    int32_t src = solver_run(q_out, T, E, k, Ce, o, assign, prices, nullptr, stats, (char *)workspace, s);
+    if (src != MAXSCORE_OK && src != MAXSCORE_ERR_NOT_CONVERGED) return src;
+    rc = gates_run(scores_out, assign, T, E, k, gates, s);
+    if (rc) return rc;
+    rc = dispatch_run(assign, gates, T, E, k, expert_offsets, disp_token, disp_gate, token_pos, (char *)workspace,
+                      s);
+    if (rc) return rc;
+    if (hipStreamSynchronize(s) != hipSuccess) return MAXSCORE_ERR_HIP;
+    return src;
+}
+
+int32_t maxscore_route_xw(const void *x, const void *W, const float *bias, int32_t in_dtype, int32_t T, int32_t d,
+                          int32_t E, int32_t k, int32_t C, const maxscore_opts *opts, float *logits_out,
+                          float *scores_out, int32_t *q_out, int32_t *assign, float *gates,
+                          int32_t *expert_offsets, int32_t *disp_token, float *disp_gate, int32_t *token_pos,
+                          int64_t *prices, maxscore_stats *stats, void *workspace, size_t workspace_bytes,
+                          void *stream)
+{
+    if (!x || !W || !logits_out) return MAXSCORE_ERR_NULL;
+    if (d < 1) return MAXSCORE_ERR_SHAPE;
+    if (in_dtype != MAXSCORE_DTYPE_BF16 && in_dtype != MAXSCORE_DTYPE_FP32) return MAXSCORE_ERR_DTYPE;
+    if (!shape_ok(T, E, k, C)) return MAXSCORE_ERR_SHAPE;
+    if (!scores_out || !q_out || !assign || !gates || !expert_offsets || !disp_token || !disp_gate || !token_pos)
+        return MAXSCORE_ERR_NULL;
+    const int Ce = C < T ? C : T;
+    if ((long long)T * k > (long long)E * Ce) return MAXSCORE_ERR_OVERSUBSCRIBED;
+    int32_t rc = check_ws(workspace, workspace_bytes, T, E, k);
+    if (rc) return rc;
+    rc = gemm_run(x, W, bias, in_dtype, T, d, E, logits_out, (hipStream_t)stream);
+    if (rc) return rc;
+    return maxscore_route_logits(logits_out, T, E, k, C, opts, scores_out, q_out, assign, gates, expert_offsets,
+                                 disp_token, disp_gate, token_pos, prices, stats, workspace, workspace_bytes,
+                                 stream);
+}
+
+void maxscore_set_kernel_timing(int32_t on) { g_kernel_timing = on ? 1 : 0; }
+
+int32_t maxscore_copy_bytes(const void *src, void *dst, size_t bytes, void *stream)
+{
+    if (!src || !dst) return MAXSCORE_ERR_NULL;
+    if (bytes % 16 != 0) return MAXSCORE_ERR_SHAPE;
+    return copy_run(src, dst, bytes, (hipStream_t)stream);
+}
+
+const char *maxscore_status_string(int32_t status)
+{
+    switch (status) {
+        case MAXSCORE_OK: return "ok";
+        case MAXSCORE_ERR_NULL: return "a required pointer is NULL";
+        case MAXSCORE_ERR_SHAPE: return "unsupported or inconsistent sizes";
+        case MAXSCORE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case MAXSCORE_ERR_DTYPE: return "unknown input dtype";
+        case MAXSCORE_ERR_HIP: return "HIP runtime error";
+        case MAXSCORE_ERR_OVERSUBSCRIBED: return "T*k exceeds E*min(C,T)";
+        case MAXSCORE_ERR_RANGE: return "reward range too wide";
+        case MAXSCORE_ERR_NOT_CONVERGED: return "solver hit max_rounds";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

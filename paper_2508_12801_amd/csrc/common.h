@@ -1,0 +1,69 @@
+// Shared host/device declarations of the MaxScore routing library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "maxscore.h"
+
+namespace maxscore {
+
+constexpr int kMaxE = 1024;
+constexpr int kMaxK = 64;
+constexpr int kMaxTBits = 21;
+constexpr int64_t kBidBig = (int64_t)1 << 40;   // bid of a token that has no alternative left
+
+// Device-resident control block of one assignment solve.
+struct SolverState {
+    long long eps;         // current epsilon (in units of 1/S of a reward unit)
+    long long eps_prev;    // epsilon of the previous phase (0 in the first phase)
+    long long beta;        // price-lowering factor applied between phases when capacity is slack
+    long long qmin, qmax;  // reward range
+    long long total;       // sum of q over chosen pairs (finalize)
+    int sbits;             // S = 1 << sbits > E
+    int tbits;             // token id bits inside a bid key
+    int eps_div;
+    int max_rounds;
+    int round;
+    int phases;
+    int done;              // 1 once the final phase is quiescent (or on error)
+    int status;
+    int moves;             // drops + fills of the current bid pass
+    int blocks_done;       // completion counter of the select pass
+    int flow;
+    int slack;             // E*Ce - T*k > 0
+    int pad[4];
+};
+
+struct WorkspaceLayout {
+    size_t state_off, theta_off, gcount_off, klist_off, tiles_off, total;
+    int n_tiles;
+};
+
+WorkspaceLayout workspace_layout(int T, int E, int k);
+
+inline bool hip_ok(hipError_t e) { return e == hipSuccess; }
+
+#define MS_HIP(call)                                   \
+    do {                                               \
+        if ((call) != hipSuccess) return MAXSCORE_ERR_HIP; \
+    } while (0)
+
+// --- solver.hip
+int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore_opts &o, int32_t *assign,
+                   int64_t *prices, int64_t *price_scale, maxscore_stats *stats, char *ws, hipStream_t s);
+// --- softtopk.hip
+int32_t softtopk_run(const float *logits, int T, int E, int k, float t, int shift, float *scores, int32_t *q,
+                     hipStream_t s);
+int32_t gates_run(const float *scores, const int32_t *assign, int T, int E, int k, float *gates, hipStream_t s);
+// --- dispatch.hip
+int32_t dispatch_run(const int32_t *assign, const float *gates, int T, int E, int k, int32_t *offsets,
+                     int32_t *disp_token, float *disp_gate, int32_t *token_pos, char *ws, hipStream_t s);
+// --- gemm.hip
+int32_t gemm_run(const void *x, const void *W, const float *bias, int dtype, int T, int d, int E, float *logits,
+                 hipStream_t s);
+int32_t copy_run(const void *src, void *dst, size_t bytes, hipStream_t s);
+
+extern int g_kernel_timing;
+
+}  // namespace maxscore

@@ -1,0 +1,127 @@
+// a6: dispatch permutation into per-expert buffers (Section 2.3: every expert owns a buffer of
+// c = k*n/e token places).  Pairs (token, expert) are ordered by expert and, inside an expert, by
+// ascending token id, which is what a stable sort of the token-major pair list by expert gives.
+//
+// Three launches: per-tile expert histograms, a scan over tiles and experts, and a scatter that
+// recomputes each pair's stable rank inside its tile.  A tile is kTile consecutive slots of the
+// token-major [T, k] assignment and is owned by one wavefront.
+#include "common.h"
+
+namespace maxscore {
+namespace {
+
+constexpr int kTile = 1024;      // slots per wavefront tile
+constexpr int kWavesPerWg = 4;
+
+__global__ __launch_bounds__(256) void k_tile_hist(const int32_t *__restrict__ assign, size_t n, int E,
+                                                   int *__restrict__ tiles, int n_tiles)
+{
+    extern __shared__ int s_cnt[];   // [kWavesPerWg][E]
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int tile = blockIdx.x * kWavesPerWg + wave;
+    int *cnt = s_cnt + wave * E;
+    for (int e = lane; e < E; e += 64) cnt[e] = 0;
+    __syncthreads();
+    if (tile < n_tiles) {
+        size_t a0 = (size_t)tile * kTile;
+        for (int c = lane; c < kTile; c += 64) {
+            size_t a = a0 + c;
+            if (a < n) {
+                int e = assign[a];
+                if (e >= 0) atomicAdd(&cnt[e], 1);
+            }
+        }
+    }
+    __syncthreads();
+    if (tile < n_tiles)
+        for (int e = lane; e < E; e += 64) tiles[(size_t)tile * E + e] = cnt[e];
+}
+
+// tiles[tile][e] <- number of pairs of expert e in earlier tiles; offsets[E+1] <- expert prefix sums.
+__global__ __launch_bounds__(1024) void k_scan(int *__restrict__ tiles, int n_tiles, int E,
+                                               int32_t *__restrict__ offsets)
+{
+    __shared__ int s_tot[kMaxE];
+    const int e = threadIdx.x;
+    if (e < E) {
+        int run = 0;
+        for (int tl = 0; tl < n_tiles; ++tl) {
+            int c = tiles[(size_t)tl * E + e];
+            tiles[(size_t)tl * E + e] = run;
+            run += c;
+        }
+        s_tot[e] = run;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int j = 0; j < E; ++j) {
+            offsets[j] = run;
+            run += s_tot[j];
+        }
+        offsets[E] = run;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_scatter(const int32_t *__restrict__ assign, const float *__restrict__ gates,
+                                                 size_t n, int E, int k, const int *__restrict__ tiles, int n_tiles,
+                                                 const int32_t *__restrict__ offsets, int32_t *__restrict__ disp_token,
+                                                 float *__restrict__ disp_gate, int32_t *__restrict__ token_pos)
+{
+    extern __shared__ int s_run[];   // [kWavesPerWg][E] running position per expert
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int tile = blockIdx.x * kWavesPerWg + wave;
+    if (tile >= n_tiles) return;     // whole wavefront leaves; no block barrier below
+    int *run = s_run + wave * E;
+    for (int e = lane; e < E; e += 64) run[e] = tiles[(size_t)tile * E + e];
+    __builtin_amdgcn_wave_barrier();
+    const size_t a0 = (size_t)tile * kTile;
+    for (int c = 0; c < kTile; c += 64) {
+        const size_t a = a0 + c + lane;
+        const int e = a < n ? assign[a] : -1;
+        int pos = -1;
+        // lanes holding the same expert take consecutive positions in lane order
+        unsigned long long todo = __ballot(e >= 0);
+        while (todo) {
+            const int leader = __ffsll((long long)todo) - 1;
+            const int el = __shfl(e, leader);
+            const unsigned long long same = __ballot(e == el) & todo;
+            if (e == el && ((todo >> lane) & 1ull)) {
+                pos = run[el] + __popcll(same & ((1ull << lane) - 1));
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (lane == leader) run[el] += __popcll(same);
+            __builtin_amdgcn_wave_barrier();
+            todo &= ~same;
+        }
+        if (a < n) {
+            token_pos[a] = pos;
+            if (e >= 0) {
+                const int dst = offsets[e] + pos;
+                disp_token[dst] = (int32_t)(a / k);
+                if (disp_gate) disp_gate[dst] = gates[a];
+            }
+        }
+    }
+}
+
+}  // namespace
+
+int32_t dispatch_run(const int32_t *assign, const float *gates, int T, int E, int k, int32_t *offsets,
+                     int32_t *disp_token, float *disp_gate, int32_t *token_pos, char *ws, hipStream_t s)
+{
+    WorkspaceLayout L = workspace_layout(T, E, k);
+    int *tiles = (int *)(ws + L.tiles_off);
+    const size_t n = (size_t)T * k;
+    const int n_tiles = L.n_tiles;
+    const int grid = (n_tiles + kWavesPerWg - 1) / kWavesPerWg;
+    const size_t shm = (size_t)kWavesPerWg * E * sizeof(int);
+    hipLaunchKernelGGL(k_tile_hist, dim3(grid), dim3(256), shm, s, assign, n, E, tiles, n_tiles);
+    hipLaunchKernelGGL(k_scan, dim3(1), dim3(1024), 0, s, tiles, n_tiles, E, offsets);
+    hipLaunchKernelGGL(k_scatter, dim3(grid), dim3(256), shm, s, assign, gates, n, E, k, tiles, n_tiles, offsets,
+                       disp_token, disp_gate, token_pos);
+    MS_HIP(hipGetLastError());
+    return MAXSCORE_OK;
+}
+
+}  // namespace maxscore

@@ -1,0 +1,194 @@
+// a1: router projection  logits = x . W_g (+ bias)   (Eq. 2, Algorithm 1 step 2).
+//
+// bf16 inputs run on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).  The output
+// is only E <= 128 columns wide per workgroup, so the kernel is bound by streaming x from HBM:
+// each workgroup owns 128 token rows, walks d in steps of 64, stages the x tile and the transposed
+// W tile in LDS and prefetches the next tiles into registers while the matrix cores work.
+// fp32 inputs (the tiny configuration) use a plain FMA kernel.
+#include "common.h"
+
+namespace maxscore {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+constexpr int BM = 128, BK = 64, LDP = BK + 8;   // LDS row pitch in bf16 elements (pad 16 B)
+
+// 16-byte load of 8 bf16 starting at element (r, c) of a row-major [R, Ccols] matrix, zero outside.
+template <bool ALIGNED>
+__device__ __forceinline__ u32x4 load8(const unsigned short *__restrict__ p, int r, int c, int R, int Ccols)
+{
+    u32x4 out = {0u, 0u, 0u, 0u};
+    if (r >= R || c >= Ccols) return out;
+    const unsigned short *src = p + (size_t)r * Ccols + c;
+    if (ALIGNED && c + 8 <= Ccols) {
+        out = *(const u32x4 *)src;
+    } else {
+        unsigned short tmp[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) tmp[i] = (c + i < Ccols) ? src[i] : (unsigned short)0;
+        out.x = tmp[0] | ((unsigned)tmp[1] << 16);
+        out.y = tmp[2] | ((unsigned)tmp[3] << 16);
+        out.z = tmp[4] | ((unsigned)tmp[5] << 16);
+        out.w = tmp[6] | ((unsigned)tmp[7] << 16);
+    }
+    return out;
+}
+
+// NT = number of 32-column output tiles per workgroup (BN = 32*NT <= 128).
+template <int NT, bool ALIGNED>
+__global__ __launch_bounds__(256) void k_gemm_bf16(const unsigned short *__restrict__ x,
+                                                   const unsigned short *__restrict__ W,
+                                                   const float *__restrict__ bias, int T, int d, int E,
+                                                   float *__restrict__ out)
+{
+    constexpr int BN = 32 * NT;
+    __shared__ __attribute__((aligned(16))) unsigned short sA[BM * LDP];
+    __shared__ __attribute__((aligned(16))) unsigned short sB[BN * LDP];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int row0 = blockIdx.x * BM, col0 = blockIdx.y * 128;
+
+    // global -> register staging: A tile 128 x 64 (4 x 16 B per thread), B tile 64 x BN
+    const int a_r = tid >> 3, a_c = (tid & 7) * 8;              // + 32 rows per pass
+    constexpr int B_VEC_PER_ROW = BN / 8;                        // 16-byte vectors per k-row
+    constexpr int B_VECS = BK * B_VEC_PER_ROW;                   // per tile
+    constexpr int B_PER_THREAD = (B_VECS + 255) / 256;
+    u32x4 ra[4], rb[B_PER_THREAD];
+
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) ra[p] = load8<ALIGNED>(x, row0 + a_r + 32 * p, k0 + a_c, T, d);
+#pragma unroll
+        for (int p = 0; p < B_PER_THREAD; ++p) {
+            int v = tid + 256 * p;
+            int kr = v / B_VEC_PER_ROW, nc = (v % B_VEC_PER_ROW) * 8;
+            rb[p] = (v < B_VECS) ? load8<ALIGNED>(W, k0 + kr, col0 + nc, d, E) : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) *(u32x4 *)&sA[(a_r + 32 * p) * LDP + a_c] = ra[p];
+#pragma unroll
+        for (int p = 0; p < B_PER_THREAD; ++p) {
+            int v = tid + 256 * p;
+            if (v < B_VECS) {
+                int kr = v / B_VEC_PER_ROW, nc = (v % B_VEC_PER_ROW) * 8;
+                unsigned w4[4] = {rb[p].x, rb[p].y, rb[p].z, rb[p].w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {      // transpose: sB[n][k]
+                    sB[(nc + 2 * i) * LDP + kr] = (unsigned short)(w4[i] & 0xffffu);
+                    sB[(nc + 2 * i + 1) * LDP + kr] = (unsigned short)(w4[i] >> 16);
+                }
+            }
+        }
+    };
+
+    f32x16 acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[nt][i] = 0.f;
+
+    fetch(0);
+    for (int k0 = 0; k0 < d; k0 += BK) {
+        __syncthreads();            // previous tile fully consumed
+        stash();
+        __syncthreads();
+        if (k0 + BK < d) fetch(k0 + BK);
+        const int ar = wave * 32 + (lane & 31), kq = 8 * (lane >> 5);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 16) {
+            bf16x8 a = *(const bf16x8 *)&sA[ar * LDP + kk + kq];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                bf16x8 b = *(const bf16x8 *)&sB[(nt * 32 + (lane & 31)) * LDP + kk + kq];
+                acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[nt], 0, 0, 0);
+            }
+        }
+    }
+    // epilogue: acc[nt][4*j + i] is row 8*j + 4*(lane/32) + i, column lane%32 of the 32 x 32 tile
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int col = col0 + nt * 32 + (lane & 31);
+        if (col >= E) continue;
+        const float bv = bias ? bias[col] : 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int row = row0 + wave * 32 + 8 * j + 4 * (lane >> 5) + i;
+                if (row < T) out[(size_t)row * E + col] = acc[nt][4 * j + i] + bv;
+            }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_gemm_f32(const float *__restrict__ x, const float *__restrict__ W,
+                                                  const float *__restrict__ bias, int T, int d, int E,
+                                                  float *__restrict__ out)
+{
+    size_t n = (size_t)T * E;
+    for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < n; o += (size_t)gridDim.x * blockDim.x) {
+        int row = (int)(o / E), col = (int)(o % E);
+        float acc = 0.f;
+        for (int m = 0; m < d; ++m) acc = fmaf(x[(size_t)row * d + m], W[(size_t)m * E + col], acc);
+        out[o] = acc + (bias ? bias[col] : 0.f);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_copy16(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
+
+}  // namespace
+
+int32_t gemm_run(const void *x, const void *W, const float *bias, int dtype, int T, int d, int E, float *logits,
+                 hipStream_t s)
+{
+    if (dtype == MAXSCORE_DTYPE_FP32) {
+        size_t n = (size_t)T * E;
+        int grid = (int)((n + 255) / 256);
+        if (grid > 8192) grid = 8192;
+        hipLaunchKernelGGL(k_gemm_f32, dim3(grid), dim3(256), 0, s, (const float *)x, (const float *)W, bias, T, d,
+                           E, logits);
+        MS_HIP(hipGetLastError());
+        return MAXSCORE_OK;
+    }
+    const unsigned short *xb = (const unsigned short *)x, *wb = (const unsigned short *)W;
+    const bool aligned = (d % 8 == 0) && (E % 8 == 0) && (((uintptr_t)x | (uintptr_t)W) % 16 == 0);
+    dim3 grid((T + BM - 1) / BM, (E + 127) / 128);
+    int et = E >= 128 ? 128 : E;
+    int nt = (et + 31) / 32;
+#define MS_GEMM(NT_, AL_) \
+    hipLaunchKernelGGL((k_gemm_bf16<NT_, AL_>), grid, dim3(256), 0, s, xb, wb, bias, T, d, E, logits)
+    if (aligned) {
+        if (nt == 1) MS_GEMM(1, true);
+        else if (nt == 2) MS_GEMM(2, true);
+        else if (nt == 3) MS_GEMM(3, true);
+        else MS_GEMM(4, true);
+    } else {
+        if (nt == 1) MS_GEMM(1, false);
+        else if (nt == 2) MS_GEMM(2, false);
+        else if (nt == 3) MS_GEMM(3, false);
+        else MS_GEMM(4, false);
+    }
+#undef MS_GEMM
+    MS_HIP(hipGetLastError());
+    return MAXSCORE_OK;
+}
+
+int32_t copy_run(const void *src, void *dst, size_t bytes, hipStream_t s)
+{
+    size_t n = bytes / 16;
+    int grid = (int)((n + 255) / 256);
+    if (grid > 16384) grid = 16384;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(k_copy16, dim3(grid), dim3(256), 0, s, (const u32x4 *)src, (u32x4 *)dst, n);
+    MS_HIP(hipGetLastError());
+    return MAXSCORE_OK;
+}
+
+}  // namespace maxscore
