@@ -36,8 +36,8 @@ struct SolverState {
 };
 
 struct WorkspaceLayout {
-    size_t state_off, theta_off, gcount_off, klist_off, tiles_off, total;
-    int n_tiles;
+    size_t state_off, theta_off, gcount_off, klist_off, wcnt_off, wmoves_off, tiles_off, total;
+    int n_tiles, max_wg;
 };
 
 WorkspaceLayout workspace_layout(int T, int E, int k);

@@ -21,8 +21,11 @@
 //     (T*k < E*C) prices are lowered by beta*eps_prev (clamped at 0) at each phase start, and a
 //     phase that ends with an unfilled expert at a positive price is repeated with beta doubled,
 //     so the final state always has price 0 on unfilled experts.
-//   * The last block of the select pass is the controller: it detects quiescence, advances the
-//     phase and raises `done`.  The host only enqueues rounds and polls `done`.
+//   * Control is on the device.  State, thresholds and per-expert loads are double-buffered by
+//     round parity; every block of the select pass recomputes the same decision (quiescence,
+//     phase change, price lowering, done) from the previous round's loads and this round's move
+//     counts, so no block waits for another and no device-wide fence is needed.  The host only
+//     enqueues rounds and polls `done`.
 #include <vector>
 
 #include "common.h"
@@ -60,13 +63,14 @@ __global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm,
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t n = (size_t)T * k;
     for (size_t a = i; a < n; a += (size_t)gridDim.x * blockDim.x) assign[a] = -1;
-    if (i < (size_t)kMaxE) {
+    if (i < (size_t)2 * kMaxE) {
         theta[i] = 0;
         gcount[i] = 0;
     }
     if (i == 0) {
         qmm[0] = 0x7fffffff;
         qmm[1] = -0x7fffffff - 1;
+        qmm[2] = 0;                      // internal error flag
         st->eps = 1; st->eps_prev = 0; st->beta = 2;
         st->qmin = 0x7fffffff; st->qmax = -0x7fffffff - 1; st->total = 0;
         st->sbits = 0; st->tbits = 0; st->eps_div = eps_div; st->max_rounds = max_rounds;
@@ -77,6 +81,7 @@ __global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm,
 
 __global__ __launch_bounds__(256) void k_minmax(const int32_t *__restrict__ q, size_t n, int *qmin, int *qmax)
 {
+    __shared__ int s_lo[4], s_hi[4];
     int lo = 0x7fffffff, hi = -0x7fffffff - 1;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
         int v = q[i];
@@ -89,6 +94,15 @@ __global__ __launch_bounds__(256) void k_minmax(const int32_t *__restrict__ q, s
         hi = b > hi ? b : hi;
     }
     if ((threadIdx.x & 63) == 0) {
+        s_lo[threadIdx.x >> 6] = lo;
+        s_hi[threadIdx.x >> 6] = hi;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w) {
+            lo = s_lo[w] < lo ? s_lo[w] : lo;
+            hi = s_hi[w] > hi ? s_hi[w] : hi;
+        }
         atomicMin(qmin, lo);
         atomicMax(qmax, hi);
     }
@@ -114,19 +128,24 @@ __global__ void k_setup(SolverState *st, const int *qmin, const int *qmax, int T
     st->eps = eps;
 }
 
-// Bid pass.  A group of G lanes owns one token row; lane l of the group owns experts l, l+G, ...
-// (EPL per lane) and slot l of the token (k <= G).
-template <int G, int EPL>
+// Bid pass.  A group of G lanes owns one token row; lane l of the group owns the EPL consecutive
+// experts l*EPL .. l*EPL+EPL-1 and slot l of the token (k <= G).  A wavefront therefore works on
+// 64/G rows at once and its loads of consecutive rows are contiguous.  The next row of each group
+// is prefetched into registers while the current one is evaluated.
+template <int G, int EPL, bool VEC>
 __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int32_t *__restrict__ assign,
-                                             const long long *__restrict__ theta, SolverState *__restrict__ st,
-                                             long long *__restrict__ klist, int *__restrict__ gcount, int T,
-                                             int E, int k, int rows_per_wg)
+                                             const long long *__restrict__ theta, const SolverState *__restrict__ st,
+                                             long long *__restrict__ klist, int *__restrict__ wcnt,
+                                             int *__restrict__ wmoves, int *__restrict__ errflag, int T, int E, int k,
+                                             int rows_per_wg)
 {
     if (st->done) return;
     constexpr int EP = G * EPL;
+    constexpr int NG = 256 / G;
+    constexpr int LOGP = EPL == 1 ? 0 : EPL == 2 ? 1 : EPL == 4 ? 2 : EPL == 8 ? 3 : 4;
     __shared__ long long s_theta[EP];
     __shared__ int s_cnt[EP];
-    __shared__ int s_base[EP];
+    __shared__ __attribute__((aligned(16))) int s_q[NG * EP];
     __shared__ long long s_key[1024];
     __shared__ short s_exp[1024];
     __shared__ short s_pos[1024];
@@ -143,56 +162,98 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
     __syncthreads();
 
     const int lane = tid & 63, lg = lane & (G - 1), gbase = lane & ~(G - 1);
-    const int grp = tid / G, ngrp = 256 / G;
+    const int grp = tid / G;
     const int row0 = blockIdx.x * rows_per_wg;
     const unsigned long long gmask = (G == 64) ? ~0ull : (((1ull << G) - 1) << gbase);
+    int *sq = s_q + grp * EP;
 
-    for (int lr = grp; lr < rows_per_wg; lr += ngrp) {
+    long long p[EPL];
+    unsigned validm = 0;
+#pragma unroll
+    for (int m = 0; m < EPL; ++m) {
+        int e = lg * EPL + m;
+        p[m] = s_theta[e] >> tb;
+        if (e < E) validm |= 1u << m;
+    }
+
+    int qn[EPL];
+    int an = -2;
+    auto load_row = [&](int row) {
+        const int32_t *qr = q + (size_t)row * E + lg * EPL;
+        if (VEC) {
+            if (EPL >= 4) {
+#pragma unroll
+                for (int m = 0; m < EPL; m += 4) {
+                    int4 t4 = *(const int4 *)(qr + m);
+                    qn[m] = t4.x; qn[m + 1] = t4.y; qn[m + 2] = t4.z; qn[m + 3] = t4.w;
+                }
+            } else if (EPL == 2) {
+                int2 t2 = *(const int2 *)qr;
+                qn[0] = t2.x; qn[1] = t2.y;
+            } else {
+                qn[0] = qr[0];
+            }
+        } else {
+#pragma unroll
+            for (int m = 0; m < EPL; ++m) qn[m] = (lg * EPL + m < E) ? qr[m] : 0;
+        }
+        an = (lg < k) ? assign[(size_t)row * k + lg] : -2;
+    };
+    if (row0 + grp < T && grp < rows_per_wg) load_row(row0 + grp);
+
+    for (int lr = grp; lr < rows_per_wg; lr += NG) {
         const int row = row0 + lr;
         if (row >= T) break;
-        const int32_t *qr = q + (size_t)row * E;
-        const int r0 = row % E;
+        int qc[EPL];
+#pragma unroll
+        for (int m = 0; m < EPL; ++m) qc[m] = qn[m];
+        int my_e = an;
+        if (lr + NG < rows_per_wg && row + NG < T) load_row(row + NG);
+
+        // stage the raw rewards of the row for the slot lanes
+#pragma unroll
+        for (int m = 0; m < EPL; ++m) sq[lg * EPL + m] = qc[m];
 
         long long v[EPL];
-        unsigned validm = 0, heldm = 0;
 #pragma unroll
-        for (int m = 0; m < EPL; ++m) {
-            int e = lg + m * G;
-            if (e < E) {
-                v[m] = (((long long)qr[e] - qmin) << sb) - (s_theta[e] >> tb);
-                validm |= 1u << m;
-            } else {
-                v[m] = 0;
-            }
-        }
-        int my_e = (lg < k) ? assign[(size_t)row * k + lg] : -2;
+        for (int m = 0; m < EPL; ++m) v[m] = (((long long)qc[m] - qmin) << sb) - p[m];
+        unsigned heldm = 0;
         for (int s = 0; s < k; ++s) {
             int es = __shfl(my_e, s, G);
-            if (es >= 0 && (es & (G - 1)) == lg) heldm |= 1u << (es / G);
+            if (es >= 0 && (es >> LOGP) == lg) heldm |= 1u << (es & (EPL - 1));
         }
+        // packed candidate: value, then a per-row rotation of the lane order, then the lower expert
+        const unsigned long long pbase = (kVB << 10) | ((unsigned long long)((lg + row) & (G - 1)) << 4);
         auto local_best = [&]() {
             unsigned long long b = 0;
+            const unsigned cand = validm & ~heldm;
 #pragma unroll
             for (int m = 0; m < EPL; ++m) {
-                if (((validm & ~heldm) >> m) & 1u) {
-                    int tieb = lg + m * G - r0;
-                    if (tieb < 0) tieb += E;
-                    unsigned long long pk = ((unsigned long long)(v[m] + (long long)kVB) << 10) | (unsigned)(1023 - tieb);
-                    b = pk > b ? pk : b;
-                }
+                unsigned long long pk = (unsigned long long)(v[m] << 10) + (pbase | (unsigned)(15 - m));
+                pk = ((cand >> m) & 1u) ? pk : 0ull;
+                b = pk > b ? pk : b;
             }
             return b;
+        };
+        auto decode = [&](unsigned long long pk) {
+            int field = (int)((pk >> 4) & 63), m = 15 - (int)(pk & 15);
+            int l = (field - row) & (G - 1);
+            return l * EPL + m;
         };
         unsigned long long pk = group_max<G>(local_best());
         bool has_alt = pk != 0;
         long long a = (long long)(pk >> 10) - (long long)kVB;
+
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
         // re-validate the held experts against the current prices and thresholds
         long long my_sq = 0;
         const int was_e = my_e;
         bool dropped = false;
         if (my_e >= 0) {
-            my_sq = ((long long)qr[my_e] - qmin) << sb;
+            my_sq = ((long long)sq[my_e] - qmin) << sb;
             long long bid = has_alt ? my_sq - a + eps : kBidBig;
             long long key = bid * ((long long)1 << tb) + row;
             if (key < s_theta[my_e]) {
@@ -208,20 +269,19 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
                 heldm = 0;
                 for (int s = 0; s < k; ++s) {
                     int es = __shfl(my_e, s, G);
-                    if (es >= 0 && (es & (G - 1)) == lg) heldm |= 1u << (es / G);
+                    if (es >= 0 && (es >> LOGP) == lg) heldm |= 1u << (es & (EPL - 1));
                 }
             }
             const int my_rank = (my_e == -1) ? __popcll(gfb & ((1ull << lg) - 1)) : -1;
             for (int r = 0; r < f; ++r) {
                 pk = group_max<G>(local_best());
-                int e = 1023 - (int)(pk & 1023) + r0;
-                if (e >= E) e -= E;
+                int e = decode(pk);
                 if (pk == 0 || e >= E) {          // cannot happen while k <= E; never index out of range
                     e = 0;
-                    st->status = MAXSCORE_ERR_HIP;
+                    *errflag = 1;
                 }
                 long long val = (long long)(pk >> 10) - (long long)kVB;
-                if ((e & (G - 1)) == lg) heldm |= 1u << (e / G);
+                if ((e >> LOGP) == lg) heldm |= 1u << (e & (EPL - 1));
                 if (my_rank == r) {
                     my_e = e;
                     my_sq = val + (s_theta[e] >> tb);
@@ -243,140 +303,264 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
             s_exp[idx] = (short)my_e;
             s_pos[idx] = (short)pos;
         }
+        __builtin_amdgcn_wave_barrier();   // the next row reuses this group's staging buffer
     }
     __syncthreads();
-    for (int e = tid; e < E; e += 256) {
-        int c = s_cnt[e];
-        s_base[e] = c ? atomicAdd(&gcount[e], c) : 0;
-    }
-    if (tid == 0 && s_moves) atomicAdd(&st->moves, s_moves);
-    __syncthreads();
+    // workgroup w owns positions [w*rows_per_wg, (w+1)*rows_per_wg) of every expert's key list (a token
+    // contributes at most one key per expert), so no global atomics are needed
+    const int n_wg = gridDim.x;
+    for (int e = tid; e < E; e += 256) wcnt[(size_t)e * n_wg + blockIdx.x] = s_cnt[e];
+    if (tid == 0) wmoves[blockIdx.x] = s_moves;
     int rows_here = T - row0;
     rows_here = rows_here < rows_per_wg ? rows_here : rows_per_wg;
     const int nslots = rows_here * k;
     for (int idx = tid; idx < nslots; idx += 256) {
         int e = s_exp[idx];
-        klist[(size_t)e * T + s_base[e] + s_pos[idx]] = s_key[idx];
+        klist[(size_t)e * T + row0 + s_pos[idx]] = s_key[idx];
     }
 }
 
 // Select pass: one workgroup per expert; exact (n-Ce+1)-th smallest key by radix select.
 constexpr int kSelThreads = 1024;
 constexpr int kSelCache = 6144;
+constexpr int kSmallRank = 6;
 
-__global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restrict__ klist, int *gcount,
-                                                        long long *theta, SolverState *st, int T, int E, int Ce)
+__global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restrict__ klist,
+                                                        const int *__restrict__ wcnt, const int *__restrict__ wmoves,
+                                                        int *gcount2, long long *theta2, SolverState *st2,
+                                                        const int *__restrict__ errflag, int par, int T, int E,
+                                                        int Ce, int n_wg, int rows_per_wg)
 {
-    if (st->done) return;
+    const SolverState *st = st2 + par;
+    SolverState *st_out = st2 + (par ^ 1);
+    if (st->done) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) *st_out = *st;
+        return;
+    }
+    const long long *theta_in = theta2 + par * kMaxE;
+    long long *theta_out = theta2 + (par ^ 1) * kMaxE;
+    const int *gprev = gcount2 + (par ^ 1) * kMaxE;   // loads after the previous round
+    int *gcur = gcount2 + par * kMaxE;
     __shared__ long long s_keys[kSelCache];
     __shared__ int s_hist[256];
+    __shared__ int s_inc[256];
+    __shared__ int s_wsum[4];
     __shared__ unsigned long long s_red[kSelThreads / 64];
-    __shared__ int s_d, s_rank, s_last, s_over, s_viol, s_action;
+    __shared__ int s_redi[kSelThreads / 64];
+    __shared__ int s_d, s_rank, s_over, s_viol, s_action, s_moves, s_quiet;
     __shared__ long long s_lower;
-    const int tid = threadIdx.x, j = blockIdx.x;
-    const int n = gcount[j];
-    if (n > Ce) {
-        const long long base = theta[j];
-        const long long *keys = klist + (size_t)j * T;
-        const bool cached = n <= kSelCache;
-        unsigned long long umax = 0;
-        for (int i = tid; i < n; i += kSelThreads) {
-            long long kv = keys[i];
-            if (cached) s_keys[i] = kv;
-            unsigned long long u = (unsigned long long)(kv - base);
-            umax = u > umax ? u : umax;
-        }
-        for (int off = 32; off > 0; off >>= 1) {
-            unsigned long long o = shfl_xor_u64(umax, off);
-            umax = o > umax ? o : umax;
-        }
-        if ((tid & 63) == 0) s_red[tid >> 6] = umax;
-        __syncthreads();
-        umax = 0;
-        for (int w = 0; w < kSelThreads / 64; ++w) umax = s_red[w] > umax ? s_red[w] : umax;
-        int nd = 1;
-        while (nd < 8 && (umax >> (8 * nd)) != 0) ++nd;
-        unsigned long long prefix = 0, pmask = 0;
-        int rank = n - Ce;   // 0-based rank of the new threshold among the keys, ascending
-        for (int pass = nd - 1; pass >= 0; --pass) {
-            const int shift = pass * 8;
-            if (tid < 256) s_hist[tid] = 0;
-            __syncthreads();
-            for (int i = tid; i < n; i += kSelThreads) {
-                unsigned long long u = (unsigned long long)((cached ? s_keys[i] : keys[i]) - base);
-                if ((u & pmask) == prefix) atomicAdd(&s_hist[(int)((u >> shift) & 255)], 1);
-            }
-            __syncthreads();
-            if (tid == 0) {
-                int cum = 0, dsel = 0;
-                for (; dsel < 256; ++dsel) {
-                    if (cum + s_hist[dsel] > rank) break;
-                    cum += s_hist[dsel];
-                }
-                s_d = dsel;
-                s_rank = rank - cum;
-            }
-            __syncthreads();
-            prefix |= (unsigned long long)s_d << shift;
-            pmask |= 255ull << shift;
-            rank = s_rank;
-        }
-        if (tid == 0) theta[j] = base + (long long)prefix;
+    const int tid = threadIdx.x, j = blockIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int *cj = wcnt + (size_t)j * n_wg;
+    // number of keys of this expert = sum of the per-workgroup counts; exclusive scan gives each
+    // thread the place of its keys in the LDS copy
+    int ct = 0;
+    for (int w = tid; w < n_wg; w += kSelThreads) ct += cj[w];
+    int inc = ct;
+    for (int off = 1; off < 64; off <<= 1) {
+        int o = __shfl_up(inc, off);
+        if (lane >= off) inc += o;
     }
+    if (lane == 63) s_redi[wv] = inc;
+    __syncthreads();
+    int woff = 0, n = 0;
+    for (int w = 0; w < kSelThreads / 64; ++w) {
+        int v = s_redi[w];
+        if (w < wv) woff += v;
+        n += v;
+    }
+    if (tid == 0) gcur[j] = n;
 
-    // controller: the last block to finish decides what the next round does
-    __threadfence();
+    // the decision every block takes identically: nothing moved in this bid pass and no expert was
+    // above capacity after the previous one  =>  the phase is quiescent
+    if (tid == 0) { s_over = 0; s_viol = 0; s_moves = 0; }
     __syncthreads();
-    if (tid == 0) s_last = (atomicAdd(&st->blocks_done, 1) == (int)gridDim.x - 1);
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    if (tid == 0) { s_over = 0; s_viol = 0; s_action = 0; s_lower = 0; }
-    __syncthreads();
-    const int tb = st->tbits;
-    for (int e = tid; e < E; e += kSelThreads) {
-        int c = __atomic_load_n(&gcount[e], __ATOMIC_RELAXED);
-        long long th = __atomic_load_n(&theta[e], __ATOMIC_RELAXED);
-        if (c > Ce) atomicAdd(&s_over, 1);
-        if (c < Ce && th > 0) atomicAdd(&s_viol, 1);
+    {
+        int mv = 0;
+        for (int w = tid; w < n_wg; w += kSelThreads) mv += wmoves[w];
+        int ov = 0, vi = 0;
+        for (int e = tid; e < E; e += kSelThreads) {
+            const int c = gprev[e];
+            ov += c > Ce;
+            vi += (c < Ce && theta_in[e] > 0);
+        }
+        if (mv) atomicAdd(&s_moves, mv);
+        if (ov) atomicAdd(&s_over, ov);
+        if (vi) atomicAdd(&s_viol, vi);
     }
     __syncthreads();
     if (tid == 0) {
+        SolverState ns = *st;
         const int round = st->round + 1;
-        const bool quiet = (st->moves == 0 && s_over == 0);
+        const bool quiet = (s_moves == 0 && s_over == 0 && st->round > 0);
+        int action = 0;
+        long long lower = 0;
         if (quiet) {
             if (st->slack && s_viol > 0 && st->eps_prev > 0) {
-                st->beta *= 2;          // an unfilled expert kept a positive price: redo the phase lower
-                s_action = 1;
-                s_lower = st->beta * st->eps_prev;
-                st->phases++;
+                ns.beta = st->beta * 2;      // an unfilled expert kept a positive price: redo the phase lower
+                action = 1;
+                lower = ns.beta * st->eps_prev;
+                ns.phases = st->phases + 1;
             } else if (st->eps == 1) {
-                st->done = 1;
+                ns.done = 1;
             } else {
-                st->eps_prev = st->eps;
+                ns.eps_prev = st->eps;
                 long long ne = st->eps / st->eps_div;
-                st->eps = ne > 1 ? ne : 1;
-                st->phases++;
+                ns.eps = ne > 1 ? ne : 1;
+                ns.phases = st->phases + 1;
                 if (st->slack) {
-                    s_action = 1;
-                    s_lower = st->beta * st->eps_prev;
+                    action = 1;
+                    lower = st->beta * st->eps;
                 }
             }
         } else if (round >= st->max_rounds) {
-            st->status = MAXSCORE_ERR_NOT_CONVERGED;
-            st->done = 1;
+            ns.status = MAXSCORE_ERR_NOT_CONVERGED;
+            ns.done = 1;
         }
-        st->round = round;
-        st->moves = 0;
-        st->blocks_done = 0;
+        if (*errflag) {
+            ns.status = MAXSCORE_ERR_HIP;
+            ns.done = 1;
+        }
+        ns.round = round;
+        if (j == 0) *st_out = ns;
+        s_quiet = quiet;
+        s_action = action;
+        s_lower = lower;
     }
     __syncthreads();
-    for (int e = tid; e < E; e += kSelThreads) {
-        gcount[e] = 0;
-        if (s_action) {
-            long long p = (theta[e] >> tb) - s_lower;
-            theta[e] = (p > 0 ? p : 0) << tb;
+    long long new_theta = theta_in[j];
+    if (n > Ce) {
+        const long long base = theta_in[j];
+        const long long *keys = klist + (size_t)j * T;
+        const bool cached = n <= kSelCache;
+        int rank = n - Ce;   // 0-based rank of the new threshold among the keys, ascending
+        unsigned long long umax = 0;
+        {
+            int pos = woff + inc - ct;
+            for (int w = tid; w < n_wg; w += kSelThreads) {
+                const int c = cj[w];
+                const long long *seg = keys + (size_t)w * rows_per_wg;
+                for (int i = 0; i < c; ++i) {
+                    long long kv = seg[i];
+                    if (cached) s_keys[pos++] = kv;
+                    unsigned long long u = (unsigned long long)(kv - base);
+                    umax = u > umax ? u : umax;
+                }
+            }
         }
+        __syncthreads();
+        if (rank < kSmallRank) {
+            // few holders to drop: take the rank+1 smallest keys one at a time (keys are distinct)
+            long long last = -1;
+            for (int it = 0; it <= rank; ++it) {
+                unsigned long long best = ~0ull;
+                if (cached) {
+                    for (int i = tid; i < n; i += kSelThreads) {
+                        long long kv = s_keys[i];
+                        if (kv > last && (unsigned long long)kv < best) best = (unsigned long long)kv;
+                    }
+                } else {
+                    for (int w = tid; w < n_wg; w += kSelThreads) {
+                        const int c = cj[w];
+                        const long long *seg = keys + (size_t)w * rows_per_wg;
+                        for (int i = 0; i < c; ++i) {
+                            long long kv = seg[i];
+                            if (kv > last && (unsigned long long)kv < best) best = (unsigned long long)kv;
+                        }
+                    }
+                }
+                for (int off = 32; off > 0; off >>= 1) {
+                    unsigned long long o = shfl_xor_u64(best, off);
+                    best = o < best ? o : best;
+                }
+                if (lane == 0) s_red[wv] = best;
+                __syncthreads();
+                best = s_red[0];
+                for (int w = 1; w < kSelThreads / 64; ++w) best = s_red[w] < best ? s_red[w] : best;
+                last = (long long)best;
+                __syncthreads();
+            }
+            new_theta = last;
+        } else {
+            for (int off = 32; off > 0; off >>= 1) {
+                unsigned long long o = shfl_xor_u64(umax, off);
+                umax = o > umax ? o : umax;
+            }
+            if (lane == 0) s_red[wv] = umax;
+            __syncthreads();
+            umax = 0;
+            for (int w = 0; w < kSelThreads / 64; ++w) umax = s_red[w] > umax ? s_red[w] : umax;
+            int nd = 1;
+            while (nd < 8 && (umax >> (8 * nd)) != 0) ++nd;
+            unsigned long long prefix = 0, pmask = 0;
+            auto tally = [&](long long kv, int shift) {
+                unsigned long long u = (unsigned long long)(kv - base);
+                const bool act = (u & pmask) == prefix;
+                const int dg = (int)((u >> shift) & 255);
+                // a whole wavefront often lands in one bin: add it once instead of 64 colliding atomics
+                const unsigned long long am = __ballot(act);
+                if (am) {
+                    const int leader = __ffsll((long long)am) - 1;
+                    const int dl = __shfl(dg, leader);
+                    const unsigned long long same = __ballot(act && dg == dl);
+                    if (same == am) {
+                        if (lane == leader) atomicAdd(&s_hist[dl], __popcll(same));
+                    } else if (act) {
+                        atomicAdd(&s_hist[dg], 1);
+                    }
+                }
+            };
+            for (int pass = nd - 1; pass >= 0; --pass) {
+                const int shift = pass * 8;
+                if (tid < 256) s_hist[tid] = 0;
+                __syncthreads();
+                if (cached) {
+                    for (int i = tid; i < n; i += kSelThreads) tally(s_keys[i], shift);
+                } else {
+                    for (int w = tid; w < n_wg; w += kSelThreads) {
+                        const int c = cj[w];
+                        const long long *seg = keys + (size_t)w * rows_per_wg;
+                        for (int i = 0; i < c; ++i) {
+                            unsigned long long u = (unsigned long long)(seg[i] - base);
+                            if ((u & pmask) == prefix) atomicAdd(&s_hist[(int)((u >> shift) & 255)], 1);
+                        }
+                    }
+                }
+                __syncthreads();
+                if (tid < 256) {        // inclusive scan of the 256 bins by four wavefronts
+                    const int h = s_hist[tid];
+                    int hi = h;
+                    for (int off = 1; off < 64; off <<= 1) {
+                        int o = __shfl_up(hi, off);
+                        if (lane >= off) hi += o;
+                    }
+                    if (lane == 63) s_wsum[wv] = hi;
+                    s_inc[tid] = hi;
+                }
+                __syncthreads();
+                if (tid < 256) {
+                    int add = 0;
+                    for (int w = 0; w < wv; ++w) add += s_wsum[w];
+                    const int hi = s_inc[tid] + add, exc = hi - s_hist[tid];
+                    if (exc <= rank && rank < hi) {
+                        s_d = tid;
+                        s_rank = rank - exc;
+                    }
+                }
+                __syncthreads();
+                prefix |= (unsigned long long)s_d << shift;
+                pmask |= 255ull << shift;
+                rank = s_rank;
+            }
+            new_theta = base + (long long)prefix;
+        }
+    }
+
+    if (tid == 0) {
+        if (s_action) {
+            long long p = (new_theta >> st->tbits) - s_lower;
+            new_theta = (p > 0 ? p : 0) << st->tbits;
+        }
+        theta_out[j] = new_theta;
     }
 }
 
@@ -411,12 +595,31 @@ __global__ __launch_bounds__(256) void k_finalize(const int32_t *__restrict__ q,
 }
 
 template <int G, int EPL>
-void launch_bid(const int32_t *q, int32_t *assign, const long long *theta, SolverState *st, long long *klist,
-                int *gcount, int T, int E, int k, int rows_per_wg, hipStream_t s)
+void launch_bid(bool vec, const int32_t *q, int32_t *assign, const long long *theta, const SolverState *st,
+                long long *klist, int *wcnt, int *wmoves, int *errflag, int T, int E, int k, int rows_per_wg,
+                hipStream_t s)
 {
     int grid = (T + rows_per_wg - 1) / rows_per_wg;
-    hipLaunchKernelGGL((k_bid<G, EPL>), dim3(grid), dim3(256), 0, s, q, assign, theta, st, klist, gcount, T, E, k,
-                       rows_per_wg);
+    if (vec)
+        hipLaunchKernelGGL((k_bid<G, EPL, true>), dim3(grid), dim3(256), 0, s, q, assign, theta, st, klist, wcnt,
+                           wmoves, errflag, T, E, k, rows_per_wg);
+    else
+        hipLaunchKernelGGL((k_bid<G, EPL, false>), dim3(grid), dim3(256), 0, s, q, assign, theta, st, klist,
+                           wcnt, wmoves, errflag, T, E, k, rows_per_wg);
+}
+
+template <int G>
+void launch_bid_g(int EPL, bool vec, const int32_t *q, int32_t *assign, const long long *theta,
+                  const SolverState *st, long long *klist, int *wcnt, int *wmoves, int *errflag, int T, int E, int k,
+                  int rows_per_wg, hipStream_t s)
+{
+#define MS_B(PP) launch_bid<G, PP>(vec, q, assign, theta, st, klist, wcnt, wmoves, errflag, T, E, k, rows_per_wg, s)
+    if (EPL == 1) MS_B(1);
+    else if (EPL == 2) MS_B(2);
+    else if (EPL == 4) MS_B(4);
+    else if (EPL == 8) MS_B(8);
+    else MS_B(16);
+#undef MS_B
 }
 
 }  // namespace
@@ -429,18 +632,23 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     long long *theta = (long long *)(ws + L.theta_off);
     int *gcount = (int *)(ws + L.gcount_off);
     long long *klist = (long long *)(ws + L.klist_off);
-    int *qmm = gcount + kMaxE;   // two ints after the counters: reward min / max
+    int *qmm = gcount + 2 * kMaxE;   // after the counters: reward min, max, internal error flag
+    int *wcnt = (int *)(ws + L.wcnt_off);
+    int *wmoves = (int *)(ws + L.wmoves_off);
 
-    // group size / elements per lane
+    // lanes per token row (G >= k) and consecutive experts per lane
     int G = 8, EPL = 1;
-    while (G < 64 && G < E) G *= 2;
+    while (G < k) G *= 2;
+    while (G * 16 < E) G *= 2;
     while (G * EPL < E) EPL *= 2;
     const int ngrp = 256 / G;
-    int rows = (T + 1023) / 1024;
-    if (rows > 1024 / k) rows = 1024 / k;
-    rows = ((rows + ngrp - 1) / ngrp) * ngrp;
-    if (rows * k > 1024) rows = (1024 / k / ngrp) * ngrp;
-    if (rows < 1) return MAXSCORE_ERR_SHAPE;
+    int rows = ngrp * 2;
+    while (rows * 2 * k <= 1024 && (T + rows - 1) / rows > 4096) rows *= 2;
+    if (rows * k > 1024) rows = ngrp;
+    if (rows * k > 1024) return MAXSCORE_ERR_SHAPE;
+    const bool vec = (E == G * EPL) && (((uintptr_t)q) % 16 == 0);
+    const int n_wg = (T + rows - 1) / rows;
+    if (n_wg > L.max_wg) return MAXSCORE_ERR_WORKSPACE;
 
     const int slack = ((long long)E * Ce - (long long)T * k) > 0 ? 1 : 0;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
@@ -456,7 +664,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
                            o.eps_div, o.max_rounds, slack);
         size_t nq = (size_t)T * E;
         int g2 = (int)((nq + 256 * 16 - 1) / (256 * 16));
-        if (g2 > 2048) g2 = 2048;
+        if (g2 > 1024) g2 = 1024;
         if (g2 < 1) g2 = 1;
         hipLaunchKernelGGL(k_minmax, dim3(g2), dim3(256), 0, s, q, nq, qmm, qmm + 1);
         hipLaunchKernelGGL(k_setup, dim3(1), dim3(1), 0, s, st, qmm, qmm + 1, T, E);
@@ -467,6 +675,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     int h_done = 0;
     while (!h_done) {
         for (int b = 0; b < batch; ++b) {
+            const int par = launched & 1;
             if (g_kernel_timing) {
                 hipEvent_t e0, e1;
                 MS_HIP(hipEventCreate(&e0));
@@ -475,29 +684,30 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
                 tev.push_back(e1);
                 MS_HIP(hipEventRecord(e0, s));
             }
-#define MS_BID(GG, PP) launch_bid<GG, PP>(q, assign, theta, st, klist, gcount, T, E, k, rows, s)
-            if (G == 8) MS_BID(8, 1);
-            else if (G == 16) MS_BID(16, 1);
-            else if (G == 32) MS_BID(32, 1);
-            else if (EPL == 1) MS_BID(64, 1);
-            else if (EPL == 2) MS_BID(64, 2);
-            else if (EPL == 4) MS_BID(64, 4);
-            else if (EPL == 8) MS_BID(64, 8);
-            else MS_BID(64, 16);
+#define MS_BID(GG)                                                                                   \
+    launch_bid_g<GG>(EPL, vec, q, assign, theta + par * kMaxE, st + par, klist, wcnt, wmoves, qmm + 2, T, E, k, \
+                     rows, s)
+            if (G == 8) MS_BID(8);
+            else if (G == 16) MS_BID(16);
+            else if (G == 32) MS_BID(32);
+            else MS_BID(64);
 #undef MS_BID
             if (g_kernel_timing) MS_HIP(hipEventRecord(tev.back(), s));
-            hipLaunchKernelGGL(k_select, dim3(E), dim3(kSelThreads), 0, s, klist, gcount, theta, st, T, E, Ce);
+            hipLaunchKernelGGL(k_select, dim3(E), dim3(kSelThreads), 0, s, klist, wcnt, wmoves, gcount, theta, st,
+                               qmm + 2, par, T, E, Ce, n_wg, rows);
             ++launched;
         }
-        MS_HIP(hipMemcpyAsync(&h_done, &st->done, sizeof(int), hipMemcpyDeviceToHost, s));
+        MS_HIP(hipMemcpyAsync(&h_done, &st[launched & 1].done, sizeof(int), hipMemcpyDeviceToHost, s));
         MS_HIP(hipStreamSynchronize(s));
         if (launched > o.max_rounds + 64) break;
         if (batch < 64) batch *= 2;
     }
-    hipLaunchKernelGGL(k_finalize, dim3(256), dim3(256), 0, s, q, assign, theta, st, prices, price_scale, T, E, k);
+    const int fpar = launched & 1;
+    hipLaunchKernelGGL(k_finalize, dim3(256), dim3(256), 0, s, q, assign, theta + fpar * kMaxE, st + fpar, prices,
+                       price_scale, T, E, k);
     MS_HIP(hipEventRecord(ev1, s));
     SolverState h;
-    MS_HIP(hipMemcpyAsync(&h, st, sizeof(h), hipMemcpyDeviceToHost, s));
+    MS_HIP(hipMemcpyAsync(&h, st + fpar, sizeof(h), hipMemcpyDeviceToHost, s));
     MS_HIP(hipStreamSynchronize(s));
     MS_HIP(hipGetLastError());
     float ms = 0.f, bid_ms = 0.f;
