@@ -32,7 +32,7 @@ struct SolverState {
     int blocks_done;       // completion counter of the select pass
     int flow;
     int slack;             // E*Ce - T*k > 0
-    int pad[4];
+    int phase_round[28];   // round index at which each phase ended (diagnostic)
 };
 
 struct WorkspaceLayout {

@@ -26,6 +26,8 @@
 //     phase change, price lowering, done) from the previous round's loads and this round's move
 //     counts, so no block waits for another and no device-wide fence is needed.  The host only
 //     enqueues rounds and polls `done`.
+#include <cstdio>
+#include <cstdlib>
 #include <vector>
 
 #include "common.h"
@@ -76,6 +78,7 @@ __global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm,
         st->sbits = 0; st->tbits = 0; st->eps_div = eps_div; st->max_rounds = max_rounds;
         st->round = 0; st->phases = 1; st->done = 0; st->status = MAXSCORE_OK; st->moves = 0;
         st->blocks_done = 0; st->flow = 0; st->slack = slack;
+        for (int a = 0; a < 28; ++a) st->phase_round[a] = 0;
     }
 }
 
@@ -152,30 +155,13 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
     __shared__ int s_moves;
 
     const int tid = threadIdx.x;
-    const long long eps = st->eps, qmin = st->qmin;
-    const int sb = st->sbits, tb = st->tbits;
-    for (int e = tid; e < EP; e += 256) {
-        s_theta[e] = e < E ? theta[e] : 0;
-        s_cnt[e] = 0;
-    }
-    if (tid == 0) s_moves = 0;
-    __syncthreads();
-
     const int lane = tid & 63, lg = lane & (G - 1), gbase = lane & ~(G - 1);
     const int grp = tid / G;
     const int row0 = blockIdx.x * rows_per_wg;
     const unsigned long long gmask = (G == 64) ? ~0ull : (((1ull << G) - 1) << gbase);
     int *sq = s_q + grp * EP;
 
-    long long p[EPL];
-    unsigned validm = 0;
-#pragma unroll
-    for (int m = 0; m < EPL; ++m) {
-        int e = lg * EPL + m;
-        p[m] = s_theta[e] >> tb;
-        if (e < E) validm |= 1u << m;
-    }
-
+    // the first row of every group is requested before anything else
     int qn[EPL];
     int an = -2;
     auto load_row = [&](int row) {
@@ -200,6 +186,24 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
         an = (lg < k) ? assign[(size_t)row * k + lg] : -2;
     };
     if (row0 + grp < T && grp < rows_per_wg) load_row(row0 + grp);
+
+    const long long eps = st->eps, qmin = st->qmin;
+    const int sb = st->sbits, tb = st->tbits;
+    for (int e = tid; e < EP; e += 256) {
+        s_theta[e] = e < E ? theta[e] : 0;
+        s_cnt[e] = 0;
+    }
+    if (tid == 0) s_moves = 0;
+    __syncthreads();
+
+    long long p[EPL];
+    unsigned validm = 0;
+#pragma unroll
+    for (int m = 0; m < EPL; ++m) {
+        int e = lg * EPL + m;
+        p[m] = s_theta[e] >> tb;
+        if (e < E) validm |= 1u << m;
+    }
 
     for (int lr = grp; lr < rows_per_wg; lr += NG) {
         const int row = row0 + lr;
@@ -347,72 +351,76 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     __shared__ int s_wsum[4];
     __shared__ unsigned long long s_red[kSelThreads / 64];
     __shared__ int s_redi[kSelThreads / 64];
-    __shared__ int s_d, s_rank, s_over, s_viol, s_action, s_moves, s_quiet;
-    __shared__ long long s_lower;
+    __shared__ int s_d, s_rank;
+    __shared__ int s_flag[kSelThreads / 64];
     const int tid = threadIdx.x, j = blockIdx.x, lane = tid & 63, wv = tid >> 6;
     const int *cj = wcnt + (size_t)j * n_wg;
-    // number of keys of this expert = sum of the per-workgroup counts; exclusive scan gives each
-    // thread the place of its keys in the LDS copy
-    int ct = 0;
-    for (int w = tid; w < n_wg; w += kSelThreads) ct += cj[w];
+    // One reduction for everything the block needs: the number of keys of this expert (sum of the
+    // per-workgroup counts, with an exclusive scan that places each thread's keys in the LDS copy),
+    // the moves of this bid pass, and the over-capacity / unfilled-but-priced experts after the
+    // previous round.  All loads are issued before the single barrier.
+    int ct = 0, mv = 0, ov = 0, vi = 0;
+    for (int w = tid; w < n_wg; w += kSelThreads) {
+        ct += cj[w];
+        mv += wmoves[w];
+    }
+    for (int e = tid; e < E; e += kSelThreads) {
+        const int c = gprev[e];
+        ov += c > Ce;
+        vi += (c < Ce && theta_in[e] > 0);
+    }
+    const int cur_round = st->round, cur_slack = st->slack, cur_tbits = st->tbits;
+    const long long cur_eps = st->eps, cur_eps_prev = st->eps_prev, cur_beta = st->beta;
     int inc = ct;
     for (int off = 1; off < 64; off <<= 1) {
         int o = __shfl_up(inc, off);
         if (lane >= off) inc += o;
     }
+    int flags = (mv ? 1 : 0) | (ov ? 2 : 0) | (vi ? 4 : 0);
+    for (int off = 32; off > 0; off >>= 1) flags |= __shfl_xor(flags, off);
     if (lane == 63) s_redi[wv] = inc;
+    if (lane == 0) s_flag[wv] = flags;
     __syncthreads();
     int woff = 0, n = 0;
+    flags = 0;
     for (int w = 0; w < kSelThreads / 64; ++w) {
         int v = s_redi[w];
         if (w < wv) woff += v;
         n += v;
+        flags |= s_flag[w];
     }
     if (tid == 0) gcur[j] = n;
 
-    // the decision every block takes identically: nothing moved in this bid pass and no expert was
-    // above capacity after the previous one  =>  the phase is quiescent
-    if (tid == 0) { s_over = 0; s_viol = 0; s_moves = 0; }
-    __syncthreads();
-    {
-        int mv = 0;
-        for (int w = tid; w < n_wg; w += kSelThreads) mv += wmoves[w];
-        int ov = 0, vi = 0;
-        for (int e = tid; e < E; e += kSelThreads) {
-            const int c = gprev[e];
-            ov += c > Ce;
-            vi += (c < Ce && theta_in[e] > 0);
-        }
-        if (mv) atomicAdd(&s_moves, mv);
-        if (ov) atomicAdd(&s_over, ov);
-        if (vi) atomicAdd(&s_viol, vi);
+    // the decision every thread of every block takes identically: nothing moved in this bid pass and
+    // no expert was above capacity after the previous one  =>  the phase is quiescent
+    const bool quiet = ((flags & 3) == 0 && cur_round > 0);
+    const bool redo = quiet && cur_slack && (flags & 4) && cur_eps_prev > 0;
+    int action = 0;
+    long long lower = 0;
+    if (redo) {
+        action = 1;                          // an unfilled expert kept a positive price: redo the phase lower
+        lower = cur_beta * 2 * cur_eps_prev;
+    } else if (quiet && cur_eps != 1 && cur_slack) {
+        action = 1;
+        lower = cur_beta * cur_eps;
     }
-    __syncthreads();
-    if (tid == 0) {
+    if (j == 0 && tid == 0) {
         SolverState ns = *st;
-        const int round = st->round + 1;
-        const bool quiet = (s_moves == 0 && s_over == 0 && st->round > 0);
-        int action = 0;
-        long long lower = 0;
+        const int round = cur_round + 1;
         if (quiet) {
-            if (st->slack && s_viol > 0 && st->eps_prev > 0) {
-                ns.beta = st->beta * 2;      // an unfilled expert kept a positive price: redo the phase lower
-                action = 1;
-                lower = ns.beta * st->eps_prev;
-                ns.phases = st->phases + 1;
-            } else if (st->eps == 1) {
+            if (ns.phases <= 28) ns.phase_round[ns.phases - 1] = round;
+            if (redo) {
+                ns.beta = cur_beta * 2;
+                ns.phases += 1;
+            } else if (cur_eps == 1) {
                 ns.done = 1;
             } else {
-                ns.eps_prev = st->eps;
-                long long ne = st->eps / st->eps_div;
+                ns.eps_prev = cur_eps;
+                long long ne = cur_eps / ns.eps_div;
                 ns.eps = ne > 1 ? ne : 1;
-                ns.phases = st->phases + 1;
-                if (st->slack) {
-                    action = 1;
-                    lower = st->beta * st->eps;
-                }
+                ns.phases += 1;
             }
-        } else if (round >= st->max_rounds) {
+        } else if (round >= ns.max_rounds) {
             ns.status = MAXSCORE_ERR_NOT_CONVERGED;
             ns.done = 1;
         }
@@ -421,12 +429,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             ns.done = 1;
         }
         ns.round = round;
-        if (j == 0) *st_out = ns;
-        s_quiet = quiet;
-        s_action = action;
-        s_lower = lower;
+        *st_out = ns;
     }
-    __syncthreads();
     long long new_theta = theta_in[j];
     if (n > Ce) {
         const long long base = theta_in[j];
@@ -439,11 +443,18 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             for (int w = tid; w < n_wg; w += kSelThreads) {
                 const int c = cj[w];
                 const long long *seg = keys + (size_t)w * rows_per_wg;
-                for (int i = 0; i < c; ++i) {
-                    long long kv = seg[i];
-                    if (cached) s_keys[pos++] = kv;
-                    unsigned long long u = (unsigned long long)(kv - base);
-                    umax = u > umax ? u : umax;
+                for (int i0 = 0; i0 < c; i0 += 8) {      // eight independent loads in flight per thread
+                    long long kv[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) kv[u] = (i0 + u < c) ? seg[i0 + u] : base;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        if (i0 + u < c) {
+                            if (cached) s_keys[pos++] = kv[u];
+                            unsigned long long uu = (unsigned long long)(kv[u] - base);
+                            umax = uu > umax ? uu : umax;
+                        }
+                    }
                 }
             }
         }
@@ -556,9 +567,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     }
 
     if (tid == 0) {
-        if (s_action) {
-            long long p = (new_theta >> st->tbits) - s_lower;
-            new_theta = (p > 0 ? p : 0) << st->tbits;
+        if (action) {
+            long long p = (new_theta >> cur_tbits) - lower;
+            new_theta = (p > 0 ? p : 0) << cur_tbits;
         }
         theta_out[j] = new_theta;
     }
@@ -725,6 +736,11 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     }
     (void)hipEventDestroy(ev0);
     (void)hipEventDestroy(ev1);
+    if (getenv("MAXSCORE_DEBUG")) {
+        fprintf(stderr, "[maxscore] phase end rounds:");
+        for (int a = 0; a < 28 && a < h.phases; ++a) fprintf(stderr, " %d", h.phase_round[a]);
+        fprintf(stderr, "\n");
+    }
     if (stats) {
         stats->total_score_q = h.total;
         stats->flow_value = h.flow;
