@@ -15,7 +15,7 @@ def build(verbose: bool = False) -> str:
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB] + os.environ.get("MAXSCORE_CXXFLAGS", "").split() + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)

@@ -18,6 +18,7 @@ WorkspaceLayout workspace_layout(int T, int E, int k)
     L.max_wg = (T + 3) / 4 < 1 ? 1 : (T + 3) / 4;   // a bid workgroup covers at least 4 token rows
     L.wcnt_off = off; off = align_up(off + sizeof(int) * (size_t)E * L.max_wg, 256);
     L.wmoves_off = off; off = align_up(off + sizeof(int) * (size_t)L.max_wg, 256);
+    L.cand_off = off; off = align_up(off + sizeof(long long) * (size_t)kMaxE * (kCand + 2), 256);
     L.n_tiles = (int)(((size_t)T * k + 1023) / 1024);
     L.tiles_off = off; off = align_up(off + sizeof(int) * (size_t)L.n_tiles * E, 256);
     L.total = off;

@@ -12,6 +12,8 @@ constexpr int kMaxE = 1024;
 constexpr int kMaxK = 64;
 constexpr int kMaxTBits = 21;
 constexpr int64_t kBidBig = (int64_t)1 << 40;   // bid of a token that has no alternative left
+constexpr int kCand = 32;          // lowest keys per expert handed to the tail pass
+constexpr int kTailMaxE = 256;     // the tail pass keeps all candidate lists in LDS
 
 // Device-resident control block of one assignment solve.
 struct SolverState {
@@ -32,11 +34,16 @@ struct SolverState {
     int blocks_done;       // completion counter of the select pass
     int flow;
     int slack;             // E*Ce - T*k > 0
+    int wide;              // 1: prices near 2^30, the bid pass must use 64-bit values
+    int tail_go;           // the select pass built candidate lists: the tail pass may run
+    int after_tail;        // the tail pass changed the state: the next round cannot be declared quiescent
+    int tail_block;        // the tail pass could not proceed: the next select pass must do a normal select
+    int tail_runs, tail_iters;   // diagnostics
     int phase_round[28];   // round index at which each phase ended (diagnostic)
 };
 
 struct WorkspaceLayout {
-    size_t state_off, theta_off, gcount_off, klist_off, wcnt_off, wmoves_off, tiles_off, total;
+    size_t state_off, theta_off, gcount_off, klist_off, wcnt_off, wmoves_off, cand_off, tiles_off, total;
     int n_tiles, max_wg;
 };
 

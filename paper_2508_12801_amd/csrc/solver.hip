@@ -78,6 +78,8 @@ __global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm,
         st->sbits = 0; st->tbits = 0; st->eps_div = eps_div; st->max_rounds = max_rounds;
         st->round = 0; st->phases = 1; st->done = 0; st->status = MAXSCORE_OK; st->moves = 0;
         st->blocks_done = 0; st->flow = 0; st->slack = slack;
+        st->wide = 0; st->tail_go = 0; st->after_tail = 0; st->tail_block = 0; st->tail_runs = 0;
+        st->tail_iters = 0;
         for (int a = 0; a < 28; ++a) st->phase_round[a] = 0;
     }
 }
@@ -328,12 +330,15 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
 constexpr int kSelThreads = 1024;
 constexpr int kSelCache = 6144;
 constexpr int kSmallRank = 6;
+constexpr int kTailMoves = 96;            // hand over to the tail pass when a bid pass moved this few slots
+constexpr long long kKeyInf = (long long)1 << 62;
 
 __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restrict__ klist,
                                                         const int *__restrict__ wcnt, const int *__restrict__ wmoves,
                                                         int *gcount2, long long *theta2, SolverState *st2,
-                                                        const int *__restrict__ errflag, int par, int T, int E,
-                                                        int Ce, int n_wg, int rows_per_wg)
+                                                        const int *__restrict__ errflag, long long *__restrict__ cand,
+                                                        int par, int T, int E, int Ce, int n_wg, int rows_per_wg,
+                                                        int tail_on)
 {
     const SolverState *st = st2 + par;
     SolverState *st_out = st2 + (par ^ 1);
@@ -351,8 +356,10 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     __shared__ int s_wsum[4];
     __shared__ unsigned long long s_red[kSelThreads / 64];
     __shared__ int s_redi[kSelThreads / 64];
-    __shared__ int s_d, s_rank;
     __shared__ int s_flag[kSelThreads / 64];
+    __shared__ int s_mvw[kSelThreads / 64];
+    __shared__ long long s_cl[kCand];
+    __shared__ int s_d, s_rank, s_ncl;
     const int tid = threadIdx.x, j = blockIdx.x, lane = tid & 63, wv = tid >> 6;
     const int *cj = wcnt + (size_t)j * n_wg;
     // One reduction for everything the block needs: the number of keys of this expert (sum of the
@@ -369,32 +376,45 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
         ov += c > Ce;
         vi += (c < Ce && theta_in[e] > 0);
     }
-    const int cur_round = st->round, cur_slack = st->slack, cur_tbits = st->tbits;
+    const int cur_round = st->round, cur_slack = st->slack, cur_tbits = st->tbits, cur_after_tail = st->after_tail,
+              cur_tail_block = st->tail_block;
     const long long cur_eps = st->eps, cur_eps_prev = st->eps_prev, cur_beta = st->beta;
     int inc = ct;
     for (int off = 1; off < 64; off <<= 1) {
         int o = __shfl_up(inc, off);
         if (lane >= off) inc += o;
     }
-    int flags = (mv ? 1 : 0) | (ov ? 2 : 0) | (vi ? 4 : 0);
-    for (int off = 32; off > 0; off >>= 1) flags |= __shfl_xor(flags, off);
+    int flags = (ov ? 2 : 0) | (vi ? 4 : 0);
+    for (int off = 32; off > 0; off >>= 1) {
+        flags |= __shfl_xor(flags, off);
+        mv += __shfl_xor(mv, off);
+    }
     if (lane == 63) s_redi[wv] = inc;
-    if (lane == 0) s_flag[wv] = flags;
+    if (lane == 0) {
+        s_flag[wv] = flags;
+        s_mvw[wv] = mv;
+    }
+    if (tid == 0) s_ncl = 0;
     __syncthreads();
-    int woff = 0, n = 0;
+    int woff = 0, n = 0, moves = 0;
     flags = 0;
     for (int w = 0; w < kSelThreads / 64; ++w) {
         int v = s_redi[w];
         if (w < wv) woff += v;
         n += v;
         flags |= s_flag[w];
+        moves += s_mvw[w];
     }
     if (tid == 0) gcur[j] = n;
 
     // the decision every thread of every block takes identically: nothing moved in this bid pass and
     // no expert was above capacity after the previous one  =>  the phase is quiescent
-    const bool quiet = ((flags & 3) == 0 && cur_round > 0);
+    const bool quiet = (moves == 0 && (flags & 2) == 0 && cur_round > 0 && !cur_after_tail);
     const bool redo = quiet && cur_slack && (flags & 4) && cur_eps_prev > 0;
+    // few slots moved: leave the thresholds alone, publish each expert's lowest keys and let the
+    // single-workgroup tail pass run the next rounds on them
+    const bool tail_go = tail_on && !quiet && !cur_tail_block && cur_round > 0 && moves <= kTailMoves &&
+                         (moves > 0 || (flags & 2));
     int action = 0;
     long long lower = 0;
     if (redo) {
@@ -429,14 +449,18 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             ns.done = 1;
         }
         ns.round = round;
+        ns.tail_go = tail_go ? 1 : 0;
+        ns.after_tail = 0;
+        ns.tail_block = 0;
         *st_out = ns;
     }
     long long new_theta = theta_in[j];
-    if (n > Ce) {
+    const bool need_select = !tail_go && n > Ce;
+    const bool need_cand = tail_go;
+    if (need_select || need_cand) {
         const long long base = theta_in[j];
         const long long *keys = klist + (size_t)j * T;
         const bool cached = n <= kSelCache;
-        int rank = n - Ce;   // 0-based rank of the new threshold among the keys, ascending
         unsigned long long umax = 0;
         {
             int pos = woff + inc - ct;
@@ -459,26 +483,26 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             }
         }
         __syncthreads();
-        if (rank < kSmallRank) {
-            // few holders to drop: take the rank+1 smallest keys one at a time (keys are distinct)
+        // visit every key of this expert (LDS copy when it fits, else the global segments)
+        auto for_keys = [&](auto fn) {
+            if (cached) {
+                for (int i = tid; i < n; i += kSelThreads) fn(s_keys[i]);
+            } else {
+                for (int w = tid; w < n_wg; w += kSelThreads) {
+                    const int c = cj[w];
+                    const long long *seg = keys + (size_t)w * rows_per_wg;
+                    for (int i = 0; i < c; ++i) fn(seg[i]);
+                }
+            }
+        };
+        // key of 0-based rank `rank` in ascending order, by successive minima (small rank) ...
+        auto nth_by_minima = [&](int rank) {
             long long last = -1;
             for (int it = 0; it <= rank; ++it) {
                 unsigned long long best = ~0ull;
-                if (cached) {
-                    for (int i = tid; i < n; i += kSelThreads) {
-                        long long kv = s_keys[i];
-                        if (kv > last && (unsigned long long)kv < best) best = (unsigned long long)kv;
-                    }
-                } else {
-                    for (int w = tid; w < n_wg; w += kSelThreads) {
-                        const int c = cj[w];
-                        const long long *seg = keys + (size_t)w * rows_per_wg;
-                        for (int i = 0; i < c; ++i) {
-                            long long kv = seg[i];
-                            if (kv > last && (unsigned long long)kv < best) best = (unsigned long long)kv;
-                        }
-                    }
-                }
+                for_keys([&](long long kv) {
+                    if (kv > last && (unsigned long long)kv < best) best = (unsigned long long)kv;
+                });
                 for (int off = 32; off > 0; off >>= 1) {
                     unsigned long long o = shfl_xor_u64(best, off);
                     best = o < best ? o : best;
@@ -490,52 +514,30 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                 last = (long long)best;
                 __syncthreads();
             }
-            new_theta = last;
-        } else {
+            return last;
+        };
+        // ... or by most-significant-digit radix select on key - base
+        auto nth_by_radix = [&](int rank) {
+            unsigned long long um = umax;
             for (int off = 32; off > 0; off >>= 1) {
-                unsigned long long o = shfl_xor_u64(umax, off);
-                umax = o > umax ? o : umax;
+                unsigned long long o = shfl_xor_u64(um, off);
+                um = o > um ? o : um;
             }
-            if (lane == 0) s_red[wv] = umax;
+            if (lane == 0) s_red[wv] = um;
             __syncthreads();
-            umax = 0;
-            for (int w = 0; w < kSelThreads / 64; ++w) umax = s_red[w] > umax ? s_red[w] : umax;
+            um = 0;
+            for (int w = 0; w < kSelThreads / 64; ++w) um = s_red[w] > um ? s_red[w] : um;
             int nd = 1;
-            while (nd < 8 && (umax >> (8 * nd)) != 0) ++nd;
+            while (nd < 8 && (um >> (8 * nd)) != 0) ++nd;
             unsigned long long prefix = 0, pmask = 0;
-            auto tally = [&](long long kv, int shift) {
-                unsigned long long u = (unsigned long long)(kv - base);
-                const bool act = (u & pmask) == prefix;
-                const int dg = (int)((u >> shift) & 255);
-                // a whole wavefront often lands in one bin: add it once instead of 64 colliding atomics
-                const unsigned long long am = __ballot(act);
-                if (am) {
-                    const int leader = __ffsll((long long)am) - 1;
-                    const int dl = __shfl(dg, leader);
-                    const unsigned long long same = __ballot(act && dg == dl);
-                    if (same == am) {
-                        if (lane == leader) atomicAdd(&s_hist[dl], __popcll(same));
-                    } else if (act) {
-                        atomicAdd(&s_hist[dg], 1);
-                    }
-                }
-            };
             for (int pass = nd - 1; pass >= 0; --pass) {
                 const int shift = pass * 8;
                 if (tid < 256) s_hist[tid] = 0;
                 __syncthreads();
-                if (cached) {
-                    for (int i = tid; i < n; i += kSelThreads) tally(s_keys[i], shift);
-                } else {
-                    for (int w = tid; w < n_wg; w += kSelThreads) {
-                        const int c = cj[w];
-                        const long long *seg = keys + (size_t)w * rows_per_wg;
-                        for (int i = 0; i < c; ++i) {
-                            unsigned long long u = (unsigned long long)(seg[i] - base);
-                            if ((u & pmask) == prefix) atomicAdd(&s_hist[(int)((u >> shift) & 255)], 1);
-                        }
-                    }
-                }
+                for_keys([&](long long kv) {
+                    unsigned long long u = (unsigned long long)(kv - base);
+                    if ((u & pmask) == prefix) atomicAdd(&s_hist[(int)((u >> shift) & 255)], 1);
+                });
                 __syncthreads();
                 if (tid < 256) {        // inclusive scan of the 256 bins by four wavefronts
                     const int h = s_hist[tid];
@@ -562,16 +564,343 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                 pmask |= 255ull << shift;
                 rank = s_rank;
             }
-            new_theta = base + (long long)prefix;
+            return base + (long long)prefix;
+        };
+        if (need_select) {
+            const int rank = n - Ce;   // 0-based rank of the new threshold among the keys, ascending
+            new_theta = rank < kSmallRank ? nth_by_minima(rank) : nth_by_radix(rank);
+        } else {
+            // candidate list for the tail pass: the kCand smallest keys in ascending order, their
+            // count, and a bound no other key of this expert lies under
+            const long long bound = n > kCand ? nth_by_radix(kCand) : kKeyInf;
+            for_keys([&](long long kv) {
+                if (kv < bound) s_cl[atomicAdd(&s_ncl, 1)] = kv;
+            });
+            __syncthreads();
+            const int nc = s_ncl;            // = min(n, kCand): keys are distinct
+            long long *cj_out = cand + (size_t)j * (kCand + 2);
+            if (tid < nc) {
+                const long long mine = s_cl[tid];
+                int r = 0;
+                for (int i = 0; i < nc; ++i) r += s_cl[i] < mine;
+                cj_out[r] = mine;
+            }
+            if (tid == 0) {
+                cj_out[kCand] = nc;
+                cj_out[kCand + 1] = bound;
+            }
         }
     }
-
     if (tid == 0) {
         if (action) {
             long long p = (new_theta >> cur_tbits) - lower;
             new_theta = (p > 0 ? p : 0) << cur_tbits;
         }
         theta_out[j] = new_theta;
+    }
+}
+
+// Tail pass: when a bid pass moved only a few slots, one workgroup continues the same auction on the
+// candidate lists (each expert's lowest bid keys) published by the select pass, without touching the
+// other tokens: an over-full expert drops its lowest candidates and raises its threshold to the next
+// one; every dropped token is re-evaluated against the current prices by one wavefront exactly as in
+// the bid pass, and its new keys enter the candidate lists.  Keys of tokens that were not touched
+// can only be lower than their current values, so the expert still removes a token whose true key is
+// the lowest (a candidate that is re-evaluated and survives is put back with its new key).  The pass
+// stops when nothing is over capacity, when a list runs out or after max_iters rounds; the next bid
+// pass re-validates every token, so this pass only has to make valid moves, not complete ones.
+constexpr int kTailThreads = 256;
+constexpr int kTailVict = 64;
+constexpr int kTailIns = 256;
+constexpr int kTailEPL = kTailMaxE / 64;
+
+// maximum over the 64 lanes with DPP row operations (the result is wavefront-uniform)
+__device__ __forceinline__ unsigned wave_max_u32(unsigned v)
+{
+    unsigned o;
+    o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x111, 0xf, 0xf, false); v = o > v ? o : v;  // row_shr:1
+    o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x112, 0xf, 0xf, false); v = o > v ? o : v;  // row_shr:2
+    o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x114, 0xf, 0xf, false); v = o > v ? o : v;  // row_shr:4
+    o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x118, 0xf, 0xf, false); v = o > v ? o : v;  // row_shr:8
+    o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x142, 0xa, 0xf, false); v = o > v ? o : v;  // row_bcast:15
+    o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x143, 0xc, 0xf, false); v = o > v ? o : v;  // row_bcast:31
+    return (unsigned)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
+{
+    const unsigned hi = (unsigned)(v >> 32), lo = (unsigned)v;
+    const unsigned mhi = wave_max_u32(hi);
+    const unsigned mlo = wave_max_u32(hi == mhi ? lo : 0u);
+    return ((unsigned long long)mhi << 32) | mlo;
+}
+
+__global__ __launch_bounds__(kTailThreads) void k_tail(const int32_t *__restrict__ q, int32_t *assign,
+                                                      long long *theta2, int *gcount2, SolverState *st2,
+                                                      const long long *__restrict__ cand, int *errflag, int par,
+                                                      int T, int E, int k, int Ce, int max_iters)
+{
+    SolverState *st = st2 + (par ^ 1);          // the state the next bid pass will read
+    {
+        const int d0 = st->done, g0 = st->tail_go;   // both loads in flight at once
+        if (d0 | !g0) return;
+    }
+    long long *theta = theta2 + (par ^ 1) * kMaxE;
+    int *gcur = gcount2 + par * kMaxE;
+    // candidate lists are kept in DESCENDING order: the lowest keys sit at the end and leave by
+    // shortening the list
+    __shared__ long long s_cand[kTailMaxE * kCand];
+    __shared__ long long s_theta[kTailMaxE];
+    __shared__ long long s_bound[kTailMaxE];
+    __shared__ int s_n[kTailMaxE];
+    __shared__ int s_cn[kTailMaxE];
+    __shared__ int s_vtok[kTailVict], s_vexp[kTailVict];
+    __shared__ int s_iexp[kTailIns];
+    __shared__ long long s_ikey[kTailIns];
+    __shared__ int s_qrow[kTailThreads / 64][kTailMaxE];
+    __shared__ int s_nv, s_ni, s_stop, s_over, s_moves, s_changed;
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const long long eps = st->eps, qmin = st->qmin;
+    const int sb = st->sbits, tb = st->tbits;
+    const long long tmask = ((long long)1 << tb) - 1;
+    for (int i = tid; i < E * (kCand + 2); i += kTailThreads) {
+        const int e = i / (kCand + 2), c = i - e * (kCand + 2);
+        const long long val = cand[i];
+        const int cn = (int)cand[(size_t)e * (kCand + 2) + kCand];
+        if (c < kCand) {
+            if (c < cn) s_cand[e * kCand + (cn - 1 - c)] = val;     // ascending in memory -> descending here
+        } else if (c == kCand) {
+            s_cn[e] = (int)val;
+        } else {
+            s_bound[e] = val;
+        }
+    }
+    for (int e = tid; e < E; e += kTailThreads) {
+        s_theta[e] = theta[e];
+        s_n[e] = gcur[e];
+    }
+    if (tid == 0) { s_stop = 0; s_moves = 0; s_changed = 0; }
+    __syncthreads();
+
+#ifdef MS_TAIL_PROF
+    long long c_p1 = 0, c_p2 = 0, c_p3 = 0, c_t0 = clock64(), c_init = 0;
+#define MS_TP(var) { long long c_now = clock64(); var += c_now - c_t0; c_t0 = c_now; }
+#else
+#define MS_TP(var)
+#endif
+    int it = 0;
+    for (; it < max_iters; ++it) {
+        if (tid == 0) { s_nv = 0; s_ni = 0; s_over = 0; }
+        __syncthreads();
+        // 1. every over-full expert drops its lowest candidates and raises its threshold
+        for (int e = tid; e < E; e += kTailThreads) {
+            const int m = s_n[e] - Ce;
+            if (m > 0) {
+                s_over = 1;
+                const int cn = s_cn[e];
+                if (cn < m) {
+                    s_stop = 1;                        // list exhausted: the select pass has to rebuild it
+                } else {
+                    const int b = atomicAdd(&s_nv, m);
+                    if (b + m > kTailVict) {
+                        s_stop = 1;
+                    } else {
+                        const long long *ce = s_cand + e * kCand;
+                        for (int i = 0; i < m; ++i) {
+                            s_vtok[b + i] = (int)(ce[cn - 1 - i] & tmask);
+                            s_vexp[b + i] = e;
+                        }
+                        const long long nt = cn > m ? ce[cn - 1 - m] : s_bound[e];
+                        s_cn[e] = cn - m;
+                        s_changed = 1;
+                        if (nt > s_theta[e] && nt < kKeyInf) s_theta[e] = nt;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        MS_TP(c_p1)
+        if (s_stop || !s_over) break;
+        // 2. one wavefront per dropped token: the bid pass's row evaluation
+        const int nv = s_nv < kTailVict ? s_nv : kTailVict;
+        for (int vi = wv; vi < nv; vi += kTailThreads / 64) {
+            const int tok = s_vtok[vi];
+            bool dup = false;          // a token challenged by several experts is evaluated once
+            for (int u = 0; u < vi; ++u) dup |= (s_vtok[u] == tok);
+            if (dup) continue;
+            int *qrow = s_qrow[wv];
+            const int32_t *qr = q + (size_t)tok * E;
+            int my_e = lane < k ? assign[(size_t)tok * k + lane] : -2;
+            int qv[kTailEPL];
+#pragma unroll
+            for (int m = 0; m < kTailEPL; ++m) qv[m] = (lane + 64 * m < E) ? qr[lane + 64 * m] : 0;
+            long long v[kTailEPL];
+            unsigned validm = 0, heldm = 0;
+#pragma unroll
+            for (int m = 0; m < kTailEPL; ++m) {
+                const int e = lane + 64 * m;
+                if (e < E) {
+                    qrow[e] = qv[m];
+                    v[m] = (((long long)qv[m] - qmin) << sb) - (s_theta[e] >> tb);
+                    validm |= 1u << m;
+                } else {
+                    v[m] = 0;
+                }
+            }
+            for (int s2 = 0; s2 < k; ++s2) {
+                const int es = __builtin_amdgcn_readlane(my_e, s2);
+                if (es >= 0 && (es & 63) == lane) heldm |= 1u << (es >> 6);
+            }
+            const int r0 = tok % E;
+            auto best_unheld = [&]() {
+                unsigned long long b = 0;
+#pragma unroll
+                for (int m = 0; m < kTailEPL; ++m) {
+                    if (((validm & ~heldm) >> m) & 1u) {
+                        int tieb = lane + 64 * m - r0;
+                        if (tieb < 0) tieb += E;
+                        unsigned long long pk =
+                            ((unsigned long long)(v[m] + (long long)kVB) << 10) | (unsigned)(1023 - tieb);
+                        b = pk > b ? pk : b;
+                    }
+                }
+                return wave_max_u64(b);
+            };
+            unsigned long long pk = best_unheld();
+            bool has_alt = pk != 0;
+            long long a = (long long)(pk >> 10) - (long long)kVB;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            long long my_sq = 0;
+            bool dropped = false;
+            if (my_e >= 0) {
+                my_sq = ((long long)qrow[my_e] - qmin) << sb;
+                long long bid = has_alt ? my_sq - a + eps : kBidBig;
+                long long key = bid * ((long long)1 << tb) + tok;
+                if (key < s_theta[my_e]) {
+                    dropped = true;
+                    atomicAdd(&s_n[my_e], -1);
+                }
+            }
+            // dropped experts become candidates again
+            {
+                unsigned long long db = __ballot(dropped);
+                while (db) {
+                    const int sl = __ffsll((long long)db) - 1;
+                    db &= db - 1;
+                    const int es = __builtin_amdgcn_readlane(my_e, sl);
+                    if ((es & 63) == lane) heldm &= ~(1u << (es >> 6));
+                }
+            }
+            if (dropped) my_e = -1;
+            const unsigned long long fb = __ballot(my_e == -1);
+            const int f = __popcll(fb);
+            bool picked = false;
+            if (f > 0) {
+                const int my_rank = (my_e == -1) ? __popcll(fb & ((1ull << lane) - 1)) : -1;
+                for (int r = 0; r < f; ++r) {
+                    pk = best_unheld();
+                    int e = 1023 - (int)(pk & 1023) + r0;
+                    if (e >= E) e -= E;
+                    if (pk == 0 || e >= E) {
+                        e = 0;
+                        *errflag = 1;
+                    }
+                    const long long val = (long long)(pk >> 10) - (long long)kVB;
+                    if ((e & 63) == lane) heldm |= 1u << (e >> 6);
+                    if (my_rank == r) {
+                        my_e = e;
+                        my_sq = val + (s_theta[e] >> tb);
+                        picked = true;
+                    }
+                }
+                pk = best_unheld();
+                has_alt = pk != 0;
+                a = (long long)(pk >> 10) - (long long)kVB;
+                if (lane == 0) atomicAdd(&s_moves, f);
+            }
+            if (lane < k && my_e >= 0) {
+                long long bid = has_alt ? my_sq - a + eps : kBidBig;
+                bid = bid < kBidBig ? bid : kBidBig;
+                const long long key = bid * ((long long)1 << tb) + tok;
+                bool challenged = false;   // kept a hold it was challenged on: the key goes back on the list
+                if (!picked)
+                    for (int u = 0; u < nv; ++u) challenged |= (s_vtok[u] == tok && s_vexp[u] == my_e);
+                if (picked) {
+                    assign[(size_t)tok * k + lane] = my_e;
+                    atomicAdd(&s_n[my_e], 1);
+                }
+                if ((picked || challenged) && key < s_bound[my_e]) {
+                    const int slot = atomicAdd(&s_ni, 1);
+                    if (slot < kTailIns) {
+                        s_iexp[slot] = my_e;
+                        s_ikey[slot] = key;
+                    } else {
+                        s_stop = 1;
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        __syncthreads();
+        MS_TP(c_p2)
+        // 3. the new keys enter the lists in order: wavefront 0 takes the requests one by one, its
+        //    first kCand lanes hold one list entry each
+        if (wv == 0) {
+            const int ni = s_ni < kTailIns ? s_ni : kTailIns;
+            for (int r = 0; r < ni; ++r) {
+                const int e = s_iexp[r];
+                const long long key = s_ikey[r];
+                long long *ce = s_cand + e * kCand;
+                int cn = s_cn[e];
+                long long val = (lane < cn && lane < kCand) ? ce[lane] : -1;
+                bool skip = false;
+                if (cn == kCand) {
+                    const long long top = ce[0];                 // largest listed key
+                    if (key > top) {
+                        if (lane == 0 && key < s_bound[e]) s_bound[e] = key;   // stays off the list
+                        skip = true;
+                    } else {
+                        if (lane == 0) s_bound[e] = top;         // the largest listed key leaves the list
+                        val = (lane + 1 < cn) ? ce[lane + 1] : -1;
+                        --cn;
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+                if (!skip) {
+                    const bool above = lane < cn && val > key;
+                    const int pos = __popcll(__ballot(above));
+                    if (lane < cn) ce[above ? lane : lane + 1] = val;
+                    if (lane == 0) {
+                        ce[pos] = key;
+                        s_cn[e] = cn + 1;
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+        }
+        __syncthreads();
+        MS_TP(c_p3)
+        if (s_stop) break;
+    }
+    for (int e = tid; e < E; e += kTailThreads) {
+        theta[e] = s_theta[e];
+        gcur[e] = s_n[e];
+    }
+    if (tid == 0) {
+        st->after_tail = (s_changed || s_moves) ? 1 : 0;
+        st->tail_block = s_stop;
+        st->tail_go = 0;
+        st->tail_runs += 1;
+        st->tail_iters += it;
+#ifdef MS_TAIL_PROF
+        st->phase_round[20] += (int)(c_init >> 6); st->phase_round[21] += (int)(c_p1 >> 6);
+        st->phase_round[22] += (int)(c_p2 >> 6); st->phase_round[23] += (int)(c_p3 >> 6);
+#endif
     }
 }
 
@@ -646,6 +975,12 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     int *qmm = gcount + 2 * kMaxE;   // after the counters: reward min, max, internal error flag
     int *wcnt = (int *)(ws + L.wcnt_off);
     int *wmoves = (int *)(ws + L.wmoves_off);
+    long long *cand = (long long *)(ws + L.cand_off);
+    int tail_on = E <= kTailMaxE ? 1 : 0, tail_iters = 256;
+    if (const char *ev = getenv("MAXSCORE_TAIL")) {   // tuning override (debug): 0 disables the tail pass
+        tail_iters = atoi(ev);
+        if (tail_iters <= 0) tail_on = 0;
+    }
 
     // lanes per token row (G >= k) and consecutive experts per lane
     int G = 8, EPL = 1;
@@ -657,6 +992,10 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     while (rows * 2 * k <= 1024 && (T + rows - 1) / rows > 4096) rows *= 2;
     if (rows * k > 1024) rows = ngrp;
     if (rows * k > 1024) return MAXSCORE_ERR_SHAPE;
+    if (const char *ev = getenv("MAXSCORE_ROWS")) {   // tuning override (debug)
+        int r = atoi(ev);
+        if (r >= ngrp && r % ngrp == 0 && r * k <= 1024) rows = r;
+    }
     const bool vec = (E == G * EPL) && (((uintptr_t)q) % 16 == 0);
     const int n_wg = (T + rows - 1) / rows;
     if (n_wg > L.max_wg) return MAXSCORE_ERR_WORKSPACE;
@@ -682,7 +1021,8 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     }
 
     std::vector<hipEvent_t> tev;
-    int batch = 8, launched = 0;
+    const int batch = 8;
+    int launched = 0;
     int h_done = 0;
     while (!h_done) {
         for (int b = 0; b < batch; ++b) {
@@ -705,13 +1045,15 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
 #undef MS_BID
             if (g_kernel_timing) MS_HIP(hipEventRecord(tev.back(), s));
             hipLaunchKernelGGL(k_select, dim3(E), dim3(kSelThreads), 0, s, klist, wcnt, wmoves, gcount, theta, st,
-                               qmm + 2, par, T, E, Ce, n_wg, rows);
+                               qmm + 2, cand, par, T, E, Ce, n_wg, rows, tail_on);
+            if (tail_on)
+                hipLaunchKernelGGL(k_tail, dim3(1), dim3(kTailThreads), 0, s, q, assign, theta, gcount, st, cand,
+                                   qmm + 2, par, T, E, k, Ce, tail_iters);
             ++launched;
         }
         MS_HIP(hipMemcpyAsync(&h_done, &st[launched & 1].done, sizeof(int), hipMemcpyDeviceToHost, s));
         MS_HIP(hipStreamSynchronize(s));
         if (launched > o.max_rounds + 64) break;
-        if (batch < 64) batch *= 2;
     }
     const int fpar = launched & 1;
     hipLaunchKernelGGL(k_finalize, dim3(256), dim3(256), 0, s, q, assign, theta + fpar * kMaxE, st + fpar, prices,
@@ -739,7 +1081,8 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     if (getenv("MAXSCORE_DEBUG")) {
         fprintf(stderr, "[maxscore] phase end rounds:");
         for (int a = 0; a < 28 && a < h.phases; ++a) fprintf(stderr, " %d", h.phase_round[a]);
-        fprintf(stderr, "\n");
+        fprintf(stderr, "  tail runs %d iters %d  [cyc/64: init %d p1 %d p2 %d p3 %d]\n", h.tail_runs, h.tail_iters,
+                h.phase_round[20], h.phase_round[21], h.phase_round[22], h.phase_round[23]);
     }
     if (stats) {
         stats->total_score_q = h.total;
