@@ -684,7 +684,7 @@ __global__ __launch_bounds__(kTailThreads) void k_tail(const int32_t *__restrict
     __syncthreads();
 
 #ifdef MS_TAIL_PROF
-    long long c_p1 = 0, c_p2 = 0, c_p3 = 0, c_t0 = clock64(), c_init = 0;
+    long long c_p1 = 0, c_p2 = 0, c_p3 = 0, c_t0 = clock64(), c_init = 0, c_x = 0, c_y = 0;
 #define MS_TP(var) { long long c_now = clock64(); var += c_now - c_t0; c_t0 = c_now; }
 #else
 #define MS_TP(var)
@@ -735,6 +735,9 @@ __global__ __launch_bounds__(kTailThreads) void k_tail(const int32_t *__restrict
             int qv[kTailEPL];
 #pragma unroll
             for (int m = 0; m < kTailEPL; ++m) qv[m] = (lane + 64 * m < E) ? qr[lane + 64 * m] : 0;
+#ifdef MS_TAIL_PROF
+            long long c_a = clock64();
+#endif
             long long v[kTailEPL];
             unsigned validm = 0, heldm = 0;
 #pragma unroll
@@ -748,6 +751,9 @@ __global__ __launch_bounds__(kTailThreads) void k_tail(const int32_t *__restrict
                     v[m] = 0;
                 }
             }
+#ifdef MS_TAIL_PROF
+            long long c_b = clock64();
+#endif
             for (int s2 = 0; s2 < k; ++s2) {
                 const int es = __builtin_amdgcn_readlane(my_e, s2);
                 if (es >= 0 && (es & 63) == lane) heldm |= 1u << (es >> 6);
@@ -843,8 +849,17 @@ __global__ __launch_bounds__(kTailThreads) void k_tail(const int32_t *__restrict
                 }
             }
             __builtin_amdgcn_wave_barrier();
+#ifdef MS_TAIL_PROF
+            if (wv == 0) { long long c_c = clock64(); c_init += c_b - c_a; c_x += c_c - c_b; }
+#endif
         }
+#ifdef MS_TAIL_PROF
+        long long c_d = clock64();
+#endif
         __syncthreads();
+#ifdef MS_TAIL_PROF
+        c_y += clock64() - c_d;
+#endif
         MS_TP(c_p2)
         // 3. the new keys enter the lists in order: wavefront 0 takes the requests one by one, its
         //    first kCand lanes hold one list entry each
@@ -900,6 +915,7 @@ __global__ __launch_bounds__(kTailThreads) void k_tail(const int32_t *__restrict
 #ifdef MS_TAIL_PROF
         st->phase_round[20] += (int)(c_init >> 6); st->phase_round[21] += (int)(c_p1 >> 6);
         st->phase_round[22] += (int)(c_p2 >> 6); st->phase_round[23] += (int)(c_p3 >> 6);
+        st->phase_round[24] += (int)(c_x >> 6); st->phase_round[25] += (int)(c_y >> 6);
 #endif
     }
 }
@@ -1083,6 +1099,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         for (int a = 0; a < 28 && a < h.phases; ++a) fprintf(stderr, " %d", h.phase_round[a]);
         fprintf(stderr, "  tail runs %d iters %d  [cyc/64: init %d p1 %d p2 %d p3 %d]\n", h.tail_runs, h.tail_iters,
                 h.phase_round[20], h.phase_round[21], h.phase_round[22], h.phase_round[23]);
+        fprintf(stderr, "  p2 detail: load-wait %d eval %d barrier %d\n", h.phase_round[20], h.phase_round[24], h.phase_round[25]);
     }
     if (stats) {
         stats->total_score_q = h.total;
