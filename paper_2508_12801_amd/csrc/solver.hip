@@ -410,7 +410,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     // the decision every thread of every block takes identically: nothing moved in this bid pass and
     // no expert was above capacity after the previous one  =>  the phase is quiescent
     const bool quiet = (moves == 0 && (flags & 2) == 0 && cur_round > 0 && !cur_after_tail);
-    const bool redo = quiet && cur_slack && (flags & 4) && cur_eps_prev > 0;
+    const bool redo = quiet && cur_slack && (flags & 4);
+    const long long eps_ref = cur_eps_prev > 0 ? cur_eps_prev : cur_eps;
     // few slots moved: leave the thresholds alone, publish each expert's lowest keys and let the
     // single-workgroup tail pass run the next rounds on them
     const bool tail_go = tail_on && !quiet && !cur_tail_block && cur_round > 0 && moves <= kTailMoves &&
@@ -419,7 +420,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     long long lower = 0;
     if (redo) {
         action = 1;                          // an unfilled expert kept a positive price: redo the phase lower
-        lower = cur_beta * 2 * cur_eps_prev;
+        lower = cur_beta * 2 * eps_ref;
     } else if (quiet && cur_eps != 1 && cur_slack) {
         action = 1;
         lower = cur_beta * cur_eps;
@@ -609,7 +610,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
 // the lowest (a candidate that is re-evaluated and survives is put back with its new key).  The pass
 // stops when nothing is over capacity, when a list runs out or after max_iters rounds; the next bid
 // pass re-validates every token, so this pass only has to make valid moves, not complete ones.
-constexpr int kTailThreads = 256;
+constexpr int kTailThreads = 1024;
 constexpr int kTailVict = 64;
 constexpr int kTailIns = 256;
 constexpr int kTailEPL = kTailMaxE / 64;
@@ -731,7 +732,11 @@ __global__ __launch_bounds__(kTailThreads) void k_tail(const int32_t *__restrict
             if (dup) continue;
             int *qrow = s_qrow[wv];
             const int32_t *qr = q + (size_t)tok * E;
-            int my_e = lane < k ? assign[(size_t)tok * k + lane] : -2;
+            // other wavefronts of this workgroup may have rewritten the row in an earlier round: read
+            // and write it at workgroup scope
+            int my_e = lane < k ? __hip_atomic_load(&assign[(size_t)tok * k + lane], __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_WORKGROUP)
+                                : -2;
             int qv[kTailEPL];
 #pragma unroll
             for (int m = 0; m < kTailEPL; ++m) qv[m] = (lane + 64 * m < E) ? qr[lane + 64 * m] : 0;
@@ -814,11 +819,10 @@ __global__ __launch_bounds__(kTailThreads) void k_tail(const int32_t *__restrict
                         e = 0;
                         *errflag = 1;
                     }
-                    const long long val = (long long)(pk >> 10) - (long long)kVB;
                     if ((e & 63) == lane) heldm |= 1u << (e >> 6);
                     if (my_rank == r) {
                         my_e = e;
-                        my_sq = val + (s_theta[e] >> tb);
+                        my_sq = ((long long)qrow[e] - qmin) << sb;
                         picked = true;
                     }
                 }
@@ -835,7 +839,8 @@ __global__ __launch_bounds__(kTailThreads) void k_tail(const int32_t *__restrict
                 if (!picked)
                     for (int u = 0; u < nv; ++u) challenged |= (s_vtok[u] == tok && s_vexp[u] == my_e);
                 if (picked) {
-                    assign[(size_t)tok * k + lane] = my_e;
+                    __hip_atomic_store(&assign[(size_t)tok * k + lane], my_e, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_WORKGROUP);
                     atomicAdd(&s_n[my_e], 1);
                 }
                 if ((picked || challenged) && key < s_bound[my_e]) {
