@@ -81,9 +81,12 @@ typedef struct {
 size_t maxscore_workspace_bytes(int32_t T, int32_t d, int32_t E, int32_t k, int32_t C);
 
 /* a1.  logits[T,E] (fp32) = x[T,d] . W[d,E] + bias[E].  x and W are bf16 (16-bit patterns,
- * fp32 accumulation on the matrix cores) or fp32 according to in_dtype; bias may be NULL. */
+ * fp32 accumulation on the matrix cores) or fp32 according to in_dtype; bias may be NULL.
+ * `workspace` is optional here: with at least 2*d*E bytes (256-byte aligned) the bf16 path first
+ * writes a transposed copy of W into it and runs its fast kernel; with NULL it uses a slower one. */
 int32_t maxscore_router_logits(const void *x, const void *W, const float *bias, int32_t in_dtype,
-                               int32_t T, int32_t d, int32_t E, float *logits, void *stream);
+                               int32_t T, int32_t d, int32_t E, float *logits, void *workspace,
+                               size_t workspace_bytes, void *stream);
 
 /* a2 + a3.  Per row: p = softmax(logits); rank r (1 = largest, ties to the lower index);
  * scores = p * (1 + t*(min(r,k) - 1)), the level-by-level reading of Eq. 6;

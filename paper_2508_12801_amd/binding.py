@@ -41,7 +41,7 @@ _SIGS = {
     "maxscore_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int32] * 5),
     "maxscore_router_logits": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
                                                 ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
-                                                ctypes.c_void_p]),
+                                                ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "maxscore_softtopk": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.c_float, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                            ctypes.c_void_p]),
@@ -122,9 +122,9 @@ def workspace_bytes(T: int, d: int, E: int, k: int, C: int) -> int:
     return int(load_library().maxscore_workspace_bytes(T, d, E, k, C))
 
 
-def _workspace(T, E, k, C, device):
+def _workspace(T, E, k, C, device, d=0):
     torch = _torch()
-    need = workspace_bytes(T, 1, E, k, C)
+    need = workspace_bytes(T, d, E, k, C)
     if need == 0:
         raise MaxScoreError(-2, "workspace_bytes")
     key = (str(device),)
@@ -157,15 +157,23 @@ def _in_dtype(x):
     raise MaxScoreError(-4, "input dtype")
 
 
-def router_logits(x, W, bias=None):
+def router_logits(x, W, bias=None, use_workspace=True):
     """a1: logits[T,E] fp32 = x[T,d] . W[d,E] + bias.  x, W: bf16 (or int16 bit patterns) or fp32."""
     torch = _torch()
     T, d = x.shape
     E = W.shape[1]
     assert W.shape[0] == d and x.is_contiguous() and W.is_contiguous() and x.dtype == W.dtype
     out = torch.empty((T, E), dtype=torch.float32, device=x.device)
+    ws, need = (None, 0)
+    if use_workspace:
+        need = 2 * d * E
+        key = ("wt", str(x.device))
+        ws = _WS.get(key)
+        if ws is None or ws.numel() < need:
+            ws = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+            _WS[key] = ws
     rc = load_library().maxscore_router_logits(_ptr(x), _ptr(W), _ptr(bias), _in_dtype(x), T, d, E, _ptr(out),
-                                               _stream())
+                                               _ptr(ws), need, _stream())
     _check(rc, "maxscore_router_logits")
     return out
 
@@ -270,7 +278,7 @@ def route_xw(x, W, bias, k: int, C: int, t: float = 1.0, quant_shift: int = 20, 
     o = out if out is not None else _route_outputs(T, E, k, x.device)
     if "logits" not in o:
         o["logits"] = torch.empty((T, E), dtype=torch.float32, device=x.device)
-    ws, need = _workspace(T, E, k, C, x.device)
+    ws, need = _workspace(T, E, k, C, x.device, d)
     stats = Stats()
     opts = _opts(t, quant_shift, max_rounds, eps_div)
     rc = load_library().maxscore_route_xw(

@@ -7,7 +7,7 @@ namespace maxscore {
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-WorkspaceLayout workspace_layout(int T, int E, int k)
+WorkspaceLayout workspace_layout(int T, int E, int k, int d)
 {
     WorkspaceLayout L;
     size_t off = 0;
@@ -20,7 +20,8 @@ WorkspaceLayout workspace_layout(int T, int E, int k)
     L.wmoves_off = off; off = align_up(off + sizeof(int) * (size_t)L.max_wg, 256);
     L.cand_off = off; off = align_up(off + sizeof(long long) * (size_t)kMaxE * (kCand + 2), 256);
     L.n_tiles = (int)(((size_t)T * k + 1023) / 1024);
-    L.tiles_off = off; off = align_up(off + sizeof(int) * (size_t)L.n_tiles * E, 256);
+    L.tiles_off = off; off = align_up(off + sizeof(int) * ((size_t)L.n_tiles * E + kMaxE), 256);
+    L.wt_off = off; off = align_up(off + sizeof(unsigned short) * (size_t)E * (d > 0 ? d : 0), 256);
     L.total = off;
     return L;
 }
@@ -57,18 +58,20 @@ extern "C" {
 
 size_t maxscore_workspace_bytes(int32_t T, int32_t d, int32_t E, int32_t k, int32_t C)
 {
-    (void)d;
-    if (!shape_ok(T, E, k, C)) return 0;
-    return workspace_layout(T, E, k).total;
+    if (!shape_ok(T, E, k, C) || d < 0) return 0;
+    return workspace_layout(T, E, k, d).total;
 }
 
 int32_t maxscore_router_logits(const void *x, const void *W, const float *bias, int32_t in_dtype, int32_t T,
-                               int32_t d, int32_t E, float *logits, void *stream)
+                               int32_t d, int32_t E, float *logits, void *workspace, size_t workspace_bytes,
+                               void *stream)
 {
     if (!x || !W || !logits) return MAXSCORE_ERR_NULL;
     if (T < 1 || d < 1 || E < 1 || E > kMaxE || T > (1 << kMaxTBits)) return MAXSCORE_ERR_SHAPE;
     if (in_dtype != MAXSCORE_DTYPE_BF16 && in_dtype != MAXSCORE_DTYPE_FP32) return MAXSCORE_ERR_DTYPE;
-    return gemm_run(x, W, bias, in_dtype, T, d, E, logits, (hipStream_t)stream);
+    void *wt = nullptr;     // optional scratch for the transposed weight: d*E 16-bit values, 256-byte aligned
+    if (workspace && ((uintptr_t)workspace % 256) == 0 && workspace_bytes >= (size_t)d * E * 2) wt = workspace;
+    return gemm_run(x, W, bias, in_dtype, T, d, E, logits, wt, (hipStream_t)stream);
 }
 
 int32_t maxscore_softtopk(const float *logits, int32_t T, int32_t E, int32_t k, float t, int32_t quant_shift,
@@ -165,7 +168,12 @@ int32_t maxscore_route_xw(const void *x, const void *W, const float *bias, int32
     if ((long long)T * k > (long long)E * Ce) return MAXSCORE_ERR_OVERSUBSCRIBED;
     int32_t rc = check_ws(workspace, workspace_bytes, T, E, k);
     if (rc) return rc;
-    rc = gemm_run(x, W, bias, in_dtype, T, d, E, logits_out, (hipStream_t)stream);
+    void *wt = nullptr;
+    {
+        WorkspaceLayout L = workspace_layout(T, E, k, d);
+        if (workspace_bytes >= L.total) wt = (char *)workspace + L.wt_off;
+    }
+    rc = gemm_run(x, W, bias, in_dtype, T, d, E, logits_out, wt, (hipStream_t)stream);
     if (rc) return rc;
     return maxscore_route_logits(logits_out, T, E, k, C, opts, scores_out, q_out, assign, gates, expert_offsets,
                                  disp_token, disp_gate, token_pos, prices, stats, workspace, workspace_bytes,

@@ -43,11 +43,11 @@ struct SolverState {
 };
 
 struct WorkspaceLayout {
-    size_t state_off, theta_off, gcount_off, klist_off, wcnt_off, wmoves_off, cand_off, tiles_off, total;
+    size_t state_off, theta_off, gcount_off, klist_off, wcnt_off, wmoves_off, cand_off, tiles_off, wt_off, total;
     int n_tiles, max_wg;
 };
 
-WorkspaceLayout workspace_layout(int T, int E, int k);
+WorkspaceLayout workspace_layout(int T, int E, int k, int d = 0);
 
 inline bool hip_ok(hipError_t e) { return e == hipSuccess; }
 
@@ -68,7 +68,7 @@ int32_t dispatch_run(const int32_t *assign, const float *gates, int T, int E, in
                      int32_t *disp_token, float *disp_gate, int32_t *token_pos, char *ws, hipStream_t s);
 // --- gemm.hip
 int32_t gemm_run(const void *x, const void *W, const float *bias, int dtype, int T, int d, int E, float *logits,
-                 hipStream_t s);
+                 void *wt_scratch, hipStream_t s);
 int32_t copy_run(const void *src, void *dst, size_t bytes, hipStream_t s);
 
 extern int g_kernel_timing;

@@ -2,7 +2,7 @@
 // c = k*n/e token places).  Pairs (token, expert) are ordered by expert and, inside an expert, by
 // ascending token id, which is what a stable sort of the token-major pair list by expert gives.
 //
-// Three launches: per-tile expert histograms, a scan over tiles and experts, and a scatter that
+// Four launches: per-tile expert histograms, a scan over tiles, a scan over experts, and a scatter that
 // recomputes each pair's stable rank inside its tile.  A tile is kTile consecutive slots of the
 // token-major [T, k] assignment and is owned by one wavefront.
 #include "common.h"
@@ -37,36 +37,60 @@ __global__ __launch_bounds__(256) void k_tile_hist(const int32_t *__restrict__ a
         for (int e = lane; e < E; e += 64) tiles[(size_t)tile * E + e] = cnt[e];
 }
 
-// tiles[tile][e] <- number of pairs of expert e in earlier tiles; offsets[E+1] <- expert prefix sums.
-__global__ __launch_bounds__(1024) void k_scan(int *__restrict__ tiles, int n_tiles, int E,
-                                               int32_t *__restrict__ offsets)
+// tiles[tile][e] <- number of pairs of expert e in earlier tiles; totals[e] <- pairs of expert e.
+// One wavefront per expert: every lane scans a contiguous run of tiles, the lane totals are scanned
+// with shuffles.
+__global__ __launch_bounds__(64) void k_scan_tiles(int *__restrict__ tiles, int n_tiles, int E,
+                                                   int *__restrict__ totals)
 {
-    __shared__ int s_tot[kMaxE];
-    const int e = threadIdx.x;
-    if (e < E) {
-        int run = 0;
-        for (int tl = 0; tl < n_tiles; ++tl) {
-            int c = tiles[(size_t)tl * E + e];
+    const int e = blockIdx.x, lane = threadIdx.x;
+    const int per = (n_tiles + 63) / 64;
+    const int t0 = lane * per;
+    int sum = 0;
+    for (int i = 0; i < per; ++i) {
+        const int tl = t0 + i;
+        if (tl < n_tiles) sum += tiles[(size_t)tl * E + e];
+    }
+    int inc = sum;
+    for (int off = 1; off < 64; off <<= 1) {
+        int o = __shfl_up(inc, off);
+        if (lane >= off) inc += o;
+    }
+    int run = inc - sum;
+    for (int i = 0; i < per; ++i) {
+        const int tl = t0 + i;
+        if (tl < n_tiles) {
+            const int c = tiles[(size_t)tl * E + e];
             tiles[(size_t)tl * E + e] = run;
             run += c;
         }
-        s_tot[e] = run;
     }
+    if (lane == 63) totals[e] = inc;
+}
+
+__global__ __launch_bounds__(1024) void k_offsets(const int *__restrict__ totals, int E, int32_t *__restrict__ offsets)
+{
+    __shared__ int s_w[16];
+    const int e = threadIdx.x, lane = e & 63, wv = e >> 6;
+    const int c = e < E ? totals[e] : 0;
+    int inc = c;
+    for (int off = 1; off < 64; off <<= 1) {
+        int o = __shfl_up(inc, off);
+        if (lane >= off) inc += o;
+    }
+    if (lane == 63) s_w[wv] = inc;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int j = 0; j < E; ++j) {
-            offsets[j] = run;
-            run += s_tot[j];
-        }
-        offsets[E] = run;
-    }
+    int base = 0;
+    for (int w = 0; w < wv; ++w) base += s_w[w];
+    if (e < E) offsets[e] = base + inc - c;
+    if (e == E - 1) offsets[E] = base + inc;
 }
 
 __global__ __launch_bounds__(256) void k_scatter(const int32_t *__restrict__ assign, const float *__restrict__ gates,
-                                                 size_t n, int E, int k, const int *__restrict__ tiles, int n_tiles,
-                                                 const int32_t *__restrict__ offsets, int32_t *__restrict__ disp_token,
-                                                 float *__restrict__ disp_gate, int32_t *__restrict__ token_pos)
+                                                 size_t n, int E, int k, int ebits, const int *__restrict__ tiles,
+                                                 int n_tiles, const int32_t *__restrict__ offsets,
+                                                 int32_t *__restrict__ disp_token, float *__restrict__ disp_gate,
+                                                 int32_t *__restrict__ token_pos)
 {
     extern __shared__ int s_run[];   // [kWavesPerWg][E] running position per expert
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -74,26 +98,28 @@ __global__ __launch_bounds__(256) void k_scatter(const int32_t *__restrict__ ass
     if (tile >= n_tiles) return;     // whole wavefront leaves; no block barrier below
     int *run = s_run + wave * E;
     for (int e = lane; e < E; e += 64) run[e] = tiles[(size_t)tile * E + e];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const size_t a0 = (size_t)tile * kTile;
     for (int c = 0; c < kTile; c += 64) {
         const size_t a = a0 + c + lane;
         const int e = a < n ? assign[a] : -1;
-        int pos = -1;
-        // lanes holding the same expert take consecutive positions in lane order
-        unsigned long long todo = __ballot(e >= 0);
-        while (todo) {
-            const int leader = __ffsll((long long)todo) - 1;
-            const int el = __shfl(e, leader);
-            const unsigned long long same = __ballot(e == el) & todo;
-            if (e == el && ((todo >> lane) & 1ull)) {
-                pos = run[el] + __popcll(same & ((1ull << lane) - 1));
-            }
-            __builtin_amdgcn_wave_barrier();
-            if (lane == leader) run[el] += __popcll(same);
-            __builtin_amdgcn_wave_barrier();
-            todo &= ~same;
+        // lanes holding the same expert: intersect the ballots of every bit of the expert id
+        unsigned long long same = __ballot(e >= 0);
+        for (int b = 0; b < ebits; ++b) {
+            const unsigned long long bal = __ballot((e >> b) & 1);
+            same &= ((e >> b) & 1) ? bal : ~bal;
         }
+        int pos = -1;
+        if (e >= 0) pos = run[e] + __popcll(same & ((1ull << lane) - 1));   // lane order = token order
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (e >= 0 && lane == __ffsll((long long)same) - 1) run[e] += __popcll(same);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         if (a < n) {
             token_pos[a] = pos;
             if (e >= 0) {
@@ -117,9 +143,13 @@ int32_t dispatch_run(const int32_t *assign, const float *gates, int T, int E, in
     const int grid = (n_tiles + kWavesPerWg - 1) / kWavesPerWg;
     const size_t shm = (size_t)kWavesPerWg * E * sizeof(int);
     hipLaunchKernelGGL(k_tile_hist, dim3(grid), dim3(256), shm, s, assign, n, E, tiles, n_tiles);
-    hipLaunchKernelGGL(k_scan, dim3(1), dim3(1024), 0, s, tiles, n_tiles, E, offsets);
-    hipLaunchKernelGGL(k_scatter, dim3(grid), dim3(256), shm, s, assign, gates, n, E, k, tiles, n_tiles, offsets,
-                       disp_token, disp_gate, token_pos);
+    int *totals = tiles + (size_t)n_tiles * E;
+    int ebits = 0;
+    while ((1 << ebits) < E) ++ebits;
+    hipLaunchKernelGGL(k_scan_tiles, dim3(E), dim3(64), 0, s, tiles, n_tiles, E, totals);
+    hipLaunchKernelGGL(k_offsets, dim3(1), dim3(1024), 0, s, totals, E, offsets);
+    hipLaunchKernelGGL(k_scatter, dim3(grid), dim3(256), shm, s, assign, gates, n, E, k, ebits, tiles, n_tiles,
+                       offsets, disp_token, disp_gate, token_pos);
     MS_HIP(hipGetLastError());
     return MAXSCORE_OK;
 }

@@ -124,6 +124,112 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const unsigned short *__restr
     }
 }
 
+// Transposed copy of the router weight: wt[E, d] <- W[d, E] (bf16 patterns), so that both MFMA
+// operands are contiguous along the reduction index.
+__global__ __launch_bounds__(256) void k_transpose_w(const unsigned short *__restrict__ W,
+                                                     unsigned short *__restrict__ wt, int d, int E)
+{
+    __shared__ unsigned short tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+    const int k0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
+    for (int r = ty; r < 32; r += 8) {
+        const int kk = k0 + r, n = n0 + tx;
+        tile[r][tx] = (kk < d && n < E) ? W[(size_t)kk * E + n] : (unsigned short)0;
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const int n = n0 + r, kk = k0 + tx;
+        if (n < E && kk < d) wt[(size_t)n * d + kk] = tile[tx][r];
+    }
+}
+
+// Main bf16 kernel (d % 8 == 0, 16-byte aligned x and wt).  Workgroup = 4 wavefronts = 128 token rows
+// x (32*NT) experts; wavefront w owns rows 32w..32w+31.  Per 64-wide slab of d: the A fragments come
+// straight from global memory into registers (each lane reads 16 bytes per MFMA step: row l%32,
+// columns 8*(l/32).. of the step), the transposed-W slab goes through a double-buffered LDS tile shared
+// by the four wavefronts.  The next slab of both is requested before the MFMAs of the current one.
+template <int NT>
+__global__ __launch_bounds__(256) void k_gemm_bf16_wt(const unsigned short *__restrict__ x,
+                                                      const unsigned short *__restrict__ wt,
+                                                      const float *__restrict__ bias, int T, int d, int E,
+                                                      float *__restrict__ out)
+{
+    constexpr int BN = 32 * NT;
+    __shared__ __attribute__((aligned(16))) unsigned short sB[2][BN * LDP];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int row0 = blockIdx.x * BM, col0 = blockIdx.y * 128;
+    const int arow = row0 + wave * 32 + (lane & 31), kq = 8 * (lane >> 5);
+    const bool arow_ok = arow < T;
+    const unsigned short *xrow = x + (size_t)(arow_ok ? arow : 0) * d;
+
+    // B staging: BN rows x 64 columns = BN*8 16-byte vectors, B_PER per thread
+    constexpr int B_VECS = BN * 8;
+    constexpr int B_PER = (B_VECS + 255) / 256;
+    u32x4 ra[4], rb[B_PER];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int kk = k0 + 16 * j + kq;
+            ra[j] = (arow_ok && kk < d) ? *(const u32x4 *)(xrow + kk) : u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int p = 0; p < B_PER; ++p) {
+            const int v = tid + 256 * p;
+            const int n = v >> 3, kk = k0 + (v & 7) * 8;
+            rb[p] = (v < B_VECS && col0 + n < E && kk < d) ? *(const u32x4 *)(wt + (size_t)(col0 + n) * d + kk)
+                                                           : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    auto stash_b = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < B_PER; ++p) {
+            const int v = tid + 256 * p;
+            if (v < B_VECS) *(u32x4 *)&sB[buf][(v >> 3) * LDP + (v & 7) * 8] = rb[p];
+        }
+    };
+    f32x16 acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[nt][i] = 0.f;
+
+    fetch(0);
+    stash_b(0);
+    int buf = 0;
+    for (int k0 = 0; k0 < d; k0 += BK) {
+        u32x4 a_cur[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a_cur[j] = ra[j];
+        __syncthreads();                         // sB[buf] is complete; sB[buf^1] is free again
+        const bool more = k0 + BK < d;
+        if (more) fetch(k0 + BK);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            bf16x8 a = __builtin_bit_cast(bf16x8, a_cur[j]);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                bf16x8 b = *(const bf16x8 *)&sB[buf][(nt * 32 + (lane & 31)) * LDP + 16 * j + kq];
+                acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[nt], 0, 0, 0);
+            }
+        }
+        if (more) stash_b(buf ^ 1);
+        buf ^= 1;
+    }
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int col = col0 + nt * 32 + (lane & 31);
+        if (col >= E) continue;
+        const float bv = bias ? bias[col] : 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int row = row0 + wave * 32 + 8 * j + 4 * (lane >> 5) + i;
+                if (row < T) out[(size_t)row * E + col] = acc[nt][4 * j + i] + bv;
+            }
+    }
+}
+
 __global__ __launch_bounds__(256) void k_gemm_f32(const float *__restrict__ x, const float *__restrict__ W,
                                                   const float *__restrict__ bias, int T, int d, int E,
                                                   float *__restrict__ out)
@@ -146,7 +252,7 @@ __global__ __launch_bounds__(256) void k_copy16(const u32x4 *__restrict__ src, u
 }  // namespace
 
 int32_t gemm_run(const void *x, const void *W, const float *bias, int dtype, int T, int d, int E, float *logits,
-                 hipStream_t s)
+                 void *wt_scratch, hipStream_t s)
 {
     if (dtype == MAXSCORE_DTYPE_FP32) {
         size_t n = (size_t)T * E;
@@ -158,10 +264,22 @@ int32_t gemm_run(const void *x, const void *W, const float *bias, int dtype, int
         return MAXSCORE_OK;
     }
     const unsigned short *xb = (const unsigned short *)x, *wb = (const unsigned short *)W;
-    const bool aligned = (d % 8 == 0) && (E % 8 == 0) && (((uintptr_t)x | (uintptr_t)W) % 16 == 0);
     dim3 grid((T + BM - 1) / BM, (E + 127) / 128);
     int et = E >= 128 ? 128 : E;
     int nt = (et + 31) / 32;
+    if (wt_scratch && d % 8 == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)wt_scratch % 16) == 0) {
+        unsigned short *wt = (unsigned short *)wt_scratch;
+        hipLaunchKernelGGL(k_transpose_w, dim3((d + 31) / 32, (E + 31) / 32), dim3(256), 0, s, wb, wt, d, E);
+#define MS_GEMM2(NT_) hipLaunchKernelGGL((k_gemm_bf16_wt<NT_>), grid, dim3(256), 0, s, xb, wt, bias, T, d, E, logits)
+        if (nt == 1) MS_GEMM2(1);
+        else if (nt == 2) MS_GEMM2(2);
+        else if (nt == 3) MS_GEMM2(3);
+        else MS_GEMM2(4);
+#undef MS_GEMM2
+        MS_HIP(hipGetLastError());
+        return MAXSCORE_OK;
+    }
+    const bool aligned = (d % 8 == 0) && (E % 8 == 0) && (((uintptr_t)x | (uintptr_t)W) % 16 == 0);
 #define MS_GEMM(NT_, AL_) \
     hipLaunchKernelGGL((k_gemm_bf16<NT_, AL_>), grid, dim3(256), 0, s, xb, wb, bias, T, d, E, logits)
     if (aligned) {

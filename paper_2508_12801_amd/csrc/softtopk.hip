@@ -24,8 +24,9 @@ __device__ __forceinline__ unsigned ord_f32(float x)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// A group of G lanes owns one row; lane l owns columns l, l+G, ... (EPL per lane).
-template <int G, int EPL>
+// A group of G lanes owns one row; lane l owns the EPL consecutive columns l*EPL .. l*EPL+EPL-1, so a
+// wavefront reads 64/G consecutive rows with contiguous 16-byte loads.
+template <int G, int EPL, bool VEC>
 __global__ __launch_bounds__(256) void k_softtopk(const float *__restrict__ logits, int T, int E, int k, float t,
                                                   float qscale, float *__restrict__ scores,
                                                   int32_t *__restrict__ q)
@@ -33,53 +34,60 @@ __global__ __launch_bounds__(256) void k_softtopk(const float *__restrict__ logi
     const int tid = threadIdx.x, lane = tid & 63, lg = lane & (G - 1);
     const int grp = tid / G, ngrp = 256 / G;
     for (int row = blockIdx.x * ngrp + grp; row < T; row += gridDim.x * ngrp) {
-        const float *lr = logits + (size_t)row * E;
+        const float *lr = logits + (size_t)row * E + lg * EPL;
         float x[EPL];
+        if (VEC && EPL >= 4) {
+#pragma unroll
+            for (int m = 0; m < EPL; m += 4) {
+                float4 v4 = *(const float4 *)(lr + m);
+                x[m] = v4.x; x[m + 1] = v4.y; x[m + 2] = v4.z; x[m + 3] = v4.w;
+            }
+        } else {
+#pragma unroll
+            for (int m = 0; m < EPL; ++m) x[m] = (lg * EPL + m < E) ? lr[m] : -3.4e38f;
+        }
         float mx = -3.4e38f;
 #pragma unroll
-        for (int m = 0; m < EPL; ++m) {
-            int e = lg + m * G;
-            x[m] = e < E ? lr[e] : -3.4e38f;
-            mx = fmaxf(mx, x[m]);
-        }
+        for (int m = 0; m < EPL; ++m) mx = fmaxf(mx, x[m]);
 #pragma unroll
         for (int off = G / 2; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
         float ex[EPL];
         float sum = 0.f;
 #pragma unroll
         for (int m = 0; m < EPL; ++m) {
-            int e = lg + m * G;
-            ex[m] = e < E ? expf(x[m] - mx) : 0.f;
+            ex[m] = (lg * EPL + m < E) ? expf(x[m] - mx) : 0.f;
             sum += ex[m];
         }
 #pragma unroll
         for (int off = G / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
         const float inv = 1.0f / sum;
 
-        // ranks 1..k-1 by repeated arg-max; everything else has min(rank, k) = k
+        // ranks 1..k-1 by repeated arg-max (equal logits: lower column first); the rest has min(rank,k) = k
         int rk[EPL];
 #pragma unroll
         for (int m = 0; m < EPL; ++m) rk[m] = k;
         unsigned taken = 0;
         if (t != 0.f) {
             for (int r = 1; r < k; ++r) {
-                unsigned long long best = 0;
+                unsigned bo = 0;
+                int bm = -1;
 #pragma unroll
                 for (int m = 0; m < EPL; ++m) {
-                    int e = lg + m * G;
-                    if (e < E && !((taken >> m) & 1u)) {
-                        unsigned long long pk = ((unsigned long long)ord_f32(x[m]) << 10) | (unsigned)(1023 - e);
-                        best = pk > best ? pk : best;
-                    }
+                    const unsigned o = ord_f32(x[m]);
+                    const bool take = (lg * EPL + m < E) && !((taken >> m) & 1u) && (bm < 0 || o > bo);
+                    bo = take ? o : bo;
+                    bm = take ? m : bm;
                 }
+                unsigned long long best =
+                    bm >= 0 ? (((unsigned long long)bo << 10) | (unsigned)(1023 - (lg * EPL + bm))) : 0ull;
 #pragma unroll
                 for (int off = G / 2; off > 0; off >>= 1) {
                     unsigned long long o = shfl_xor_u64(best, off);
                     best = o > best ? o : best;
                 }
-                int e = 1023 - (int)(best & 1023);
-                if ((e & (G - 1)) == lg) {
-                    int m = e / G;
+                const int e = 1023 - (int)(best & 1023);
+                if (e / EPL == lg) {
+                    const int m = e % EPL;
 #pragma unroll
                     for (int mm = 0; mm < EPL; ++mm)
                         if (mm == m) rk[mm] = r;
@@ -87,14 +95,28 @@ __global__ __launch_bounds__(256) void k_softtopk(const float *__restrict__ logi
                 }
             }
         }
+        float sc[EPL];
+        int qq[EPL];
 #pragma unroll
         for (int m = 0; m < EPL; ++m) {
-            int e = lg + m * G;
-            if (e < E) {
-                float p = ex[m] * inv;
-                float sc = p * (1.0f + t * (float)(rk[m] - 1));
-                if (scores) scores[(size_t)row * E + e] = sc;
-                if (q) q[(size_t)row * E + e] = __float2int_rn(sc * qscale);
+            const float p = ex[m] * inv;
+            sc[m] = p * (1.0f + t * (float)(rk[m] - 1));
+            qq[m] = __float2int_rn(sc[m] * qscale);
+        }
+        const size_t o0 = (size_t)row * E + lg * EPL;
+        if (VEC && EPL >= 4) {
+#pragma unroll
+            for (int m = 0; m < EPL; m += 4) {
+                if (scores) *(float4 *)(scores + o0 + m) = make_float4(sc[m], sc[m + 1], sc[m + 2], sc[m + 3]);
+                if (q) *(int4 *)(q + o0 + m) = make_int4(qq[m], qq[m + 1], qq[m + 2], qq[m + 3]);
+            }
+        } else {
+#pragma unroll
+            for (int m = 0; m < EPL; ++m) {
+                if (lg * EPL + m < E) {
+                    if (scores) scores[o0 + m] = sc[m];
+                    if (q) q[o0 + m] = qq[m];
+                }
             }
         }
     }
@@ -115,23 +137,37 @@ int32_t softtopk_run(const float *logits, int T, int E, int k, float t, int shif
                      hipStream_t s)
 {
     int G = 8, EPL = 1;
-    while (G < 64 && G < E) G *= 2;
+    while (G * 16 < E) G *= 2;
     while (G * EPL < E) EPL *= 2;
     const int ngrp = 256 / G;
     int grid = (T + ngrp - 1) / ngrp;
-    if (grid > 8192) grid = 8192;
+    if (grid > 4096) grid = 4096;
     const float qscale = (float)(1 << shift);
-#define MS_ST(GG, PP) \
-    hipLaunchKernelGGL((k_softtopk<GG, PP>), dim3(grid), dim3(256), 0, s, logits, T, E, k, t, qscale, scores, q)
-    if (G == 8) MS_ST(8, 1);
-    else if (G == 16) MS_ST(16, 1);
-    else if (G == 32) MS_ST(32, 1);
-    else if (EPL == 1) MS_ST(64, 1);
-    else if (EPL == 2) MS_ST(64, 2);
-    else if (EPL == 4) MS_ST(64, 4);
-    else if (EPL == 8) MS_ST(64, 8);
-    else MS_ST(64, 16);
+    const bool vec = (E == G * EPL) && EPL >= 4 &&
+                     ((((uintptr_t)logits) | ((uintptr_t)scores) | ((uintptr_t)q)) % 16 == 0);
+#define MS_ST2(GG, PP)                                                                                              \
+    do {                                                                                                            \
+        if (vec)                                                                                                    \
+            hipLaunchKernelGGL((k_softtopk<GG, PP, true>), dim3(grid), dim3(256), 0, s, logits, T, E, k, t, qscale, \
+                               scores, q);                                                                          \
+        else                                                                                                        \
+            hipLaunchKernelGGL((k_softtopk<GG, PP, false>), dim3(grid), dim3(256), 0, s, logits, T, E, k, t,        \
+                               qscale, scores, q);                                                                  \
+    } while (0)
+#define MS_ST(GG)                    \
+    do {                             \
+        if (EPL == 1) MS_ST2(GG, 1); \
+        else if (EPL == 2) MS_ST2(GG, 2); \
+        else if (EPL == 4) MS_ST2(GG, 4); \
+        else if (EPL == 8) MS_ST2(GG, 8); \
+        else MS_ST2(GG, 16);         \
+    } while (0)
+    if (G == 8) MS_ST(8);
+    else if (G == 16) MS_ST(16);
+    else if (G == 32) MS_ST(32);
+    else MS_ST(64);
 #undef MS_ST
+#undef MS_ST2
     MS_HIP(hipGetLastError());
     return MAXSCORE_OK;
 }

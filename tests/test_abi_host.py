@@ -49,7 +49,7 @@ def test_argument_errors_are_found_on_the_host(lib):
     # NULL pointers
     assert lib.maxscore_assign_i32(null, 4, 4, 2, 2, null, one, null, null, null, one, 1 << 20, null) == -1
     assert lib.maxscore_softtopk(null, 4, 4, 2, 1.0, 20, one, one, null) == -1
-    assert lib.maxscore_router_logits(one, null, null, 0, 4, 4, 4, one, null) == -1
+    assert lib.maxscore_router_logits(one, null, null, 0, 4, 4, 4, one, null, 0, null) == -1
     assert lib.maxscore_gates(one, null, 4, 4, 2, one, null) == -1
     # shapes
     assert lib.maxscore_assign_i32(one, 4, 4, 5, 2, null, one, null, null, null, one, 1 << 20, null) == -2   # k > E
@@ -63,7 +63,7 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert lib.maxscore_assign_i32(one, 8, 4, 2, 4, null, one, null, null, null, ctypes.c_void_p(260), 1 << 20, null) == -3
     assert lib.maxscore_assign_i32(one, 8, 4, 2, 4, null, one, null, null, null, one, 16, null) == -3
     # dtype
-    assert lib.maxscore_router_logits(one, one, null, 7, 4, 4, 4, one, null) == -4
+    assert lib.maxscore_router_logits(one, one, null, 7, 4, 4, 4, one, null, 0, null) == -4
     assert lib.maxscore_copy_bytes(one, one, 10, null) == -2
     for code in range(-8, 1):
         assert len(lib.maxscore_status_string(code)) > 1
