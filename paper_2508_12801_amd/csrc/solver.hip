@@ -150,6 +150,8 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
     constexpr int LOGP = EPL == 1 ? 0 : EPL == 2 ? 1 : EPL == 4 ? 2 : EPL == 8 ? 3 : 4;
     __shared__ long long s_theta[EP];
     __shared__ int s_cnt[EP];
+    __shared__ int s_off[EP];
+    __shared__ int s_wtot[4];
     __shared__ __attribute__((aligned(16))) int s_q[NG * EP];
     __shared__ long long s_key[1024];
     __shared__ short s_exp[1024];
@@ -312,17 +314,45 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
         __builtin_amdgcn_wave_barrier();   // the next row reuses this group's staging buffer
     }
     __syncthreads();
-    // workgroup w owns positions [w*rows_per_wg, (w+1)*rows_per_wg) of every expert's key list (a token
-    // contributes at most one key per expert), so no global atomics are needed
-    const int n_wg = gridDim.x;
-    for (int e = tid; e < E; e += 256) wcnt[(size_t)e * n_wg + blockIdx.x] = s_cnt[e];
+    // The keys of this workgroup are stored sorted by expert in one contiguous block of the key
+    // buffer (block w starts at w*rows_per_wg*k), with (offset << 16 | count) per expert beside it:
+    // full cache lines are written and no global atomics are needed.
+    {
+        constexpr int PER = (EP + 255) / 256;
+        int loc[PER];
+        int sum = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int e = tid * PER + i;
+            loc[i] = e < EP ? s_cnt[e] : 0;
+            sum += loc[i];
+        }
+        int inc = sum;
+        for (int off = 1; off < 64; off <<= 1) {
+            int o = __shfl_up(inc, off);
+            if ((tid & 63) >= off) inc += o;
+        }
+        if ((tid & 63) == 63) s_wtot[tid >> 6] = inc;
+        __syncthreads();
+        int base = inc - sum;
+        for (int w = 0; w < (tid >> 6); ++w) base += s_wtot[w];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int e = tid * PER + i;
+            if (e < EP) s_off[e] = base;
+            if (e < E) wcnt[(size_t)blockIdx.x * E + e] = (base << 16) | loc[i];
+            base += loc[i];
+        }
+    }
     if (tid == 0) wmoves[blockIdx.x] = s_moves;
+    __syncthreads();
     int rows_here = T - row0;
     rows_here = rows_here < rows_per_wg ? rows_here : rows_per_wg;
     const int nslots = rows_here * k;
+    long long *blk = klist + (size_t)blockIdx.x * rows_per_wg * k;
     for (int idx = tid; idx < nslots; idx += 256) {
-        int e = s_exp[idx];
-        klist[(size_t)e * T + row0 + s_pos[idx]] = s_key[idx];
+        const int e = s_exp[idx];
+        blk[s_off[e] + s_pos[idx]] = s_key[idx];
     }
 }
 
@@ -337,8 +367,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                                                         const int *__restrict__ wcnt, const int *__restrict__ wmoves,
                                                         int *gcount2, long long *theta2, SolverState *st2,
                                                         const int *__restrict__ errflag, long long *__restrict__ cand,
-                                                        int par, int T, int E, int Ce, int n_wg, int rows_per_wg,
-                                                        int tail_on)
+                                                        int par, int T, int E, int k, int Ce, int n_wg,
+                                                        int rows_per_wg, int tail_on)
 {
     const SolverState *st = st2 + par;
     SolverState *st_out = st2 + (par ^ 1);
@@ -361,14 +391,16 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     __shared__ long long s_cl[kCand];
     __shared__ int s_d, s_rank, s_ncl;
     const int tid = threadIdx.x, j = blockIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int *cj = wcnt + (size_t)j * n_wg;
+    // (offset << 16 | count) of this expert inside the key block of bid workgroup w
+    auto meta = [&](int w) { return wcnt[(size_t)w * E + j]; };
+    const size_t blk_stride = (size_t)rows_per_wg * k;
     // One reduction for everything the block needs: the number of keys of this expert (sum of the
     // per-workgroup counts, with an exclusive scan that places each thread's keys in the LDS copy),
     // the moves of this bid pass, and the over-capacity / unfilled-but-priced experts after the
     // previous round.  All loads are issued before the single barrier.
     int ct = 0, mv = 0, ov = 0, vi = 0;
     for (int w = tid; w < n_wg; w += kSelThreads) {
-        ct += cj[w];
+        ct += meta(w) & 0xffff;
         mv += wmoves[w];
     }
     for (int e = tid; e < E; e += kSelThreads) {
@@ -460,14 +492,13 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     const bool need_cand = tail_go;
     if (need_select || need_cand) {
         const long long base = theta_in[j];
-        const long long *keys = klist + (size_t)j * T;
         const bool cached = n <= kSelCache;
         unsigned long long umax = 0;
         {
             int pos = woff + inc - ct;
             for (int w = tid; w < n_wg; w += kSelThreads) {
-                const int c = cj[w];
-                const long long *seg = keys + (size_t)w * rows_per_wg;
+                const int mt = meta(w), c = mt & 0xffff;
+                const long long *seg = klist + (size_t)w * blk_stride + (mt >> 16);
                 for (int i0 = 0; i0 < c; i0 += 8) {      // eight independent loads in flight per thread
                     long long kv[8];
 #pragma unroll
@@ -490,8 +521,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                 for (int i = tid; i < n; i += kSelThreads) fn(s_keys[i]);
             } else {
                 for (int w = tid; w < n_wg; w += kSelThreads) {
-                    const int c = cj[w];
-                    const long long *seg = keys + (size_t)w * rows_per_wg;
+                    const int mt = meta(w), c = mt & 0xffff;
+                    const long long *seg = klist + (size_t)w * blk_stride + (mt >> 16);
                     for (int i = 0; i < c; ++i) fn(seg[i]);
                 }
             }
@@ -1066,7 +1097,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
 #undef MS_BID
             if (g_kernel_timing) MS_HIP(hipEventRecord(tev.back(), s));
             hipLaunchKernelGGL(k_select, dim3(E), dim3(kSelThreads), 0, s, klist, wcnt, wmoves, gcount, theta, st,
-                               qmm + 2, cand, par, T, E, Ce, n_wg, rows, tail_on);
+                               qmm + 2, cand, par, T, E, k, Ce, n_wg, rows, tail_on);
             if (tail_on)
                 hipLaunchKernelGGL(k_tail, dim3(1), dim3(kTailThreads), 0, s, q, assign, theta, gcount, st, cand,
                                    qmm + 2, par, T, E, k, Ce, tail_iters);
@@ -1087,15 +1118,34 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     float ms = 0.f, bid_ms = 0.f;
     (void)hipEventElapsedTime(&ms, ev0, ev1);
     int timed = 0;
-    for (size_t i = 0; i + 1 < tev.size(); i += 2) {
-        if ((int)(i / 2) < h.round) {
-            float t = 0.f;
-            (void)hipEventElapsedTime(&t, tev[i], tev[i + 1]);
-            bid_ms += t;
-            ++timed;
+    if (!tev.empty()) {
+        // what a pair of event records costs with nothing between them is taken off every launch time
+        float empty_ms = 0.f;
+        const int n_cal = 16;
+        hipEvent_t ce[2 * n_cal];
+        for (int i = 0; i < 2 * n_cal; ++i) MS_HIP(hipEventCreate(&ce[i]));
+        for (int i = 0; i < n_cal; ++i) {
+            MS_HIP(hipEventRecord(ce[2 * i], s));
+            MS_HIP(hipEventRecord(ce[2 * i + 1], s));
         }
-        (void)hipEventDestroy(tev[i]);
-        (void)hipEventDestroy(tev[i + 1]);
+        MS_HIP(hipStreamSynchronize(s));
+        for (int i = 0; i < n_cal; ++i) {
+            float t = 0.f;
+            (void)hipEventElapsedTime(&t, ce[2 * i], ce[2 * i + 1]);
+            empty_ms += t / n_cal;
+        }
+        for (int i = 0; i < 2 * n_cal; ++i) (void)hipEventDestroy(ce[i]);
+        for (size_t i = 0; i + 1 < tev.size(); i += 2) {
+            if ((int)(i / 2) < h.round) {
+                float t = 0.f;
+                (void)hipEventElapsedTime(&t, tev[i], tev[i + 1]);
+                t -= empty_ms;
+                bid_ms += t > 0.f ? t : 0.f;
+                ++timed;
+            }
+            (void)hipEventDestroy(tev[i]);
+            (void)hipEventDestroy(tev[i + 1]);
+        }
     }
     (void)hipEventDestroy(ev0);
     (void)hipEventDestroy(ev1);
