@@ -20,6 +20,17 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E published peak
 
 
+def measured_traffic(name="k_bid_cfg5_pmc_traffic.txt", key="k_bid_traffic_bytes"):
+    """HBM bytes per launch of the bid pass from the committed rocprofv3 counter summary (None if absent)."""
+    try:
+        for line in open(os.path.join(ROOT, "profiles", name)):
+            if line.startswith(key):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(name: str, sample_T: int):
     """The CPU checker as it stands, timed on the host cores over a bounded sample of the workload."""
     import numpy as np
@@ -126,7 +137,8 @@ def main():
                    "latency_ms_per_call": ms_per_step, "solver_rounds": stats["rounds"],
                    "solver_phases": stats["phases"]},
         "roofline": {"bound": "hbm", "kernel": "k_bid (solver bid pass)", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic() if args.config == "cfg5" else None,
                      "bytes_per_launch": bid_bytes, "launch_ms": bid_launch_ms,
                      "launches_per_call": st["bid_launches"], "copy_kernel_GBs": copy_gbs},
         "stages_ms": {"router_gemm": gemm_ms, "softtopk_quantise": soft_ms, "assignment": st["solver_ms"],

@@ -360,7 +360,7 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
 constexpr int kSelThreads = 1024;
 constexpr int kSelCache = 6144;
 constexpr int kSmallRank = 6;
-constexpr int kTailMoves = 96;            // hand over to the tail pass when a bid pass moved this few slots
+constexpr int kTailMoves = 16;            // hand over to the tail pass when a bid pass moved this few slots
 constexpr long long kKeyInf = (long long)1 << 62;
 
 __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restrict__ klist,
@@ -368,7 +368,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                                                         int *gcount2, long long *theta2, SolverState *st2,
                                                         const int *__restrict__ errflag, long long *__restrict__ cand,
                                                         int par, int T, int E, int k, int Ce, int n_wg,
-                                                        int rows_per_wg, int tail_on)
+                                                        int rows_per_wg, int tail_on, int tail_moves)
 {
     const SolverState *st = st2 + par;
     SolverState *st_out = st2 + (par ^ 1);
@@ -446,7 +446,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     const long long eps_ref = cur_eps_prev > 0 ? cur_eps_prev : cur_eps;
     // few slots moved: leave the thresholds alone, publish each expert's lowest keys and let the
     // single-workgroup tail pass run the next rounds on them
-    const bool tail_go = tail_on && !quiet && !cur_tail_block && cur_round > 0 && moves <= kTailMoves &&
+    const bool tail_go = tail_on && !quiet && !cur_tail_block && cur_round > 0 && moves <= tail_moves &&
                          (moves > 0 || (flags & 2));
     int action = 0;
     long long lower = 0;
@@ -1028,7 +1028,8 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     int *wcnt = (int *)(ws + L.wcnt_off);
     int *wmoves = (int *)(ws + L.wmoves_off);
     long long *cand = (long long *)(ws + L.cand_off);
-    int tail_on = E <= kTailMaxE ? 1 : 0, tail_iters = 256;
+    int tail_on = E <= kTailMaxE ? 1 : 0, tail_iters = 256, tail_moves = kTailMoves;
+    if (const char *ev = getenv("MAXSCORE_TAIL_MOVES")) tail_moves = atoi(ev);   // tuning override (debug)
     if (const char *ev = getenv("MAXSCORE_TAIL")) {   // tuning override (debug): 0 disables the tail pass
         tail_iters = atoi(ev);
         if (tail_iters <= 0) tail_on = 0;
@@ -1097,7 +1098,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
 #undef MS_BID
             if (g_kernel_timing) MS_HIP(hipEventRecord(tev.back(), s));
             hipLaunchKernelGGL(k_select, dim3(E), dim3(kSelThreads), 0, s, klist, wcnt, wmoves, gcount, theta, st,
-                               qmm + 2, cand, par, T, E, k, Ce, n_wg, rows, tail_on);
+                               qmm + 2, cand, par, T, E, k, Ce, n_wg, rows, tail_on, tail_moves);
             if (tail_on)
                 hipLaunchKernelGGL(k_tail, dim3(1), dim3(kTailThreads), 0, s, q, assign, theta, gcount, st, cand,
                                    qmm + 2, par, T, E, k, Ce, tail_iters);
