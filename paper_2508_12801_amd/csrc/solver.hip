@@ -359,9 +359,18 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
 // Select pass: one workgroup per expert; exact (n-Ce+1)-th smallest key by radix select.
 constexpr int kSelThreads = 1024;
 constexpr int kSelCache = 6144;
-constexpr int kSmallRank = 6;
+constexpr int kSelDirect = 256;           // at most this many keys are ranked against each other directly
 constexpr int kTailMoves = 16;            // hand over to the tail pass when a bid pass moved this few slots
 constexpr long long kKeyInf = (long long)1 << 62;
+
+#ifdef MS_SEL_PROF
+__device__ long long g_selprof[kMaxE * 8];
+__device__ long long g_selwall[2];
+__device__ unsigned long long g_selround[1024];
+#define MS_SP(slot) { if (tid == 0) { long long c_now = clock64(); g_selprof[j * 8 + slot] += c_now - c_sp; c_sp = c_now; } }
+#else
+#define MS_SP(slot)
+#endif
 
 __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restrict__ klist,
                                                         const int *__restrict__ wcnt, const int *__restrict__ wmoves,
@@ -381,15 +390,15 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     const int *gprev = gcount2 + (par ^ 1) * kMaxE;   // loads after the previous round
     int *gcur = gcount2 + par * kMaxE;
     __shared__ long long s_keys[kSelCache];
-    __shared__ int s_hist[256];
-    __shared__ int s_inc[256];
-    __shared__ int s_wsum[4];
-    __shared__ unsigned long long s_red[kSelThreads / 64];
+    __shared__ __attribute__((aligned(16))) int s_hist[2][256];
+    __shared__ unsigned long long s_small[kSelDirect];
     __shared__ int s_redi[kSelThreads / 64];
     __shared__ int s_flag[kSelThreads / 64];
     __shared__ int s_mvw[kSelThreads / 64];
     __shared__ long long s_cl[kCand];
-    __shared__ int s_d, s_rank, s_ncl;
+    __shared__ unsigned long long s_res;
+    __shared__ int s_meta[kSelThreads];
+    __shared__ int s_d, s_rank, s_m, s_nsm, s_ncl, s_fill;
     const int tid = threadIdx.x, j = blockIdx.x, lane = tid & 63, wv = tid >> 6;
     // (offset << 16 | count) of this expert inside the key block of bid workgroup w
     auto meta = [&](int w) { return wcnt[(size_t)w * E + j]; };
@@ -398,8 +407,17 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     // per-workgroup counts, with an exclusive scan that places each thread's keys in the LDS copy),
     // the moves of this bid pass, and the over-capacity / unfilled-but-priced experts after the
     // previous round.  All loads are issued before the single barrier.
-    int ct = 0, mv = 0, ov = 0, vi = 0;
-    for (int w = tid; w < n_wg; w += kSelThreads) {
+#ifdef MS_SEL_PROF
+    long long c_sp = clock64();
+    const long long c_w0 = wall_clock64(), c_c0 = c_sp;
+#endif
+    int ct = 0, mv = 0, ov = 0, vi = 0, mt0 = 0;
+    if (tid < n_wg) {
+        mt0 = meta(tid);
+        ct = mt0 & 0xffff;
+        mv = wmoves[tid];
+    }
+    for (int w = tid + kSelThreads; w < n_wg; w += kSelThreads) {
         ct += meta(w) & 0xffff;
         mv += wmoves[w];
     }
@@ -411,33 +429,39 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     const int cur_round = st->round, cur_slack = st->slack, cur_tbits = st->tbits, cur_after_tail = st->after_tail,
               cur_tail_block = st->tail_block;
     const long long cur_eps = st->eps, cur_eps_prev = st->eps_prev, cur_beta = st->beta;
-    int inc = ct;
-    for (int off = 1; off < 64; off <<= 1) {
-        int o = __shfl_up(inc, off);
-        if (lane >= off) inc += o;
-    }
+    const long long base = theta_in[j];
     int flags = (ov ? 2 : 0) | (vi ? 4 : 0);
     for (int off = 32; off > 0; off >>= 1) {
         flags |= __shfl_xor(flags, off);
         mv += __shfl_xor(mv, off);
+        ct += __shfl_xor(ct, off);
     }
-    if (lane == 63) s_redi[wv] = inc;
     if (lane == 0) {
+        s_redi[wv] = ct;
         s_flag[wv] = flags;
         s_mvw[wv] = mv;
     }
-    if (tid == 0) s_ncl = 0;
+    if (tid < 256) {
+        s_hist[0][tid] = 0;
+        s_hist[1][tid] = 0;
+    }
+    s_meta[tid] = mt0;
+    if (tid == 0) {
+        s_ncl = 0;
+        s_nsm = 0;
+        s_fill = 0;
+    }
     __syncthreads();
-    int woff = 0, n = 0, moves = 0;
+    int n = 0, moves = 0;
     flags = 0;
     for (int w = 0; w < kSelThreads / 64; ++w) {
         int v = s_redi[w];
-        if (w < wv) woff += v;
         n += v;
         flags |= s_flag[w];
         moves += s_mvw[w];
     }
     if (tid == 0) gcur[j] = n;
+    MS_SP(0)
 
     // the decision every thread of every block takes identically: nothing moved in this bid pass and
     // no expert was above capacity after the previous one  =>  the phase is quiescent
@@ -487,124 +511,164 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
         ns.tail_block = 0;
         *st_out = ns;
     }
-    long long new_theta = theta_in[j];
+    long long new_theta = base;
     const bool need_select = !tail_go && n > Ce;
     const bool need_cand = tail_go;
     if (need_select || need_cand) {
-        const long long base = theta_in[j];
         const bool cached = n <= kSelCache;
-        unsigned long long umax = 0;
-        {
-            int pos = woff + inc - ct;
-            for (int w = tid; w < n_wg; w += kSelThreads) {
-                const int mt = meta(w), c = mt & 0xffff;
-                const long long *seg = klist + (size_t)w * blk_stride + (mt >> 16);
-                for (int i0 = 0; i0 < c; i0 += 8) {      // eight independent loads in flight per thread
-                    long long kv[8];
+        // Eight consecutive lanes share one segment (the keys one bid workgroup wrote for this expert,
+        // a few dozen bytes), so that one load instruction of a wavefront touches 8 cache lines
+        // instead of 64.
+        const int sub = tid & 7, grp8 = tid >> 3;
+        auto seg_meta = [&](int w) { return w < kSelThreads ? s_meta[w] : meta(w); };
+        if (cached) {
+            const int iters = (n_wg + 127) >> 7;
+            for (int it0 = 0; it0 < iters; it0 += 8) {
+                int cs[8];
+                long long kvv[8];
+                const long long *sp[8];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) kv[u] = (i0 + u < c) ? seg[i0 + u] : base;
+                for (int u = 0; u < 8; ++u) {
+                    const int w = grp8 + 128 * (it0 + u);
+                    cs[u] = 0;
+                    sp[u] = klist;
+                    if (w < n_wg) {
+                        const int mt = seg_meta(w);
+                        cs[u] = mt & 0xffff;
+                        sp[u] = klist + (size_t)w * blk_stride + (mt >> 16);
+                    }
+                }
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        if (i0 + u < c) {
-                            if (cached) s_keys[pos++] = kv[u];
-                            unsigned long long uu = (unsigned long long)(kv[u] - base);
-                            umax = uu > umax ? uu : umax;
+                for (int u = 0; u < 8; ++u) kvv[u] = sub < cs[u] ? sp[u][sub] : 0;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (it0 + u < iters) {           // the same for the whole wavefront
+                        int inc = cs[u];             // all 8 lanes of a group hold their segment's count
+                        for (int off = 8; off < 64; off <<= 1) {
+                            int o = __shfl_up(inc, off);
+                            if (lane >= off) inc += o;
                         }
+                        const int tot = __shfl(inc, 63);
+                        int bp = 0;
+                        if (lane == 63 && tot > 0) bp = atomicAdd(&s_fill, tot);
+                        bp = __shfl(bp, 63);
+                        const int gpos = bp + inc - cs[u];
+                        if (sub < cs[u]) s_keys[gpos + sub] = kvv[u];
+                        for (int i = sub + 8; i < cs[u]; i += 8) s_keys[gpos + i] = sp[u][i];
                     }
                 }
             }
+            __syncthreads();
         }
-        __syncthreads();
+        MS_SP(1)
         // visit every key of this expert (LDS copy when it fits, else the global segments)
         auto for_keys = [&](auto fn) {
             if (cached) {
                 for (int i = tid; i < n; i += kSelThreads) fn(s_keys[i]);
             } else {
-                for (int w = tid; w < n_wg; w += kSelThreads) {
-                    const int mt = meta(w), c = mt & 0xffff;
+                for (int w = grp8; w < n_wg; w += 128) {
+                    const int mt = seg_meta(w), c = mt & 0xffff;
                     const long long *seg = klist + (size_t)w * blk_stride + (mt >> 16);
-                    for (int i = 0; i < c; ++i) fn(seg[i]);
+                    for (int i = sub; i < c; i += 8) fn(seg[i]);
                 }
             }
         };
-        // key of 0-based rank `rank` in ascending order, by successive minima (small rank) ...
-        auto nth_by_minima = [&](int rank) {
-            long long last = -1;
-            for (int it = 0; it <= rank; ++it) {
-                unsigned long long best = ~0ull;
-                for_keys([&](long long kv) {
-                    if (kv > last && (unsigned long long)kv < best) best = (unsigned long long)kv;
-                });
-                for (int off = 32; off > 0; off >>= 1) {
-                    unsigned long long o = shfl_xor_u64(best, off);
-                    best = o < best ? o : best;
-                }
-                if (lane == 0) s_red[wv] = best;
-                __syncthreads();
-                best = s_red[0];
-                for (int w = 1; w < kSelThreads / 64; ++w) best = s_red[w] < best ? s_red[w] : best;
-                last = (long long)best;
-                __syncthreads();
-            }
-            return last;
-        };
-        // ... or by most-significant-digit radix select on key - base
-        auto nth_by_radix = [&](int rank) {
-            unsigned long long um = umax;
-            for (int off = 32; off > 0; off >>= 1) {
-                unsigned long long o = shfl_xor_u64(um, off);
-                um = o > um ? o : um;
-            }
-            if (lane == 0) s_red[wv] = um;
+        // key of 0-based rank `rank` in ascending order, by narrowing on u = key - base (>= 0: every key of this pass is at or above the old
+        // threshold): first the bit length of u (the keys crowd near the threshold with a long tail
+        // above, so equal-width digits from the top would separate little), then 8-bit digits below
+        // it, and as soon as at most kSelDirect keys share the prefix they are ranked directly.
+        // Wavefront 0 scans the histogram (4 bins per lane) while the others clear the next one.
+        auto nth_by_narrowing = [&](int rank) {
+            int hsel = 0;
+            for_keys([&](long long kv) {
+                const unsigned long long u = (unsigned long long)(kv - base);
+                atomicAdd(&s_hist[0][u ? 64 - __clzll((long long)u) : 0], 1);
+            });
             __syncthreads();
-            um = 0;
-            for (int w = 0; w < kSelThreads / 64; ++w) um = s_red[w] > um ? s_red[w] : um;
-            int nd = 1;
-            while (nd < 8 && (um >> (8 * nd)) != 0) ++nd;
-            unsigned long long prefix = 0, pmask = 0;
-            for (int pass = nd - 1; pass >= 0; --pass) {
-                const int shift = pass * 8;
-                if (tid < 256) s_hist[tid] = 0;
-                __syncthreads();
-                for_keys([&](long long kv) {
-                    unsigned long long u = (unsigned long long)(kv - base);
-                    if ((u & pmask) == prefix) atomicAdd(&s_hist[(int)((u >> shift) & 255)], 1);
-                });
-                __syncthreads();
-                if (tid < 256) {        // inclusive scan of the 256 bins by four wavefronts
-                    const int h = s_hist[tid];
-                    int hi = h;
+            MS_SP(2)
+            auto scan_find = [&](int h) {       // finds the bin holding `rank`; call from all threads
+                if (wv == 0) {
+                    const int4 b4 = *(const int4 *)&s_hist[h][lane * 4];
+                    const int sum = b4.x + b4.y + b4.z + b4.w;
+                    int hi = sum;
                     for (int off = 1; off < 64; off <<= 1) {
                         int o = __shfl_up(hi, off);
                         if (lane >= off) hi += o;
                     }
-                    if (lane == 63) s_wsum[wv] = hi;
-                    s_inc[tid] = hi;
-                }
-                __syncthreads();
-                if (tid < 256) {
-                    int add = 0;
-                    for (int w = 0; w < wv; ++w) add += s_wsum[w];
-                    const int hi = s_inc[tid] + add, exc = hi - s_hist[tid];
+                    const int exc = hi - sum;
                     if (exc <= rank && rank < hi) {
-                        s_d = tid;
-                        s_rank = rank - exc;
+                        int r = rank - exc, d = 0, m = b4.x;
+                        if (r >= b4.x) { r -= b4.x; d = 1; m = b4.y;
+                            if (r >= b4.y) { r -= b4.y; d = 2; m = b4.z;
+                                if (r >= b4.z) { r -= b4.z; d = 3; m = b4.w; } } }
+                        s_d = lane * 4 + d;
+                        s_rank = r;
+                        s_m = m;
                     }
+                } else if (tid - 64 < 256) {
+                    s_hist[h ^ 1][tid - 64] = 0;
                 }
                 __syncthreads();
+            };
+            scan_find(0);
+            MS_SP(3)
+            const int bl = s_d;                  // bit length of the wanted u
+            if (bl <= 1) return base + (long long)bl;     // u = 0 or u = 1
+            rank = s_rank;
+            int m = s_m, shift = bl - 1;         // bits below the leading one are still open
+            unsigned long long prefix = 1ull << shift, pmask = ~(prefix - 1);
+            while (m > kSelDirect && shift > 0) {
+                hsel ^= 1;
+                const int wd = shift < 8 ? shift : 8;
+                shift -= wd;
+                const unsigned dm = (1u << wd) - 1;
+                for_keys([&](long long kv) {
+                    const unsigned long long u = (unsigned long long)(kv - base);
+                    if ((u & pmask) == prefix) atomicAdd(&s_hist[hsel][(unsigned)(u >> shift) & dm], 1);
+                });
+                __syncthreads();
+                scan_find(hsel);
                 prefix |= (unsigned long long)s_d << shift;
-                pmask |= 255ull << shift;
+                pmask |= (unsigned long long)dm << shift;
                 rank = s_rank;
+                m = s_m;
             }
-            return base + (long long)prefix;
+            MS_SP(4)
+            if (shift == 0) return base + (long long)prefix;
+            for_keys([&](long long kv) {
+                const unsigned long long u = (unsigned long long)(kv - base);
+                if ((u & pmask) == prefix) {
+                    const int slot = atomicAdd(&s_nsm, 1);
+                    if (slot < kSelDirect) s_small[slot] = u;
+                }
+            });
+            __syncthreads();
+            {   // four threads per listed key count the keys below it
+                const int el = tid >> 2, part = tid & 3;
+                int r = 0;
+                unsigned long long mine = 0;
+                if (el < m) {
+                    mine = s_small[el];
+                    for (int i = part; i < m; i += 4) r += s_small[i] < mine;
+                }
+                r += __shfl_xor(r, 1);
+                r += __shfl_xor(r, 2);
+                if (el < m && part == 0 && r == rank) s_res = mine;
+            }
+            __syncthreads();
+            const unsigned long long res = s_res;
+            __syncthreads();
+            if (tid == 0) s_nsm = 0;
+            MS_SP(5)
+            return base + (long long)res;
         };
         if (need_select) {
             const int rank = n - Ce;   // 0-based rank of the new threshold among the keys, ascending
-            new_theta = rank < kSmallRank ? nth_by_minima(rank) : nth_by_radix(rank);
+            new_theta = nth_by_narrowing(rank);
         } else {
             // candidate list for the tail pass: the kCand smallest keys in ascending order, their
             // count, and a bound no other key of this expert lies under
-            const long long bound = n > kCand ? nth_by_radix(kCand) : kKeyInf;
+            const long long bound = n > kCand ? nth_by_narrowing(kCand) : kKeyInf;
             for_keys([&](long long kv) {
                 if (kv < bound) s_cl[atomicAdd(&s_ncl, 1)] = kv;
             });
@@ -630,6 +694,12 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
         }
         theta_out[j] = new_theta;
     }
+    MS_SP(6)
+#ifdef MS_SEL_PROF
+    if (tid == 0) g_selprof[j * 8 + 7] += 1;
+    if (tid == 0 && j == 0) { g_selwall[0] += wall_clock64() - c_w0; g_selwall[1] += clock64() - c_c0; }
+    if (tid == 0) atomicMax(&g_selround[cur_round & 1023], ((unsigned long long)(clock64() - c_c0) << 32) | ((unsigned)n << 8) | (need_select ? 1 : 0) | (need_cand ? 2 : 0));
+#endif
 }
 
 // Tail pass: when a bid pass moved only a few slots, one workgroup continues the same auction on the
@@ -1150,6 +1220,28 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     }
     (void)hipEventDestroy(ev0);
     (void)hipEventDestroy(ev1);
+#ifdef MS_SEL_PROF
+    {
+        static long long hp[kMaxE * 8];
+        (void)hipMemcpyFromSymbol(hp, HIP_SYMBOL(g_selprof), sizeof(hp));
+        long long sum[8] = {0}, mx[8] = {0};
+        for (int e = 0; e < E; ++e)
+            for (int a = 0; a < 8; ++a) {
+                sum[a] += hp[e * 8 + a];
+                mx[a] = hp[e * 8 + a] > mx[a] ? hp[e * 8 + a] : mx[a];
+            }
+        fprintf(stderr, "[selprof] cumulative cycles, mean over experts (max): ");
+        const char *nm[8] = {"prologue", "gather", "bitlen-hist", "scan0", "digits", "direct", "rest", "launches"};
+        for (int a = 0; a < 8; ++a) fprintf(stderr, "%s %lld (%lld)  ", nm[a], sum[a] / E, mx[a]);
+        fprintf(stderr, "\n");
+        long long hw[2];
+        (void)hipMemcpyFromSymbol(hw, HIP_SYMBOL(g_selwall), sizeof(hw));
+        static unsigned long long hr[1024];
+        (void)hipMemcpyFromSymbol(hr, HIP_SYMBOL(g_selround), sizeof(hr));
+        for (int a = 0; a < 90; ++a) fprintf(stderr, "[selround] %d cyc %llu n %llu fl %llu\n", a, hr[a] >> 32, (hr[a] >> 8) & 0xffffff, hr[a] & 3);
+        fprintf(stderr, "[selprof] block 0: wall ticks (100 MHz) %lld, clock64 ticks %lld\n", hw[0], hw[1]);
+    }
+#endif
     if (getenv("MAXSCORE_DEBUG")) {
         fprintf(stderr, "[maxscore] phase end rounds:");
         for (int a = 0; a < 28 && a < h.phases; ++a) fprintf(stderr, " %d", h.phase_round[a]);
