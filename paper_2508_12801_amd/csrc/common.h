@@ -38,6 +38,7 @@ struct SolverState {
     int tail_go;           // the select pass built candidate lists: the tail pass may run
     int after_tail;        // the tail pass changed the state: the next round cannot be declared quiescent
     int tail_block;        // the tail pass could not proceed: the next select pass must do a normal select
+    int tail_gos;          // rounds so far in which the select pass handed over to the tail pass
     int tail_runs, tail_iters;   // diagnostics
     int phase_round[28];   // round index at which each phase ended (diagnostic)
 };

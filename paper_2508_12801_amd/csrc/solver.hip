@@ -73,12 +73,13 @@ __global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm,
         qmm[0] = 0x7fffffff;
         qmm[1] = -0x7fffffff - 1;
         qmm[2] = 0;                      // internal error flag
+        qmm[3] = 0;                      // hand-over counter of the select pass
         st->eps = 1; st->eps_prev = 0; st->beta = 2;
         st->qmin = 0x7fffffff; st->qmax = -0x7fffffff - 1; st->total = 0;
         st->sbits = 0; st->tbits = 0; st->eps_div = eps_div; st->max_rounds = max_rounds;
         st->round = 0; st->phases = 1; st->done = 0; st->status = MAXSCORE_OK; st->moves = 0;
         st->blocks_done = 0; st->flow = 0; st->slack = slack;
-        st->wide = 0; st->tail_go = 0; st->after_tail = 0; st->tail_block = 0; st->tail_runs = 0;
+        st->wide = 0; st->tail_go = 0; st->after_tail = 0; st->tail_block = 0; st->tail_runs = 0; st->tail_gos = 0;
         st->tail_iters = 0;
         for (int a = 0; a < 28; ++a) st->phase_round[a] = 0;
     }
@@ -356,352 +357,6 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
     }
 }
 
-// Select pass: one workgroup per expert; exact (n-Ce+1)-th smallest key by radix select.
-constexpr int kSelThreads = 1024;
-constexpr int kSelCache = 6144;
-constexpr int kSelDirect = 256;           // at most this many keys are ranked against each other directly
-constexpr int kTailMoves = 16;            // hand over to the tail pass when a bid pass moved this few slots
-constexpr long long kKeyInf = (long long)1 << 62;
-
-#ifdef MS_SEL_PROF
-__device__ long long g_selprof[kMaxE * 8];
-__device__ long long g_selwall[2];
-__device__ unsigned long long g_selround[1024];
-#define MS_SP(slot) { if (tid == 0) { long long c_now = clock64(); g_selprof[j * 8 + slot] += c_now - c_sp; c_sp = c_now; } }
-#else
-#define MS_SP(slot)
-#endif
-
-__global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restrict__ klist,
-                                                        const int *__restrict__ wcnt, const int *__restrict__ wmoves,
-                                                        int *gcount2, long long *theta2, SolverState *st2,
-                                                        const int *__restrict__ errflag, long long *__restrict__ cand,
-                                                        int par, int T, int E, int k, int Ce, int n_wg,
-                                                        int rows_per_wg, int tail_on, int tail_moves)
-{
-    const SolverState *st = st2 + par;
-    SolverState *st_out = st2 + (par ^ 1);
-    if (st->done) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) *st_out = *st;
-        return;
-    }
-    const long long *theta_in = theta2 + par * kMaxE;
-    long long *theta_out = theta2 + (par ^ 1) * kMaxE;
-    const int *gprev = gcount2 + (par ^ 1) * kMaxE;   // loads after the previous round
-    int *gcur = gcount2 + par * kMaxE;
-    __shared__ long long s_keys[kSelCache];
-    __shared__ __attribute__((aligned(16))) int s_hist[2][256];
-    __shared__ unsigned long long s_small[kSelDirect];
-    __shared__ int s_redi[kSelThreads / 64];
-    __shared__ int s_flag[kSelThreads / 64];
-    __shared__ int s_mvw[kSelThreads / 64];
-    __shared__ long long s_cl[kCand];
-    __shared__ unsigned long long s_res;
-    __shared__ int s_meta[kSelThreads];
-    __shared__ int s_d, s_rank, s_m, s_nsm, s_ncl, s_fill;
-    const int tid = threadIdx.x, j = blockIdx.x, lane = tid & 63, wv = tid >> 6;
-    // (offset << 16 | count) of this expert inside the key block of bid workgroup w
-    auto meta = [&](int w) { return wcnt[(size_t)w * E + j]; };
-    const size_t blk_stride = (size_t)rows_per_wg * k;
-    // One reduction for everything the block needs: the number of keys of this expert (sum of the
-    // per-workgroup counts, with an exclusive scan that places each thread's keys in the LDS copy),
-    // the moves of this bid pass, and the over-capacity / unfilled-but-priced experts after the
-    // previous round.  All loads are issued before the single barrier.
-#ifdef MS_SEL_PROF
-    long long c_sp = clock64();
-    const long long c_w0 = wall_clock64(), c_c0 = c_sp;
-#endif
-    int ct = 0, mv = 0, ov = 0, vi = 0, mt0 = 0;
-    if (tid < n_wg) {
-        mt0 = meta(tid);
-        ct = mt0 & 0xffff;
-        mv = wmoves[tid];
-    }
-    for (int w = tid + kSelThreads; w < n_wg; w += kSelThreads) {
-        ct += meta(w) & 0xffff;
-        mv += wmoves[w];
-    }
-    for (int e = tid; e < E; e += kSelThreads) {
-        const int c = gprev[e];
-        ov += c > Ce;
-        vi += (c < Ce && theta_in[e] > 0);
-    }
-    const int cur_round = st->round, cur_slack = st->slack, cur_tbits = st->tbits, cur_after_tail = st->after_tail,
-              cur_tail_block = st->tail_block;
-    const long long cur_eps = st->eps, cur_eps_prev = st->eps_prev, cur_beta = st->beta;
-    const long long base = theta_in[j];
-    int flags = (ov ? 2 : 0) | (vi ? 4 : 0);
-    for (int off = 32; off > 0; off >>= 1) {
-        flags |= __shfl_xor(flags, off);
-        mv += __shfl_xor(mv, off);
-        ct += __shfl_xor(ct, off);
-    }
-    if (lane == 0) {
-        s_redi[wv] = ct;
-        s_flag[wv] = flags;
-        s_mvw[wv] = mv;
-    }
-    if (tid < 256) {
-        s_hist[0][tid] = 0;
-        s_hist[1][tid] = 0;
-    }
-    s_meta[tid] = mt0;
-    if (tid == 0) {
-        s_ncl = 0;
-        s_nsm = 0;
-        s_fill = 0;
-    }
-    __syncthreads();
-    int n = 0, moves = 0;
-    flags = 0;
-    for (int w = 0; w < kSelThreads / 64; ++w) {
-        int v = s_redi[w];
-        n += v;
-        flags |= s_flag[w];
-        moves += s_mvw[w];
-    }
-    if (tid == 0) gcur[j] = n;
-    MS_SP(0)
-
-    // the decision every thread of every block takes identically: nothing moved in this bid pass and
-    // no expert was above capacity after the previous one  =>  the phase is quiescent
-    const bool quiet = (moves == 0 && (flags & 2) == 0 && cur_round > 0 && !cur_after_tail);
-    const bool redo = quiet && cur_slack && (flags & 4);
-    const long long eps_ref = cur_eps_prev > 0 ? cur_eps_prev : cur_eps;
-    // few slots moved: leave the thresholds alone, publish each expert's lowest keys and let the
-    // single-workgroup tail pass run the next rounds on them
-    const bool tail_go = tail_on && !quiet && !cur_tail_block && cur_round > 0 && moves <= tail_moves &&
-                         (moves > 0 || (flags & 2));
-    int action = 0;
-    long long lower = 0;
-    if (redo) {
-        action = 1;                          // an unfilled expert kept a positive price: redo the phase lower
-        lower = cur_beta * 2 * eps_ref;
-    } else if (quiet && cur_eps != 1 && cur_slack) {
-        action = 1;
-        lower = cur_beta * cur_eps;
-    }
-    if (j == 0 && tid == 0) {
-        SolverState ns = *st;
-        const int round = cur_round + 1;
-        if (quiet) {
-            if (ns.phases <= 28) ns.phase_round[ns.phases - 1] = round;
-            if (redo) {
-                ns.beta = cur_beta * 2;
-                ns.phases += 1;
-            } else if (cur_eps == 1) {
-                ns.done = 1;
-            } else {
-                ns.eps_prev = cur_eps;
-                long long ne = cur_eps / ns.eps_div;
-                ns.eps = ne > 1 ? ne : 1;
-                ns.phases += 1;
-            }
-        } else if (round >= ns.max_rounds) {
-            ns.status = MAXSCORE_ERR_NOT_CONVERGED;
-            ns.done = 1;
-        }
-        if (*errflag) {
-            ns.status = MAXSCORE_ERR_HIP;
-            ns.done = 1;
-        }
-        ns.round = round;
-        ns.tail_go = tail_go ? 1 : 0;
-        ns.after_tail = 0;
-        ns.tail_block = 0;
-        *st_out = ns;
-    }
-    long long new_theta = base;
-    const bool need_select = !tail_go && n > Ce;
-    const bool need_cand = tail_go;
-    if (need_select || need_cand) {
-        const bool cached = n <= kSelCache;
-        // Eight consecutive lanes share one segment (the keys one bid workgroup wrote for this expert,
-        // a few dozen bytes), so that one load instruction of a wavefront touches 8 cache lines
-        // instead of 64.
-        const int sub = tid & 7, grp8 = tid >> 3;
-        auto seg_meta = [&](int w) { return w < kSelThreads ? s_meta[w] : meta(w); };
-        if (cached) {
-            const int iters = (n_wg + 127) >> 7;
-            for (int it0 = 0; it0 < iters; it0 += 8) {
-                int cs[8];
-                long long kvv[8];
-                const long long *sp[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int w = grp8 + 128 * (it0 + u);
-                    cs[u] = 0;
-                    sp[u] = klist;
-                    if (w < n_wg) {
-                        const int mt = seg_meta(w);
-                        cs[u] = mt & 0xffff;
-                        sp[u] = klist + (size_t)w * blk_stride + (mt >> 16);
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) kvv[u] = sub < cs[u] ? sp[u][sub] : 0;
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    if (it0 + u < iters) {           // the same for the whole wavefront
-                        int inc = cs[u];             // all 8 lanes of a group hold their segment's count
-                        for (int off = 8; off < 64; off <<= 1) {
-                            int o = __shfl_up(inc, off);
-                            if (lane >= off) inc += o;
-                        }
-                        const int tot = __shfl(inc, 63);
-                        int bp = 0;
-                        if (lane == 63 && tot > 0) bp = atomicAdd(&s_fill, tot);
-                        bp = __shfl(bp, 63);
-                        const int gpos = bp + inc - cs[u];
-                        if (sub < cs[u]) s_keys[gpos + sub] = kvv[u];
-                        for (int i = sub + 8; i < cs[u]; i += 8) s_keys[gpos + i] = sp[u][i];
-                    }
-                }
-            }
-            __syncthreads();
-        }
-        MS_SP(1)
-        // visit every key of this expert (LDS copy when it fits, else the global segments)
-        auto for_keys = [&](auto fn) {
-            if (cached) {
-                for (int i = tid; i < n; i += kSelThreads) fn(s_keys[i]);
-            } else {
-                for (int w = grp8; w < n_wg; w += 128) {
-                    const int mt = seg_meta(w), c = mt & 0xffff;
-                    const long long *seg = klist + (size_t)w * blk_stride + (mt >> 16);
-                    for (int i = sub; i < c; i += 8) fn(seg[i]);
-                }
-            }
-        };
-        // key of 0-based rank `rank` in ascending order, by narrowing on u = key - base (>= 0: every key of this pass is at or above the old
-        // threshold): first the bit length of u (the keys crowd near the threshold with a long tail
-        // above, so equal-width digits from the top would separate little), then 8-bit digits below
-        // it, and as soon as at most kSelDirect keys share the prefix they are ranked directly.
-        // Wavefront 0 scans the histogram (4 bins per lane) while the others clear the next one.
-        auto nth_by_narrowing = [&](int rank) {
-            int hsel = 0;
-            for_keys([&](long long kv) {
-                const unsigned long long u = (unsigned long long)(kv - base);
-                atomicAdd(&s_hist[0][u ? 64 - __clzll((long long)u) : 0], 1);
-            });
-            __syncthreads();
-            MS_SP(2)
-            auto scan_find = [&](int h) {       // finds the bin holding `rank`; call from all threads
-                if (wv == 0) {
-                    const int4 b4 = *(const int4 *)&s_hist[h][lane * 4];
-                    const int sum = b4.x + b4.y + b4.z + b4.w;
-                    int hi = sum;
-                    for (int off = 1; off < 64; off <<= 1) {
-                        int o = __shfl_up(hi, off);
-                        if (lane >= off) hi += o;
-                    }
-                    const int exc = hi - sum;
-                    if (exc <= rank && rank < hi) {
-                        int r = rank - exc, d = 0, m = b4.x;
-                        if (r >= b4.x) { r -= b4.x; d = 1; m = b4.y;
-                            if (r >= b4.y) { r -= b4.y; d = 2; m = b4.z;
-                                if (r >= b4.z) { r -= b4.z; d = 3; m = b4.w; } } }
-                        s_d = lane * 4 + d;
-                        s_rank = r;
-                        s_m = m;
-                    }
-                } else if (tid - 64 < 256) {
-                    s_hist[h ^ 1][tid - 64] = 0;
-                }
-                __syncthreads();
-            };
-            scan_find(0);
-            MS_SP(3)
-            const int bl = s_d;                  // bit length of the wanted u
-            if (bl <= 1) return base + (long long)bl;     // u = 0 or u = 1
-            rank = s_rank;
-            int m = s_m, shift = bl - 1;         // bits below the leading one are still open
-            unsigned long long prefix = 1ull << shift, pmask = ~(prefix - 1);
-            while (m > kSelDirect && shift > 0) {
-                hsel ^= 1;
-                const int wd = shift < 8 ? shift : 8;
-                shift -= wd;
-                const unsigned dm = (1u << wd) - 1;
-                for_keys([&](long long kv) {
-                    const unsigned long long u = (unsigned long long)(kv - base);
-                    if ((u & pmask) == prefix) atomicAdd(&s_hist[hsel][(unsigned)(u >> shift) & dm], 1);
-                });
-                __syncthreads();
-                scan_find(hsel);
-                prefix |= (unsigned long long)s_d << shift;
-                pmask |= (unsigned long long)dm << shift;
-                rank = s_rank;
-                m = s_m;
-            }
-            MS_SP(4)
-            if (shift == 0) return base + (long long)prefix;
-            for_keys([&](long long kv) {
-                const unsigned long long u = (unsigned long long)(kv - base);
-                if ((u & pmask) == prefix) {
-                    const int slot = atomicAdd(&s_nsm, 1);
-                    if (slot < kSelDirect) s_small[slot] = u;
-                }
-            });
-            __syncthreads();
-            {   // four threads per listed key count the keys below it
-                const int el = tid >> 2, part = tid & 3;
-                int r = 0;
-                unsigned long long mine = 0;
-                if (el < m) {
-                    mine = s_small[el];
-                    for (int i = part; i < m; i += 4) r += s_small[i] < mine;
-                }
-                r += __shfl_xor(r, 1);
-                r += __shfl_xor(r, 2);
-                if (el < m && part == 0 && r == rank) s_res = mine;
-            }
-            __syncthreads();
-            const unsigned long long res = s_res;
-            __syncthreads();
-            if (tid == 0) s_nsm = 0;
-            MS_SP(5)
-            return base + (long long)res;
-        };
-        if (need_select) {
-            const int rank = n - Ce;   // 0-based rank of the new threshold among the keys, ascending
-            new_theta = nth_by_narrowing(rank);
-        } else {
-            // candidate list for the tail pass: the kCand smallest keys in ascending order, their
-            // count, and a bound no other key of this expert lies under
-            const long long bound = n > kCand ? nth_by_narrowing(kCand) : kKeyInf;
-            for_keys([&](long long kv) {
-                if (kv < bound) s_cl[atomicAdd(&s_ncl, 1)] = kv;
-            });
-            __syncthreads();
-            const int nc = s_ncl;            // = min(n, kCand): keys are distinct
-            long long *cj_out = cand + (size_t)j * (kCand + 2);
-            if (tid < nc) {
-                const long long mine = s_cl[tid];
-                int r = 0;
-                for (int i = 0; i < nc; ++i) r += s_cl[i] < mine;
-                cj_out[r] = mine;
-            }
-            if (tid == 0) {
-                cj_out[kCand] = nc;
-                cj_out[kCand + 1] = bound;
-            }
-        }
-    }
-    if (tid == 0) {
-        if (action) {
-            long long p = (new_theta >> cur_tbits) - lower;
-            new_theta = (p > 0 ? p : 0) << cur_tbits;
-        }
-        theta_out[j] = new_theta;
-    }
-    MS_SP(6)
-#ifdef MS_SEL_PROF
-    if (tid == 0) g_selprof[j * 8 + 7] += 1;
-    if (tid == 0 && j == 0) { g_selwall[0] += wall_clock64() - c_w0; g_selwall[1] += clock64() - c_c0; }
-    if (tid == 0) atomicMax(&g_selround[cur_round & 1023], ((unsigned long long)(clock64() - c_c0) << 32) | ((unsigned)n << 8) | (need_select ? 1 : 0) | (need_cand ? 2 : 0));
-#endif
-}
-
 // Tail pass: when a bid pass moved only a few slots, one workgroup continues the same auction on the
 // candidate lists (each expert's lowest bid keys) published by the select pass, without touching the
 // other tokens: an over-full expert drops its lowest candidates and raises its threshold to the next
@@ -712,6 +367,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
 // stops when nothing is over capacity, when a list runs out or after max_iters rounds; the next bid
 // pass re-validates every token, so this pass only has to make valid moves, not complete ones.
 constexpr int kTailThreads = 1024;
+constexpr int kTailMoves = 16;            // hand over to the tail pass when a bid pass moved this few slots
+constexpr long long kKeyInf = (long long)1 << 62;
+constexpr int kTailSpinMax = 1 << 20;     // polls of the tail workgroup for the candidate lists before it gives up
 constexpr int kTailVict = 64;
 constexpr int kTailIns = 256;
 constexpr int kTailEPL = kTailMaxE / 64;
@@ -737,16 +395,13 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
     return ((unsigned long long)mhi << 32) | mlo;
 }
 
-__global__ __launch_bounds__(kTailThreads) void k_tail(const int32_t *__restrict__ q, int32_t *assign,
-                                                      long long *theta2, int *gcount2, SolverState *st2,
-                                                      const long long *__restrict__ cand, int *errflag, int par,
-                                                      int T, int E, int k, int Ce, int max_iters)
+// Runs in the extra workgroup of the select pass (all kTailThreads threads), after the other
+// workgroups have published their candidate lists.
+__device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t *assign, long long *theta2,
+                                          int *gcount2, SolverState *st2, const long long *cand, int *errflag,
+                                          int par, int T, int E, int k, int Ce, int max_iters)
 {
     SolverState *st = st2 + (par ^ 1);          // the state the next bid pass will read
-    {
-        const int d0 = st->done, g0 = st->tail_go;   // both loads in flight at once
-        if (d0 | !g0) return;
-    }
     long long *theta = theta2 + (par ^ 1) * kMaxE;
     int *gcur = gcount2 + par * kMaxE;
     // candidate lists are kept in DESCENDING order: the lowest keys sit at the end and leave by
@@ -1026,6 +681,389 @@ __global__ __launch_bounds__(kTailThreads) void k_tail(const int32_t *__restrict
     }
 }
 
+// Select pass: one workgroup per expert; exact (n-Ce+1)-th smallest key by radix select.
+constexpr int kSelThreads = 1024;
+constexpr int kSelCache = 6144;
+constexpr int kSelDirect = 256;           // at most this many keys are ranked against each other directly
+
+#ifdef MS_SEL_PROF
+__device__ long long g_selprof[kMaxE * 8];
+__device__ long long g_selwall[2];
+__device__ unsigned long long g_selround[1024];
+#define MS_SP(slot) { if (tid == 0 && !is_tail) { long long c_now = clock64(); g_selprof[j * 8 + slot] += c_now - c_sp; c_sp = c_now; } }
+#else
+#define MS_SP(slot)
+#endif
+
+static_assert(kSelThreads == kTailThreads, "the tail pass runs in a workgroup of the select pass");
+
+// Grid: E workgroups, one per expert, plus (when tail_on) one more that runs the tail pass on the
+// candidate lists the others publish in rounds that hand over to it.
+__global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restrict__ klist,
+                                                        const int *__restrict__ wcnt, const int *__restrict__ wmoves,
+                                                        int *gcount2, long long *theta2, SolverState *st2,
+                                                        int *errflag, long long *cand, const int32_t *__restrict__ q,
+                                                        int32_t *assign, int *ready, int par, int T, int E, int k,
+                                                        int Ce, int n_wg, int rows_per_wg, int tail_on,
+                                                        int tail_moves, int tail_iters)
+{
+    const SolverState *st = st2 + par;
+    SolverState *st_out = st2 + (par ^ 1);
+    if (st->done) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) *st_out = *st;
+        return;
+    }
+    const long long *theta_in = theta2 + par * kMaxE;
+    long long *theta_out = theta2 + (par ^ 1) * kMaxE;
+    const int *gprev = gcount2 + (par ^ 1) * kMaxE;   // loads after the previous round
+    int *gcur = gcount2 + par * kMaxE;
+    __shared__ long long s_keys[kSelCache];
+    __shared__ __attribute__((aligned(16))) int s_hist[2][256];
+    __shared__ unsigned long long s_small[kSelDirect];
+    __shared__ int s_redi[kSelThreads / 64];
+    __shared__ int s_flag[kSelThreads / 64];
+    __shared__ int s_mvw[kSelThreads / 64];
+    __shared__ long long s_cl[kCand];
+    __shared__ unsigned long long s_res;
+    __shared__ int s_meta[kSelThreads];
+    __shared__ int s_d, s_rank, s_m, s_nsm, s_ncl, s_fill, s_ok;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const bool is_tail = (int)blockIdx.x == E;          // the extra workgroup
+    const int j = is_tail ? 0 : blockIdx.x;
+    // (offset << 16 | count) of this expert inside the key block of bid workgroup w
+    auto meta = [&](int w) { return wcnt[(size_t)w * E + j]; };
+    const size_t blk_stride = (size_t)rows_per_wg * k;
+    // One reduction for everything the block needs: the number of keys of this expert (sum of the
+    // per-workgroup counts, with an exclusive scan that places each thread's keys in the LDS copy),
+    // the moves of this bid pass, and the over-capacity / unfilled-but-priced experts after the
+    // previous round.  All loads are issued before the single barrier.
+#ifdef MS_SEL_PROF
+    long long c_sp = clock64();
+    const long long c_w0 = wall_clock64(), c_c0 = c_sp;
+#endif
+    int ct = 0, mv = 0, ov = 0, vi = 0, mt0 = 0;
+    if (tid < n_wg) {
+        mt0 = meta(tid);
+        ct = mt0 & 0xffff;
+        mv = wmoves[tid];
+    }
+    for (int w = tid + kSelThreads; w < n_wg; w += kSelThreads) {
+        ct += meta(w) & 0xffff;
+        mv += wmoves[w];
+    }
+    for (int e = tid; e < E; e += kSelThreads) {
+        const int c = gprev[e];
+        ov += c > Ce;
+        vi += (c < Ce && theta_in[e] > 0);
+    }
+    const int cur_round = st->round, cur_slack = st->slack, cur_tbits = st->tbits, cur_after_tail = st->after_tail,
+              cur_tail_block = st->tail_block, cur_tail_gos = st->tail_gos, cur_max_rounds = st->max_rounds;
+    const long long cur_eps = st->eps, cur_eps_prev = st->eps_prev, cur_beta = st->beta;
+    const long long base = theta_in[j];
+    int flags = (ov ? 2 : 0) | (vi ? 4 : 0);
+    for (int off = 32; off > 0; off >>= 1) {
+        flags |= __shfl_xor(flags, off);
+        mv += __shfl_xor(mv, off);
+        ct += __shfl_xor(ct, off);
+    }
+    if (lane == 0) {
+        s_redi[wv] = ct;
+        s_flag[wv] = flags;
+        s_mvw[wv] = mv;
+    }
+    if (tid < 256) {
+        s_hist[0][tid] = 0;
+        s_hist[1][tid] = 0;
+    }
+    s_meta[tid] = mt0;
+    if (tid == 0) {
+        s_ncl = 0;
+        s_nsm = 0;
+        s_fill = 0;
+    }
+    __syncthreads();
+    int n = 0, moves = 0;
+    flags = 0;
+    for (int w = 0; w < kSelThreads / 64; ++w) {
+        int v = s_redi[w];
+        n += v;
+        flags |= s_flag[w];
+        moves += s_mvw[w];
+    }
+    if (tid == 0 && !is_tail) gcur[j] = n;
+    MS_SP(0)
+
+    // the decision every thread of every block takes identically: nothing moved in this bid pass and
+    // no expert was above capacity after the previous one  =>  the phase is quiescent
+    const bool quiet = (moves == 0 && (flags & 2) == 0 && cur_round > 0 && !cur_after_tail);
+    const bool redo = quiet && cur_slack && (flags & 4);
+    const long long eps_ref = cur_eps_prev > 0 ? cur_eps_prev : cur_eps;
+    // few slots moved: leave the thresholds alone, publish each expert's lowest keys and let the
+    // single-workgroup tail pass run the next rounds on them
+    const bool tail_go = tail_on && !quiet && !cur_tail_block && cur_round > 0 && moves <= tail_moves &&
+                         (moves > 0 || (flags & 2));
+    int action = 0;
+    long long lower = 0;
+    if (redo) {
+        action = 1;                          // an unfilled expert kept a positive price: redo the phase lower
+        lower = cur_beta * 2 * eps_ref;
+    } else if (quiet && cur_eps != 1 && cur_slack) {
+        action = 1;
+        lower = cur_beta * cur_eps;
+    }
+    const bool stopping = cur_round + 1 >= cur_max_rounds || *errflag != 0;
+    if (blockIdx.x == 0 && tid == 0) {
+        SolverState ns = *st;
+        const int round = cur_round + 1;
+        if (quiet) {
+            if (ns.phases <= 28) ns.phase_round[ns.phases - 1] = round;
+            if (redo) {
+                ns.beta = cur_beta * 2;
+                ns.phases += 1;
+            } else if (cur_eps == 1) {
+                ns.done = 1;
+            } else {
+                ns.eps_prev = cur_eps;
+                long long ne = cur_eps / ns.eps_div;
+                ns.eps = ne > 1 ? ne : 1;
+                ns.phases += 1;
+            }
+        } else if (round >= ns.max_rounds) {
+            ns.status = MAXSCORE_ERR_NOT_CONVERGED;
+            ns.done = 1;
+        }
+        if (*errflag) {
+            ns.status = MAXSCORE_ERR_HIP;
+            ns.done = 1;
+        }
+        ns.round = round;
+        ns.tail_go = tail_go ? 1 : 0;
+        ns.tail_gos = cur_tail_gos + (tail_go ? 1 : 0);
+        ns.after_tail = 0;
+        ns.tail_block = 0;
+        *st_out = ns;
+    }
+    if (is_tail) {
+        // The other workgroups publish their candidate lists, thresholds, loads and the next state, then
+        // count themselves in (device-scope release); this one waits for all E of this hand-over
+        // (the counter is never reset: E per hand-over so far), drops its stale cache lines and runs the
+        // tail pass.  The wait is bounded; nothing the others do depends on this workgroup.
+        if (!tail_go || stopping) return;
+        if (tid == 0) {
+            const int target = (cur_tail_gos + 1) * E;
+            int spins = 0;
+            while (__hip_atomic_load(ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target &&
+                   ++spins < kTailSpinMax)
+                __builtin_amdgcn_s_sleep(8);
+            s_ok = spins < kTailSpinMax ? 1 : 0;
+        }
+        __syncthreads();
+        __threadfence();
+        if (!s_ok) {
+            if (tid == 0) *errflag = 1;       // reported as MAXSCORE_ERR_HIP by the next select pass
+            return;
+        }
+        tail_pass(q, assign, theta2, gcount2, st2, cand, errflag, par, T, E, k, Ce, tail_iters);
+        return;
+    }
+    long long new_theta = base;
+    const bool need_select = !tail_go && n > Ce;
+    const bool need_cand = tail_go;
+    if (need_select || need_cand) {
+        const bool cached = n <= kSelCache;
+        // Eight consecutive lanes share one segment (the keys one bid workgroup wrote for this expert,
+        // a few dozen bytes), so that one load instruction of a wavefront touches 8 cache lines
+        // instead of 64.
+        const int sub = tid & 7, grp8 = tid >> 3;
+        auto seg_meta = [&](int w) { return w < kSelThreads ? s_meta[w] : meta(w); };
+        if (cached) {
+            const int iters = (n_wg + 127) >> 7;
+            for (int it0 = 0; it0 < iters; it0 += 8) {
+                int cs[8];
+                long long kvv[8];
+                const long long *sp[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int w = grp8 + 128 * (it0 + u);
+                    cs[u] = 0;
+                    sp[u] = klist;
+                    if (w < n_wg) {
+                        const int mt = seg_meta(w);
+                        cs[u] = mt & 0xffff;
+                        sp[u] = klist + (size_t)w * blk_stride + (mt >> 16);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) kvv[u] = sub < cs[u] ? sp[u][sub] : 0;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (it0 + u < iters) {           // the same for the whole wavefront
+                        int inc = cs[u];             // all 8 lanes of a group hold their segment's count
+                        for (int off = 8; off < 64; off <<= 1) {
+                            int o = __shfl_up(inc, off);
+                            if (lane >= off) inc += o;
+                        }
+                        const int tot = __shfl(inc, 63);
+                        int bp = 0;
+                        if (lane == 63 && tot > 0) bp = atomicAdd(&s_fill, tot);
+                        bp = __shfl(bp, 63);
+                        const int gpos = bp + inc - cs[u];
+                        if (sub < cs[u]) s_keys[gpos + sub] = kvv[u];
+                        for (int i = sub + 8; i < cs[u]; i += 8) s_keys[gpos + i] = sp[u][i];
+                    }
+                }
+            }
+            __syncthreads();
+        }
+        MS_SP(1)
+        // visit every key of this expert (LDS copy when it fits, else the global segments)
+        auto for_keys = [&](auto fn) {
+            if (cached) {
+                for (int i = tid; i < n; i += kSelThreads) fn(s_keys[i]);
+            } else {
+                for (int w = grp8; w < n_wg; w += 128) {
+                    const int mt = seg_meta(w), c = mt & 0xffff;
+                    const long long *seg = klist + (size_t)w * blk_stride + (mt >> 16);
+                    for (int i = sub; i < c; i += 8) fn(seg[i]);
+                }
+            }
+        };
+        // key of 0-based rank `rank` in ascending order, by narrowing on u = key - base (>= 0: every key of this pass is at or above the old
+        // threshold): first the bit length of u (the keys crowd near the threshold with a long tail
+        // above, so equal-width digits from the top would separate little), then 8-bit digits below
+        // it, and as soon as at most kSelDirect keys share the prefix they are ranked directly.
+        // Wavefront 0 scans the histogram (4 bins per lane) while the others clear the next one.
+        auto nth_by_narrowing = [&](int rank) {
+            int hsel = 0;
+            for_keys([&](long long kv) {
+                const unsigned long long u = (unsigned long long)(kv - base);
+                atomicAdd(&s_hist[0][u ? 64 - __clzll((long long)u) : 0], 1);
+            });
+            __syncthreads();
+            MS_SP(2)
+            auto scan_find = [&](int h) {       // finds the bin holding `rank`; call from all threads
+                if (wv == 0) {
+                    const int4 b4 = *(const int4 *)&s_hist[h][lane * 4];
+                    const int sum = b4.x + b4.y + b4.z + b4.w;
+                    int hi = sum;
+                    for (int off = 1; off < 64; off <<= 1) {
+                        int o = __shfl_up(hi, off);
+                        if (lane >= off) hi += o;
+                    }
+                    const int exc = hi - sum;
+                    if (exc <= rank && rank < hi) {
+                        int r = rank - exc, d = 0, m = b4.x;
+                        if (r >= b4.x) { r -= b4.x; d = 1; m = b4.y;
+                            if (r >= b4.y) { r -= b4.y; d = 2; m = b4.z;
+                                if (r >= b4.z) { r -= b4.z; d = 3; m = b4.w; } } }
+                        s_d = lane * 4 + d;
+                        s_rank = r;
+                        s_m = m;
+                    }
+                } else if (tid - 64 < 256) {
+                    s_hist[h ^ 1][tid - 64] = 0;
+                }
+                __syncthreads();
+            };
+            scan_find(0);
+            MS_SP(3)
+            const int bl = s_d;                  // bit length of the wanted u
+            if (bl <= 1) return base + (long long)bl;     // u = 0 or u = 1
+            rank = s_rank;
+            int m = s_m, shift = bl - 1;         // bits below the leading one are still open
+            unsigned long long prefix = 1ull << shift, pmask = ~(prefix - 1);
+            while (m > kSelDirect && shift > 0) {
+                hsel ^= 1;
+                const int wd = shift < 8 ? shift : 8;
+                shift -= wd;
+                const unsigned dm = (1u << wd) - 1;
+                for_keys([&](long long kv) {
+                    const unsigned long long u = (unsigned long long)(kv - base);
+                    if ((u & pmask) == prefix) atomicAdd(&s_hist[hsel][(unsigned)(u >> shift) & dm], 1);
+                });
+                __syncthreads();
+                scan_find(hsel);
+                prefix |= (unsigned long long)s_d << shift;
+                pmask |= (unsigned long long)dm << shift;
+                rank = s_rank;
+                m = s_m;
+            }
+            MS_SP(4)
+            if (shift == 0) return base + (long long)prefix;
+            for_keys([&](long long kv) {
+                const unsigned long long u = (unsigned long long)(kv - base);
+                if ((u & pmask) == prefix) {
+                    const int slot = atomicAdd(&s_nsm, 1);
+                    if (slot < kSelDirect) s_small[slot] = u;
+                }
+            });
+            __syncthreads();
+            {   // four threads per listed key count the keys below it
+                const int el = tid >> 2, part = tid & 3;
+                int r = 0;
+                unsigned long long mine = 0;
+                if (el < m) {
+                    mine = s_small[el];
+                    for (int i = part; i < m; i += 4) r += s_small[i] < mine;
+                }
+                r += __shfl_xor(r, 1);
+                r += __shfl_xor(r, 2);
+                if (el < m && part == 0 && r == rank) s_res = mine;
+            }
+            __syncthreads();
+            const unsigned long long res = s_res;
+            __syncthreads();
+            if (tid == 0) s_nsm = 0;
+            MS_SP(5)
+            return base + (long long)res;
+        };
+        if (need_select) {
+            const int rank = n - Ce;   // 0-based rank of the new threshold among the keys, ascending
+            new_theta = nth_by_narrowing(rank);
+        } else {
+            // candidate list for the tail pass: the kCand smallest keys in ascending order, their
+            // count, and a bound no other key of this expert lies under
+            const long long bound = n > kCand ? nth_by_narrowing(kCand) : kKeyInf;
+            for_keys([&](long long kv) {
+                if (kv < bound) s_cl[atomicAdd(&s_ncl, 1)] = kv;
+            });
+            __syncthreads();
+            const int nc = s_ncl;            // = min(n, kCand): keys are distinct
+            long long *cj_out = cand + (size_t)j * (kCand + 2);
+            if (tid < nc) {
+                const long long mine = s_cl[tid];
+                int r = 0;
+                for (int i = 0; i < nc; ++i) r += s_cl[i] < mine;
+                cj_out[r] = mine;
+            }
+            if (tid == 0) {
+                cj_out[kCand] = nc;
+                cj_out[kCand + 1] = bound;
+            }
+        }
+    }
+    if (tid == 0) {
+        if (action) {
+            long long p = (new_theta >> cur_tbits) - lower;
+            new_theta = (p > 0 ? p : 0) << cur_tbits;
+        }
+        theta_out[j] = new_theta;
+    }
+    if (tail_go) {
+        __syncthreads();
+        if (tid == 0) {
+            __threadfence();                  // lists, threshold, load and (workgroup 0) the next state are out
+            atomicAdd(ready, 1);
+        }
+    }
+    MS_SP(6)
+#ifdef MS_SEL_PROF
+    if (tid == 0) g_selprof[j * 8 + 7] += 1;
+    if (tid == 0 && j == 0) { g_selwall[0] += wall_clock64() - c_w0; g_selwall[1] += clock64() - c_c0; }
+    if (tid == 0) atomicMax(&g_selround[cur_round & 1023], ((unsigned long long)(clock64() - c_c0) << 32) | ((unsigned)n << 8) | (need_select ? 1 : 0) | (need_cand ? 2 : 0));
+#endif
+}
+
 __global__ __launch_bounds__(256) void k_finalize(const int32_t *__restrict__ q, const int32_t *__restrict__ assign,
                                                   const long long *__restrict__ theta, SolverState *st,
                                                   int64_t *prices, int64_t *price_scale, int T, int E, int k)
@@ -1098,7 +1136,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     int *wcnt = (int *)(ws + L.wcnt_off);
     int *wmoves = (int *)(ws + L.wmoves_off);
     long long *cand = (long long *)(ws + L.cand_off);
-    int tail_on = E <= kTailMaxE ? 1 : 0, tail_iters = 256, tail_moves = kTailMoves;
+    int tail_on = E <= kTailMaxE ? 1 : 0, tail_iters = 64, tail_moves = kTailMoves;
     if (const char *ev = getenv("MAXSCORE_TAIL_MOVES")) tail_moves = atoi(ev);   // tuning override (debug)
     if (const char *ev = getenv("MAXSCORE_TAIL")) {   // tuning override (debug): 0 disables the tail pass
         tail_iters = atoi(ev);
@@ -1167,11 +1205,9 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             else MS_BID(64);
 #undef MS_BID
             if (g_kernel_timing) MS_HIP(hipEventRecord(tev.back(), s));
-            hipLaunchKernelGGL(k_select, dim3(E), dim3(kSelThreads), 0, s, klist, wcnt, wmoves, gcount, theta, st,
-                               qmm + 2, cand, par, T, E, k, Ce, n_wg, rows, tail_on, tail_moves);
-            if (tail_on)
-                hipLaunchKernelGGL(k_tail, dim3(1), dim3(kTailThreads), 0, s, q, assign, theta, gcount, st, cand,
-                                   qmm + 2, par, T, E, k, Ce, tail_iters);
+            hipLaunchKernelGGL(k_select, dim3(E + tail_on), dim3(kSelThreads), 0, s, klist, wcnt, wmoves, gcount, theta,
+                               st, qmm + 2, cand, q, assign, qmm + 3, par, T, E, k, Ce, n_wg, rows, tail_on,
+                               tail_moves, tail_iters);
             ++launched;
         }
         MS_HIP(hipMemcpyAsync(&h_done, &st[launched & 1].done, sizeof(int), hipMemcpyDeviceToHost, s));
