@@ -1181,11 +1181,19 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         hipLaunchKernelGGL(k_setup, dim3(1), dim3(1), 0, s, st, qmm, qmm + 1, T, E);
     }
 
+    // Rounds are enqueued in batches; after each batch the `done` flag is copied to pinned host memory.
+    // The next batch is always enqueued BEFORE the host waits for the flag of the current one, so the
+    // device never idles during the host round trip; once the solve is over the rounds still in the
+    // queue exit at once.
+    static thread_local int *tl_flags = nullptr;     // pinned, one flag per batch slot; lives until the process ends
+    if (!tl_flags) MS_HIP(hipHostMalloc((void **)&tl_flags, 64, hipHostMallocDefault));
     std::vector<hipEvent_t> tev;
-    const int batch = 8;
+    const int batch = 4;
     int launched = 0;
-    int h_done = 0;
-    while (!h_done) {
+    hipEvent_t evb[2] = {nullptr, nullptr};
+    MS_HIP(hipEventCreateWithFlags(&evb[0], hipEventDisableTiming));
+    MS_HIP(hipEventCreateWithFlags(&evb[1], hipEventDisableTiming));
+    auto enqueue_batch = [&](int slot) -> int32_t {
         for (int b = 0; b < batch; ++b) {
             const int par = launched & 1;
             if (g_kernel_timing) {
@@ -1210,9 +1218,24 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
                                tail_moves, tail_iters);
             ++launched;
         }
-        MS_HIP(hipMemcpyAsync(&h_done, &st[launched & 1].done, sizeof(int), hipMemcpyDeviceToHost, s));
-        MS_HIP(hipStreamSynchronize(s));
-        if (launched > o.max_rounds + 64) break;
+        MS_HIP(hipMemcpyAsync(&tl_flags[slot], &st[launched & 1].done, sizeof(int), hipMemcpyDeviceToHost, s));
+        MS_HIP(hipEventRecord(evb[slot], s));
+        return MAXSCORE_OK;
+    };
+    {
+        int cur = 0;
+        int32_t rc = enqueue_batch(cur);
+        while (rc == MAXSCORE_OK) {
+            const int launched_cur = launched;
+            rc = enqueue_batch(cur ^ 1);
+            if (rc != MAXSCORE_OK) break;
+            MS_HIP(hipEventSynchronize(evb[cur]));
+            if (tl_flags[cur] || launched_cur > o.max_rounds + 64) break;
+            cur ^= 1;
+        }
+        (void)hipEventDestroy(evb[0]);
+        (void)hipEventDestroy(evb[1]);
+        if (rc != MAXSCORE_OK) return rc;
     }
     const int fpar = launched & 1;
     hipLaunchKernelGGL(k_finalize, dim3(256), dim3(256), 0, s, q, assign, theta + fpar * kMaxE, st + fpar, prices,
