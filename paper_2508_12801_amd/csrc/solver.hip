@@ -421,6 +421,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
     const long long eps = st->eps, qmin = st->qmin;
     const int sb = st->sbits, tb = st->tbits;
     const long long tmask = ((long long)1 << tb) - 1;
+    const int eplt = (E + 63) >> 6;            // expert slots per lane actually in use
     for (int i = tid; i < E * (kCand + 2); i += kTailThreads) {
         const int e = i / (kCand + 2), c = i - e * (kCand + 2);
         const long long val = cand[i];
@@ -482,11 +483,11 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         // 2. one wavefront per dropped token: the bid pass's row evaluation
         const int nv = s_nv < kTailVict ? s_nv : kTailVict;
         for (int vi = wv; vi < nv; vi += kTailThreads / 64) {
-            const int tok = s_vtok[vi];
-            bool dup = false;          // a token challenged by several experts is evaluated once
-            for (int u = 0; u < vi; ++u) dup |= (s_vtok[u] == tok);
-            if (dup) continue;
-            int *qrow = s_qrow[wv];
+            const int tok = __builtin_amdgcn_readfirstlane(s_vtok[vi]);
+            // a token challenged by several experts at once is evaluated once, by its first entry
+            const unsigned long long twins = __ballot(lane < nv && lane != vi && s_vtok[lane] == tok);
+            if (twins & ((1ull << vi) - 1)) continue;
+            const int ve = __builtin_amdgcn_readfirstlane(s_vexp[vi]);
             const int32_t *qr = q + (size_t)tok * E;
             // other wavefronts of this workgroup may have rewritten the row in an earlier round: read
             // and write it at workgroup scope
@@ -495,7 +496,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                                 : -2;
             int qv[kTailEPL];
 #pragma unroll
-            for (int m = 0; m < kTailEPL; ++m) qv[m] = (lane + 64 * m < E) ? qr[lane + 64 * m] : 0;
+            for (int m = 0; m < kTailEPL; ++m) qv[m] = (m < eplt && lane + 64 * m < E) ? qr[lane + 64 * m] : 0;
 #ifdef MS_TAIL_PROF
             long long c_a = clock64();
 #endif
@@ -503,13 +504,13 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
             unsigned validm = 0, heldm = 0;
 #pragma unroll
             for (int m = 0; m < kTailEPL; ++m) {
-                const int e = lane + 64 * m;
-                if (e < E) {
-                    qrow[e] = qv[m];
-                    v[m] = (((long long)qv[m] - qmin) << sb) - (s_theta[e] >> tb);
-                    validm |= 1u << m;
-                } else {
-                    v[m] = 0;
+                v[m] = 0;
+                if (m < eplt) {
+                    const int e = lane + 64 * m;
+                    if (e < E) {
+                        v[m] = (((long long)qv[m] - qmin) << sb) - (s_theta[e] >> tb);
+                        validm |= 1u << m;
+                    }
                 }
             }
 #ifdef MS_TAIL_PROF
@@ -524,7 +525,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 unsigned long long b = 0;
 #pragma unroll
                 for (int m = 0; m < kTailEPL; ++m) {
-                    if (((validm & ~heldm) >> m) & 1u) {
+                    if (m < eplt && (((validm & ~heldm) >> m) & 1u)) {
                         int tieb = lane + 64 * m - r0;
                         if (tieb < 0) tieb += E;
                         unsigned long long pk =
@@ -534,9 +535,74 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 }
                 return wave_max_u64(b);
             };
+            auto expert_of = [&](unsigned long long pk) {
+                int e = 1023 - (int)(pk & 1023) + r0;
+                return e >= E ? e - E : e;
+            };
+            auto key_of = [&](long long sq, unsigned long long pk_alt) {
+                long long bid = pk_alt != 0 ? sq - ((long long)(pk_alt >> 10) - (long long)kVB) + eps : kBidBig;
+                bid = bid < kBidBig ? bid : kBidBig;
+                return bid * ((long long)1 << tb) + tok;
+            };
+            auto request = [&](int e, long long key) {       // one lane
+                if (key < s_bound[e]) {
+                    const int slot = atomicAdd(&s_ni, 1);
+                    if (slot < kTailIns) {
+                        s_iexp[slot] = e;
+                        s_ikey[slot] = key;
+                    } else {
+                        s_stop = 1;
+                    }
+                }
+            };
             unsigned long long pk = best_unheld();
-            bool has_alt = pk != 0;
-            long long a = (long long)(pk >> 10) - (long long)kVB;
+            if (!twins) {
+                // The usual case: one hold (tok, ve) is challenged.  Every other hold of the token is
+                // still valid (its listed key was not popped and true keys only rise), so only this
+                // one is decided, with wavefront-uniform arithmetic.
+                auto reward_of = [&](int e) {             // e is wavefront-uniform
+                    int r = 0;
+#pragma unroll
+                    for (int m = 0; m < kTailEPL; ++m)
+                        if ((e >> 6) == m) r = __builtin_amdgcn_readlane(qv[m], e & 63);
+                    return ((long long)r - qmin) << sb;
+                };
+                if (__ballot(my_e == ve) != 0) {           // still held (else there is nothing to decide)
+                    const long long key = key_of(reward_of(ve), pk);
+                    if (key >= s_theta[ve]) {
+                        if (lane == 0) request(ve, key);   // survives: back on the list with its true key
+                    } else {
+                        // falls below the threshold: the best expert not held takes the slot (ve itself
+                        // cannot be it: its value is now at least eps under that best one)
+                        const int e1 = __builtin_amdgcn_readfirstlane(expert_of(pk));
+                        if (pk == 0 || e1 >= E) {          // cannot happen while k <= E
+                            *errflag = 1;
+                        } else {
+                            if ((ve & 63) == lane) heldm &= ~(1u << (ve >> 6));
+                            if ((e1 & 63) == lane) heldm |= 1u << (e1 >> 6);
+                            const long long key1 = key_of(reward_of(e1), best_unheld());
+                            if (my_e == ve)
+                                __hip_atomic_store(&assign[(size_t)tok * k + lane], e1, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_WORKGROUP);
+                            if (lane == 0) {
+                                atomicAdd(&s_n[ve], -1);
+                                atomicAdd(&s_n[e1], 1);
+                                atomicAdd(&s_moves, 1);
+                                request(e1, key1);
+                            }
+                        }
+                    }
+                }
+#ifdef MS_TAIL_PROF
+                if (wv == 0) { long long c_c = clock64(); c_init += c_b - c_a; c_x += c_c - c_b; }
+#endif
+                continue;
+            }
+            // several holds of the token are challenged at once: the bid pass's general evaluation
+            int *qrow = s_qrow[wv];
+#pragma unroll
+            for (int m = 0; m < kTailEPL; ++m)
+                if (m < eplt && lane + 64 * m < E) qrow[lane + 64 * m] = qv[m];
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -544,33 +610,36 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
             bool dropped = false;
             if (my_e >= 0) {
                 my_sq = ((long long)qrow[my_e] - qmin) << sb;
-                long long bid = has_alt ? my_sq - a + eps : kBidBig;
-                long long key = bid * ((long long)1 << tb) + tok;
-                if (key < s_theta[my_e]) {
+                if (key_of(my_sq, pk) < s_theta[my_e]) {
                     dropped = true;
                     atomicAdd(&s_n[my_e], -1);
                 }
             }
-            // dropped experts become candidates again
-            {
-                unsigned long long db = __ballot(dropped);
-                while (db) {
+            bool challenged = my_e == ve;      // a challenged hold that survives goes back on its list
+            if (my_e >= 0) {
+                unsigned long long tw = twins;
+                while (tw) {
+                    const int u = __ffsll((long long)tw) - 1;
+                    tw &= tw - 1;
+                    challenged |= s_vexp[u] == my_e;
+                }
+            }
+            unsigned long long db = __ballot(dropped);
+            const int f = __popcll(db);
+            bool picked = false;
+            if (f > 0) {
+                const unsigned long long fb = db;
+                while (db) {                           // dropped experts become candidates again
                     const int sl = __ffsll((long long)db) - 1;
                     db &= db - 1;
                     const int es = __builtin_amdgcn_readlane(my_e, sl);
                     if ((es & 63) == lane) heldm &= ~(1u << (es >> 6));
                 }
-            }
-            if (dropped) my_e = -1;
-            const unsigned long long fb = __ballot(my_e == -1);
-            const int f = __popcll(fb);
-            bool picked = false;
-            if (f > 0) {
-                const int my_rank = (my_e == -1) ? __popcll(fb & ((1ull << lane) - 1)) : -1;
+                if (dropped) my_e = -1;
+                const int my_rank = dropped ? __popcll(fb & ((1ull << lane) - 1)) : -1;
                 for (int r = 0; r < f; ++r) {
                     pk = best_unheld();
-                    int e = 1023 - (int)(pk & 1023) + r0;
-                    if (e >= E) e -= E;
+                    int e = expert_of(pk);
                     if (pk == 0 || e >= E) {
                         e = 0;
                         *errflag = 1;
@@ -583,36 +652,18 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                     }
                 }
                 pk = best_unheld();
-                has_alt = pk != 0;
-                a = (long long)(pk >> 10) - (long long)kVB;
                 if (lane == 0) atomicAdd(&s_moves, f);
             }
-            if (lane < k && my_e >= 0) {
-                long long bid = has_alt ? my_sq - a + eps : kBidBig;
-                bid = bid < kBidBig ? bid : kBidBig;
-                const long long key = bid * ((long long)1 << tb) + tok;
-                bool challenged = false;   // kept a hold it was challenged on: the key goes back on the list
-                if (!picked)
-                    for (int u = 0; u < nv; ++u) challenged |= (s_vtok[u] == tok && s_vexp[u] == my_e);
+            if (lane < k && my_e >= 0 && (picked || challenged)) {
+                const long long key = key_of(my_sq, pk);
                 if (picked) {
                     __hip_atomic_store(&assign[(size_t)tok * k + lane], my_e, __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_WORKGROUP);
                     atomicAdd(&s_n[my_e], 1);
                 }
-                if ((picked || challenged) && key < s_bound[my_e]) {
-                    const int slot = atomicAdd(&s_ni, 1);
-                    if (slot < kTailIns) {
-                        s_iexp[slot] = my_e;
-                        s_ikey[slot] = key;
-                    } else {
-                        s_stop = 1;
-                    }
-                }
+                request(my_e, key);
             }
             __builtin_amdgcn_wave_barrier();
-#ifdef MS_TAIL_PROF
-            if (wv == 0) { long long c_c = clock64(); c_init += c_b - c_a; c_x += c_c - c_b; }
-#endif
         }
 #ifdef MS_TAIL_PROF
         long long c_d = clock64();
