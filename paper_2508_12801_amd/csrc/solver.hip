@@ -153,7 +153,10 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
     __shared__ int s_cnt[EP];
     __shared__ int s_off[EP];
     __shared__ int s_wtot[4];
-    __shared__ __attribute__((aligned(16))) int s_q[NG * EP];
+    // staged rows: one padding word after every lane's EPL values and G after every row, so that the
+    // 64 lanes of a store spread over all LDS banks (lane stride EPL+1 is odd)
+    constexpr int SQ_ROW = EP + G;
+    __shared__ int s_q[NG * SQ_ROW];
     __shared__ long long s_key[1024];
     __shared__ short s_exp[1024];
     __shared__ short s_pos[1024];
@@ -164,7 +167,8 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
     const int grp = tid / G;
     const int row0 = blockIdx.x * rows_per_wg;
     const unsigned long long gmask = (G == 64) ? ~0ull : (((1ull << G) - 1) << gbase);
-    int *sq = s_q + grp * EP;
+    int *sq = s_q + grp * SQ_ROW;
+    auto sq_at = [&](int e) { return e + (e >> LOGP); };
 
     // the first row of every group is requested before anything else
     int qn[EPL];
@@ -221,7 +225,7 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
 
         // stage the raw rewards of the row for the slot lanes
 #pragma unroll
-        for (int m = 0; m < EPL; ++m) sq[lg * EPL + m] = qc[m];
+        for (int m = 0; m < EPL; ++m) sq[lg * (EPL + 1) + m] = qc[m];
 
         long long v[EPL];
 #pragma unroll
@@ -262,7 +266,7 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
         const int was_e = my_e;
         bool dropped = false;
         if (my_e >= 0) {
-            my_sq = ((long long)sq[my_e] - qmin) << sb;
+            my_sq = ((long long)sq[sq_at(my_e)] - qmin) << sb;
             long long bid = has_alt ? my_sq - a + eps : kBidBig;
             long long key = bid * ((long long)1 << tb) + row;
             if (key < s_theta[my_e]) {
