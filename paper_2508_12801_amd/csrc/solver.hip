@@ -39,6 +39,7 @@ int g_kernel_timing = 0;
 namespace {
 
 constexpr unsigned long long kVB = 1ull << 52;  // bias that makes packed values unsigned
+constexpr long long kNarrowPrice = (long long)1 << 29;   // prices below this (and a reward range below 2^28/S) fit 32-bit values
 
 __device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int off)
 {
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(256) void k_minmax(const int32_t *__restrict__ q, s
     }
 }
 
-__global__ void k_setup(SolverState *st, const int *qmin, const int *qmax, int T, int E)
+__global__ void k_setup(SolverState *st, const int *qmin, const int *qmax, int T, int E, int force_wide)
 {
     st->qmin = *qmin;
     st->qmax = *qmax;
@@ -129,6 +130,9 @@ __global__ void k_setup(SolverState *st, const int *qmin, const int *qmax, int T
         st->status = MAXSCORE_ERR_RANGE;
         st->done = 1;
     }
+    // values S*(q - qmin) - price fit 32 bits unless the range is this wide or a token can be left
+    // without any alternative (k = E: bids of kBidBig)
+    st->wide = (range >= ((long long)1 << 28) || force_wide) ? 1 : 0;
     long long top = range >> 4, eps = 1;
     while (eps * st->eps_div <= top) eps *= st->eps_div;
     st->eps = eps;
@@ -139,7 +143,7 @@ __global__ void k_setup(SolverState *st, const int *qmin, const int *qmax, int T
 // 64/G rows at once and its loads of consecutive rows are contiguous.  The next row of each group
 // is prefetched into registers while the current one is evaluated.
 template <int G, int EPL, bool VEC>
-__global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int32_t *__restrict__ assign,
+__global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, int32_t *__restrict__ assign,
                                              const long long *__restrict__ theta, const SolverState *__restrict__ st,
                                              long long *__restrict__ klist, int *__restrict__ wcnt,
                                              int *__restrict__ wmoves, int *__restrict__ errflag, int T, int E, int k,
@@ -156,11 +160,13 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
     // staged rows: one padding word after every lane's EPL values and G after every row, so that the
     // 64 lanes of a store spread over all LDS banks (lane stride EPL+1 is odd)
     constexpr int SQ_ROW = EP + G;
-    __shared__ int s_q[NG * SQ_ROW];
+    constexpr int SQ_WORDS = NG * SQ_ROW > 2048 ? NG * SQ_ROW : 2048;   // doubles as the sorted key block (1024 keys)
+    __shared__ __attribute__((aligned(16))) int s_q[SQ_WORDS];
     __shared__ long long s_key[1024];
     __shared__ short s_exp[1024];
     __shared__ short s_pos[1024];
-    __shared__ int s_moves;
+    __shared__ short s_queue[1024];
+    __shared__ int s_moves, s_nq;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, lg = lane & (G - 1), gbase = lane & ~(G - 1);
@@ -170,7 +176,6 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
     int *sq = s_q + grp * SQ_ROW;
     auto sq_at = [&](int e) { return e + (e >> LOGP); };
 
-    // the first row of every group is requested before anything else
     int qn[EPL];
     int an = -2;
     auto load_row = [&](int row) {
@@ -194,35 +199,43 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
         }
         an = (lg < k) ? assign[(size_t)row * k + lg] : -2;
     };
-    if (row0 + grp < T && grp < rows_per_wg) load_row(row0 + grp);
-
+    // thresholds and state are requested first (the barrier below waits for them), then the first row
+    // of every group
     const long long eps = st->eps, qmin = st->qmin;
     const int sb = st->sbits, tb = st->tbits;
     for (int e = tid; e < EP; e += 256) {
         s_theta[e] = e < E ? theta[e] : 0;
         s_cnt[e] = 0;
     }
-    if (tid == 0) s_moves = 0;
+    if (tid == 0) {
+        s_moves = 0;
+        s_nq = 0;
+    }
+    if (row0 + grp < T && grp < rows_per_wg) load_row(row0 + grp);
     __syncthreads();
 
     long long p[EPL];
     unsigned validm = 0;
+    bool high = false;
 #pragma unroll
     for (int m = 0; m < EPL; ++m) {
         int e = lg * EPL + m;
         p[m] = s_theta[e] >> tb;
+        high |= p[m] >= kNarrowPrice;
         if (e < E) validm |= 1u << m;
     }
+    // Quick check of a row (most rows of most rounds): when rewards and prices are small enough for
+    // 32-bit values (the state says the reward range is, and every wavefront sees all prices, so all
+    // take the same branch), and few tokens moved in the previous round, a group first computes only
+    // the VALUE of its row's best expert not held, which is all the keys of an unchanged row need.
+    // If every hold of the row is still valid the keys are emitted; otherwise the row is queued and
+    // gets the full evaluation afterwards, which recomputes everything.
+    const bool quick = E == EP && st->round > 0 && !st->wide && __ballot(high) == 0 && (long long)st->moves * 4 < T;
+    const int qmin32 = (int)qmin;
 
-    for (int lr = grp; lr < rows_per_wg; lr += NG) {
+    // Full evaluation of one row by its group (lanes of other groups may be inactive).
+    auto full_row = [&](const int lr, const int(&qc)[EPL], int my_e) {
         const int row = row0 + lr;
-        if (row >= T) break;
-        int qc[EPL];
-#pragma unroll
-        for (int m = 0; m < EPL; ++m) qc[m] = qn[m];
-        int my_e = an;
-        if (lr + NG < rows_per_wg && row + NG < T) load_row(row + NG);
-
         // stage the raw rewards of the row for the slot lanes
 #pragma unroll
         for (int m = 0; m < EPL; ++m) sq[lg * (EPL + 1) + m] = qc[m];
@@ -316,7 +329,94 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
             s_exp[idx] = (short)my_e;
             s_pos[idx] = (short)pos;
         }
-        __builtin_amdgcn_wave_barrier();   // the next row reuses this group's staging buffer
+    };
+
+    if (quick) {
+        // pass 1: value-only check of every row; rows with a hold to drop or a slot to fill are queued
+        for (int lr = grp; lr < rows_per_wg; lr += NG) {
+            const int row = row0 + lr;
+            if (row >= T) break;
+            int qc[EPL];
+#pragma unroll
+            for (int m = 0; m < EPL; ++m) qc[m] = qn[m];
+            const int my_e = an;
+            if (lr + NG < rows_per_wg && row + NG < T) load_row(row + NG);
+            // u = q - qmin (>= 0, < 2^28 / S) is staged; slot lanes fetch the u of their expert and
+            // then blank it, so that the re-read row holds only experts not held
+            constexpr int kBlank = -(1 << 30);
+#pragma unroll
+            for (int m = 0; m < EPL; ++m) sq[lg * (EPL + 1) + m] = qc[m] - qmin32;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            int my_u = 0;
+            if (my_e >= 0) my_u = sq[sq_at(my_e)];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (my_e >= 0) sq[sq_at(my_e)] = kBlank >> sb;      // (blank << sb) - price stays above -2^31
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            int bv = -0x7fffffff - 1;
+#pragma unroll
+            for (int m = 0; m < EPL; ++m) {
+                const int vv = (int)((unsigned)sq[lg * (EPL + 1) + m] << sb) - (int)p[m];   // E == EP: no padding experts
+                bv = vv > bv ? vv : bv;
+            }
+#pragma unroll
+            for (int off = G / 2; off > 0; off >>= 1) {
+                const int o = __shfl_xor(bv, off);
+                bv = o > bv ? o : bv;
+            }
+            bool bad = false;
+            long long qkey = 0;
+            if (lg < k) {
+                bad = my_e < 0;
+                if (!bad) {
+                    long long bid = ((long long)my_u << sb) - (long long)bv + eps;
+                    bid = bid < kBidBig ? bid : kBidBig;
+                    qkey = bid * ((long long)1 << tb) + row;
+                    bad = qkey < s_theta[my_e];
+                }
+            }
+            if ((__ballot(bad) & gmask) == 0) {
+                if (lg < k) {
+                    int pos = atomicAdd(&s_cnt[my_e], 1);
+                    int idx = lr * k + lg;
+                    s_key[idx] = qkey;
+                    s_exp[idx] = (short)my_e;
+                    s_pos[idx] = (short)pos;
+                }
+            } else if (lg == 0) {
+                s_queue[atomicAdd(&s_nq, 1)] = (short)lr;
+            }
+            __builtin_amdgcn_wave_barrier();   // the next row reuses this group's staging buffer
+        }
+        __syncthreads();
+        // pass 2: the queued rows, compacted over the groups, get the full evaluation
+        const int nq = s_nq;
+        for (int qi = grp; qi < nq; qi += NG) {
+            const int lr = s_queue[qi];
+            load_row(row0 + lr);
+            int qc[EPL];
+#pragma unroll
+            for (int m = 0; m < EPL; ++m) qc[m] = qn[m];
+            full_row(lr, qc, an);
+            __builtin_amdgcn_wave_barrier();   // the next row reuses this group's staging buffer
+        }
+    } else {
+        for (int lr = grp; lr < rows_per_wg; lr += NG) {
+            const int row = row0 + lr;
+            if (row >= T) break;
+            int qc[EPL];
+#pragma unroll
+            for (int m = 0; m < EPL; ++m) qc[m] = qn[m];
+            const int my_e = an;
+            if (lr + NG < rows_per_wg && row + NG < T) load_row(row + NG);
+            full_row(lr, qc, my_e);
+            __builtin_amdgcn_wave_barrier();   // the next row reuses this group's staging buffer
+        }
     }
     __syncthreads();
     // The keys of this workgroup are stored sorted by expert in one contiguous block of the key
@@ -355,10 +455,14 @@ __global__ __launch_bounds__(256) void k_bid(const int32_t *__restrict__ q, int3
     rows_here = rows_here < rows_per_wg ? rows_here : rows_per_wg;
     const int nslots = rows_here * k;
     long long *blk = klist + (size_t)blockIdx.x * rows_per_wg * k;
+    // sorted inside LDS first (the row staging buffer is free by now), then copied out in order
+    long long *s_sorted = (long long *)s_q;
     for (int idx = tid; idx < nslots; idx += 256) {
         const int e = s_exp[idx];
-        blk[s_off[e] + s_pos[idx]] = s_key[idx];
+        s_sorted[s_off[e] + s_pos[idx]] = s_key[idx];
     }
+    __syncthreads();
+    for (int idx = tid; idx < nslots; idx += 256) blk[idx] = s_sorted[idx];
 }
 
 // Tail pass: when a bid pass moved only a few slots, one workgroup continues the same auction on the
@@ -892,6 +996,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             ns.done = 1;
         }
         ns.round = round;
+        ns.moves = moves;
         ns.tail_go = tail_go ? 1 : 0;
         ns.tail_gos = cur_tail_gos + (tail_go ? 1 : 0);
         ns.after_tail = 0;
@@ -1233,7 +1338,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         if (g2 > 1024) g2 = 1024;
         if (g2 < 1) g2 = 1;
         hipLaunchKernelGGL(k_minmax, dim3(g2), dim3(256), 0, s, q, nq, qmm, qmm + 1);
-        hipLaunchKernelGGL(k_setup, dim3(1), dim3(1), 0, s, st, qmm, qmm + 1, T, E);
+        hipLaunchKernelGGL(k_setup, dim3(1), dim3(1), 0, s, st, qmm, qmm + 1, T, E, k == E ? 1 : 0);
     }
 
     // Rounds are enqueued in batches; after each batch the `done` flag is copied to pinned host memory.
