@@ -827,6 +827,17 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         gcur[e] = s_n[e];
     }
     if (tid == 0) {
+        // Ended with nothing over capacity: every hold is valid, the phase is quiescent.  Without slack
+        // there is no price lowering to decide, so the next round starts the next phase right away
+        // (the last phase still gets its full check by a bid pass).
+        if (!s_stop && !s_over && !st->slack && st->eps > 1) {
+            if (st->phases <= 28) st->phase_round[st->phases - 1] = st->round;
+            st->eps_prev = st->eps;
+            const long long ne = st->eps / st->eps_div;
+            st->eps = ne > 1 ? ne : 1;
+            st->phases += 1;
+            st->moves = T;
+        }
         st->after_tail = (s_changed || s_moves) ? 1 : 0;
         st->tail_block = s_stop;
         st->tail_go = 0;
@@ -915,7 +926,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
         ov += c > Ce;
         vi += (c < Ce && theta_in[e] > 0);
     }
-    const int cur_round = st->round, cur_slack = st->slack, cur_tbits = st->tbits, cur_after_tail = st->after_tail,
+    const int cur_round = st->round, cur_slack = st->slack, cur_tbits = st->tbits,
               cur_tail_block = st->tail_block, cur_tail_gos = st->tail_gos, cur_max_rounds = st->max_rounds;
     const long long cur_eps = st->eps, cur_eps_prev = st->eps_prev, cur_beta = st->beta;
     const long long base = theta_in[j];
@@ -954,7 +965,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
 
     // the decision every thread of every block takes identically: nothing moved in this bid pass and
     // no expert was above capacity after the previous one  =>  the phase is quiescent
-    const bool quiet = (moves == 0 && (flags & 2) == 0 && cur_round > 0 && !cur_after_tail);
+    const bool quiet = (moves == 0 && (flags & 2) == 0 && cur_round > 0);
     const bool redo = quiet && cur_slack && (flags & 4);
     const long long eps_ref = cur_eps_prev > 0 ? cur_eps_prev : cur_eps;
     // few slots moved: leave the thresholds alone, publish each expert's lowest keys and let the
@@ -996,7 +1007,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             ns.done = 1;
         }
         ns.round = round;
-        ns.moves = moves;
+        ns.moves = quiet ? T : moves;        // a new phase starts with many moves: no quick checks in its first round
         ns.tail_go = tail_go ? 1 : 0;
         ns.tail_gos = cur_tail_gos + (tail_go ? 1 : 0);
         ns.after_tail = 0;
