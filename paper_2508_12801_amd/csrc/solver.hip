@@ -1048,14 +1048,15 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
         const int sub = tid & 7, grp8 = tid >> 3;
         auto seg_meta = [&](int w) { return w < kSelThreads ? s_meta[w] : meta(w); };
         if (cached) {
-            const int iters = (n_wg + 127) >> 7;
+            constexpr int kSegGroups = kSelThreads / 8;
+            const int iters = (n_wg + kSegGroups - 1) / kSegGroups;
             for (int it0 = 0; it0 < iters; it0 += 8) {
                 int cs[8];
                 long long kvv[8];
                 const long long *sp[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    const int w = grp8 + 128 * (it0 + u);
+                    const int w = grp8 + kSegGroups * (it0 + u);
                     cs[u] = 0;
                     sp[u] = klist;
                     if (w < n_wg) {
@@ -1092,7 +1093,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             if (cached) {
                 for (int i = tid; i < n; i += kSelThreads) fn(s_keys[i]);
             } else {
-                for (int w = grp8; w < n_wg; w += 128) {
+                for (int w = grp8; w < n_wg; w += kSelThreads / 8) {
                     const int mt = seg_meta(w), c = mt & 0xffff;
                     const long long *seg = klist + (size_t)w * blk_stride + (mt >> 16);
                     for (int i = sub; i < c; i += 8) fn(seg[i]);
@@ -1169,16 +1170,17 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                 }
             });
             __syncthreads();
-            {   // four threads per listed key count the keys below it
-                const int el = tid >> 2, part = tid & 3;
+            {   // a few threads per listed key count the keys below it
+                constexpr int kParts = kSelThreads / kSelDirect;
+                const int el = tid / kParts, part = tid % kParts;
                 int r = 0;
                 unsigned long long mine = 0;
                 if (el < m) {
                     mine = s_small[el];
-                    for (int i = part; i < m; i += 4) r += s_small[i] < mine;
+                    for (int i = part; i < m; i += kParts) r += s_small[i] < mine;
                 }
-                r += __shfl_xor(r, 1);
-                r += __shfl_xor(r, 2);
+#pragma unroll
+                for (int off = 1; off < kParts; off <<= 1) r += __shfl_xor(r, off);
                 if (el < m && part == 0 && r == rank) s_res = mine;
             }
             __syncthreads();
