@@ -1,0 +1,133 @@
+"""GPU parity of the assignment step (a4) on the solver's different code paths: 32-bit quick checks and
+64-bit full evaluation, with and without the tail pass, zero slack and slack capacity, several seeds,
+and the error statuses.  Every optimum is compared bit for bit with the CPU checker's."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from workloads import CONFIGS, capacity, make_logits
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def ms():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2508_12801_amd as m
+    m.load_library()
+    return m
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def solve_and_check(ms, q64, k, C, **kw):
+    T, E = q64.shape
+    out = ms.assign_i32(dev(q64.astype(np.int32)), k, C, **kw)
+    a = out["assign"].cpu().numpy()
+    P = oracle.assignment_matrix(a, E)
+    ok, why = oracle.check_feasible(P, k, C)
+    assert ok, why
+    total = int(q64[P.astype(bool)].sum())
+    ref = oracle.max_score_assignment(q64, k, C)
+    assert out["stats"]["status"] == 0 and out["stats"]["total_score_q"] == total
+    assert int(P.sum()) == ref["flow"] and total == ref["total"], (total, ref["total"], out["stats"])
+    return out
+
+
+def skewed_rewards(rng, T, E, hi_bits):
+    """Softmax-like rows with popular experts, scaled to integers below 2^hi_bits."""
+    L = rng.normal(size=(T, E)) + 2.0 * rng.normal(size=(1, E))
+    p = np.exp(L - L.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    return np.rint(p * ((1 << hi_bits) - 1)).astype(np.int64)
+
+
+# reward range below / at / above the point where S * range stops fitting the 32-bit value path
+# (S = 128 for E = 64: 2^28 / S = 2^21), zero slack (T*k = E*C) and slack capacity
+@pytest.mark.parametrize("hi_bits", [12, 20, 21, 22, 27])
+@pytest.mark.parametrize("slack", [False, True])
+def test_value_width_paths(ms, hi_bits, slack):
+    print(f"value_width hi_bits={hi_bits} slack={slack}", flush=True)
+    T, E, k = 2048, 64, 4
+    C = T * k // E + (7 if slack else 0)
+    q = skewed_rewards(np.random.default_rng(hi_bits + 100 * slack), T, E, hi_bits)
+    solve_and_check(ms, q, k, C)
+
+
+@pytest.mark.parametrize("E,k,T", [(512, 4, 4096), (320, 6, 1280), (1024, 2, 2048)])
+def test_many_experts_without_tail_pass(ms, E, k, T):
+    print(f"many_experts E={E} k={k} T={T}", flush=True)
+    C = T * k // E
+    q = skewed_rewards(np.random.default_rng(E + k), T, E, 18)
+    solve_and_check(ms, q, k, C)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+@pytest.mark.parametrize("name,T", [("cfg5", 8192), ("cfg3", 4096)])
+def test_config_seeds(ms, name, T, seed):
+    print(f"config_seeds {name} T={T} seed={seed}", flush=True)
+    cfg = CONFIGS[name]
+    L = make_logits(name, seed=seed, T=T)
+    E, k = cfg["E"], cfg["k"]
+    C = capacity(T, E, k, cfg["C"] * E / (cfg["T"] * k))
+    q = oracle.quantise(oracle.soft_topk(L, k, cfg["t"]))
+    solve_and_check(ms, q, k, C)
+
+
+def test_same_input_same_output(ms):
+    print("determinism", flush=True)
+    q = skewed_rewards(np.random.default_rng(5), 4096, 128, 20)
+    qd = dev(q.astype(np.int32))
+    a = ms.assign_i32(qd, 8, 256)
+    b = ms.assign_i32(qd, 8, 256)
+    assert torch.equal(a["assign"], b["assign"]) and torch.equal(a["prices"], b["prices"])
+    assert a["stats"]["rounds"] == b["stats"]["rounds"]
+
+
+@pytest.mark.parametrize("eps_div", [2, 5, 64])
+def test_eps_schedule_does_not_change_the_optimum(ms, eps_div):
+    print(f"eps_div {eps_div}", flush=True)
+    q = skewed_rewards(np.random.default_rng(9), 1024, 32, 20)
+    solve_and_check(ms, q, 4, 128, eps_div=eps_div)
+
+
+def test_round_cap_reports_not_converged(ms):
+    print("round_cap", flush=True)
+    q = skewed_rewards(np.random.default_rng(11), 4096, 64, 20)
+    out = ms.assign_i32(dev(q.astype(np.int32)), 8, 512, max_rounds=3, allow_not_converged=True)
+    assert out["rc"] == -8 and out["stats"]["status"] == -8 and out["stats"]["rounds"] <= 3
+    with pytest.raises(ms.MaxScoreError):
+        ms.assign_i32(dev(q.astype(np.int32)), 8, 512, max_rounds=3)
+
+
+def test_reward_range_too_wide_is_an_error(ms):
+    print("range_error", flush=True)
+    q = np.zeros((64, 1000), dtype=np.int64)          # S = 1024: range * S reaches 2^38 at 2^28
+    q[0, 0] = 1 << 29
+    with pytest.raises(ms.MaxScoreError) as e:
+        ms.assign_i32(dev(q.astype(np.int32)), 2, 64)
+    assert e.value.code == -7
+
+
+def test_tail_pass_switch_gives_the_same_optimum(ms):
+    """The debug switch that turns the tail pass off must not change the total (different, equally optimal
+    assignments are allowed)."""
+    print("tail_switch", flush=True)
+    q = skewed_rewards(np.random.default_rng(13), 4096, 64, 20)
+    qd = dev(q.astype(np.int32))
+    with_tail = ms.assign_i32(qd, 8, 512)
+    os.environ["MAXSCORE_TAIL"] = "0"
+    try:
+        without = ms.assign_i32(qd, 8, 512)
+    finally:
+        del os.environ["MAXSCORE_TAIL"]
+    assert with_tail["stats"]["total_score_q"] == without["stats"]["total_score_q"]
+    ref = oracle.max_score_assignment(q, 8, 512)["total"]
+    assert with_tail["stats"]["total_score_q"] == ref
