@@ -140,7 +140,11 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic() if args.config == "cfg5" else None,
                      "bytes_per_launch": bid_bytes, "launch_ms": bid_launch_ms,
-                     "launches_per_call": st["bid_launches"], "copy_kernel_GBs": copy_gbs},
+                     "launches_per_call": st["bid_launches"], "copy_kernel_GBs": copy_gbs,
+                     "share_of_solver_time": st["bid_ms"] / max(st["solver_ms"], 1e-9),
+                     "note": "the bid pass is the solver's bandwidth-bound kernel; the select pass (with the "
+                             "tail pass in its extra workgroup) takes the rest of the solver time and is "
+                             "latency-bound: it has no bandwidth roofline"},
         "stages_ms": {"router_gemm": gemm_ms, "softtopk_quantise": soft_ms, "assignment": st["solver_ms"],
                       "gates": gates_ms, "dispatch": disp_ms,
                       "gemm_hbm_frac": (T * d * 2 + d * E * 2 + T * E * 4) / (gemm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
