@@ -13,19 +13,26 @@
 //         held experts that violate the eps condition or fell below the expert's threshold,
 //         refills its free slots with its best experts and emits one bid key per held expert,
 //         (S*q_ij - w_i + eps) * 2^tbits + i, where w_i is its best value among experts it does
-//         not hold.  Keys are appended to a per-expert list.
+//         not hold.  Rows that turn out unchanged are recognised by a cheap value-only check; only
+//         the others get the full evaluation.  Each workgroup writes its keys as one block sorted
+//         by expert.
 //       select pass (k_select): every expert holding more than C keys raises its threshold to
-//         the (n-C+1)-th smallest key (exact radix select), which makes the n-C weakest holders
+//         the (n-C+1)-th smallest key (exact selection), which makes the n-C weakest holders
 //         drop in the next bid pass.  The expert's price is threshold >> tbits.
 //   * Phases run eps = eps0, eps0/div, ..., 1; prices carry over.  When capacity is slack
 //     (T*k < E*C) prices are lowered by beta*eps_prev (clamped at 0) at each phase start, and a
 //     phase that ends with an unfilled expert at a positive price is repeated with beta doubled,
 //     so the final state always has price 0 on unfilled experts.
+//   * When a round moves only a handful of slots, the select pass publishes each expert's lowest
+//     keys instead of selecting, and one extra workgroup of the same launch continues the auction
+//     on these lists alone (the tail pass) until nothing is over capacity, a list runs out or a
+//     hop limit is reached; the next bid pass re-validates every token.
 //   * Control is on the device.  State, thresholds and per-expert loads are double-buffered by
 //     round parity; every block of the select pass recomputes the same decision (quiescence,
 //     phase change, price lowering, done) from the previous round's loads and this round's move
-//     counts, so no block waits for another and no device-wide fence is needed.  The host only
-//     enqueues rounds and polls `done`.
+//     counts, so no block waits for another (only the tail workgroup waits, for the candidate
+//     lists, in the few rounds that hand over to it).  The host enqueues rounds ahead of the
+//     device and polls `done` from pinned memory.
 #include <cstdio>
 #include <cstdlib>
 #include <vector>
