@@ -46,6 +46,7 @@ int g_kernel_timing = 0;
 namespace {
 
 constexpr unsigned long long kVB = 1ull << 52;  // bias that makes packed values unsigned
+constexpr int kEps0Shift = 8;              // the first phase runs at eps0 <= S * range / 2^8
 constexpr long long kNarrowPrice = (long long)1 << 29;   // prices below this (and a reward range below 2^28/S) fit 32-bit values
 
 __device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int off)
@@ -122,7 +123,8 @@ __global__ __launch_bounds__(256) void k_minmax(const int32_t *__restrict__ q, s
     }
 }
 
-__global__ void k_setup(SolverState *st, const int *qmin, const int *qmax, int T, int E, int force_wide)
+__global__ void k_setup(SolverState *st, const int *qmin, const int *qmax, int T, int E, int force_wide,
+                        int eps0_shift)
 {
     st->qmin = *qmin;
     st->qmax = *qmax;
@@ -140,7 +142,7 @@ __global__ void k_setup(SolverState *st, const int *qmin, const int *qmax, int T
     // values S*(q - qmin) - price fit 32 bits unless the range is this wide or a token can be left
     // without any alternative (k = E: bids of kBidBig)
     st->wide = (range >= ((long long)1 << 28) || force_wide) ? 1 : 0;
-    long long top = range >> 4, eps = 1;
+    long long top = range >> eps0_shift, eps = 1;
     while (eps * st->eps_div <= top) eps *= st->eps_div;
     st->eps = eps;
 }
@@ -482,6 +484,9 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
 // stops when nothing is over capacity, when a list runs out or after max_iters rounds; the next bid
 // pass re-validates every token, so this pass only has to make valid moves, not complete ones.
 constexpr int kTailThreads = 1024;
+#ifdef MS_TAIL_PROF
+__device__ int g_tailstat[8];
+#endif
 constexpr int kTailMoves = 16;            // hand over to the tail pass when a bid pass moved this few slots
 constexpr long long kKeyInf = (long long)1 << 62;
 constexpr int kTailSpinMax = 1 << 20;     // polls of the tail workgroup for the candidate lists before it gives up
@@ -686,6 +691,9 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                     const long long key = key_of(reward_of(ve), pk);
                     if (key >= s_theta[ve]) {
                         if (lane == 0) request(ve, key);   // survives: back on the list with its true key
+#ifdef MS_TAIL_PROF
+                        if (lane == 0) atomicAdd(&g_tailstat[nv == 1 ? 0 : 2], 1);
+#endif
                     } else {
                         // falls below the threshold: the best expert not held takes the slot (ve itself
                         // cannot be it: its value is now at least eps under that best one)
@@ -704,6 +712,9 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                                 atomicAdd(&s_n[e1], 1);
                                 atomicAdd(&s_moves, 1);
                                 request(e1, key1);
+#ifdef MS_TAIL_PROF
+                                atomicAdd(&g_tailstat[nv == 1 ? 1 : 3], 1);
+#endif
                             }
                         }
                     }
@@ -1358,7 +1369,9 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         if (g2 > 1024) g2 = 1024;
         if (g2 < 1) g2 = 1;
         hipLaunchKernelGGL(k_minmax, dim3(g2), dim3(256), 0, s, q, nq, qmm, qmm + 1);
-        hipLaunchKernelGGL(k_setup, dim3(1), dim3(1), 0, s, st, qmm, qmm + 1, T, E, k == E ? 1 : 0);
+        int eps0_shift = kEps0Shift;
+        if (const char *ev = getenv("MAXSCORE_EPS0_SHIFT")) eps0_shift = atoi(ev);   // tuning override (debug)
+        hipLaunchKernelGGL(k_setup, dim3(1), dim3(1), 0, s, st, qmm, qmm + 1, T, E, k == E ? 1 : 0, eps0_shift);
     }
 
     // Rounds are enqueued in batches; after each batch the `done` flag is copied to pinned host memory.
@@ -1479,6 +1492,13 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         (void)hipMemcpyFromSymbol(hr, HIP_SYMBOL(g_selround), sizeof(hr));
         for (int a = 0; a < 90; ++a) fprintf(stderr, "[selround] %d cyc %llu n %llu fl %llu\n", a, hr[a] >> 32, (hr[a] >> 8) & 0xffffff, hr[a] & 3);
         fprintf(stderr, "[selprof] block 0: wall ticks (100 MHz) %lld, clock64 ticks %lld\n", hw[0], hw[1]);
+    }
+#endif
+#ifdef MS_TAIL_PROF
+    {
+        int hs[8];
+        (void)hipMemcpyFromSymbol(hs, HIP_SYMBOL(g_tailstat), sizeof(hs));
+        fprintf(stderr, "[tailstat] cumulative: single-victim iterations survive %d drop %d; multi-victim survive %d drop %d\n", hs[0], hs[1], hs[2], hs[3]);
     }
 #endif
     if (getenv("MAXSCORE_DEBUG")) {
