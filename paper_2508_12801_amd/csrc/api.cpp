@@ -14,7 +14,8 @@ WorkspaceLayout workspace_layout(int T, int E, int k, int d)
     L.state_off = off; off = align_up(off + 2 * sizeof(SolverState), 256);
     L.theta_off = off; off = align_up(off + sizeof(long long) * 2 * kMaxE, 256);
     L.gcount_off = off; off = align_up(off + sizeof(int) * (2 * kMaxE + 4), 256);
-    L.klist_off = off; off = align_up(off + sizeof(long long) * ((size_t)E * T + 1024), 256);
+    // bid keys: one block of rows*k keys per bid workgroup, rows*k <= 1024, at most T + rows - 1 rows in all
+    L.klist_off = off; off = align_up(off + sizeof(long long) * (((size_t)T + 1024) * k + 1024), 256);
     L.max_wg = (T + 3) / 4 < 1 ? 1 : (T + 3) / 4;   // a bid workgroup covers at least 4 token rows
     L.wcnt_off = off; off = align_up(off + sizeof(int) * (size_t)E * L.max_wg, 256);
     L.wmoves_off = off; off = align_up(off + sizeof(int) * (size_t)L.max_wg, 256);

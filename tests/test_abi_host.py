@@ -35,7 +35,9 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_workspace_query(lib):
-    assert ms.workspace_bytes(65536, 2048, 128, 8, 4096) > 65536 * 128 * 8
+    # room for one bid key per (token, slot), the per-workgroup counts and the transposed weight copy
+    assert ms.workspace_bytes(65536, 2048, 128, 8, 4096) > 65536 * 8 * 8 + 2048 * 128 * 2
+    assert ms.workspace_bytes(65536, 2048, 128, 8, 4096) < 64 << 20
     assert ms.workspace_bytes(64, 64, 8, 2, 16) % 256 == 0
     assert ms.workspace_bytes(64, 64, 8, 9, 16) == 0          # k > E
     assert ms.workspace_bytes(0, 64, 8, 2, 16) == 0
