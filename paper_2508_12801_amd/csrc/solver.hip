@@ -535,7 +535,8 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
     __shared__ int s_iexp[kTailIns];
     __shared__ long long s_ikey[kTailIns];
     __shared__ int s_qrow[kTailThreads / 64][kTailMaxE];
-    __shared__ int s_nv, s_ni, s_stop, s_over, s_moves, s_changed;
+    __shared__ int s_nv2[2], s_ni2[2], s_over2[2];     // per-iteration counters, double-buffered by iteration parity
+    __shared__ int s_stop, s_moves, s_changed, s_sink;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const long long eps = st->eps, qmin = st->qmin;
@@ -558,7 +559,10 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         s_theta[e] = theta[e];
         s_n[e] = gcur[e];
     }
-    if (tid == 0) { s_stop = 0; s_moves = 0; s_changed = 0; }
+    if (tid == 0) {
+        s_stop = 0; s_moves = 0; s_changed = 0;
+        s_nv2[0] = s_nv2[1] = 0; s_ni2[0] = s_ni2[1] = 0; s_over2[0] = s_over2[1] = 0;
+    }
     __syncthreads();
 
 #ifdef MS_TAIL_PROF
@@ -567,10 +571,16 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
 #else
 #define MS_TP(var)
 #endif
-    int it = 0;
+    int it = 0, over_last = 0;
     for (; it < max_iters; ++it) {
-        if (tid == 0) { s_nv = 0; s_ni = 0; s_over = 0; }
-        __syncthreads();
+        // the counters of this iteration were cleared during the previous one; clear the next ones
+        const int pi = it & 1;
+        int &s_nv = s_nv2[pi], &s_ni = s_ni2[pi], &s_over = s_over2[pi];
+        if (tid == 0) { s_nv2[pi ^ 1] = 0; s_ni2[pi ^ 1] = 0; s_over2[pi ^ 1] = 0; }
+        // rows of the first entry each expert pops are requested here, one load per cache line, so that
+        // the evaluation after the barrier finds them close by
+        int pfv[kTailMaxE / 32 + 1];
+        bool pf_live = false;
         // 1. every over-full expert drops its lowest candidates and raises its threshold
         for (int e = tid; e < E; e += kTailThreads) {
             const int m = s_n[e] - Ce;
@@ -593,12 +603,21 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                         s_cn[e] = cn - m;
                         s_changed = 1;
                         if (nt > s_theta[e] && nt < kKeyInf) s_theta[e] = nt;
+                        {
+                            const int t0 = (int)(ce[cn - 1] & tmask);
+                            const int32_t *pr = q + (size_t)t0 * E;
+#pragma unroll
+                            for (int c = 0; c < kTailMaxE / 32; ++c) pfv[c] = c * 32 < E ? pr[c * 32] : 0;
+                            pfv[kTailMaxE / 32] = assign[(size_t)t0 * k];
+                            pf_live = true;
+                        }
                     }
                 }
             }
         }
         __syncthreads();
         MS_TP(c_p1)
+        over_last = s_over;
         if (s_stop || !s_over) break;
         // 2. one wavefront per dropped token: the bid pass's row evaluation
         const int nv = s_nv < kTailVict ? s_nv : kTailVict;
@@ -799,12 +818,19 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         c_y += clock64() - c_d;
 #endif
         MS_TP(c_p2)
-        // 3. the new keys enter the lists in order: wavefront 0 takes the requests one by one, its
-        //    first kCand lanes hold one list entry each
-        if (wv == 0) {
+        if (pf_live) {          // the requested lines have long arrived; this only keeps the loads alive
+            int acc = 0;
+#pragma unroll
+            for (int c = 0; c <= kTailMaxE / 32; ++c) acc ^= pfv[c];
+            s_sink = acc;
+        }
+        // 3. the new keys enter the lists in request order; wavefront w serves the experts e with
+        //    e mod 16 = w, its first kCand lanes hold one list entry each
+        {
             const int ni = s_ni < kTailIns ? s_ni : kTailIns;
             for (int r = 0; r < ni; ++r) {
-                const int e = s_iexp[r];
+                const int e = __builtin_amdgcn_readfirstlane(s_iexp[r]);
+                if ((e & (kTailThreads / 64 - 1)) != wv) continue;
                 const long long key = s_ikey[r];
                 long long *ce = s_cand + e * kCand;
                 int cn = s_cn[e];
@@ -848,7 +874,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         // Ended with nothing over capacity: every hold is valid, the phase is quiescent.  Without slack
         // there is no price lowering to decide, so the next round starts the next phase right away
         // (the last phase still gets its full check by a bid pass).
-        if (!s_stop && !s_over && !st->slack && st->eps > 1) {
+        if (!s_stop && !over_last && !st->slack && st->eps > 1) {
             if (st->phases <= 28) st->phase_round[st->phases - 1] = st->round;
             st->eps_prev = st->eps;
             const long long ne = st->eps / st->eps_div;
