@@ -623,19 +623,20 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         const int nv = s_nv < kTailVict ? s_nv : kTailVict;
         for (int vi = wv; vi < nv; vi += kTailThreads / 64) {
             const int tok = __builtin_amdgcn_readfirstlane(s_vtok[vi]);
-            // a token challenged by several experts at once is evaluated once, by its first entry
-            const unsigned long long twins = __ballot(lane < nv && lane != vi && s_vtok[lane] == tok);
-            if (twins & ((1ull << vi) - 1)) continue;
-            const int ve = __builtin_amdgcn_readfirstlane(s_vexp[vi]);
             const int32_t *qr = q + (size_t)tok * E;
-            // other wavefronts of this workgroup may have rewritten the row in an earlier round: read
-            // and write it at workgroup scope
+            // the row is requested first, everything else is looked up while it travels.  Other
+            // wavefronts of this workgroup may have rewritten the assignment row in an earlier round:
+            // it is read and written at workgroup scope.
             int my_e = lane < k ? __hip_atomic_load(&assign[(size_t)tok * k + lane], __ATOMIC_RELAXED,
                                                     __HIP_MEMORY_SCOPE_WORKGROUP)
                                 : -2;
             int qv[kTailEPL];
 #pragma unroll
             for (int m = 0; m < kTailEPL; ++m) qv[m] = (m < eplt && lane + 64 * m < E) ? qr[lane + 64 * m] : 0;
+            // a token challenged by several experts at once is evaluated once, by its first entry
+            const unsigned long long twins = __ballot(lane < nv && lane != vi && s_vtok[lane] == tok);
+            if (twins & ((1ull << vi) - 1)) continue;
+            const int ve = __builtin_amdgcn_readfirstlane(s_vexp[vi]);
 #ifdef MS_TAIL_PROF
             long long c_a = clock64();
 #endif
@@ -659,25 +660,22 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 const int es = __builtin_amdgcn_readlane(my_e, s2);
                 if (es >= 0 && (es & 63) == lane) heldm |= 1u << (es >> 6);
             }
-            const int r0 = tok % E;
+            // equal values are ranked by expert id XOR a per-token mask (a bijection below 1024), so that
+            // identical rows spread over the experts
+            const int r0 = tok & 1023;
             auto best_unheld = [&]() {
                 unsigned long long b = 0;
 #pragma unroll
                 for (int m = 0; m < kTailEPL; ++m) {
                     if (m < eplt && (((validm & ~heldm) >> m) & 1u)) {
-                        int tieb = lane + 64 * m - r0;
-                        if (tieb < 0) tieb += E;
                         unsigned long long pk =
-                            ((unsigned long long)(v[m] + (long long)kVB) << 10) | (unsigned)(1023 - tieb);
+                            ((unsigned long long)(v[m] + (long long)kVB) << 10) | (unsigned)((lane + 64 * m) ^ r0);
                         b = pk > b ? pk : b;
                     }
                 }
                 return wave_max_u64(b);
             };
-            auto expert_of = [&](unsigned long long pk) {
-                int e = 1023 - (int)(pk & 1023) + r0;
-                return e >= E ? e - E : e;
-            };
+            auto expert_of = [&](unsigned long long pk) { return (int)(pk & 1023) ^ r0; };
             auto key_of = [&](long long sq, unsigned long long pk_alt) {
                 long long bid = pk_alt != 0 ? sq - ((long long)(pk_alt >> 10) - (long long)kVB) + eps : kBidBig;
                 bid = bid < kBidBig ? bid : kBidBig;
