@@ -55,7 +55,7 @@ enum {
 enum { MAXSCORE_DTYPE_BF16 = 0, MAXSCORE_DTYPE_FP32 = 1 };
 
 /* Options.  Pass NULL for the defaults {t = 1, quant_shift = 20, max_rounds = 200000,
- * eps_div = 8}. */
+ * eps_div = 12}. */
 typedef struct {
     float t;              /* SoftTopk temperature of Eq. 6 */
     int32_t quant_shift;  /* rewards are round(A * 2^quant_shift); 1..24 */

@@ -135,7 +135,7 @@ def _workspace(T, E, k, C, device, d=0):
     return buf, need
 
 
-def _opts(t=1.0, quant_shift=20, max_rounds=200000, eps_div=8):
+def _opts(t=1.0, quant_shift=20, max_rounds=200000, eps_div=12):
     return _Opts(float(t), int(quant_shift), int(max_rounds), int(eps_div))
 
 
@@ -191,7 +191,7 @@ def softtopk(logits, k: int, t: float, quant_shift: int = 20):
     return scores, q
 
 
-def assign_i32(q, k: int, C: int, max_rounds: int = 200000, eps_div: int = 8, allow_not_converged=False):
+def assign_i32(q, k: int, C: int, max_rounds: int = 200000, eps_div: int = 12, allow_not_converged=False):
     """a4: exact assignment on int32 rewards.  Returns dict(assign, prices, price_scale, stats)."""
     torch = _torch()
     T, E = q.shape
@@ -249,7 +249,7 @@ def _route_outputs(T, E, k, dev):
 
 
 def route_logits(logits, k: int, C: int, t: float = 1.0, quant_shift: int = 20, max_rounds: int = 200000,
-                 eps_div: int = 8, out: Optional[dict] = None):
+                 eps_div: int = 12, out: Optional[dict] = None):
     """a2..a6 from logits."""
     torch = _torch()
     T, E = logits.shape
@@ -269,7 +269,7 @@ def route_logits(logits, k: int, C: int, t: float = 1.0, quant_shift: int = 20, 
 
 
 def route_xw(x, W, bias, k: int, C: int, t: float = 1.0, quant_shift: int = 20, max_rounds: int = 200000,
-             eps_div: int = 8, out: Optional[dict] = None):
+             eps_div: int = 12, out: Optional[dict] = None):
     """a1..a6 from x and W_g."""
     torch = _torch()
     T, d = x.shape

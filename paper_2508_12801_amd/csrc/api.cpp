@@ -34,12 +34,12 @@ static bool shape_ok(int T, int E, int k, int C)
 
 static maxscore_opts resolve(const maxscore_opts *o)
 {
-    maxscore_opts r = {1.0f, 20, 200000, 8};
+    maxscore_opts r = {1.0f, 20, 200000, 12};
     if (o) {
         r = *o;
         if (r.quant_shift == 0) r.quant_shift = 20;
         if (r.max_rounds <= 0) r.max_rounds = 200000;
-        if (r.eps_div < 2) r.eps_div = 8;
+        if (r.eps_div < 2) r.eps_div = 12;
     }
     return r;
 }
