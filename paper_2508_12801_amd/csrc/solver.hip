@@ -915,14 +915,17 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                                                         const int *__restrict__ wcnt, const int *__restrict__ wmoves,
                                                         int *gcount2, long long *theta2, SolverState *st2,
                                                         int *errflag, long long *cand, const int32_t *__restrict__ q,
-                                                        int32_t *assign, int *ready, int par, int T, int E, int k,
+                                                        int32_t *assign, int *ready, int *host_done, int par, int T, int E, int k,
                                                         int Ce, int n_wg, int rows_per_wg, int tail_on,
                                                         int tail_moves, int tail_iters)
 {
     const SolverState *st = st2 + par;
     SolverState *st_out = st2 + (par ^ 1);
     if (st->done) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) *st_out = *st;
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            *st_out = *st;
+            __hip_atomic_store(host_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);   // also when set-up ended it
+        }
         return;
     }
     const long long *theta_in = theta2 + par * kMaxE;
@@ -1055,6 +1058,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
         ns.after_tail = 0;
         ns.tail_block = 0;
         *st_out = ns;
+        // the host polls this word (pinned host memory) instead of copying the state
+        if (ns.done) __hip_atomic_store(host_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
     if (is_tail) {
         // The other workgroups publish their candidate lists, thresholds, loads and the next state, then
@@ -1398,12 +1403,17 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         hipLaunchKernelGGL(k_setup, dim3(1), dim3(1), 0, s, st, qmm, qmm + 1, T, E, k == E ? 1 : 0, eps0_shift);
     }
 
-    // Rounds are enqueued in batches; after each batch the `done` flag is copied to pinned host memory.
+    // Rounds are enqueued in batches; the select pass writes `done` straight into pinned host memory.
     // The next batch is always enqueued BEFORE the host waits for the flag of the current one, so the
     // device never idles during the host round trip; once the solve is over the rounds still in the
     // queue exit at once.
-    static thread_local int *tl_flags = nullptr;     // pinned, one flag per batch slot; lives until the process ends
-    if (!tl_flags) MS_HIP(hipHostMalloc((void **)&tl_flags, 64, hipHostMallocDefault));
+    static thread_local int *tl_flag = nullptr;      // pinned and mapped; lives until the process ends
+    static thread_local int *tl_flag_dev = nullptr;  // the same word as the device sees it
+    if (!tl_flag) {
+        MS_HIP(hipHostMalloc((void **)&tl_flag, 64, hipHostMallocMapped));
+        MS_HIP(hipHostGetDevicePointer((void **)&tl_flag_dev, tl_flag, 0));
+    }
+    *(volatile int *)tl_flag = 0;
     std::vector<hipEvent_t> tev;
     const int batch = 4;
     int launched = 0;
@@ -1431,11 +1441,10 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
 #undef MS_BID
             if (g_kernel_timing) MS_HIP(hipEventRecord(tev.back(), s));
             hipLaunchKernelGGL(k_select, dim3(E + tail_on), dim3(kSelThreads), 0, s, klist, wcnt, wmoves, gcount, theta,
-                               st, qmm + 2, cand, q, assign, qmm + 3, par, T, E, k, Ce, n_wg, rows, tail_on,
+                               st, qmm + 2, cand, q, assign, qmm + 3, tl_flag_dev, par, T, E, k, Ce, n_wg, rows, tail_on,
                                tail_moves, tail_iters);
             ++launched;
         }
-        MS_HIP(hipMemcpyAsync(&tl_flags[slot], &st[launched & 1].done, sizeof(int), hipMemcpyDeviceToHost, s));
         MS_HIP(hipEventRecord(evb[slot], s));
         return MAXSCORE_OK;
     };
@@ -1447,7 +1456,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             rc = enqueue_batch(cur ^ 1);
             if (rc != MAXSCORE_OK) break;
             MS_HIP(hipEventSynchronize(evb[cur]));
-            if (tl_flags[cur] || launched_cur > o.max_rounds + 64) break;
+            if (*(volatile int *)tl_flag || launched_cur > o.max_rounds + 64) break;
             cur ^= 1;
         }
         (void)hipEventDestroy(evb[0]);
