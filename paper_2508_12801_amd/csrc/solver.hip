@@ -94,12 +94,28 @@ __global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm,
     }
 }
 
-__global__ __launch_bounds__(256) void k_minmax(const int32_t *__restrict__ q, size_t n, int *qmin, int *qmax)
+// Reward range: every workgroup leaves its minimum and maximum in part[2*b], part[2*b+1] (no atomics:
+// a thousand workgroups updating one word cost more than reading the matrix), k_setup reduces them.
+constexpr int kMinmaxBlocks = 512;
+
+__global__ __launch_bounds__(256) void k_minmax(const int32_t *__restrict__ q, size_t n, int *__restrict__ part)
 {
     __shared__ int s_lo[4], s_hi[4];
     int lo = 0x7fffffff, hi = -0x7fffffff - 1;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
-        int v = q[i];
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (((uintptr_t)q & 15) == 0) {
+        const int4 *q4 = (const int4 *)q;
+        const size_t n4 = n / 4;
+        for (; i < n4; i += stride) {
+            const int4 v = q4[i];
+            lo = min(min(lo, v.x), min(min(v.y, v.z), v.w));
+            hi = max(max(hi, v.x), max(max(v.y, v.z), v.w));
+        }
+        i = n4 * 4 + (size_t)blockIdx.x * blockDim.x + threadIdx.x;      // the last n % 4 values
+    }
+    for (; i < n; i += stride) {
+        const int v = q[i];
         lo = v < lo ? v : lo;
         hi = v > hi ? v : hi;
     }
@@ -118,23 +134,44 @@ __global__ __launch_bounds__(256) void k_minmax(const int32_t *__restrict__ q, s
             lo = s_lo[w] < lo ? s_lo[w] : lo;
             hi = s_hi[w] > hi ? s_hi[w] : hi;
         }
-        atomicMin(qmin, lo);
-        atomicMax(qmax, hi);
+        part[2 * blockIdx.x] = lo;
+        part[2 * blockIdx.x + 1] = hi;
     }
 }
 
-__global__ void k_setup(SolverState *st, const int *qmin, const int *qmax, int T, int E, int force_wide,
-                        int eps0_shift)
+__global__ __launch_bounds__(kMinmaxBlocks) void k_setup(SolverState *st, const int *__restrict__ part, int nparts,
+                                                        int T, int E, int force_wide, int eps0_shift)
 {
-    st->qmin = *qmin;
-    st->qmax = *qmax;
+    __shared__ int s_lo[kMinmaxBlocks / 64], s_hi[kMinmaxBlocks / 64];
+    int lo = 0x7fffffff, hi = -0x7fffffff - 1;
+    if ((int)threadIdx.x < nparts) {
+        lo = part[2 * threadIdx.x];
+        hi = part[2 * threadIdx.x + 1];
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        int a = __shfl_xor(lo, off), b = __shfl_xor(hi, off);
+        lo = a < lo ? a : lo;
+        hi = b > hi ? b : hi;
+    }
+    if ((threadIdx.x & 63) == 0) {
+        s_lo[threadIdx.x >> 6] = lo;
+        s_hi[threadIdx.x >> 6] = hi;
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    for (int w = 1; w < kMinmaxBlocks / 64; ++w) {
+        lo = s_lo[w] < lo ? s_lo[w] : lo;
+        hi = s_hi[w] > hi ? s_hi[w] : hi;
+    }
+    st->qmin = lo;
+    st->qmax = hi;
     int sb = 0;
     while ((1 << sb) < E + 1) ++sb;
     int tb = 1;
     while ((1 << tb) < T) ++tb;
     st->sbits = sb;
     st->tbits = tb;
-    long long range = ((long long)*qmax - (long long)*qmin) << sb;
+    long long range = ((long long)hi - (long long)lo) << sb;
     if (range >= ((long long)1 << 38)) {
         st->status = MAXSCORE_ERR_RANGE;
         st->done = 1;
@@ -1284,10 +1321,15 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
 #endif
 }
 
+// Total score and flow of the final assignment: per-workgroup partial sums (no contended atomics), then
+// one small workgroup adds them up and writes prices and scale.
+constexpr int kFinalBlocks = 256;
+
 __global__ __launch_bounds__(256) void k_finalize(const int32_t *__restrict__ q, const int32_t *__restrict__ assign,
-                                                  const long long *__restrict__ theta, SolverState *st,
-                                                  int64_t *prices, int64_t *price_scale, int T, int E, int k)
+                                                  long long *__restrict__ part, int T, int E, int k)
 {
+    __shared__ long long s_sum[4];
+    __shared__ int s_cnt[4];
     size_t n = (size_t)T * k;
     long long sum = 0;
     int cnt = 0;
@@ -1302,16 +1344,45 @@ __global__ __launch_bounds__(256) void k_finalize(const int32_t *__restrict__ q,
         sum += (long long)shfl_xor_u64((unsigned long long)sum, off);
         cnt += __shfl_xor(cnt, off);
     }
-    if ((threadIdx.x & 63) == 0 && cnt) {
-        atomicAdd((unsigned long long *)&st->total, (unsigned long long)sum);
-        atomicAdd(&st->flow, cnt);
+    if ((threadIdx.x & 63) == 0) {
+        s_sum[threadIdx.x >> 6] = sum;
+        s_cnt[threadIdx.x >> 6] = cnt;
     }
-    if (blockIdx.x == 0) {
-        const int tb = st->tbits;
-        if (prices)
-            for (int e = threadIdx.x; e < E; e += blockDim.x) prices[e] = theta[e] >> tb;
-        if (price_scale && threadIdx.x == 0) *price_scale = (int64_t)1 << st->sbits;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        part[2 * blockIdx.x] = s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3];
+        part[2 * blockIdx.x + 1] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
     }
+}
+
+__global__ __launch_bounds__(kFinalBlocks) void k_finalize2(const long long *__restrict__ part,
+                                                           const long long *__restrict__ theta, SolverState *st,
+                                                           int64_t *prices, int64_t *price_scale, int E)
+{
+    __shared__ long long s_sum[kFinalBlocks / 64], s_cnt[kFinalBlocks / 64];
+    long long sum = part[2 * threadIdx.x], cnt = part[2 * threadIdx.x + 1];
+    for (int off = 32; off > 0; off >>= 1) {
+        sum += (long long)shfl_xor_u64((unsigned long long)sum, off);
+        cnt += (long long)shfl_xor_u64((unsigned long long)cnt, off);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        s_sum[threadIdx.x >> 6] = sum;
+        s_cnt[threadIdx.x >> 6] = cnt;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long ts = 0, tc = 0;
+        for (int w = 0; w < kFinalBlocks / 64; ++w) {
+            ts += s_sum[w];
+            tc += s_cnt[w];
+        }
+        st->total = ts;
+        st->flow = (int)tc;
+        if (price_scale) *price_scale = (int64_t)1 << st->sbits;
+    }
+    const int tb = st->tbits;
+    if (prices)
+        for (int e = threadIdx.x; e < E; e += blockDim.x) prices[e] = theta[e] >> tb;
 }
 
 template <int G, int EPL>
@@ -1395,12 +1466,14 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
                            o.eps_div, o.max_rounds, slack);
         size_t nq = (size_t)T * E;
         int g2 = (int)((nq + 256 * 16 - 1) / (256 * 16));
-        if (g2 > 1024) g2 = 1024;
+        if (g2 > kMinmaxBlocks) g2 = kMinmaxBlocks;
         if (g2 < 1) g2 = 1;
-        hipLaunchKernelGGL(k_minmax, dim3(g2), dim3(256), 0, s, q, nq, qmm, qmm + 1);
+        int *part = (int *)cand;                 // the candidate lists are not in use yet
+        hipLaunchKernelGGL(k_minmax, dim3(g2), dim3(256), 0, s, q, nq, part);
         int eps0_shift = kEps0Shift;
         if (const char *ev = getenv("MAXSCORE_EPS0_SHIFT")) eps0_shift = atoi(ev);   // tuning override (debug)
-        hipLaunchKernelGGL(k_setup, dim3(1), dim3(1), 0, s, st, qmm, qmm + 1, T, E, k == E ? 1 : 0, eps0_shift);
+        hipLaunchKernelGGL(k_setup, dim3(1), dim3(kMinmaxBlocks), 0, s, st, part, g2, T, E, k == E ? 1 : 0,
+                           eps0_shift);
     }
 
     // Rounds are enqueued in batches; the select pass writes `done` straight into pinned host memory.
@@ -1464,8 +1537,9 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         if (rc != MAXSCORE_OK) return rc;
     }
     const int fpar = launched & 1;
-    hipLaunchKernelGGL(k_finalize, dim3(256), dim3(256), 0, s, q, assign, theta + fpar * kMaxE, st + fpar, prices,
-                       price_scale, T, E, k);
+    hipLaunchKernelGGL(k_finalize, dim3(kFinalBlocks), dim3(256), 0, s, q, assign, cand, T, E, k);   // lists are free again
+    hipLaunchKernelGGL(k_finalize2, dim3(1), dim3(kFinalBlocks), 0, s, cand, theta + fpar * kMaxE, st + fpar, prices,
+                       price_scale, E);
     MS_HIP(hipEventRecord(ev1, s));
     SolverState h;
     MS_HIP(hipMemcpyAsync(&h, st + fpar, sizeof(h), hipMemcpyDeviceToHost, s));
