@@ -61,7 +61,8 @@ def test_value_width_paths(ms, hi_bits, slack):
     solve_and_check(ms, q, k, C)
 
 
-@pytest.mark.parametrize("E,k,T", [(512, 4, 4096), (320, 6, 1280), (1024, 2, 2048)])
+@pytest.mark.parametrize("E,k,T", [(512, 4, 4096), (320, 6, 1280), (1024, 2, 2048), (128, 64, 512),
+                                   (1024, 64, 256), (64, 64, 300)])
 def test_many_experts_without_tail_pass(ms, E, k, T):
     print(f"many_experts E={E} k={k} T={T}", flush=True)
     C = T * k // E
@@ -131,3 +132,27 @@ def test_tail_pass_switch_gives_the_same_optimum(ms):
     assert with_tail["stats"]["total_score_q"] == without["stats"]["total_score_q"]
     ref = oracle.max_score_assignment(q, 8, 512)["total"]
     assert with_tail["stats"]["total_score_q"] == ref
+
+
+def test_large_batch_certified_by_its_prices(ms):
+    """T = 2^18 tokens: too many for the CPU flow solver in a test, so optimality is certified by the dual
+    side alone: with rewards scaled by S > E, complementary slackness within 1 and price 0 on every
+    unfilled expert leave no improving cycle (a cycle gains a multiple of S but visits at most E experts)."""
+    print("large_batch", flush=True)
+    T, E, k = 1 << 18, 64, 2
+    C = T * k // E + 3                                  # a little slack: some experts stay unfilled
+    rng = np.random.default_rng(21)
+    q = skewed_rewards(rng, T, E, 20)
+    out = ms.assign_i32(dev(q.astype(np.int32)), k, C)
+    a = out["assign"].cpu().numpy()
+    assert a.min() >= 0 and (np.sort(a, axis=1)[:, 1:] != np.sort(a, axis=1)[:, :-1]).all()   # k distinct experts
+    load = np.bincount(a.reshape(-1), minlength=E)
+    assert load.max() <= C and load.sum() == T * k == out["stats"]["flow_value"]
+    S, p = out["price_scale"], out["prices"].cpu().numpy()
+    assert S > E and (p >= 0).all() and (p[load < C] == 0).all()
+    net = q * S - p[None, :]
+    held = np.zeros((T, E), dtype=bool)
+    held[np.arange(T)[:, None], a] = True
+    big = np.int64(1) << 60
+    assert (np.where(held, net, big).min(axis=1) >= np.where(held, -big, net).max(axis=1) - 1).all()
+    assert out["stats"]["total_score_q"] == int(q[held].sum())
