@@ -165,13 +165,18 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_wt(const unsigned short *__re
     // B staging: BN rows x 64 columns = BN*8 16-byte vectors, B_PER per thread
     constexpr int B_VECS = BN * 8;
     constexpr int B_PER = (B_VECS + 255) / 256;
-    u32x4 ra[4], rb[B_PER];
-    auto fetch = [&](int k0) {
+    // Two slabs of A are in flight per wavefront (x is the stream that has to come from HBM: with one
+    // slab ahead the bytes in flight bound the kernel well below the memory rate); the transposed-W slab
+    // comes from L2 and stays one ahead.
+    u32x4 ra[2][4], rb[B_PER];
+    auto fetch_a = [&](int k0, u32x4(&dst)[4]) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int kk = k0 + 16 * j + kq;
-            ra[j] = (arow_ok && kk < d) ? *(const u32x4 *)(xrow + kk) : u32x4{0u, 0u, 0u, 0u};
+            dst[j] = (arow_ok && kk < d) ? *(const u32x4 *)(xrow + kk) : u32x4{0u, 0u, 0u, 0u};
         }
+    };
+    auto fetch_b = [&](int k0) {
 #pragma unroll
         for (int p = 0; p < B_PER; ++p) {
             const int v = tid + 256 * p;
@@ -193,16 +198,19 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_wt(const unsigned short *__re
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[nt][i] = 0.f;
 
-    fetch(0);
+    fetch_a(0, ra[0]);
+    fetch_b(0);
+    fetch_a(BK, ra[1]);
     stash_b(0);
     int buf = 0;
-    for (int k0 = 0; k0 < d; k0 += BK) {
+    auto step = [&](int k0, u32x4(&cur)[4]) {
         u32x4 a_cur[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) a_cur[j] = ra[j];
+        for (int j = 0; j < 4; ++j) a_cur[j] = cur[j];
         __syncthreads();                         // sB[buf] is complete; sB[buf^1] is free again
         const bool more = k0 + BK < d;
-        if (more) fetch(k0 + BK);
+        if (more) fetch_b(k0 + BK);
+        if (k0 + 2 * BK < d) fetch_a(k0 + 2 * BK, cur);      // this register set is free again
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             bf16x8 a = __builtin_bit_cast(bf16x8, a_cur[j]);
@@ -214,6 +222,10 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_wt(const unsigned short *__re
         }
         if (more) stash_b(buf ^ 1);
         buf ^= 1;
+    };
+    for (int k0 = 0; k0 < d; k0 += 2 * BK) {
+        step(k0, ra[0]);
+        if (k0 + BK < d) step(k0 + BK, ra[1]);
     }
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
