@@ -25,8 +25,11 @@
  *     aligned.  Two calls may overlap only if they use different workspaces.
  *   - Return value: MAXSCORE_OK or a negative MAXSCORE_ERR_* code.  Argument errors are found on
  *     the host before anything is launched.  No entry point throws or allocates device memory.
- *   - Entry points that contain the assignment step (a4) poll a device flag for convergence and
- *     therefore SYNCHRONISE `stream` before returning; the others only enqueue work.
+ *   - Entry points that contain the assignment step (a4) poll a convergence flag and therefore
+ *     SYNCHRONISE `stream` before returning; the others only enqueue work.  The flag lives in 64 bytes
+ *     of pinned host memory that the first such call of a host thread allocates and keeps until the
+ *     process ends (one solve at a time per host thread; different threads may solve concurrently on
+ *     different streams with different workspaces).
  *   - Supported sizes: 1 <= k <= E <= 1024, k <= 64, 1 <= T <= 2^21, C >= 1 (C > T acts as T),
  *     and T*k <= E*min(C,T) (true for every capacity c' = c_f*k*n/e with c_f >= 1, Section 2.3).
  */
