@@ -603,7 +603,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
     __syncthreads();
 
 #ifdef MS_TAIL_PROF
-    long long c_p1 = 0, c_p2 = 0, c_p3 = 0, c_t0 = clock64(), c_init = 0, c_x = 0, c_y = 0;
+    long long c_p1 = 0, c_p2 = 0, c_p3 = 0, c_t0 = clock64(), c_init = 0, c_x = 0, c_y = 0, c_e[5] = {0, 0, 0, 0, 0};
 #define MS_TP(var) { long long c_now = clock64(); var += c_now - c_t0; c_t0 = c_now; }
 #else
 #define MS_TP(var)
@@ -697,6 +697,9 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 const int es = __builtin_amdgcn_readlane(my_e, s2);
                 if (es >= 0 && (es & 63) == lane) heldm |= 1u << (es >> 6);
             }
+#ifdef MS_TAIL_PROF
+            long long c_h = clock64();
+#endif
             // equal values are ranked by expert id XOR a per-token mask (a bijection below 1024), so that
             // identical rows spread over the experts
             const int r0 = tok & 1023;
@@ -730,6 +733,9 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 }
             };
             unsigned long long pk = best_unheld();
+#ifdef MS_TAIL_PROF
+            long long c_r1 = clock64(), c_r2 = c_r1, c_r3 = c_r1;
+#endif
             if (!twins) {
                 // The usual case: one hold (tok, ve) is challenged.  Every other hold of the token is
                 // still valid (its listed key was not popped and true keys only rise), so only this
@@ -757,7 +763,14 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                         } else {
                             if ((ve & 63) == lane) heldm &= ~(1u << (ve >> 6));
                             if ((e1 & 63) == lane) heldm |= 1u << (e1 >> 6);
-                            const long long key1 = key_of(reward_of(e1), best_unheld());
+#ifdef MS_TAIL_PROF
+                            c_r2 = clock64();
+#endif
+                            const unsigned long long pk2 = best_unheld();
+#ifdef MS_TAIL_PROF
+                            c_r3 = clock64();
+#endif
+                            const long long key1 = key_of(reward_of(e1), pk2);
                             if (my_e == ve)
                                 __hip_atomic_store(&assign[(size_t)tok * k + lane], e1, __ATOMIC_RELAXED,
                                                    __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -774,7 +787,11 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                     }
                 }
 #ifdef MS_TAIL_PROF
-                if (wv == 0) { long long c_c = clock64(); c_init += c_b - c_a; c_x += c_c - c_b; }
+                if (wv == 0) {
+                    long long c_c = clock64();
+                    c_init += c_b - c_a; c_x += c_c - c_b;
+                    c_e[0] += c_h - c_b; c_e[1] += c_r1 - c_h; c_e[2] += c_r2 - c_r1; c_e[3] += c_r3 - c_r2; c_e[4] += c_c - c_r3;
+                }
 #endif
                 continue;
             }
@@ -926,6 +943,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         st->phase_round[20] += (int)(c_init >> 6); st->phase_round[21] += (int)(c_p1 >> 6);
         st->phase_round[22] += (int)(c_p2 >> 6); st->phase_round[23] += (int)(c_p3 >> 6);
         st->phase_round[24] += (int)(c_x >> 6); st->phase_round[25] += (int)(c_y >> 6);
+        for (int a = 0; a < 5; ++a) st->phase_round[14 + a] += (int)(c_e[a] >> 6);
 #endif
     }
 }
@@ -1614,6 +1632,8 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         fprintf(stderr, "  tail runs %d iters %d  [cyc/64: init %d p1 %d p2 %d p3 %d]\n", h.tail_runs, h.tail_iters,
                 h.phase_round[20], h.phase_round[21], h.phase_round[22], h.phase_round[23]);
         fprintf(stderr, "  p2 detail: load-wait %d eval %d barrier %d\n", h.phase_round[20], h.phase_round[24], h.phase_round[25]);
+        fprintf(stderr, "  eval detail (fast path, cyc/64): held marks %d, first best %d, decision %d, second best %d, commit %d\n",
+                h.phase_round[14], h.phase_round[15], h.phase_round[16], h.phase_round[17], h.phase_round[18]);
     }
     if (stats) {
         stats->total_score_q = h.total;
