@@ -276,6 +276,40 @@ def dispatch(assign: np.ndarray, gate: np.ndarray, E: int) -> dict:
 
 
 # ------------------------------------------------------------------------------------------------
+# activation movement around the experts (Eq. 1; capacity buffers of Section 2.3)
+
+def dispatch_tokens(x, expert_offsets, disp_token, E: int, C: int) -> np.ndarray:
+    """Expert input buffers [E, C, d]: slot s of expert j holds the activation row of the s-th token
+    dispatched to j (ascending token id); the slots past the expert's count are zero."""
+    x = np.asarray(x)
+    off = np.asarray(expert_offsets)
+    tok = np.asarray(disp_token)
+    buf = np.zeros((E, C, x.shape[1]), dtype=x.dtype)
+    for j in range(E):
+        n = int(off[j + 1] - off[j])
+        if n > C:
+            raise ValueError("an expert holds more tokens than its capacity")
+        buf[j, :n] = x[tok[off[j]:off[j + 1]]]
+    return buf
+
+
+def combine(expert_out, assign, token_pos, gate) -> np.ndarray:
+    """Eq. 1: y_i = sum over the selected experts of gate * expert output, read back from the
+    expert output buffers [E, C, d] at the slot the token was dispatched to (fp64)."""
+    buf = np.asarray(expert_out, dtype=np.float64)
+    assign = np.asarray(assign)
+    pos = np.asarray(token_pos)
+    g = np.asarray(gate, dtype=np.float64)
+    T, k = assign.shape
+    y = np.zeros((T, buf.shape[2]), dtype=np.float64)
+    for s in range(k):
+        ok = assign[:, s] >= 0
+        rows = buf[assign[ok, s], pos[ok, s]]
+        y[ok] += g[ok, s, None] * rows
+    return y
+
+
+# ------------------------------------------------------------------------------------------------
 # whole path
 
 def route(x, W, bias, k: int, C: int, t: float, shift: int = 20) -> dict:
