@@ -123,6 +123,24 @@ int32_t maxscore_dispatch(const int32_t *assign, const float *gates, int32_t T, 
                           int32_t *expert_offsets, int32_t *disp_token, float *disp_gate,
                           int32_t *token_pos, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Activation movement around the experts (the step after the routing path; Eq. 1 and the capacity
+ * buffers of Section 2.3).
+ *
+ * maxscore_dispatch_tokens: expert_in[E, C, d] (same element type as x) receives, in slot s of expert j,
+ * row disp_token[expert_offsets[j] + s] of x[T, d]; the slots past the expert's count are set to zero.
+ * Every expert must hold at most C tokens (true for the outputs of a6 when the same C was used in a4).
+ *
+ * maxscore_combine: y[T, d] (fp32) = sum over s of gates[i, s] * expert_out[assign[i, s], token_pos[i, s], :]
+ * with fp32 accumulation; slots with assign < 0 contribute nothing.  expert_out is [E, C, d] bf16 or fp32.
+ * Both only enqueue work; rows whose byte length is a multiple of 16 (and 16-byte aligned buffers) take
+ * the fast path. */
+int32_t maxscore_dispatch_tokens(const void *x, int32_t in_dtype, const int32_t *expert_offsets,
+                                 const int32_t *disp_token, int32_t T, int32_t d, int32_t E, int32_t C,
+                                 void *expert_in, void *stream);
+int32_t maxscore_combine(const void *expert_out, int32_t in_dtype, const int32_t *assign, const int32_t *token_pos,
+                         const float *gates, int32_t T, int32_t d, int32_t E, int32_t k, int32_t C, float *y,
+                         void *stream);
+
 /* a2..a6 from given logits.  scores_out[T,E] and q_out[T,E] are required (they are the working
  * storage of a2/a3).  Synchronises `stream`. */
 int32_t maxscore_route_logits(const float *logits, int32_t T, int32_t E, int32_t k, int32_t C,

@@ -54,6 +54,12 @@ _SIGS = {
     "maxscore_dispatch": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "maxscore_dispatch_tokens": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                                  ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                                  ctypes.c_void_p, ctypes.c_void_p]),
+    "maxscore_combine": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]),
     "maxscore_route_logits": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                                ctypes.c_int32, ctypes.c_void_p] + [ctypes.c_void_p] * 11 +
                               [ctypes.c_size_t, ctypes.c_void_p]),
@@ -233,6 +239,42 @@ def dispatch(assign, gate, E: int, C: int = 1):
                                           _ptr(disp_gate), _ptr(token_pos), _ptr(ws), need, _stream())
     _check(rc, "maxscore_dispatch")
     return dict(expert_offsets=offsets, disp_token=disp_token, disp_gate=disp_gate, token_pos=token_pos)
+
+
+def _dtype_code(t):
+    torch = _torch()
+    if t.dtype == torch.bfloat16:
+        return 0
+    if t.dtype == torch.float32:
+        return 1
+    raise TypeError("bf16 or fp32 expected")
+
+
+def dispatch_tokens(x, expert_offsets, disp_token, E: int, C: int, out=None):
+    """Expert input buffers [E, C, d] (dtype of x): rows of x in dispatch order, zero padding."""
+    torch = _torch()
+    T, d = x.shape
+    assert x.is_contiguous()
+    if out is None:
+        out = torch.empty((E, C, d), dtype=x.dtype, device=x.device)
+    rc = load_library().maxscore_dispatch_tokens(_ptr(x), _dtype_code(x), _ptr(expert_offsets), _ptr(disp_token),
+                                                 T, d, E, C, _ptr(out), _stream())
+    _check(rc, "maxscore_dispatch_tokens")
+    return out
+
+
+def combine(expert_out, assign, token_pos, gate, out=None):
+    """y[T, d] fp32 = sum_s gate[i, s] * expert_out[assign[i, s], token_pos[i, s], :] (Eq. 1)."""
+    torch = _torch()
+    E, C, d = expert_out.shape
+    T, k = assign.shape
+    assert expert_out.is_contiguous()
+    if out is None:
+        out = torch.empty((T, d), dtype=torch.float32, device=expert_out.device)
+    rc = load_library().maxscore_combine(_ptr(expert_out), _dtype_code(expert_out), _ptr(assign), _ptr(token_pos),
+                                         _ptr(gate), T, d, E, k, C, _ptr(out), _stream())
+    _check(rc, "maxscore_combine")
+    return out
 
 
 def _route_outputs(T, E, k, dev):

@@ -121,6 +121,26 @@ int32_t maxscore_dispatch(const int32_t *assign, const float *gates, int32_t T, 
                         (char *)workspace, (hipStream_t)stream);
 }
 
+int32_t maxscore_dispatch_tokens(const void *x, int32_t in_dtype, const int32_t *expert_offsets,
+                                 const int32_t *disp_token, int32_t T, int32_t d, int32_t E, int32_t C,
+                                 void *expert_in, void *stream)
+{
+    if (!x || !expert_offsets || !disp_token || !expert_in) return MAXSCORE_ERR_NULL;
+    if (T < 1 || T > (1 << kMaxTBits) || d < 1 || E < 1 || E > kMaxE || C < 1) return MAXSCORE_ERR_SHAPE;
+    if (in_dtype != MAXSCORE_DTYPE_BF16 && in_dtype != MAXSCORE_DTYPE_FP32) return MAXSCORE_ERR_DTYPE;
+    return dispatch_tokens_run(x, in_dtype, expert_offsets, disp_token, T, d, E, C, expert_in, (hipStream_t)stream);
+}
+
+int32_t maxscore_combine(const void *expert_out, int32_t in_dtype, const int32_t *assign, const int32_t *token_pos,
+                         const float *gates, int32_t T, int32_t d, int32_t E, int32_t k, int32_t C, float *y,
+                         void *stream)
+{
+    if (!expert_out || !assign || !token_pos || !gates || !y) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, k, C) || d < 1) return MAXSCORE_ERR_SHAPE;
+    if (in_dtype != MAXSCORE_DTYPE_BF16 && in_dtype != MAXSCORE_DTYPE_FP32) return MAXSCORE_ERR_DTYPE;
+    return combine_run(expert_out, in_dtype, assign, token_pos, gates, T, d, E, k, C, y, (hipStream_t)stream);
+}
+
 int32_t maxscore_route_logits(const float *logits, int32_t T, int32_t E, int32_t k, int32_t C,
                               const maxscore_opts *opts, float *scores_out, int32_t *q_out, int32_t *assign,
                               float *gates, int32_t *expert_offsets, int32_t *disp_token, float *disp_gate,

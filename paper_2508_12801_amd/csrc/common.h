@@ -67,6 +67,11 @@ int32_t gates_run(const float *scores, const int32_t *assign, int T, int E, int 
 // --- dispatch.hip
 int32_t dispatch_run(const int32_t *assign, const float *gates, int T, int E, int k, int32_t *offsets,
                      int32_t *disp_token, float *disp_gate, int32_t *token_pos, char *ws, hipStream_t s);
+// --- movement.hip
+int32_t dispatch_tokens_run(const void *x, int dtype, const int32_t *offsets, const int32_t *disp_token, int T, int d,
+                            int E, int C, void *out, hipStream_t s);
+int32_t combine_run(const void *buf, int dtype, const int32_t *assign, const int32_t *token_pos, const float *gates,
+                    int T, int d, int E, int k, int C, float *y, hipStream_t s);
 // --- gemm.hip
 int32_t gemm_run(const void *x, const void *W, const float *bias, int dtype, int T, int d, int E, float *logits,
                  void *wt_scratch, hipStream_t s);
