@@ -127,6 +127,23 @@ def main():
     copy_ms = timed(lambda: ms.copy_bytes(src, dst))
     copy_gbs = 2 * src.numel() / (copy_ms * 1e-3) / 1e9
 
+    # the step after the routing path (measured beside it, not part of `value`): activation rows into the
+    # expert input buffers and the gate-weighted combine back, at the same configuration
+    eb = 2 if r.dtype == "bf16" else 4
+    buf = ms.dispatch_tokens(x, out["expert_offsets"], out["disp_token"], E, C)
+    y = ms.combine(buf, out["assign"], out["token_pos"], out["gates"])
+    dtok_ms = timed(lambda: ms.dispatch_tokens(x, out["expert_offsets"], out["disp_token"], E, C, out=buf), n=5)
+    comb_ms = timed(lambda: ms.combine(buf, out["assign"], out["token_pos"], out["gates"], out=y), n=5)
+    dtok_bytes = T * k * d * eb + E * C * d * eb
+    comb_bytes = T * k * d * eb + T * d * 4
+    movement = {
+        "dispatch_tokens": {"ms": dtok_ms, "bytes": dtok_bytes, "GBps": dtok_bytes / (dtok_ms * 1e-3) / 1e9,
+                            "hbm_frac": dtok_bytes / (dtok_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "combine": {"ms": comb_ms, "bytes": comb_bytes, "GBps": comb_bytes / (comb_ms * 1e-3) / 1e9,
+                    "hbm_frac": comb_bytes / (comb_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+    }
+    del buf, y
+
     line = {
         "metric": "routed tokens/sec", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -149,6 +166,7 @@ def main():
                       "gates": gates_ms, "dispatch": disp_ms,
                       "gemm_hbm_frac": (T * d * 2 + d * E * 2 + T * E * 4) / (gemm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                       "gemm_tflops": 2.0 * T * d * E / (gemm_ms * 1e-3) / 1e12},
+        "activation_movement": movement,
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(args.config, min(args.cpu_sample, T))
