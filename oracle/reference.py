@@ -13,6 +13,9 @@ Everything is fp64 / int64 and written to be checked against the paper by eye:
   gates              Eq. 2: the affinity of each selected (token, expert) pair, not renormalised
   dispatch           per-expert buffers (Section 2.3 capacity layout): stable sort by expert
   verify_optimal     independent optimality proof for any assignment (no negative residual cycle)
+  iter_reroute       Section 2.3 iterative rerouting: top-k with capacity, then greedy re-proposal rounds
+                     (a heuristic; the processing orders are a stated reading, parity with the
+                     authors' code is unpinned)
 """
 from __future__ import annotations
 
@@ -334,3 +337,81 @@ def route_from_logits(L, k: int, C: int, t: float, shift: int = 20) -> dict:
                flow=sol["flow"], prices=sol.get("prices"))
     out.update(dispatch(assign, g, E))
     return out
+
+
+# ------------------------------------------------------------------------------------------------
+# iterative rerouting (Section 2.3; the assignment step of the "-I" variants of Section 4)
+
+def _accept_in_order(e_sorted_by_priority: np.ndarray, room: np.ndarray) -> np.ndarray:
+    """For a list of expert ids in priority order, mark the entries an expert still has room for:
+    expert j takes its first room[j] entries."""
+    e = np.asarray(e_sorted_by_priority)
+    order = np.argsort(e, kind="stable")
+    es = e[order]
+    within = np.arange(es.size) - np.searchsorted(es, es, side="left")
+    ok = np.zeros(e.size, dtype=bool)
+    ok[order] = within < room[es]
+    return ok
+
+
+def iter_reroute(q, k: int, C: int, max_rounds: Optional[int] = None) -> dict:
+    """Two-stage greedy assignment on integer rewards.  The paper gives the two stages in one
+    sentence; the orders below are this build's reading of it.
+
+    Stage 1 (top-k with capacity): every token lists its k highest-reward experts (ties to the
+    lower expert id).  The pairs are taken in the order (choice rank, token id): all first choices
+    before all second choices, tokens in sequence order inside a rank.  An expert keeps the first
+    C pairs that name it; the others are dropped and leave a hole in slot `rank` of the token.
+
+    Stage 2 (rerouting), in synchronous rounds: at the start of a round the experts with room left
+    are fixed.  Every token fills its holes in slot order with proposals: the highest-reward expert
+    that has room, that the token does not hold and has not proposed in this round.  The
+    proposals are then taken in the order (slot, token id) and an expert accepts while it has room.
+    Rounds repeat until nobody can propose.
+
+    Returns assign [T, k] (-1 = hole left), the stage-1 assignment, per-expert load, total reward,
+    flow and the number of stage-2 rounds that had proposals."""
+    q = _as_q(q)
+    T, E = q.shape
+    assert 1 <= k <= E
+    choice = np.argsort(-q, axis=1, kind="stable")[:, :k]
+    assign = np.full((T, k), -1, dtype=np.int64)
+    load = np.zeros(E, dtype=np.int64)
+    for s in range(k):                                   # stage 1, one choice rank at a time
+        e = choice[:, s]
+        ok = _accept_in_order(e, C - load)               # tokens already in id order
+        assign[ok, s] = e[ok]
+        load += np.bincount(e[ok], minlength=E)
+    stage1 = assign.copy()
+    rounds = 0
+    NEG = -(np.int64(1) << 62)                       # below any reward; its negation still fits
+    while max_rounds is None or rounds < max_rounds:
+        holes = assign < 0
+        rows = np.nonzero(holes.any(axis=1))[0]
+        room = C - load
+        if rows.size == 0 or not (room > 0).any():
+            break
+        sub = assign[rows]
+        held = np.zeros((rows.size, E), dtype=bool)
+        r_idx, s_idx = np.nonzero(sub >= 0)
+        held[r_idx, sub[r_idx, s_idx]] = True
+        cand = (room > 0)[None, :] & ~held
+        pref = np.argsort(-np.where(cand, q[rows], NEG), axis=1, kind="stable")   # best candidate first
+        ncand = cand.sum(axis=1)
+        nth_hole = np.cumsum(holes[rows], axis=1) - 1                              # per slot: index among the token's holes
+        prop = np.full((T, k), -1, dtype=np.int64)
+        r_idx, s_idx = np.nonzero(holes[rows])
+        h = nth_hole[r_idx, s_idx]
+        can = h < ncand[r_idx]
+        prop[rows[r_idx[can]], s_idx[can]] = pref[r_idx[can], h[can]]
+        if not (prop >= 0).any():
+            break
+        rounds += 1
+        s_list, i_list = np.nonzero(prop.T >= 0)          # (slot, token) order
+        e_list = prop[i_list, s_list]
+        ok = _accept_in_order(e_list, room)
+        assign[i_list[ok], s_list[ok]] = e_list[ok]
+        load += np.bincount(e_list[ok], minlength=E)
+    got = assign >= 0
+    total = int(q[np.nonzero(got)[0], assign[got]].sum())
+    return dict(assign=assign, stage1=stage1, load=load, total=total, flow=int(got.sum()), rounds=rounds)
