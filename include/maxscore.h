@@ -123,6 +123,24 @@ int32_t maxscore_dispatch(const int32_t *assign, const float *gates, int32_t T, 
                           int32_t *expert_offsets, int32_t *disp_token, float *disp_gate,
                           int32_t *token_pos, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Iterative rerouting (Section 2.3, the second stage drawn in Figure 1(c); the assignment step of the
+ * "-I" variants of Section 4): a fast greedy alternative to maxscore_assign_i32 on the same integer rewards.
+ * Stage 1 keeps, per expert, the first C of the tokens' top-k choices taken in the order (choice rank, token
+ * id); stage 2 runs synchronous rounds in which every token proposes, for its holes in slot order, its best
+ * experts among those with room at the start of the round (not held, not proposed twice), and an expert
+ * accepts proposals in the order (slot, token id) while it has room; rounds end when nobody can propose.
+ * The paper states the two stages in a sentence; these orders are this library's reading.
+ *
+ * q[T, E] device; assign[T, k] device out (slot s holds the token's s-th choice or its replacement, -1 = hole
+ * that nobody could take).  total (sum of q over the chosen pairs), flow (number of pairs) and rounds (stage-2
+ * rounds that had proposals) are host pointers and may be NULL.  max_rounds <= 0 means 1000.  Any C >= 1 is
+ * accepted (no over-subscription error: holes simply stay).  The call synchronises the stream; workspace as for
+ * maxscore_assign_i32.  Returns MAXSCORE_ERR_NOT_CONVERGED if proposals were still pending after max_rounds
+ * (the assignment is feasible all the same). */
+int32_t maxscore_assign_iter_i32(const int32_t *q, int32_t T, int32_t E, int32_t k, int32_t C, int32_t max_rounds,
+                                 int32_t *assign, int64_t *total, int32_t *flow, int32_t *rounds, void *workspace,
+                                 size_t workspace_bytes, void *stream);
+
 /* Activation movement around the experts (the step after the routing path; Eq. 1 and the capacity
  * buffers of Section 2.3).
  *

@@ -42,6 +42,8 @@ _SIGS = {
     "maxscore_router_logits": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
                                                 ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
                                                 ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "maxscore_assign_iter_i32": (ctypes.c_int32, [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p] * 5 +
+                                 [ctypes.c_size_t, ctypes.c_void_p]),
     "maxscore_softtopk": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.c_float, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                            ctypes.c_void_p]),
@@ -212,6 +214,21 @@ def assign_i32(q, k: int, C: int, max_rounds: int = 200000, eps_div: int = 12, a
                                             _ptr(scale), ctypes.byref(stats), _ptr(ws), need, _stream())
     _check(rc, "maxscore_assign_i32", allow=(ERR_NOT_CONVERGED,) if allow_not_converged else ())
     return dict(assign=assign, prices=prices, price_scale=int(scale.item()), stats=stats.as_dict(), rc=rc)
+
+
+def assign_iter_i32(q, k: int, C: int, max_rounds: int = 0, allow_not_converged=False):
+    """Iterative rerouting on int32 rewards (Section 2.3).  Returns dict(assign, total, flow, rounds, rc)."""
+    torch = _torch()
+    T, E = q.shape
+    assert q.dtype == torch.int32 and q.is_contiguous()
+    assign = torch.empty((T, k), dtype=torch.int32, device=q.device)
+    total, flow, rounds = ctypes.c_int64(), ctypes.c_int32(), ctypes.c_int32()
+    ws, need = _workspace(T, E, k, C, q.device)
+    rc = load_library().maxscore_assign_iter_i32(_ptr(q), T, E, k, C, max_rounds, _ptr(assign),
+                                                 ctypes.addressof(total), ctypes.addressof(flow),
+                                                 ctypes.addressof(rounds), _ptr(ws), need, _stream())
+    _check(rc, "maxscore_assign_iter_i32", allow=(ERR_NOT_CONVERGED,) if allow_not_converged else ())
+    return dict(assign=assign, total=total.value, flow=flow.value, rounds=rounds.value, rc=rc)
 
 
 def gates(scores, assign):

@@ -100,6 +100,18 @@ int32_t maxscore_assign_i32(const int32_t *q, int32_t T, int32_t E, int32_t k, i
                       (hipStream_t)stream);
 }
 
+int32_t maxscore_assign_iter_i32(const int32_t *q, int32_t T, int32_t E, int32_t k, int32_t C, int32_t max_rounds,
+                                 int32_t *assign, int64_t *total, int32_t *flow, int32_t *rounds, void *workspace,
+                                 size_t workspace_bytes, void *stream)
+{
+    if (!q || !assign) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, k, C)) return MAXSCORE_ERR_SHAPE;
+    int32_t rc = check_ws(workspace, workspace_bytes, T, E, k);
+    if (rc) return rc;
+    if (max_rounds <= 0) max_rounds = 1000;
+    return iter_run(q, T, E, k, C, max_rounds, assign, total, flow, rounds, (char *)workspace, (hipStream_t)stream);
+}
+
 int32_t maxscore_gates(const float *scores, const int32_t *assign, int32_t T, int32_t E, int32_t k, float *gates,
                        void *stream)
 {

@@ -67,6 +67,15 @@ int32_t gates_run(const float *scores, const int32_t *assign, int T, int E, int 
 // --- dispatch.hip
 int32_t dispatch_run(const int32_t *assign, const float *gates, int T, int E, int k, int32_t *offsets,
                      int32_t *disp_token, float *disp_gate, int32_t *token_pos, char *ws, hipStream_t s);
+// Stable position of every entry of `list` (n expert ids, -1 = none) among the entries of the same expert, and
+// the exclusive prefix sums of the per-expert counts; disp_token / disp_gate may be null.  `tiles` needs
+// n_tiles*E + kMaxE ints with n_tiles = ceil(n / 1024).
+int32_t dispatch_core(const int32_t *list, const float *gates, size_t n, int E, int k, int32_t *offsets,
+                      int32_t *disp_token, float *disp_gate, int32_t *token_pos, int *tiles, int n_tiles,
+                      hipStream_t s);
+// --- iter.hip
+int32_t iter_run(const int32_t *q, int T, int E, int k, int C, int max_rounds, int32_t *assign, int64_t *total,
+                 int32_t *flow, int32_t *rounds, char *ws, hipStream_t s);
 // --- movement.hip
 int32_t dispatch_tokens_run(const void *x, int dtype, const int32_t *offsets, const int32_t *disp_token, int T, int d,
                             int E, int C, void *out, hipStream_t s);

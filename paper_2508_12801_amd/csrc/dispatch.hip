@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void k_scatter(const int32_t *__restrict__ ass
             token_pos[a] = pos;
             if (e >= 0) {
                 const int dst = offsets[e] + pos;
-                disp_token[dst] = (int32_t)(a / k);
+                if (disp_token) disp_token[dst] = (int32_t)(a / k);
                 if (disp_gate) disp_gate[dst] = gates[a];
             }
         }
@@ -133,25 +133,30 @@ __global__ __launch_bounds__(256) void k_scatter(const int32_t *__restrict__ ass
 
 }  // namespace
 
-int32_t dispatch_run(const int32_t *assign, const float *gates, int T, int E, int k, int32_t *offsets,
-                     int32_t *disp_token, float *disp_gate, int32_t *token_pos, char *ws, hipStream_t s)
+int32_t dispatch_core(const int32_t *list, const float *gates, size_t n, int E, int k, int32_t *offsets,
+                      int32_t *disp_token, float *disp_gate, int32_t *token_pos, int *tiles, int n_tiles,
+                      hipStream_t s)
 {
-    WorkspaceLayout L = workspace_layout(T, E, k);
-    int *tiles = (int *)(ws + L.tiles_off);
-    const size_t n = (size_t)T * k;
-    const int n_tiles = L.n_tiles;
     const int grid = (n_tiles + kWavesPerWg - 1) / kWavesPerWg;
     const size_t shm = (size_t)kWavesPerWg * E * sizeof(int);
-    hipLaunchKernelGGL(k_tile_hist, dim3(grid), dim3(256), shm, s, assign, n, E, tiles, n_tiles);
+    hipLaunchKernelGGL(k_tile_hist, dim3(grid), dim3(256), shm, s, list, n, E, tiles, n_tiles);
     int *totals = tiles + (size_t)n_tiles * E;
     int ebits = 0;
     while ((1 << ebits) < E) ++ebits;
     hipLaunchKernelGGL(k_scan_tiles, dim3(E), dim3(64), 0, s, tiles, n_tiles, E, totals);
     hipLaunchKernelGGL(k_offsets, dim3(1), dim3(1024), 0, s, totals, E, offsets);
-    hipLaunchKernelGGL(k_scatter, dim3(grid), dim3(256), shm, s, assign, gates, n, E, k, ebits, tiles, n_tiles,
+    hipLaunchKernelGGL(k_scatter, dim3(grid), dim3(256), shm, s, list, gates, n, E, k, ebits, tiles, n_tiles,
                        offsets, disp_token, disp_gate, token_pos);
     MS_HIP(hipGetLastError());
     return MAXSCORE_OK;
+}
+
+int32_t dispatch_run(const int32_t *assign, const float *gates, int T, int E, int k, int32_t *offsets,
+                     int32_t *disp_token, float *disp_gate, int32_t *token_pos, char *ws, hipStream_t s)
+{
+    WorkspaceLayout L = workspace_layout(T, E, k);
+    return dispatch_core(assign, gates, (size_t)T * k, E, k, offsets, disp_token, disp_gate, token_pos,
+                         (int *)(ws + L.tiles_off), L.n_tiles, s);
 }
 
 }  // namespace maxscore
