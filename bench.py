@@ -144,6 +144,13 @@ def main():
     }
     del buf, y
 
+    # the paper's fast alternative to the exact assignment (iterative rerouting), on the same rewards: time,
+    # rounds and how much of the exact optimum it reaches
+    it = ms.assign_iter_i32(out["q"], k, C)
+    iter_ms = timed(lambda: ms.assign_iter_i32(out["q"], k, C), n=5)
+    iter_variant = {"ms": iter_ms, "rounds": it["rounds"], "flow": it["flow"], "max_flow": stats["flow_value"],
+                    "score_over_exact_optimum": it["total"] / max(stats["total_score_q"], 1)}
+
     line = {
         "metric": "routed tokens/sec", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -167,6 +174,7 @@ def main():
                       "gemm_hbm_frac": (T * d * 2 + d * E * 2 + T * E * 4) / (gemm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                       "gemm_tflops": 2.0 * T * d * E / (gemm_ms * 1e-3) / 1e12},
         "activation_movement": movement,
+        "iterative_rerouting": iter_variant,
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(args.config, min(args.cpu_sample, T))

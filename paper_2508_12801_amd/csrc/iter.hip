@@ -17,8 +17,6 @@
 namespace maxscore {
 namespace {
 
-constexpr long long kNoKey = LLONG_MIN;
-
 struct IterState {
     unsigned long long total;
     int flow;
@@ -27,28 +25,32 @@ struct IterState {
     int pad;
 };
 
-// larger reward first, then the lower expert id
-__device__ inline long long pref_key(int q, int e) { return (long long)q * 1024 + (1023 - e); }
-
+// Best live expert of a row spread over a wavefront (lane l holds experts l, l+64, ...; bit c of `live` says
+// whether the lane's c-th expert may still be chosen): largest reward, ties to the lower expert id; -1 if no
+// expert is live.
 template <int EPL>
-__device__ inline long long wave_max(const long long (&key)[EPL])
+__device__ inline int wave_best(const int (&val)[EPL], unsigned live)
 {
-    long long m = key[0];
-#pragma unroll
-    for (int c = 1; c < EPL; ++c) m = key[c] > m ? key[c] : m;
-    for (int off = 32; off >= 1; off >>= 1) {
-        const long long o = __shfl_xor(m, off);
-        m = o > m ? o : m;
-    }
-    return m;
-}
-
-template <int EPL>
-__device__ inline void drop_expert(long long (&key)[EPL], int e, int lane)
-{
+    int m = INT_MIN;
 #pragma unroll
     for (int c = 0; c < EPL; ++c)
-        if (c == (e >> 6) && lane == (e & 63)) key[c] = kNoKey;
+        if (((live >> c) & 1) && val[c] > m) m = val[c];
+    for (int off = 32; off >= 1; off >>= 1) {
+        const int o = __shfl_xor(m, off);
+        m = o > m ? o : m;
+    }
+    int e = -1;
+#pragma unroll
+    for (int c = 0; c < EPL; ++c) {
+        const unsigned long long b = __ballot(((live >> c) & 1) && val[c] == m);
+        if (e < 0 && b) e = 64 * c + __ffsll((long long)b) - 1;
+    }
+    return e;
+}
+
+__device__ inline unsigned drop_expert(unsigned live, int e, int lane)
+{
+    return (e >= 0 && lane == (e & 63)) ? live & ~(1u << (e >> 6)) : live;
 }
 
 // choice[s*T + i] <- the token's s-th best expert, s < k (slot-major list).  One wavefront per token row;
@@ -61,17 +63,18 @@ __global__ __launch_bounds__(256) void k_iter_topk(const int32_t *__restrict__ q
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
     for (int row = wave; row < T; row += n_waves) {
-        long long key[EPL];
+        int val[EPL];
+        unsigned live = 0;
 #pragma unroll
         for (int c = 0; c < EPL; ++c) {
             const int e = lane + 64 * c;
-            key[c] = e < E ? pref_key(q[(size_t)row * E + e], e) : kNoKey;
+            val[c] = e < E ? q[(size_t)row * E + e] : 0;
+            live |= (e < E ? 1u : 0u) << c;
         }
         int mine = -1;
         for (int s = 0; s < k; ++s) {
-            const long long best = wave_max<EPL>(key);
-            const int e = 1023 - (int)(best & 1023);
-            drop_expert<EPL>(key, e, lane);
+            const int e = wave_best<EPL>(val, live);
+            live = drop_expert(live, e, lane);
             if (lane == s) mine = e;
         }
         if (lane < k) choice[(size_t)lane * T + row] = mine;
@@ -122,23 +125,22 @@ __global__ __launch_bounds__(256) void k_iter_propose(const int32_t *__restrict_
         unsigned long long holes = __ballot(slot < 0);
         int mine = -1;
         if (holes) {
-            long long key[EPL];
+            int val[EPL];
+            unsigned live = 0;
 #pragma unroll
             for (int c = 0; c < EPL; ++c) {
                 const int e = lane + 64 * c;
-                key[c] = (e < E && s_room[e]) ? pref_key(q[(size_t)row * E + e], e) : kNoKey;
+                const bool ok = e < E && s_room[e];
+                val[c] = ok ? q[(size_t)row * E + e] : 0;
+                live |= (ok ? 1u : 0u) << c;
             }
-            for (int s = 0; s < k; ++s) {
-                const int e = __shfl(slot, s);
-                if (e >= 0) drop_expert<EPL>(key, e, lane);
-            }
+            for (int s = 0; s < k; ++s) live = drop_expert(live, __shfl(slot, s), lane);
             while (holes) {
                 const int s = __ffsll((long long)holes) - 1;
                 holes &= holes - 1;
-                const long long best = wave_max<EPL>(key);
-                if (best == kNoKey) break;
-                const int e = 1023 - (int)(best & 1023);
-                drop_expert<EPL>(key, e, lane);
+                const int e = wave_best<EPL>(val, live);
+                if (e < 0) break;
+                live = drop_expert(live, e, lane);
                 if (lane == s) mine = e;
             }
         }
