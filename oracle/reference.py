@@ -13,6 +13,8 @@ Everything is fp64 / int64 and written to be checked against the paper by eye:
   gates              Eq. 2: the affinity of each selected (token, expert) pair, not renormalised
   dispatch           per-expert buffers (Section 2.3 capacity layout): stable sort by expert
   verify_optimal     independent optimality proof for any assignment (no negative residual cycle)
+  aux_loss           Eq. 9 load-balance loss and its derivative with respect to the scores
+  gates_backward     derivative of the selected scores (and of Eq. 9) with respect to the logits
   iter_reroute       Section 2.3 iterative rerouting: top-k with capacity, then greedy re-proposal rounds
                      (a heuristic; the processing orders are a stated reading, parity with the
                      authors' code is unpinned)
@@ -415,3 +417,40 @@ def iter_reroute(q, k: int, C: int, max_rounds: Optional[int] = None) -> dict:
     got = assign >= 0
     total = int(q[np.nonzero(got)[0], assign[got]].sum())
     return dict(assign=assign, stage1=stage1, load=load, total=total, flow=int(got.sum()), rounds=rounds)
+
+
+# ------------------------------------------------------------------------------------------------
+# training-side by-products: load-balance loss (Eq. 9) and the derivative of the gates
+
+def aux_loss(A, assign, lam: float) -> dict:
+    """Eq. 9: lambda * (1/e) * sum_j mean_i(A_ij) * mean_i(P_ij), P the binary assignment.
+    Also returns the two column means and dL/dA_ij = lambda/(e*n) * mean_i(P_ij) (P is a constant)."""
+    A = np.asarray(A, dtype=np.float64)
+    T, E = A.shape
+    P = assignment_matrix(assign, E).astype(np.float64)
+    mean_A = A.sum(axis=0) / T
+    mean_P = P.sum(axis=0) / T
+    loss = lam * (mean_A * mean_P).sum() / E
+    return dict(loss=float(loss), mean_A=mean_A, mean_P=mean_P, dA=lam / (E * T) * mean_P)
+
+
+def gates_backward(L, k: int, t: float, assign, dgate, dA_all=None) -> np.ndarray:
+    """d(loss)/d(logits) through the gates of Eq. 2 with SoftTopk scores (Eq. 6) whose rank
+    multipliers are constants (they are piecewise constant in the logits, so this is the derivative
+    wherever no two logits of a row tie): A_ij = m_ij * p_ij, p = Softmax(L_i), hence
+    dA_ij/dL_il = A_ij * (delta_jl - p_il).  The upstream gradient is dgate[i, s] on the selected
+    pairs plus, optionally, dA_all[j] on every entry of column j (the Eq. 9 term)."""
+    L = np.asarray(L, dtype=np.float64)
+    T, E = L.shape
+    p = softmax_rows(L)
+    A = soft_topk(L, k, t)
+    gA = np.zeros((T, E), dtype=np.float64)
+    assign = np.asarray(assign)
+    dgate = np.asarray(dgate, dtype=np.float64)
+    for s in range(assign.shape[1]):
+        ok = assign[:, s] >= 0
+        np.add.at(gA, (np.nonzero(ok)[0], assign[ok, s]), dgate[ok, s])
+    if dA_all is not None:
+        gA = gA + np.asarray(dA_all, dtype=np.float64)[None, :]
+    w = gA * A
+    return w - p * w.sum(axis=1, keepdims=True)
