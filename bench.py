@@ -151,6 +151,16 @@ def main():
     iter_variant = {"ms": iter_ms, "rounds": it["rounds"], "flow": it["flow"], "max_flow": stats["flow_value"],
                     "score_over_exact_optimum": it["total"] / max(stats["total_score_q"], 1)}
 
+    # training-side by-products at the same configuration: Eq. 9 loss and the gates' derivative
+    dg = torch.randn(T, k, device=dev)
+    aux = ms.aux_loss(out["scores"], out["expert_offsets"], 0.01)
+    aux_ms = timed(lambda: ms.aux_loss(out["scores"], out["expert_offsets"], 0.01))
+    bwd_ms = timed(lambda: ms.gates_backward(logits, out["scores"], out["assign"], dg, aux["dscores_col"]))
+    bwd_bytes = 3 * T * E * 4 + 2 * T * k * 4
+    training_side = {"aux_loss_ms": aux_ms, "aux_loss": float(aux["loss"].item()),
+                     "gates_backward_ms": bwd_ms, "gates_backward_bytes": bwd_bytes,
+                     "gates_backward_hbm_frac": bwd_bytes / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
     line = {
         "metric": "routed tokens/sec", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -175,6 +185,7 @@ def main():
                       "gemm_tflops": 2.0 * T * d * E / (gemm_ms * 1e-3) / 1e12},
         "activation_movement": movement,
         "iterative_rerouting": iter_variant,
+        "training_side": training_side,
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(args.config, min(args.cpu_sample, T))

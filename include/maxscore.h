@@ -123,6 +123,28 @@ int32_t maxscore_dispatch(const int32_t *assign, const float *gates, int32_t T, 
                           int32_t *expert_offsets, int32_t *disp_token, float *disp_gate,
                           int32_t *token_pos, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Training-side by-products.
+ *
+ * maxscore_aux_loss: the load-balance loss of Eq. 9 (Section 4.1),
+ *   loss = lambda * (1/E) * sum_j mean_i(scores[i, j]) * mean_i(P[i, j]),
+ * with the column counts of P taken from expert_offsets[E+1] (output of maxscore_dispatch).  Device outputs:
+ * loss[1]; mean_scores[E] (may be NULL); dscores_col[E] (may be NULL) = d loss / d scores[i, j], which is the
+ * same for every token i: lambda / (E*T) * mean_i(P[i, j]) (P is a constant).  Column sums are accumulated in
+ * a fixed order (fp32 inside a block of rows, fp64 across blocks): the result is deterministic.  Workspace as
+ * for the other calls (any k); only enqueues.
+ *
+ * maxscore_gates_backward: d loss / d logits through the gates of Eq. 2 with the SoftTopk scores of Eq. 6.
+ * The rank multipliers of Eq. 6 are piecewise constant in the logits, so with A = scores and p = Softmax(logits)
+ *   dlogits[i, l] = gA[i, l]*A[i, l] - p[i, l] * sum_j gA[i, j]*A[i, j],
+ *   gA[i, j] = sum over slots s with assign[i, s] == j of dgates[i, s]  (+ dscores_col[j] if given).
+ * logits, scores [T, E]; assign, dgates [T, k]; dscores_col [E] or NULL; dlogits [T, E] out.  Only enqueues. */
+int32_t maxscore_aux_loss(const float *scores, const int32_t *expert_offsets, int32_t T, int32_t E, float lambda,
+                          float *loss, float *mean_scores, float *dscores_col, void *workspace,
+                          size_t workspace_bytes, void *stream);
+int32_t maxscore_gates_backward(const float *logits, const float *scores, const int32_t *assign,
+                                const float *dgates, const float *dscores_col, int32_t T, int32_t E, int32_t k,
+                                float *dlogits, void *stream);
+
 /* Iterative rerouting (Section 2.3, the second stage drawn in Figure 1(c); the assignment step of the
  * "-I" variants of Section 4): a fast greedy alternative to maxscore_assign_i32 on the same integer rewards.
  * Stage 1 keeps, per expert, the first C of the tokens' top-k choices taken in the order (choice rank, token

@@ -44,6 +44,11 @@ _SIGS = {
                                                 ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "maxscore_assign_iter_i32": (ctypes.c_int32, [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p] * 5 +
                                  [ctypes.c_size_t, ctypes.c_void_p]),
+    "maxscore_aux_loss": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                           ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "maxscore_gates_backward": (ctypes.c_int32, [ctypes.c_void_p] * 5 + [ctypes.c_int32] * 3 +
+                                [ctypes.c_void_p, ctypes.c_void_p]),
     "maxscore_softtopk": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.c_float, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                            ctypes.c_void_p]),
@@ -229,6 +234,38 @@ def assign_iter_i32(q, k: int, C: int, max_rounds: int = 0, allow_not_converged=
                                                  ctypes.addressof(rounds), _ptr(ws), need, _stream())
     _check(rc, "maxscore_assign_iter_i32", allow=(ERR_NOT_CONVERGED,) if allow_not_converged else ())
     return dict(assign=assign, total=total.value, flow=flow.value, rounds=rounds.value, rc=rc)
+
+
+def aux_loss(scores, expert_offsets, lam: float):
+    """Eq. 9.  Returns dict(loss[1], mean_scores[E], dscores_col[E]) as device tensors."""
+    torch = _torch()
+    T, E = scores.shape
+    assert scores.dtype == torch.float32 and scores.is_contiguous()
+    assert expert_offsets.dtype == torch.int32 and expert_offsets.numel() == E + 1
+    dev = scores.device
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    mean_scores = torch.empty(E, dtype=torch.float32, device=dev)
+    dcol = torch.empty(E, dtype=torch.float32, device=dev)
+    ws, need = _workspace(T, E, 1, 1, dev)
+    rc = load_library().maxscore_aux_loss(_ptr(scores), _ptr(expert_offsets), T, E, float(lam), _ptr(loss),
+                                          _ptr(mean_scores), _ptr(dcol), _ptr(ws), need, _stream())
+    _check(rc, "maxscore_aux_loss")
+    return dict(loss=loss, mean_scores=mean_scores, dscores_col=dcol)
+
+
+def gates_backward(logits, scores, assign, dgates, dscores_col=None):
+    """d loss / d logits [T, E] from d loss / d gates [T, k] (and, optionally, a per-column score gradient)."""
+    torch = _torch()
+    T, E = logits.shape
+    k = assign.shape[1]
+    for a in (logits, scores, dgates):
+        assert a.dtype == torch.float32 and a.is_contiguous()
+    assert assign.dtype == torch.int32 and assign.is_contiguous() and dgates.shape == assign.shape
+    out = torch.empty_like(logits)
+    rc = load_library().maxscore_gates_backward(_ptr(logits), _ptr(scores), _ptr(assign), _ptr(dgates),
+                                                _ptr(dscores_col), T, E, k, _ptr(out), _stream())
+    _check(rc, "maxscore_gates_backward")
+    return out
 
 
 def gates(scores, assign):

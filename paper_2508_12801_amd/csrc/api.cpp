@@ -100,6 +100,27 @@ int32_t maxscore_assign_i32(const int32_t *q, int32_t T, int32_t E, int32_t k, i
                       (hipStream_t)stream);
 }
 
+int32_t maxscore_aux_loss(const float *scores, const int32_t *expert_offsets, int32_t T, int32_t E, float lambda,
+                          float *loss, float *mean_scores, float *dscores_col, void *workspace,
+                          size_t workspace_bytes, void *stream)
+{
+    if (!scores || !expert_offsets || !loss) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, 1, 1)) return MAXSCORE_ERR_SHAPE;
+    int32_t rc = check_ws(workspace, workspace_bytes, T, E, 1);
+    if (rc) return rc;
+    return aux_loss_run(scores, expert_offsets, T, E, lambda, loss, mean_scores, dscores_col, (char *)workspace,
+                        (hipStream_t)stream);
+}
+
+int32_t maxscore_gates_backward(const float *logits, const float *scores, const int32_t *assign,
+                                const float *dgates, const float *dscores_col, int32_t T, int32_t E, int32_t k,
+                                float *dlogits, void *stream)
+{
+    if (!logits || !scores || !assign || !dgates || !dlogits) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, k, 1)) return MAXSCORE_ERR_SHAPE;
+    return gates_backward_run(logits, scores, assign, dgates, dscores_col, T, E, k, dlogits, (hipStream_t)stream);
+}
+
 int32_t maxscore_assign_iter_i32(const int32_t *q, int32_t T, int32_t E, int32_t k, int32_t C, int32_t max_rounds,
                                  int32_t *assign, int64_t *total, int32_t *flow, int32_t *rounds, void *workspace,
                                  size_t workspace_bytes, void *stream)

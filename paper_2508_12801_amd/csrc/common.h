@@ -76,6 +76,11 @@ int32_t dispatch_core(const int32_t *list, const float *gates, size_t n, int E, 
 // --- iter.hip
 int32_t iter_run(const int32_t *q, int T, int E, int k, int C, int max_rounds, int32_t *assign, int64_t *total,
                  int32_t *flow, int32_t *rounds, char *ws, hipStream_t s);
+// --- training.hip
+int32_t aux_loss_run(const float *scores, const int32_t *offsets, int T, int E, float lam, float *loss,
+                     float *mean_scores, float *dscores_col, char *ws, hipStream_t s);
+int32_t gates_backward_run(const float *logits, const float *scores, const int32_t *assign, const float *dgates,
+                           const float *dscores_col, int T, int E, int k, float *dlogits, hipStream_t s);
 // --- movement.hip
 int32_t dispatch_tokens_run(const void *x, int dtype, const int32_t *offsets, const int32_t *disp_token, int T, int d,
                             int E, int C, void *out, hipStream_t s);
