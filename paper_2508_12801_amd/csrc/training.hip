@@ -50,8 +50,10 @@ __global__ __launch_bounds__(1024) void k_aux_final(const float *__restrict__ pa
     {
         const int j = tid % epad, g = tid / epad;
         double sum = 0.0;
-        if (j < E)
+        if (j < E) {
+#pragma unroll 8
             for (int b = g; b < n_blocks; b += groups) sum += (double)part[(size_t)b * E + j];
+        }
         s_red[g * epad + j] = sum;
     }
     __syncthreads();
