@@ -13,6 +13,7 @@ Everything is fp64 / int64 and written to be checked against the paper by eye:
   gates              Eq. 2: the affinity of each selected (token, expert) pair, not renormalised
   dispatch           per-expert buffers (Section 2.3 capacity layout): stable sort by expert
   verify_optimal     independent optimality proof for any assignment (no negative residual cycle)
+  sigmoid_scores, softkmax, itertopk   other operators of Table 2 (base cases are a stated reading)
   aux_loss           Eq. 9 load-balance loss and its derivative with respect to the scores
   gates_backward     derivative of the selected scores (and of Eq. 9) with respect to the logits
   iter_reroute       Section 2.3 iterative rerouting: top-k with capacity, then greedy re-proposal rounds
@@ -454,3 +455,35 @@ def gates_backward(L, k: int, t: float, assign, dgate, dA_all=None) -> np.ndarra
         gA = gA + np.asarray(dA_all, dtype=np.float64)[None, :]
     w = gA * A
     return w - p * w.sum(axis=1, keepdims=True)
+
+
+# ------------------------------------------------------------------------------------------------
+# other routing operators of Table 2 (alternatives to SoftTopk for the affinity scores)
+
+def sigmoid_scores(L: np.ndarray) -> np.ndarray:
+    """Table 2, row 2: y = 1 / (1 + e^-x), element-wise."""
+    return 1.0 / (1.0 + np.exp(-np.asarray(L, dtype=np.float64)))
+
+
+def softkmax(L: np.ndarray, k: int) -> np.ndarray:
+    """Table 2, SoftKmax: y^(m) = y^(m-1) + Softmax(g^(m-1)), g^(m-1) = (1 - y^(m-1)) (x) x.
+    The table gives no base case; reading: y^(0) = 0, so that level 1 is Softmax(x)."""
+    x = np.asarray(L, dtype=np.float64)
+    y = np.zeros_like(x)
+    for _ in range(k):
+        g = (1.0 - y) * x
+        y = y + softmax_rows(g)
+    return y
+
+
+def itertopk(L: np.ndarray, k: int) -> np.ndarray:
+    """Table 2, IterTopk: y^(m) = y^(m-1) + g(x; 1 - y^(m-1)), g(x; w) = w e^x / sum_j w_j e^x_j.
+    Base case as above: y^(0) = 0.  The weights 1 - y may turn negative from level 3 on; the
+    expression is evaluated as printed."""
+    x = np.asarray(L, dtype=np.float64)
+    ex = np.exp(x - x.max(axis=1, keepdims=True))      # a common factor of e^x cancels in g
+    y = np.zeros_like(x)
+    for _ in range(k):
+        w = 1.0 - y
+        y = y + w * ex / (w * ex).sum(axis=1, keepdims=True)
+    return y
