@@ -161,6 +161,13 @@ def main():
                      "gates_backward_ms": bwd_ms, "gates_backward_bytes": bwd_bytes,
                      "gates_backward_hbm_frac": bwd_bytes / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
+    # the other operators of Table 2 as alternative score kernels (same rows, 12*T*E bytes each)
+    operators = {}
+    for op, levels in (("sigmoid", 1), ("softkmax", k), ("itertopk", 2)):
+        op_ms = timed(lambda: ms.scores_op(logits, levels, op))
+        operators[op] = {"levels": levels, "ms": op_ms,
+                         "hbm_frac": 12 * T * E / (op_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
     line = {
         "metric": "routed tokens/sec", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -186,6 +193,7 @@ def main():
         "activation_movement": movement,
         "iterative_rerouting": iter_variant,
         "training_side": training_side,
+        "table2_operators": operators,
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(args.config, min(args.cpu_sample, T))

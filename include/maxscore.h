@@ -123,6 +123,20 @@ int32_t maxscore_dispatch(const int32_t *assign, const float *gates, int32_t T, 
                           int32_t *expert_offsets, int32_t *disp_token, float *disp_gate,
                           int32_t *token_pos, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Other routing operators of Table 2 (Section 3.1) in place of SoftTopk: scores[T, E] and/or the integer
+ * rewards q = round-half-even(score * 2^quant_shift) (either output may be NULL, not both).
+ *   MAXSCORE_OP_SIGMOID   y = 1 / (1 + e^-x)
+ *   MAXSCORE_OP_SOFTKMAX  y^(m) = y^(m-1) + Softmax((1 - y^(m-1)) * x), m = 1..k
+ *   MAXSCORE_OP_ITERTOPK  y^(m) = y^(m-1) + w e^x / sum_j w_j e^x_j with w = 1 - y^(m-1), m = 1..k
+ * The table gives no base case: y^(0) = 0 is used (level 1 is Softmax).  IterTopk is evaluated as printed
+ * (its weights may turn negative from level 3 on; a row whose weighted sum reaches 0 gives non-finite
+ * values).  The integer rewards are only meaningful when score * 2^quant_shift fits 32 bits.  Only enqueues. */
+#define MAXSCORE_OP_SIGMOID 1
+#define MAXSCORE_OP_SOFTKMAX 2
+#define MAXSCORE_OP_ITERTOPK 3
+int32_t maxscore_scores_op(const float *logits, int32_t T, int32_t E, int32_t k, int32_t op, int32_t quant_shift,
+                           float *scores, int32_t *q, void *stream);
+
 /* Training-side by-products.
  *
  * maxscore_aux_loss: the load-balance loss of Eq. 9 (Section 4.1),

@@ -49,6 +49,7 @@ _SIGS = {
                                            ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "maxscore_gates_backward": (ctypes.c_int32, [ctypes.c_void_p] * 5 + [ctypes.c_int32] * 3 +
                                 [ctypes.c_void_p, ctypes.c_void_p]),
+    "maxscore_scores_op": (ctypes.c_int32, [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p] * 3),
     "maxscore_softtopk": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.c_float, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                            ctypes.c_void_p]),
@@ -201,6 +202,22 @@ def softtopk(logits, k: int, t: float, quant_shift: int = 20):
     rc = load_library().maxscore_softtopk(_ptr(logits), T, E, k, float(t), quant_shift, _ptr(scores), _ptr(q),
                                           _stream())
     _check(rc, "maxscore_softtopk")
+    return scores, q
+
+
+OPS = {"sigmoid": 1, "softkmax": 2, "itertopk": 3}
+
+
+def scores_op(logits, k: int, op: str, quant_shift: int = 20):
+    """Another operator of Table 2 in place of SoftTopk: (scores fp32 [T,E], q int32 [T,E])."""
+    torch = _torch()
+    T, E = logits.shape
+    assert logits.dtype == torch.float32 and logits.is_contiguous()
+    scores = torch.empty_like(logits)
+    q = torch.empty((T, E), dtype=torch.int32, device=logits.device)
+    rc = load_library().maxscore_scores_op(_ptr(logits), T, E, k, OPS[op], quant_shift, _ptr(scores), _ptr(q),
+                                           _stream())
+    _check(rc, "maxscore_scores_op")
     return scores, q
 
 

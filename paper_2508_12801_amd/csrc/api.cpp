@@ -100,6 +100,16 @@ int32_t maxscore_assign_i32(const int32_t *q, int32_t T, int32_t E, int32_t k, i
                       (hipStream_t)stream);
 }
 
+int32_t maxscore_scores_op(const float *logits, int32_t T, int32_t E, int32_t k, int32_t op, int32_t quant_shift,
+                           float *scores, int32_t *q, void *stream)
+{
+    if (!logits || (!scores && !q)) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, k, 1) || quant_shift < 1 || quant_shift > 24) return MAXSCORE_ERR_SHAPE;
+    if (op != MAXSCORE_OP_SIGMOID && op != MAXSCORE_OP_SOFTKMAX && op != MAXSCORE_OP_ITERTOPK)
+        return MAXSCORE_ERR_SHAPE;
+    return scores_op_run(logits, T, E, k, op, quant_shift, scores, q, (hipStream_t)stream);
+}
+
 int32_t maxscore_aux_loss(const float *scores, const int32_t *expert_offsets, int32_t T, int32_t E, float lambda,
                           float *loss, float *mean_scores, float *dscores_col, void *workspace,
                           size_t workspace_bytes, void *stream)

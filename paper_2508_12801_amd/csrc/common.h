@@ -76,6 +76,9 @@ int32_t dispatch_core(const int32_t *list, const float *gates, size_t n, int E, 
 // --- iter.hip
 int32_t iter_run(const int32_t *q, int T, int E, int k, int C, int max_rounds, int32_t *assign, int64_t *total,
                  int32_t *flow, int32_t *rounds, char *ws, hipStream_t s);
+// --- operators.hip
+int32_t scores_op_run(const float *logits, int T, int E, int k, int op, int shift, float *scores, int32_t *q,
+                      hipStream_t s);
 // --- training.hip
 int32_t aux_loss_run(const float *scores, const int32_t *offsets, int T, int E, float lam, float *loss,
                      float *mean_scores, float *dscores_col, char *ws, hipStream_t s);
