@@ -148,7 +148,18 @@ def main():
     # rounds and how much of the exact optimum it reaches
     it = ms.assign_iter_i32(out["q"], k, C)
     iter_ms = timed(lambda: ms.assign_iter_i32(out["q"], k, C), n=5)
-    iter_variant = {"ms": iter_ms, "rounds": it["rounds"], "flow": it["flow"], "max_flow": stats["flow_value"],
+    out_i = None
+    for _ in range(2):
+        out_i = ms.route_xw(x, W, b, k, C, t=r.t, out=out_i, assignment="iter")
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(10):
+        out_i = ms.route_xw(x, W, b, k, C, t=r.t, out=out_i, assignment="iter")
+    torch.cuda.synchronize()
+    iter_path_ms = (time.perf_counter() - t0) / 10 * 1e3
+    del out_i
+    iter_variant = {"ms": iter_ms, "whole_path_ms_per_call": iter_path_ms,
+                    "whole_path_tokens_per_s": T / (iter_path_ms * 1e-3), "rounds": it["rounds"], "flow": it["flow"], "max_flow": stats["flow_value"],
                     "score_over_exact_optimum": it["total"] / max(stats["total_score_q"], 1)}
 
     # training-side by-products at the same configuration: Eq. 9 loss and the gates' derivative

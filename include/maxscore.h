@@ -64,7 +64,12 @@ typedef struct {
     int32_t quant_shift;  /* rewards are round(A * 2^quant_shift); 1..24 */
     int32_t max_rounds;   /* cap on solver rounds (bid pass + select pass) */
     int32_t eps_div;      /* eps-scaling ratio between solver phases, >= 2 */
+    int32_t assignment;   /* maxscore_route_* only: MAXSCORE_ASSIGN_EXACT (0, the exact solver) or
+                             MAXSCORE_ASSIGN_ITER (1, iterative rerouting: prices are not written,
+                             stats carry total, flow and the number of rerouting rounds) */
 } maxscore_opts;
+#define MAXSCORE_ASSIGN_EXACT 0
+#define MAXSCORE_ASSIGN_ITER 1
 
 /* Filled on the HOST when the call returns (may be NULL). */
 typedef struct {

@@ -21,7 +21,7 @@ class MaxScoreError(RuntimeError):
 
 class _Opts(ctypes.Structure):
     _fields_ = [("t", ctypes.c_float), ("quant_shift", ctypes.c_int32), ("max_rounds", ctypes.c_int32),
-                ("eps_div", ctypes.c_int32)]
+                ("eps_div", ctypes.c_int32), ("assignment", ctypes.c_int32)]
 
 
 class Stats(ctypes.Structure):
@@ -149,8 +149,11 @@ def _workspace(T, E, k, C, device, d=0):
     return buf, need
 
 
-def _opts(t=1.0, quant_shift=20, max_rounds=200000, eps_div=12):
-    return _Opts(float(t), int(quant_shift), int(max_rounds), int(eps_div))
+ASSIGNMENTS = {"exact": 0, "iter": 1}
+
+
+def _opts(t=1.0, quant_shift=20, max_rounds=200000, eps_div=12, assignment="exact"):
+    return _Opts(float(t), int(quant_shift), int(max_rounds), int(eps_div), ASSIGNMENTS[assignment])
 
 
 def set_kernel_timing(on: bool) -> None:
@@ -362,15 +365,15 @@ def _route_outputs(T, E, k, dev):
 
 
 def route_logits(logits, k: int, C: int, t: float = 1.0, quant_shift: int = 20, max_rounds: int = 200000,
-                 eps_div: int = 12, out: Optional[dict] = None):
-    """a2..a6 from logits."""
+                 eps_div: int = 12, out: Optional[dict] = None, assignment: str = "exact"):
+    """a2..a6 from logits; assignment = "exact" (the solver) or "iter" (iterative rerouting)."""
     torch = _torch()
     T, E = logits.shape
     assert logits.dtype == torch.float32 and logits.is_contiguous()
     o = out if out is not None else _route_outputs(T, E, k, logits.device)
     ws, need = _workspace(T, E, k, C, logits.device)
     stats = Stats()
-    opts = _opts(t, quant_shift, max_rounds, eps_div)
+    opts = _opts(t, quant_shift, max_rounds, eps_div, assignment)
     rc = load_library().maxscore_route_logits(
         _ptr(logits), T, E, k, C, ctypes.byref(opts), _ptr(o["scores"]), _ptr(o["q"]), _ptr(o["assign"]),
         _ptr(o["gates"]), _ptr(o["expert_offsets"]), _ptr(o["disp_token"]), _ptr(o["disp_gate"]),
@@ -382,7 +385,7 @@ def route_logits(logits, k: int, C: int, t: float = 1.0, quant_shift: int = 20, 
 
 
 def route_xw(x, W, bias, k: int, C: int, t: float = 1.0, quant_shift: int = 20, max_rounds: int = 200000,
-             eps_div: int = 12, out: Optional[dict] = None):
+             eps_div: int = 12, out: Optional[dict] = None, assignment: str = "exact"):
     """a1..a6 from x and W_g."""
     torch = _torch()
     T, d = x.shape
@@ -393,7 +396,7 @@ def route_xw(x, W, bias, k: int, C: int, t: float = 1.0, quant_shift: int = 20, 
         o["logits"] = torch.empty((T, E), dtype=torch.float32, device=x.device)
     ws, need = _workspace(T, E, k, C, x.device, d)
     stats = Stats()
-    opts = _opts(t, quant_shift, max_rounds, eps_div)
+    opts = _opts(t, quant_shift, max_rounds, eps_div, assignment)
     rc = load_library().maxscore_route_xw(
         _ptr(x), _ptr(W), _ptr(bias), _in_dtype(x), T, d, E, k, C, ctypes.byref(opts), _ptr(o["logits"]),
         _ptr(o["scores"]), _ptr(o["q"]), _ptr(o["assign"]), _ptr(o["gates"]), _ptr(o["expert_offsets"]),

@@ -34,7 +34,7 @@ static bool shape_ok(int T, int E, int k, int C)
 
 static maxscore_opts resolve(const maxscore_opts *o)
 {
-    maxscore_opts r = {1.0f, 20, 200000, 12};
+    maxscore_opts r = {1.0f, 20, 200000, 12, MAXSCORE_ASSIGN_EXACT};
     if (o) {
         r = *o;
         if (r.quant_shift == 0) r.quant_shift = 20;
@@ -204,7 +204,22 @@ int32_t maxscore_route_logits(const float *logits, int32_t T, int32_t E, int32_t
     if (stats) std::memset(stats, 0, sizeof(*stats));
     rc = softtopk_run(logits, T, E, k, o.t, o.quant_shift, scores_out, q_out, s);
     if (rc) return rc;
-    int32_t src = solver_run(q_out, T, E, k, Ce, o, assign, prices, nullptr, stats, (char *)workspace, s);
+    int32_t src;
+    if (o.assignment == MAXSCORE_ASSIGN_ITER) {
+        int64_t total = 0;
+        int32_t flow = 0, rounds = 0;
+        src = iter_run(q_out, T, E, k, C, o.max_rounds, assign, &total, &flow, &rounds, (char *)workspace, s);
+        if (stats) {
+            stats->total_score_q = total;
+            stats->flow_value = flow;
+            stats->rounds = rounds;
+            stats->status = src;
+        }
+    } else if (o.assignment == MAXSCORE_ASSIGN_EXACT) {
+        src = solver_run(q_out, T, E, k, Ce, o, assign, prices, nullptr, stats, (char *)workspace, s);
+    } else {
+        return MAXSCORE_ERR_SHAPE;
+    }
     if (src != MAXSCORE_OK && src != MAXSCORE_ERR_NOT_CONVERGED) return src;
     rc = gates_run(scores_out, assign, T, E, k, gates, s);
     if (rc) return rc;

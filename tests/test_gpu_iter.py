@@ -115,3 +115,23 @@ def test_gates_and_dispatch_accept_the_result(ms):
     assert np.array_equal(d["expert_offsets"].cpu().numpy(), ref_d["expert_offsets"])
     assert np.array_equal(d["disp_token"].cpu().numpy()[: out["flow"]], ref_d["disp_token"])
     assert np.array_equal(d["token_pos"].cpu().numpy(), ref_d["token_pos"])
+
+
+def test_whole_path_with_iterative_rerouting(ms):
+    print("iter whole path", flush=True)
+    c = CONFIGS["cfg3"]
+    L = make_logits("cfg3", 3)
+    out = ms.route_logits(dev(L), c["k"], c["C"], t=c["t"], assignment="iter")
+    q = out["q"].cpu().numpy().astype(np.int64)
+    ref = oracle.iter_reroute(q, c["k"], c["C"])
+    a = out["assign"].cpu().numpy()
+    assert np.array_equal(a, ref["assign"])
+    st = out["stats"]
+    assert st["total_score_q"] == ref["total"] and st["flow_value"] == ref["flow"] and st["rounds"] == ref["rounds"]
+    sc = out["scores"].cpu().numpy().astype(np.float64)
+    ref_g = oracle.gates(sc, a)
+    assert np.allclose(out["gates"].cpu().numpy(), ref_g, rtol=1e-6, atol=0)
+    ref_d = oracle.dispatch(a, ref_g, c["E"])
+    assert np.array_equal(out["expert_offsets"].cpu().numpy(), ref_d["expert_offsets"])
+    assert np.array_equal(out["token_pos"].cpu().numpy(), ref_d["token_pos"])
+    assert np.array_equal(out["disp_token"].cpu().numpy()[: ref["flow"]], ref_d["disp_token"])
