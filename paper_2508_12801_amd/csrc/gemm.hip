@@ -3,7 +3,8 @@
 // bf16 inputs run on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).  The output
 // is only E <= 128 columns wide per workgroup, so the kernel is bound by streaming x from HBM:
 // each workgroup owns 128 token rows, walks d in steps of 64, stages the x tile and the transposed
-// W tile in LDS and prefetches the next tiles into registers while the matrix cores work.
+// W tile in LDS and prefetches the next tiles into registers while the matrix cores work.  The fast
+// kernel (k_gemm_bf16_wtc) reads x with whole-line loads and restores the operand layout through LDS.
 // fp32 inputs (the tiny configuration) use a plain FMA kernel.
 #include "common.h"
 
@@ -242,6 +243,126 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_wt(const unsigned short *__re
     }
 }
 
+// Same tiling, but x reaches the matrix cores through a wavefront-private LDS tile: every global load
+// instruction then reads whole 128-byte lines (8 rows x 128 B, 8 lanes per row) instead of 32 rows x 32 B in the
+// MFMA operand layout, which is what the memory pipeline prefers; the operand layout is restored by the LDS
+// read.  Needs d to be a multiple of 64.
+template <int NT, int RB, int NS>
+__global__ __launch_bounds__(256) void k_gemm_bf16_wtc(const unsigned short *__restrict__ x,
+                                                       const unsigned short *__restrict__ wt,
+                                                       const float *__restrict__ bias, int T, int d, int E,
+                                                       float *__restrict__ out)
+{
+    constexpr int BN = 32 * NT;
+    constexpr int RW = 32 * RB;                  // rows per wavefront
+    constexpr int NL = 4 * RB;                   // global loads per lane and slab
+    __shared__ __attribute__((aligned(16))) unsigned short sB[2][BN * LDP];
+    __shared__ __attribute__((aligned(16))) unsigned short sA[4][RW * LDP];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int row0 = blockIdx.x * (4 * RW), col0 = blockIdx.y * 128;
+    const int kq = 8 * (lane >> 5);
+    const int lr = lane >> 3, lc = (lane & 7) * 8;          // loader: row inside a group of 8, column of the slab
+    const unsigned short *xp[NL];
+    bool ok[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        const int r = row0 + wave * RW + 8 * i + lr;
+        ok[i] = r < T;
+        xp[i] = x + (size_t)(ok[i] ? r : 0) * d + lc;
+    }
+    constexpr int B_VECS = BN * 8;
+    constexpr int B_PER = (B_VECS + 255) / 256;
+    u32x4 ra[NS][NL], rb[B_PER];          // NS slabs of x in flight per wavefront
+    auto fetch_a = [&](int k0, u32x4(&dst)[NL]) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) dst[i] = ok[i] ? *(const u32x4 *)(xp[i] + k0) : u32x4{0u, 0u, 0u, 0u};
+    };
+    auto fetch_b = [&](int k0) {
+#pragma unroll
+        for (int p = 0; p < B_PER; ++p) {
+            const int v = tid + 256 * p;
+            const int n = v >> 3, kk = k0 + (v & 7) * 8;
+            rb[p] = (v < B_VECS && col0 + n < E) ? *(const u32x4 *)(wt + (size_t)(col0 + n) * d + kk)
+                                                 : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    auto stash_b = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < B_PER; ++p) {
+            const int v = tid + 256 * p;
+            if (v < B_VECS) *(u32x4 *)&sB[buf][(v >> 3) * LDP + (v & 7) * 8] = rb[p];
+        }
+    };
+    f32x16 acc[RB][NT];
+#pragma unroll
+    for (int b = 0; b < RB; ++b)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[b][nt][i] = 0.f;
+
+    // Workgroups walk d in rotated orders: at any moment they read different column slabs of x, which spreads
+    // the 2*d-byte row stride over the memory channels.
+    const int nslab = d / BK;
+    const int rot = (int)((blockIdx.x * 7u + (blockIdx.x >> 5)) % (unsigned)nslab);
+    auto kof = [&](int i) {
+        int sidx = i + rot;
+        if (sidx >= nslab) sidx -= nslab;
+        return sidx * BK;
+    };
+    fetch_a(kof(0), ra[0]);
+    fetch_b(kof(0));
+#pragma unroll
+    for (int i = 1; i < NS; ++i)
+        if (i < nslab) fetch_a(kof(i), ra[i]);
+    stash_b(0);
+    int buf = 0;
+    unsigned short *myA = sA[wave];
+    auto step = [&](int it, u32x4(&cur)[NL]) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) *(u32x4 *)&myA[(8 * i + lr) * LDP + lc] = cur[i];
+        __syncthreads();                         // sB[buf] and this wavefront's x tile are complete
+        const bool more = it + 1 < nslab;
+        if (more) fetch_b(kof(it + 1));
+        if (it + NS < nslab) fetch_a(kof(it + NS), cur);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            bf16x8 a[RB];
+#pragma unroll
+            for (int b = 0; b < RB; ++b) a[b] = *(const bf16x8 *)&myA[(32 * b + (lane & 31)) * LDP + 16 * j + kq];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                bf16x8 bv = *(const bf16x8 *)&sB[buf][(nt * 32 + (lane & 31)) * LDP + 16 * j + kq];
+#pragma unroll
+                for (int b = 0; b < RB; ++b)
+                    acc[b][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[b], bv, acc[b][nt], 0, 0, 0);
+            }
+        }
+        if (more) stash_b(buf ^ 1);
+        buf ^= 1;
+    };
+    for (int it = 0; it < nslab; it += NS) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+            if (it + i < nslab) step(it + i, ra[i]);
+    }
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int col = col0 + nt * 32 + (lane & 31);
+        if (col >= E) continue;
+        const float bvs = bias ? bias[col] : 0.f;
+#pragma unroll
+        for (int b = 0; b < RB; ++b)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    int row = row0 + wave * RW + 32 * b + 8 * j + 4 * (lane >> 5) + i;
+                    if (row < T) out[(size_t)row * E + col] = acc[b][nt][4 * j + i] + bvs;
+                }
+    }
+}
+
 __global__ __launch_bounds__(256) void k_gemm_f32(const float *__restrict__ x, const float *__restrict__ W,
                                                   const float *__restrict__ bias, int T, int d, int E,
                                                   float *__restrict__ out)
@@ -282,6 +403,17 @@ int32_t gemm_run(const void *x, const void *W, const float *bias, int dtype, int
     if (wt_scratch && d % 8 == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)wt_scratch % 16) == 0) {
         unsigned short *wt = (unsigned short *)wt_scratch;
         hipLaunchKernelGGL(k_transpose_w, dim3((d + 31) / 32, (E + 31) / 32), dim3(256), 0, s, wb, wt, d, E);
+#define MS_GEMM3(NT_) \
+    hipLaunchKernelGGL((k_gemm_bf16_wtc<NT_, 1, 2>), grid, dim3(256), 0, s, xb, wt, bias, T, d, E, logits)
+        if (d % BK == 0) {
+            if (nt == 1) MS_GEMM3(1);
+            else if (nt == 2) MS_GEMM3(2);
+            else if (nt == 3) MS_GEMM3(3);
+            else MS_GEMM3(4);
+            MS_HIP(hipGetLastError());
+            return MAXSCORE_OK;
+        }
+#undef MS_GEMM3
 #define MS_GEMM2(NT_) hipLaunchKernelGGL((k_gemm_bf16_wt<NT_>), grid, dim3(256), 0, s, xb, wt, bias, T, d, E, logits)
         if (nt == 1) MS_GEMM2(1);
         else if (nt == 2) MS_GEMM2(2);
