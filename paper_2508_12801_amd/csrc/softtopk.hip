@@ -24,8 +24,9 @@ __device__ __forceinline__ unsigned ord_f32(float x)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// A group of G lanes owns one row; lane l owns the EPL consecutive columns l*EPL .. l*EPL+EPL-1, so a
-// wavefront reads 64/G consecutive rows with contiguous 16-byte loads.
+// A group of G lanes owns one row.  Vector path (E == G*EPL): lane l owns the 4-column pieces l, l+G, l+2G, ...
+// of the row, so each 16-byte load instruction of a wavefront covers whole 128-byte lines of 64/G consecutive
+// rows.  Scalar path: lane l owns the EPL consecutive columns l*EPL .. l*EPL+EPL-1.
 template <int G, int EPL, bool VEC>
 __global__ __launch_bounds__(256) void k_softtopk(const float *__restrict__ logits, int T, int E, int k, float t,
                                                   float qscale, float *__restrict__ scores,
@@ -33,13 +34,15 @@ __global__ __launch_bounds__(256) void k_softtopk(const float *__restrict__ logi
 {
     const int tid = threadIdx.x, lane = tid & 63, lg = lane & (G - 1);
     const int grp = tid / G, ngrp = 256 / G;
+    constexpr bool kVec = VEC && EPL >= 4;
+    auto colof = [&](int m) { return kVec ? ((m >> 2) * (4 * G) + lg * 4 + (m & 3)) : (lg * EPL + m); };
     for (int row = blockIdx.x * ngrp + grp; row < T; row += gridDim.x * ngrp) {
         const float *lr = logits + (size_t)row * E + lg * EPL;
         float x[EPL];
-        if (VEC && EPL >= 4) {
+        if (kVec) {
 #pragma unroll
             for (int m = 0; m < EPL; m += 4) {
-                float4 v4 = *(const float4 *)(lr + m);
+                float4 v4 = *(const float4 *)(logits + (size_t)row * E + colof(m));
                 x[m] = v4.x; x[m + 1] = v4.y; x[m + 2] = v4.z; x[m + 3] = v4.w;
             }
         } else {
@@ -55,7 +58,7 @@ __global__ __launch_bounds__(256) void k_softtopk(const float *__restrict__ logi
         float sum = 0.f;
 #pragma unroll
         for (int m = 0; m < EPL; ++m) {
-            ex[m] = (lg * EPL + m < E) ? expf(x[m] - mx) : 0.f;
+            ex[m] = (colof(m) < E) ? expf(x[m] - mx) : 0.f;
             sum += ex[m];
         }
 #pragma unroll
@@ -74,20 +77,21 @@ __global__ __launch_bounds__(256) void k_softtopk(const float *__restrict__ logi
 #pragma unroll
                 for (int m = 0; m < EPL; ++m) {
                     const unsigned o = ord_f32(x[m]);
-                    const bool take = (lg * EPL + m < E) && !((taken >> m) & 1u) && (bm < 0 || o > bo);
+                    const bool take = (colof(m) < E) && !((taken >> m) & 1u) && (bm < 0 || o > bo);
                     bo = take ? o : bo;
                     bm = take ? m : bm;
                 }
                 unsigned long long best =
-                    bm >= 0 ? (((unsigned long long)bo << 10) | (unsigned)(1023 - (lg * EPL + bm))) : 0ull;
+                    bm >= 0 ? (((unsigned long long)bo << 10) | (unsigned)(1023 - colof(bm))) : 0ull;
 #pragma unroll
                 for (int off = G / 2; off > 0; off >>= 1) {
                     unsigned long long o = shfl_xor_u64(best, off);
                     best = o > best ? o : best;
                 }
                 const int e = 1023 - (int)(best & 1023);
-                if (e / EPL == lg) {
-                    const int m = e % EPL;
+                const bool mine = kVec ? (((e >> 2) & (G - 1)) == lg) : (e / EPL == lg);
+                if (mine) {
+                    const int m = kVec ? ((e / (4 * G)) * 4 + (e & 3)) : (e % EPL);
 #pragma unroll
                     for (int mm = 0; mm < EPL; ++mm)
                         if (mm == m) rk[mm] = r;
@@ -104,11 +108,12 @@ __global__ __launch_bounds__(256) void k_softtopk(const float *__restrict__ logi
             qq[m] = __float2int_rn(sc[m] * qscale);
         }
         const size_t o0 = (size_t)row * E + lg * EPL;
-        if (VEC && EPL >= 4) {
+        if (kVec) {
 #pragma unroll
             for (int m = 0; m < EPL; m += 4) {
-                if (scores) *(float4 *)(scores + o0 + m) = make_float4(sc[m], sc[m + 1], sc[m + 2], sc[m + 3]);
-                if (q) *(int4 *)(q + o0 + m) = make_int4(qq[m], qq[m + 1], qq[m + 2], qq[m + 3]);
+                const size_t o = (size_t)row * E + colof(m);
+                if (scores) *(float4 *)(scores + o) = make_float4(sc[m], sc[m + 1], sc[m + 2], sc[m + 3]);
+                if (q) *(int4 *)(q + o) = make_int4(qq[m], qq[m + 1], qq[m + 2], qq[m + 3]);
             }
         } else {
 #pragma unroll
