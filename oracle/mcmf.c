@@ -47,10 +47,12 @@ static void g_add(graph_t *g, int a, int b, int cap, int64_t cost)
 
 /* Returns 0 on success.  P[T*E] receives the assignment, *flow the flow value, *total the
  * reward sum, *n_arcs the number of arcs of Table 1 that were built (without twins). */
-int mcmf_literal(const int64_t *q, int T, int E, int k, int C, uint8_t *P, int64_t *flow,
-                 int64_t *total, int64_t *n_arcs)
+/* caps[j] is the capacity of the arc Expert_j -> Sink (the capacity vector c of Eq. 7). */
+int mcmf_literal_caps(const int64_t *q, int T, int E, int k, const int *caps, uint8_t *P, int64_t *flow,
+                      int64_t *total, int64_t *n_arcs)
 {
-    if (T <= 0 || E <= 0 || k < 0 || C < 0) return 1;
+    if (T <= 0 || E <= 0 || k < 0 || !caps) return 1;
+    for (int j = 0; j < E; j++) if (caps[j] < 0) return 1;
     int S = 0, Z = T + E + 1, n = T + E + 2;
     int64_t arcs = (int64_t)T + E + (int64_t)T * E;
     graph_t g;
@@ -65,7 +67,7 @@ int mcmf_literal(const int64_t *q, int T, int E, int k, int C, uint8_t *P, int64
     uint8_t *inq = malloc(n);
     for (int v = 0; v < n; v++) g.head[v] = -1;
     for (int i = 0; i < T; i++) g_add(&g, S, 1 + i, k, 0);                  /* Source -> Token_i  */
-    for (int j = 0; j < E; j++) g_add(&g, 1 + T + j, Z, C, 0);              /* Expert_j -> Sink   */
+    for (int j = 0; j < E; j++) g_add(&g, 1 + T + j, Z, caps[j], 0);        /* Expert_j -> Sink   */
     int first_te = g.m;
     for (int i = 0; i < T; i++)                                             /* Token_i -> Expert_j */
         for (int j = 0; j < E; j++) g_add(&g, 1 + i, 1 + T + j, 1, -q[(int64_t)i * E + j]);
@@ -105,6 +107,18 @@ int mcmf_literal(const int64_t *q, int T, int E, int k, int C, uint8_t *P, int64
     free(g.head); free(g.nxt); free(g.to); free(g.cap); free(g.cost);
     free(dist); free(par); free(queue); free(inq);
     return 0;
+}
+
+/* Uniform capacity C on every expert (Table 1 as printed). */
+int mcmf_literal(const int64_t *q, int T, int E, int k, int C, uint8_t *P, int64_t *flow,
+                 int64_t *total, int64_t *n_arcs)
+{
+    if (E <= 0 || C < 0) return 1;
+    int *caps = malloc(sizeof(int) * E);
+    for (int j = 0; j < E; j++) caps[j] = C;
+    int rc = mcmf_literal_caps(q, T, E, k, caps, P, flow, total, n_arcs);
+    free(caps);
+    return rc;
 }
 
 /* ------------------------------------------------------------------------------------------ */
@@ -172,23 +186,30 @@ static void c_remove(cstate_t *s, int u, int j)
     }
 }
 
-/* Returns 0 on success, 1 bad arguments, 2 precondition T*k <= E*min(C,T) violated, 3 internal
+/* Per-expert capacities caps[j] (clamped to T); the precondition is T*k <= sum_j min(caps[j], T).
+ * Returns 0 on success, 1 bad arguments, 2 precondition violated, 3 internal
  * invariant (negative reduced cost) violated.  prices[E] receives expert prices p_j >= 0 with
  * p_j = 0 on every expert left with spare capacity, such that every token holds k experts of
  * largest q_ij - p_j (a dual optimum).  *n_paths = augmentations, *n_hops = expert hops. */
-int mcmf_contracted(const int64_t *q, int T, int E, int k, int C, uint8_t *P, int64_t *prices,
-                    int64_t *flow, int64_t *total, int64_t *n_paths, int64_t *n_hops)
+int mcmf_contracted_caps(const int64_t *q, int T, int E, int k, const int *caps, uint8_t *P, int64_t *prices,
+                         int64_t *flow, int64_t *total, int64_t *n_paths, int64_t *n_hops)
 {
-    if (T <= 0 || E <= 0 || k < 0 || C < 0 || k > E) return 1;
-    int Ce = C < T ? C : T;
-    if ((int64_t)T * k > (int64_t)E * Ce) return 2;
+    if (T <= 0 || E <= 0 || k < 0 || !caps || k > E) return 1;
+    int *cap = malloc(sizeof(int) * E);
+    int64_t room = 0;
+    for (int j = 0; j < E; j++) {
+        if (caps[j] < 0) { free(cap); return 1; }
+        cap[j] = caps[j] < T ? caps[j] : T;
+        room += cap[j];
+    }
+    if ((int64_t)T * k > room) { free(cap); return 2; }
     cstate_t s;
     s.T = T; s.E = E; s.q = q;
     s.held = calloc((size_t)T * E, 1);
     s.pos = malloc(sizeof(int) * (size_t)T * E);
     s.mem = malloc(sizeof(int *) * E);
     s.load = calloc(E, sizeof(int));
-    for (int j = 0; j < E; j++) s.mem[j] = malloc(sizeof(int) * (Ce > 0 ? Ce : 1));
+    for (int j = 0; j < E; j++) s.mem[j] = malloc(sizeof(int) * (cap[j] > 0 ? cap[j] : 1));
     s.L = malloc(sizeof(int64_t) * E * E);
     s.arg = malloc(sizeof(int) * E * E);
     s.dirty = calloc((size_t)E * E, 1);
@@ -213,7 +234,7 @@ int mcmf_contracted(const int64_t *q, int T, int E, int k, int C, uint8_t *P, in
                 for (int a = 0; a < E; a++) if (!done[a] && d[a] < best) { best = d[a]; j = a; }
                 if (dZ <= best) break;            /* sink is the next node to settle (or nothing left) */
                 done[j] = 1;
-                if (s.load[j] < Ce) {             /* Expert_j -> Sink has residual capacity, cost 0 */
+                if (s.load[j] < cap[j]) {         /* Expert_j -> Sink has residual capacity, cost 0 */
                     int64_t c = d[j] + phi[j];
                     if (c < dZ) { dZ = c; parZ = j; }
                 }
@@ -229,7 +250,7 @@ int mcmf_contracted(const int64_t *q, int T, int E, int k, int C, uint8_t *P, in
                 if (rc) break;
             }
             if (rc) break;
-            if (parZ < 0) { rc = 3; break; }      /* cannot happen when T*k <= E*Ce */
+            if (parZ < 0) { rc = 3; break; }      /* cannot happen under the precondition */
             for (int j = 0; j < E; j++) phi[j] += (d[j] < dZ ? d[j] : dZ) - dZ;
             int len = 0;
             for (int j = parZ; j >= 0; j = par[j]) path[len++] = j;   /* sink side first */
@@ -248,6 +269,18 @@ int mcmf_contracted(const int64_t *q, int T, int E, int k, int C, uint8_t *P, in
     *flow = f; *total = tot; *n_paths = paths; *n_hops = hops;
     for (int j = 0; j < E; j++) free(s.mem[j]);
     free(s.held); free(s.pos); free(s.mem); free(s.load); free(s.L); free(s.arg); free(s.dirty);
-    free(phi); free(d); free(par); free(partok); free(path); free(done);
+    free(phi); free(d); free(par); free(partok); free(path); free(done); free(cap);
+    return rc;
+}
+
+/* Uniform capacity C on every expert. */
+int mcmf_contracted(const int64_t *q, int T, int E, int k, int C, uint8_t *P, int64_t *prices,
+                    int64_t *flow, int64_t *total, int64_t *n_paths, int64_t *n_hops)
+{
+    if (E <= 0 || C < 0) return 1;
+    int *caps = malloc(sizeof(int) * E);
+    for (int j = 0; j < E; j++) caps[j] = C;
+    int rc = mcmf_contracted_caps(q, T, E, k, caps, P, prices, flow, total, n_paths, n_hops);
+    free(caps);
     return rc;
 }

@@ -16,6 +16,8 @@ Everything is fp64 / int64 and written to be checked against the paper by eye:
   sigmoid_scores, softkmax, itertopk   other operators of Table 2 (base cases are a stated reading)
   aux_loss           Eq. 9 load-balance loss and its derivative with respect to the scores
   gates_backward     derivative of the selected scores (and of Eq. 9) with respect to the logits
+  max_score_assignment_caps   the exact assignment with one capacity per expert
+  top1_then_residual Algorithm 1 steps 4-8 with the residual problem solved exactly
   iter_reroute       Section 2.3 iterative rerouting: top-k with capacity, then greedy re-proposal rounds
                      (a heuristic; the processing orders are a stated reading, parity with the
                      authors' code is unpinned)
@@ -55,6 +57,12 @@ def _load():
         _lib.mcmf_contracted.argtypes = [i64p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                          u8p, i64p, i64p, i64p, i64p, i64p]
         _lib.mcmf_contracted.restype = ctypes.c_int
+        i32p = ctypes.POINTER(ctypes.c_int)
+        _lib.mcmf_literal_caps.argtypes = [i64p, ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p, u8p, i64p, i64p, i64p]
+        _lib.mcmf_literal_caps.restype = ctypes.c_int
+        _lib.mcmf_contracted_caps.argtypes = [i64p, ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p,
+                                              u8p, i64p, i64p, i64p, i64p, i64p]
+        _lib.mcmf_contracted_caps.restype = ctypes.c_int
     return _lib
 
 
@@ -163,6 +171,34 @@ def max_score_assignment(q, k: int, C: int) -> dict:
     if T * k <= E * min(C, T):
         return assign_contracted(q, k, C)
     return assign_literal_graph(q, k, C)
+
+
+def max_score_assignment_caps(q, k: int, caps) -> dict:
+    """The same optimum with a capacity of its own for every expert (the vector c of Eq. 7; Table 1's
+    Expert_j -> Sink arc gets capacity caps[j]).  Contracted solver when T*k <= sum_j min(caps_j, T),
+    literal graph otherwise."""
+    q = _as_q(q)
+    T, E = q.shape
+    caps = np.ascontiguousarray(caps, dtype=np.int32)
+    assert caps.shape == (E,) and (caps >= 0).all()
+    P = np.zeros((T, E), dtype=np.uint8)
+    cp = caps.ctypes.data_as(ctypes.POINTER(ctypes.c_int))
+    qp = q.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+    Pp = P.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+    if T * k <= int(np.minimum(caps, T).sum()):
+        prices = np.zeros(E, dtype=np.int64)
+        flow, total, paths, hops = (ctypes.c_int64() for _ in range(4))
+        rc = _load().mcmf_contracted_caps(qp, T, E, k, cp, Pp, prices.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                          ctypes.byref(flow), ctypes.byref(total), ctypes.byref(paths),
+                                          ctypes.byref(hops))
+        if rc:
+            raise ValueError(f"mcmf_contracted_caps failed rc={rc}")
+        return dict(P=P, prices=prices, flow=flow.value, total=total.value)
+    flow, total, arcs = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    rc = _load().mcmf_literal_caps(qp, T, E, k, cp, Pp, ctypes.byref(flow), ctypes.byref(total), ctypes.byref(arcs))
+    if rc:
+        raise ValueError(f"mcmf_literal_caps failed rc={rc}")
+    return dict(P=P, flow=flow.value, total=total.value)
 
 
 def max_flow_value(T: int, E: int, k: int, C: int) -> int:
@@ -455,6 +491,35 @@ def gates_backward(L, k: int, t: float, assign, dgate, dA_all=None) -> np.ndarra
         gA = gA + np.asarray(dA_all, dtype=np.float64)[None, :]
     w = gA * A
     return w - p * w.sum(axis=1, keepdims=True)
+
+
+# ------------------------------------------------------------------------------------------------
+# Algorithm 1 (top-2): top-1 first, then the residual problem
+
+def top1_then_residual(q, C: int) -> dict:
+    """Algorithm 1, steps 4-8, with the residual problem of step 9 solved exactly instead of by
+    Sinkhorn (the paper does not give Sinkhorn's iteration count, regulariser or rounding):
+    every token takes its highest-reward expert (ties to the lower id) whatever the load;
+    that entry of the reward matrix is set to 0; the capacities become max(0, C - load_j); each
+    token then gets one more expert (k_i = 1) by the exact assignment on the residual problem.
+    Returns assign [T, 2] = (top-1 expert, second expert), the residual capacities, the total of the
+    original rewards over both choices, and `repeat`: tokens whose second expert is their top-1
+    expert again (possible because step 5 zeroes the entry instead of forbidding it)."""
+    q = _as_q(q)
+    T, E = q.shape
+    top1 = np.argmax(q, axis=1)                       # first maximum = lower expert id
+    load = np.bincount(top1, minlength=E)
+    caps = np.maximum(0, C - load)
+    q2 = q.copy()
+    q2[np.arange(T), top1] = 0
+    sol = max_score_assignment_caps(q2, 1, caps)
+    P2 = sol["P"].astype(bool)
+    second = np.where(P2.any(axis=1), P2.argmax(axis=1), -1)
+    assign = np.stack([top1, second], axis=1).astype(np.int64)
+    got = second >= 0
+    total = int(q[np.arange(T), top1].sum() + q[np.nonzero(got)[0], second[got]].sum())
+    return dict(assign=assign, caps=caps, q_residual=q2, residual_total=sol["total"], residual_flow=sol["flow"],
+                total=total, repeat=int((second == top1).sum()))
 
 
 # ------------------------------------------------------------------------------------------------
