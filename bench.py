@@ -179,6 +179,23 @@ def main():
         operators[op] = {"levels": levels, "ms": op_ms,
                          "hbm_frac": 12 * T * E / (op_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
+    # Algorithm 1 of the paper (top-2: top-1 first, then the residual problem, here solved exactly) on the top-2
+    # configuration, beside the exact top-2 solve and iterative rerouting on the same rewards
+    from workloads import CONFIGS, make_logits
+    c2 = CONFIGS["cfg2"]
+    L2 = torch.from_numpy(make_logits("cfg2", 0)).to(dev)
+    _, q2 = ms.softtopk(L2, c2["k"], c2["t"])
+    a1 = ms.assign_top1_residual_i32(q2, c2["C"])
+    ex2 = ms.assign_i32(q2, c2["k"], c2["C"])
+    it2 = ms.assign_iter_i32(q2, c2["k"], c2["C"])
+    a1_ms = timed(lambda: ms.assign_top1_residual_i32(q2, c2["C"]), n=5)
+    ex2_ms = timed(lambda: ms.assign_i32(q2, c2["k"], c2["C"]), n=5)
+    load2 = torch.bincount(a1["assign"].flatten().clamp(min=0), minlength=c2["E"]).max().item()
+    algorithm1 = {"workload": f"cfg2: T={c2['T']} E={c2['E']} k=2 C={c2['C']}", "ms": a1_ms, "exact_top2_ms": ex2_ms,
+                  "score_over_exact_top2": a1["total"] / max(ex2["stats"]["total_score_q"], 1),
+                  "iter_score_over_exact_top2": it2["total"] / max(ex2["stats"]["total_score_q"], 1),
+                  "max_expert_load": load2, "C": c2["C"]}
+
     line = {
         "metric": "routed tokens/sec", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -205,6 +222,7 @@ def main():
         "iterative_rerouting": iter_variant,
         "training_side": training_side,
         "table2_operators": operators,
+        "algorithm1_top2": algorithm1,
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(args.config, min(args.cpu_sample, T))

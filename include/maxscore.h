@@ -164,6 +164,30 @@ int32_t maxscore_gates_backward(const float *logits, const float *scores, const 
                                 const float *dgates, const float *dscores_col, int32_t T, int32_t E, int32_t k,
                                 float *dlogits, void *stream);
 
+/* a4 with one capacity per expert (the vector c of Eq. 7; in Table 1 the arc Expert_j -> Sink gets capacity
+ * capacity[j]).  capacity is a HOST array of E values >= 0 (values above T act as T); their sum must be at least
+ * T*k (MAXSCORE_ERR_OVERSUBSCRIBED otherwise).  Everything else as maxscore_assign_i32. */
+int32_t maxscore_assign_caps_i32(const int32_t *q, int32_t T, int32_t E, int32_t k, const int32_t *capacity,
+                                 const maxscore_opts *opts, int32_t *assign, int64_t *prices, int64_t *price_scale,
+                                 maxscore_stats *stats, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Algorithm 1 (Section 3.2, top-2 routing) with its residual problem solved exactly: every token takes its
+ * highest-reward expert whatever the load (ties to the lower id); that entry of the reward matrix is set to 0
+ * (q_residual[T, E], device, out: the caller provides the storage); the capacities become max(0, C - load_j)
+ * (residual_capacity[E], HOST out, may be NULL); each token then gets one more expert by the exact assignment
+ * with k = 1 on the residual problem.  The paper solves that step approximately with Sinkhorn, whose iteration
+ * count, regulariser and rounding it does not give; this entry point gives the exact answer the approximation
+ * aims at.  assign[T, 2] device out = (top-1 expert, second expert or -1); total (sum of q over both choices)
+ * and flow (number of pairs) are HOST pointers and may be NULL; stats describe the residual solve.  Because the
+ * top-1 stage ignores the load, an expert can end above C, and because step 5 zeroes an entry instead of
+ * forbidding it, a token's second expert can be its first one again.  MAXSCORE_ERR_OVERSUBSCRIBED if the
+ * residual capacities sum to less than T.  Synchronises the stream. */
+int32_t maxscore_assign_top1_residual_i32(const int32_t *q, int32_t T, int32_t E, int32_t C,
+                                          const maxscore_opts *opts, int32_t *q_residual, int32_t *assign,
+                                          int32_t *residual_capacity, int64_t *total, int32_t *flow,
+                                          maxscore_stats *stats, void *workspace, size_t workspace_bytes,
+                                          void *stream);
+
 /* Iterative rerouting (Section 2.3, the second stage drawn in Figure 1(c); the assignment step of the
  * "-I" variants of Section 4): a fast greedy alternative to maxscore_assign_i32 on the same integer rewards.
  * Stage 1 keeps, per expert, the first C of the tokens' top-k choices taken in the order (choice rank, token

@@ -50,6 +50,10 @@ _SIGS = {
     "maxscore_gates_backward": (ctypes.c_int32, [ctypes.c_void_p] * 5 + [ctypes.c_int32] * 3 +
                                 [ctypes.c_void_p, ctypes.c_void_p]),
     "maxscore_scores_op": (ctypes.c_int32, [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p] * 3),
+    "maxscore_assign_caps_i32": (ctypes.c_int32, [ctypes.c_void_p] + [ctypes.c_int32] * 3 + [ctypes.c_void_p] * 7 +
+                                 [ctypes.c_size_t, ctypes.c_void_p]),
+    "maxscore_assign_top1_residual_i32": (ctypes.c_int32, [ctypes.c_void_p] + [ctypes.c_int32] * 3 +
+                                          [ctypes.c_void_p] * 8 + [ctypes.c_size_t, ctypes.c_void_p]),
     "maxscore_softtopk": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.c_float, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                            ctypes.c_void_p]),
@@ -286,6 +290,47 @@ def gates_backward(logits, scores, assign, dgates, dscores_col=None):
                                                 _ptr(dscores_col), T, E, k, _ptr(out), _stream())
     _check(rc, "maxscore_gates_backward")
     return out
+
+
+def assign_caps_i32(q, k: int, caps, max_rounds: int = 200000, eps_div: int = 12, allow_not_converged=False):
+    """a4 with one capacity per expert (host sequence of E ints).  Returns dict(assign, prices, price_scale, stats)."""
+    torch = _torch()
+    T, E = q.shape
+    assert q.dtype == torch.int32 and q.is_contiguous()
+    caps_arr = (ctypes.c_int32 * E)(*[int(c) for c in caps])
+    assign = torch.empty((T, k), dtype=torch.int32, device=q.device)
+    prices = torch.empty(E, dtype=torch.int64, device=q.device)
+    scale = torch.empty(1, dtype=torch.int64, device=q.device)
+    stats = Stats()
+    ws, need = _workspace(T, E, k, 1, q.device)
+    o = _opts(max_rounds=max_rounds, eps_div=eps_div)
+    rc = load_library().maxscore_assign_caps_i32(_ptr(q), T, E, k, ctypes.addressof(caps_arr), ctypes.byref(o),
+                                                 _ptr(assign), _ptr(prices), _ptr(scale), ctypes.byref(stats),
+                                                 _ptr(ws), need, _stream())
+    _check(rc, "maxscore_assign_caps_i32", allow=(ERR_NOT_CONVERGED,) if allow_not_converged else ())
+    return dict(assign=assign, prices=prices, price_scale=int(scale.item()), stats=stats.as_dict(), rc=rc)
+
+
+def assign_top1_residual_i32(q, C: int, max_rounds: int = 200000, eps_div: int = 12):
+    """Algorithm 1 with the residual problem solved exactly.  Returns dict(assign[T,2], q_residual, caps, total,
+    flow, stats)."""
+    torch = _torch()
+    T, E = q.shape
+    assert q.dtype == torch.int32 and q.is_contiguous()
+    q2 = torch.empty_like(q)
+    assign = torch.empty((T, 2), dtype=torch.int32, device=q.device)
+    caps = (ctypes.c_int32 * E)()
+    total, flow = ctypes.c_int64(), ctypes.c_int32()
+    stats = Stats()
+    ws, need = _workspace(T, E, 2, C, q.device)
+    o = _opts(max_rounds=max_rounds, eps_div=eps_div)
+    rc = load_library().maxscore_assign_top1_residual_i32(_ptr(q), T, E, C, ctypes.byref(o), _ptr(q2), _ptr(assign),
+                                                          ctypes.addressof(caps), ctypes.addressof(total),
+                                                          ctypes.addressof(flow), ctypes.byref(stats), _ptr(ws),
+                                                          need, _stream())
+    _check(rc, "maxscore_assign_top1_residual_i32")
+    return dict(assign=assign, q_residual=q2, caps=list(caps), total=total.value, flow=flow.value,
+                stats=stats.as_dict(), rc=rc)
 
 
 def gates(scores, assign):

@@ -22,6 +22,8 @@ WorkspaceLayout workspace_layout(int T, int E, int k, int d)
     L.cand_off = off; off = align_up(off + sizeof(long long) * (size_t)kMaxE * (kCand + 2), 256);
     L.n_tiles = (int)(((size_t)T * k + 1023) / 1024);
     L.tiles_off = off; off = align_up(off + sizeof(int) * ((size_t)L.n_tiles * E + kMaxE), 256);
+    L.cap_off = off; off = align_up(off + sizeof(int) * (size_t)kMaxE, 256);     // per-expert capacities
+    L.aux_off = off; off = align_up(off + sizeof(int) * 2 * (size_t)T, 256);     // two token-long lists
     L.wt_off = off; off = align_up(off + sizeof(unsigned short) * (size_t)E * (d > 0 ? d : 0), 256);
     L.total = off;
     return L;
@@ -141,6 +143,41 @@ int32_t maxscore_assign_iter_i32(const int32_t *q, int32_t T, int32_t E, int32_t
     if (rc) return rc;
     if (max_rounds <= 0) max_rounds = 1000;
     return iter_run(q, T, E, k, C, max_rounds, assign, total, flow, rounds, (char *)workspace, (hipStream_t)stream);
+}
+
+int32_t maxscore_assign_caps_i32(const int32_t *q, int32_t T, int32_t E, int32_t k, const int32_t *capacity,
+                                 const maxscore_opts *opts, int32_t *assign, int64_t *prices, int64_t *price_scale,
+                                 maxscore_stats *stats, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!q || !assign || !capacity) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, k, 1)) return MAXSCORE_ERR_SHAPE;
+    int32_t rc = check_ws(workspace, workspace_bytes, T, E, k);
+    if (rc) return rc;
+    maxscore_opts o = resolve(opts);
+    if (stats) std::memset(stats, 0, sizeof(*stats));
+    const int32_t *cap_dev = nullptr;
+    long long room = 0;
+    int cmax = 1;
+    rc = caps_to_device(capacity, T, E, k, (char *)workspace, &cap_dev, &room, &cmax, (hipStream_t)stream);
+    if (rc) return rc;
+    return solver_run(q, T, E, k, cmax, o, assign, prices, price_scale, stats, (char *)workspace, (hipStream_t)stream,
+                      cap_dev, room);
+}
+
+int32_t maxscore_assign_top1_residual_i32(const int32_t *q, int32_t T, int32_t E, int32_t C,
+                                          const maxscore_opts *opts, int32_t *q_residual, int32_t *assign,
+                                          int32_t *residual_capacity, int64_t *total, int32_t *flow,
+                                          maxscore_stats *stats, void *workspace, size_t workspace_bytes,
+                                          void *stream)
+{
+    if (!q || !q_residual || !assign) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, 2, C)) return MAXSCORE_ERR_SHAPE;
+    int32_t rc = check_ws(workspace, workspace_bytes, T, E, 2);
+    if (rc) return rc;
+    maxscore_opts o = resolve(opts);
+    if (stats) std::memset(stats, 0, sizeof(*stats));
+    return alg1_run(q, T, E, C, o, q_residual, assign, residual_capacity, total, flow, stats, (char *)workspace,
+                    (hipStream_t)stream);
 }
 
 int32_t maxscore_gates(const float *scores, const int32_t *assign, int32_t T, int32_t E, int32_t k, float *gates,

@@ -44,7 +44,8 @@ struct SolverState {
 };
 
 struct WorkspaceLayout {
-    size_t state_off, theta_off, gcount_off, klist_off, wcnt_off, wmoves_off, cand_off, tiles_off, wt_off, total;
+    size_t state_off, theta_off, gcount_off, klist_off, wcnt_off, wmoves_off, cand_off, tiles_off, cap_off, aux_off,
+        wt_off, total;
     int n_tiles, max_wg;
 };
 
@@ -58,8 +59,10 @@ inline bool hip_ok(hipError_t e) { return e == hipSuccess; }
     } while (0)
 
 // --- solver.hip
+// cap: optional device array of E per-expert capacities (each <= T) with sum `room`; NULL = Ce for all.
 int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore_opts &o, int32_t *assign,
-                   int64_t *prices, int64_t *price_scale, maxscore_stats *stats, char *ws, hipStream_t s);
+                   int64_t *prices, int64_t *price_scale, maxscore_stats *stats, char *ws, hipStream_t s,
+                   const int32_t *cap = nullptr, long long room = 0);
 // --- softtopk.hip
 int32_t softtopk_run(const float *logits, int T, int E, int k, float t, int shift, float *scores, int32_t *q,
                      hipStream_t s);
@@ -79,6 +82,16 @@ int32_t iter_run(const int32_t *q, int T, int E, int k, int C, int max_rounds, i
 // --- operators.hip
 int32_t scores_op_run(const float *logits, int T, int E, int k, int op, int shift, float *scores, int32_t *q,
                       hipStream_t s);
+int32_t top1_run(const int32_t *q, int T, int E, int32_t *top1, hipStream_t s);
+int32_t assign_total_run(const int32_t *q, const int32_t *assign, int T, int E, int k, void *state16, int64_t *total,
+                         int32_t *flow, hipStream_t s);
+// --- alg1.hip
+// Validates a host capacity vector (each >= 0, clamped to T, sum >= T*k) and copies it into the workspace.
+int32_t caps_to_device(const int32_t *caps_host, int T, int E, int k, char *ws, const int32_t **cap_dev,
+                       long long *room, int *cmax, hipStream_t s);
+int32_t alg1_run(const int32_t *q, int T, int E, int C, const maxscore_opts &o, int32_t *q_residual,
+                 int32_t *assign, int32_t *caps_out, int64_t *total, int32_t *flow, maxscore_stats *stats, char *ws,
+                 hipStream_t s);
 // --- training.hip
 int32_t aux_loss_run(const float *scores, const int32_t *offsets, int T, int E, float lam, float *loss,
                      float *mean_scores, float *dscores_col, char *ws, hipStream_t s);

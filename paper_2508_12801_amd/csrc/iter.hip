@@ -223,6 +223,36 @@ void launch_propose(const int32_t *q, const int32_t *assign, const int *load, in
 
 }  // namespace
 
+int32_t top1_run(const int32_t *q, int T, int E, int32_t *top1, hipStream_t s)
+{
+    const int epl = (E + 63) / 64;
+    if (epl <= 1) launch_topk<1>(q, T, E, 1, top1, s);
+    else if (epl <= 2) launch_topk<2>(q, T, E, 1, top1, s);
+    else if (epl <= 4) launch_topk<4>(q, T, E, 1, top1, s);
+    else if (epl <= 8) launch_topk<8>(q, T, E, 1, top1, s);
+    else launch_topk<16>(q, T, E, 1, top1, s);
+    MS_HIP(hipGetLastError());
+    return MAXSCORE_OK;
+}
+
+int32_t assign_total_run(const int32_t *q, const int32_t *assign, int T, int E, int k, void *state16,
+                         int64_t *total, int32_t *flow, hipStream_t s)
+{
+    IterState *st = (IterState *)state16;
+    IterState h = {};
+    MS_HIP(hipMemcpyAsync(st, &h, sizeof(h), hipMemcpyHostToDevice, s));
+    const size_t n = (size_t)T * k;
+    int grid = (int)((n + 255) / 256);
+    if (grid > 256) grid = 256;
+    hipLaunchKernelGGL(k_iter_total, dim3(grid), dim3(256), 0, s, q, assign, T, E, k, st);
+    MS_HIP(hipGetLastError());
+    MS_HIP(hipMemcpyAsync(&h, st, sizeof(h), hipMemcpyDeviceToHost, s));
+    MS_HIP(hipStreamSynchronize(s));
+    if (total) *total = (int64_t)h.total;
+    if (flow) *flow = h.flow;
+    return MAXSCORE_OK;
+}
+
 int32_t iter_run(const int32_t *q, int T, int E, int k, int C, int max_rounds, int32_t *assign, int64_t *total,
                  int32_t *flow, int32_t *rounds, char *ws, hipStream_t s)
 {

@@ -556,7 +556,8 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
 // workgroups have published their candidate lists.
 __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t *assign, long long *theta2,
                                           int *gcount2, SolverState *st2, const long long *cand, int *errflag,
-                                          int par, int T, int E, int k, int Ce, int max_iters)
+                                          int par, int T, int E, int k, int Ce, const int *__restrict__ cap,
+                                          int max_iters)
 {
     SolverState *st = st2 + (par ^ 1);          // the state the next bid pass will read
     long long *theta = theta2 + (par ^ 1) * kMaxE;
@@ -567,6 +568,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
     __shared__ long long s_theta[kTailMaxE];
     __shared__ long long s_bound[kTailMaxE];
     __shared__ int s_n[kTailMaxE];
+    __shared__ int s_capv[kTailMaxE];     // capacity of every expert (uniform Ce unless a vector was given)
     __shared__ int s_cn[kTailMaxE];
     __shared__ int s_vtok[kTailVict], s_vexp[kTailVict];
     __shared__ int s_iexp[kTailIns];
@@ -595,6 +597,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
     for (int e = tid; e < E; e += kTailThreads) {
         s_theta[e] = theta[e];
         s_n[e] = gcur[e];
+        s_capv[e] = cap ? cap[e] : Ce;
     }
     if (tid == 0) {
         s_stop = 0; s_moves = 0; s_changed = 0;
@@ -620,7 +623,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         bool pf_live = false;
         // 1. every over-full expert drops its lowest candidates and raises its threshold
         for (int e = tid; e < E; e += kTailThreads) {
-            const int m = s_n[e] - Ce;
+            const int m = s_n[e] - s_capv[e];
             if (m > 0) {
                 s_over = 1;
                 const int cn = s_cn[e];
@@ -636,7 +639,10 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                             s_vtok[b + i] = (int)(ce[cn - 1 - i] & tmask);
                             s_vexp[b + i] = e;
                         }
-                        const long long nt = cn > m ? ce[cn - 1 - m] : s_bound[e];
+                        long long nt = cn > m ? ce[cn - 1 - m] : s_bound[e];
+                        // an expert without capacity that dropped every key it had: nobody may stay at or
+                        // under the highest of them
+                        if (s_capv[e] == 0 && !(nt < kKeyInf)) nt = ce[cn - m] + 1;
                         s_cn[e] = cn - m;
                         s_changed = 1;
                         if (nt > s_theta[e] && nt < kKeyInf) s_theta[e] = nt;
@@ -948,7 +954,8 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
     }
 }
 
-// Select pass: one workgroup per expert; exact (n-Ce+1)-th smallest key by radix select.
+// Select pass: one workgroup per expert; exact (n-Ce+1)-th smallest key by radix select (Ce = the expert's
+// capacity: cap[e] when a capacity vector is given, else the same Ce for all).
 constexpr int kSelThreads = 1024;
 constexpr int kSelCache = 6144;
 constexpr int kSelDirect = 256;           // at most this many keys are ranked against each other directly
@@ -971,8 +978,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                                                         int *gcount2, long long *theta2, SolverState *st2,
                                                         int *errflag, long long *cand, const int32_t *__restrict__ q,
                                                         int32_t *assign, int *ready, int *host_done, int par, int T, int E, int k,
-                                                        int Ce, int n_wg, int rows_per_wg, int tail_on,
-                                                        int tail_moves, int tail_iters)
+                                                        int Ce, const int *__restrict__ cap, int n_wg,
+                                                        int rows_per_wg, int tail_on, int tail_moves,
+                                                        int tail_iters)
 {
     const SolverState *st = st2 + par;
     SolverState *st_out = st2 + (par ^ 1);
@@ -1022,9 +1030,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
         mv += wmoves[w];
     }
     for (int e = tid; e < E; e += kSelThreads) {
-        const int c = gprev[e];
-        ov += c > Ce;
-        vi += (c < Ce && theta_in[e] > 0);
+        const int c = gprev[e], ce = cap ? cap[e] : Ce;
+        ov += c > ce;
+        vi += (c < ce && theta_in[e] > 0);
     }
     const int cur_round = st->round, cur_slack = st->slack, cur_tbits = st->tbits,
               cur_tail_block = st->tail_block, cur_tail_gos = st->tail_gos, cur_max_rounds = st->max_rounds;
@@ -1136,11 +1144,12 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             if (tid == 0) *errflag = 1;       // reported as MAXSCORE_ERR_HIP by the next select pass
             return;
         }
-        tail_pass(q, assign, theta2, gcount2, st2, cand, errflag, par, T, E, k, Ce, tail_iters);
+        tail_pass(q, assign, theta2, gcount2, st2, cand, errflag, par, T, E, k, Ce, cap, tail_iters);
         return;
     }
     long long new_theta = base;
-    const bool need_select = !tail_go && n > Ce;
+    const int Cj = cap ? cap[j] : Ce;         // capacity of this workgroup's expert
+    const bool need_select = !tail_go && n > Cj;
     const bool need_cand = tail_go;
     if (need_select || need_cand) {
         const bool cached = n <= kSelCache;
@@ -1293,8 +1302,10 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             return base + (long long)res;
         };
         if (need_select) {
-            const int rank = n - Ce;   // 0-based rank of the new threshold among the keys, ascending
-            new_theta = nth_by_narrowing(rank);
+            // 0-based rank of the new threshold among the keys, ascending; an expert without capacity moves its
+            // threshold just above its largest key
+            const int rank = Cj > 0 ? n - Cj : n - 1;
+            new_theta = nth_by_narrowing(rank) + (Cj > 0 ? 0 : 1);
         } else {
             // candidate list for the tail pass: the kCand smallest keys in ascending order, their
             // count, and a bound no other key of this expert lies under
@@ -1434,7 +1445,8 @@ void launch_bid_g(int EPL, bool vec, const int32_t *q, int32_t *assign, const lo
 }  // namespace
 
 int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore_opts &o, int32_t *assign,
-                   int64_t *prices, int64_t *price_scale, maxscore_stats *stats, char *ws, hipStream_t s)
+                   int64_t *prices, int64_t *price_scale, maxscore_stats *stats, char *ws, hipStream_t s,
+                   const int32_t *cap, long long room)
 {
     WorkspaceLayout L = workspace_layout(T, E, k);
     SolverState *st = (SolverState *)(ws + L.state_off);
@@ -1470,7 +1482,8 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     const int n_wg = (T + rows - 1) / rows;
     if (n_wg > L.max_wg) return MAXSCORE_ERR_WORKSPACE;
 
-    const int slack = ((long long)E * Ce - (long long)T * k) > 0 ? 1 : 0;
+    // room = total capacity (sum of the vector, or E*Ce)
+    const int slack = ((cap ? room : (long long)E * Ce) - (long long)T * k) > 0 ? 1 : 0;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     MS_HIP(hipEventCreate(&ev0));
     MS_HIP(hipEventCreate(&ev1));
@@ -1532,7 +1545,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
 #undef MS_BID
             if (g_kernel_timing) MS_HIP(hipEventRecord(tev.back(), s));
             hipLaunchKernelGGL(k_select, dim3(E + tail_on), dim3(kSelThreads), 0, s, klist, wcnt, wmoves, gcount, theta,
-                               st, qmm + 2, cand, q, assign, qmm + 3, tl_flag_dev, par, T, E, k, Ce, n_wg, rows, tail_on,
+                               st, qmm + 2, cand, q, assign, qmm + 3, tl_flag_dev, par, T, E, k, Ce, cap, n_wg, rows, tail_on,
                                tail_moves, tail_iters);
             ++launched;
         }

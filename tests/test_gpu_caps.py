@@ -1,0 +1,106 @@
+"""GPU parity of the exact assignment with one capacity per expert and of the top-1-then-residual split of
+Algorithm 1 through the C ABI: totals bit-equal to the CPU checker's optimum, exact feasibility."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import CONFIGS, make_logits
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def ms():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2508_12801_amd as m
+    m.load_library()
+    return m
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def random_caps(rng, T, E, k, slack, zeros):
+    w = rng.random(E) + 0.2
+    w[rng.choice(E, zeros, replace=False)] = 0.0
+    caps = np.floor(w / w.sum() * (T * k + slack)).astype(np.int64)
+    caps = np.minimum(caps, T)
+    live = np.nonzero(w > 0)[0]
+    i = 0
+    while caps.sum() < T * k + slack:                    # hand out what the rounding lost
+        j = live[i % live.size]
+        if caps[j] < T:
+            caps[j] += 1
+        i += 1
+    return caps
+
+
+@pytest.mark.parametrize("T,E,k,slack,zeros", [
+    (300, 8, 2, 0, 0), (300, 8, 2, 17, 2), (2000, 16, 2, 0, 3), (4099, 64, 8, 100, 5), (5000, 128, 1, 0, 20),
+    (1500, 300, 4, 9, 40), (64, 8, 8, 0, 0),            # k = E: every expert needs room for everybody
+])
+def test_capacity_vector_matches_the_checker(ms, T, E, k, slack, zeros):
+    print(f"caps T={T} E={E} k={k} slack={slack} zeros={zeros}", flush=True)
+    rng = np.random.default_rng(T + E + k)
+    q = (rng.integers(0, 1 << 20, (T, E)) + rng.integers(0, 1 << 19, E)[None, :]).astype(np.int32)
+    caps = np.full(E, T) if k == E else random_caps(rng, T, E, k, slack, zeros)
+    out = ms.assign_caps_i32(dev(q), k, caps)
+    a = out["assign"].cpu().numpy()
+    P = oracle.assignment_matrix(a, E)
+    assert (P.sum(axis=1) == k).all() and (P.sum(axis=0) <= caps).all()
+    ref = oracle.max_score_assignment_caps(q.astype(np.int64), k, caps)
+    assert out["stats"]["total_score_q"] == ref["total"] == int(q.astype(np.int64)[P.astype(bool)].sum())
+    assert out["stats"]["flow_value"] == T * k
+
+
+def test_uniform_vector_equals_the_scalar_entry_point(ms):
+    print("caps uniform", flush=True)
+    c = CONFIGS["cfg3"]
+    q = oracle.quantise(oracle.soft_topk(make_logits("cfg3", 4), c["k"], c["t"])).astype(np.int32)
+    a = ms.assign_i32(dev(q), c["k"], c["C"])
+    b = ms.assign_caps_i32(dev(q), c["k"], [c["C"]] * c["E"])
+    assert a["stats"]["total_score_q"] == b["stats"]["total_score_q"]
+
+
+def test_capacity_vector_errors(ms):
+    print("caps errors", flush=True)
+    q = dev(np.zeros((100, 4), dtype=np.int32))
+    with pytest.raises(ms.MaxScoreError):
+        ms.assign_caps_i32(q, 2, [50, 50, 50, 49])       # 199 places for 200 pairs
+    with pytest.raises(ms.MaxScoreError):
+        ms.assign_caps_i32(q, 2, [100, 100, -1, 100])
+
+
+@pytest.mark.parametrize("name,seed", [("cfg1", 0), ("cfg2", 0), ("cfg2", 1), ("cfg2", 2)])
+def test_top1_then_residual_matches_the_checker(ms, name, seed):
+    print(f"algorithm 1 {name} seed {seed}", flush=True)
+    c = CONFIGS[name]
+    assert c["k"] == 2
+    q = oracle.quantise(oracle.soft_topk(make_logits(name, seed), 2, max(c["t"], 1.0))).astype(np.int32)
+    out = ms.assign_top1_residual_i32(dev(q), c["C"])
+    ref = oracle.top1_then_residual(q.astype(np.int64), c["C"])
+    a = out["assign"].cpu().numpy()
+    assert np.array_equal(a[:, 0], ref["assign"][:, 0])                  # arg-max with the same tie rule
+    assert out["caps"] == ref["caps"].tolist()
+    assert np.array_equal(out["q_residual"].cpu().numpy(), ref["q_residual"])
+    assert out["stats"]["total_score_q"] == ref["residual_total"]         # the residual optimum, bit for bit
+    assert out["total"] == ref["total"] and out["flow"] == 2 * c["T"]
+    second = a[:, 1]
+    assert (np.bincount(second, minlength=c["E"]) <= ref["caps"]).all()
+
+
+def test_top1_then_residual_larger_batch(ms):
+    print("algorithm 1 T=16384 E=64", flush=True)
+    rng = np.random.default_rng(3)
+    T, E = 16384, 64
+    L = (rng.normal(size=(T, E)) + 0.7 * rng.normal(size=(1, E))).astype(np.float32)
+    q = oracle.quantise(oracle.soft_topk(L, 2, 1.0)).astype(np.int32)
+    C = 2 * T // E
+    out = ms.assign_top1_residual_i32(dev(q), C)
+    ref = oracle.top1_then_residual(q.astype(np.int64), C)
+    assert out["caps"] == ref["caps"].tolist() and min(out["caps"]) == 0     # some experts are full after stage 1
+    assert out["stats"]["total_score_q"] == ref["residual_total"] and out["total"] == ref["total"]
