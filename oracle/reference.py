@@ -233,8 +233,9 @@ def check_feasible(P: np.ndarray, k: int, C: int) -> Tuple[bool, str]:
     return True, ""
 
 
-def verify_optimal(q, P, k: int, C: int) -> dict:
-    """Proof of optimality for a feasible maximum-flow P when T*k <= E*min(C,T), independent of
+def verify_optimal(q, P, k: int, C) -> dict:
+    """C is one capacity for all experts or an array with one capacity per expert.
+    Proof of optimality for a feasible maximum-flow P when T*k <= E*min(C,T), independent of
     how P was found: the residual network, with tokens contracted, has experts and the sink as
     nodes; arc j->j' costs min over tokens on j and not on j' of q_uj - q_uj'; j->sink costs 0
     if j has spare capacity; sink->j costs 0 if j holds a token.  P is optimal iff no negative
@@ -244,8 +245,8 @@ def verify_optimal(q, P, k: int, C: int) -> dict:
     q = _as_q(q)
     P = np.asarray(P).astype(bool)
     T, E = q.shape
-    Ce = min(C, T)
-    assert T * k <= E * Ce
+    Ce = np.minimum(np.broadcast_to(np.asarray(C, dtype=np.int64), (E,)), T)
+    assert T * k <= int(Ce.sum())
     load = P.sum(axis=0)
     INF = np.int64(1) << 60
     Lm = np.full((E + 1, E + 1), INF, dtype=np.int64)      # node E = sink
@@ -257,7 +258,7 @@ def verify_optimal(q, P, k: int, C: int) -> dict:
             Lm[j, :E] = diff.min(axis=0)
             Lm[E, j] = 0
         Lm[j, j] = INF
-        if load[j] < Ce:
+        if load[j] < Ce[j]:
             Lm[j, E] = 0
     dist = np.zeros(E + 1, dtype=np.int64)
     changed = True

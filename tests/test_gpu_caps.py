@@ -104,3 +104,22 @@ def test_top1_then_residual_larger_batch(ms):
     ref = oracle.top1_then_residual(q.astype(np.int64), C)
     assert out["caps"] == ref["caps"].tolist() and min(out["caps"]) == 0     # some experts are full after stage 1
     assert out["stats"]["total_score_q"] == ref["residual_total"] and out["total"] == ref["total"]
+
+
+def test_capacity_vector_at_the_headline_size(ms):
+    """T=65536, E=128, k=8 with uneven capacities and six closed experts: the checker's own solve takes about a
+    minute there, so the GPU result is proved optimal by the independent certificate instead (no negative cycle
+    in the contracted residual graph, prices that satisfy complementary slackness)."""
+    print("caps cfg5 size", flush=True)
+    c = CONFIGS["cfg5"]
+    T, E, k = c["T"], c["E"], c["k"]
+    q = oracle.quantise(oracle.soft_topk(make_logits("cfg5", 2), k, c["t"])).astype(np.int32)
+    rng = np.random.default_rng(11)
+    caps = random_caps(rng, T, E, k, slack=1000, zeros=6)
+    out = ms.assign_caps_i32(dev(q), k, caps)
+    a = out["assign"].cpu().numpy()
+    P = oracle.assignment_matrix(a, E)
+    assert (P.sum(axis=1) == k).all() and (P.sum(axis=0) <= caps).all()
+    cert = oracle.verify_optimal(q.astype(np.int64), P, k, caps)
+    assert cert["optimal"] and cert["total"] == out["stats"]["total_score_q"]
+    print("rounds", out["stats"]["rounds"], "solver ms", out["stats"]["solver_ms"], flush=True)

@@ -94,3 +94,29 @@ def test_top1_then_residual_by_hand_and_bounds():
         assert r["total"] <= exact["total"]                    # feasible for the full problem, so bounded by its optimum
     second = r["assign"][:, 1]
     assert (np.bincount(second[second >= 0], minlength=8) <= r["caps"]).all()
+
+
+def test_certificate_accepts_the_optimum_and_rejects_a_worse_matrix_with_a_capacity_vector():
+    rng = np.random.default_rng(21)
+    T, E, k = 80, 6, 2
+    caps = np.array([40, 0, 35, 30, 25, 40])
+    q = rng.integers(0, 10 ** 5, (T, E))
+    best = oracle.max_score_assignment_caps(q, k, caps)
+    cert = oracle.verify_optimal(q, best["P"], k, caps)
+    assert cert["optimal"] and cert["total"] == best["total"]
+    # swap one token's expert for a worse free one: still feasible, no longer optimal
+    P = best["P"].copy()
+    load = P.sum(axis=0)
+    done = False
+    for i in range(T):
+        for j in np.nonzero(P[i])[0]:
+            for j2 in range(E):
+                if not P[i, j2] and load[j2] < caps[j2] and q[i, j2] < q[i, j]:
+                    P[i, j], P[i, j2] = 0, 1
+                    done = True
+                    break
+            if done:
+                break
+        if done:
+            break
+    assert done and not oracle.verify_optimal(q, P, k, caps)["optimal"]
