@@ -198,7 +198,8 @@ int32_t maxscore_assign_top1_residual_i32(const int32_t *q, int32_t T, int32_t E
  *
  * q[T, E] device; assign[T, k] device out (slot s holds the token's s-th choice or its replacement, -1 = hole
  * that nobody could take).  total (sum of q over the chosen pairs), flow (number of pairs) and rounds (stage-2
- * rounds that had proposals) are host pointers and may be NULL.  max_rounds <= 0 means 1000.  Any C >= 1 is
+ * rounds that had proposals) are host pointers and may be NULL.  max_rounds < 0 means 1000; max_rounds = 0
+ * stops after stage 1, which is plain top-k routing with token dropping (Section 2.3, Figure 1(b)).  Any C >= 1 is
  * accepted (no over-subscription error: holes simply stay).  The call synchronises the stream; workspace as for
  * maxscore_assign_i32.  Returns MAXSCORE_ERR_NOT_CONVERGED if proposals were still pending after max_rounds
  * (the assignment is feasible all the same). */

@@ -245,8 +245,9 @@ def assign_i32(q, k: int, C: int, max_rounds: int = 200000, eps_div: int = 12, a
     return dict(assign=assign, prices=prices, price_scale=int(scale.item()), stats=stats.as_dict(), rc=rc)
 
 
-def assign_iter_i32(q, k: int, C: int, max_rounds: int = 0, allow_not_converged=False):
-    """Iterative rerouting on int32 rewards (Section 2.3).  Returns dict(assign, total, flow, rounds, rc)."""
+def assign_iter_i32(q, k: int, C: int, max_rounds: int = -1, allow_not_converged=False):
+    """Iterative rerouting on int32 rewards (Section 2.3); max_rounds=0 stops after the top-k-with-capacity stage
+    (plain token dropping), a negative value means the default limit.  Returns dict(assign, total, flow, rounds, rc)."""
     torch = _torch()
     T, E = q.shape
     assert q.dtype == torch.int32 and q.is_contiguous()

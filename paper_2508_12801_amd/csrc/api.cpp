@@ -141,7 +141,7 @@ int32_t maxscore_assign_iter_i32(const int32_t *q, int32_t T, int32_t E, int32_t
     if (!shape_ok(T, E, k, C)) return MAXSCORE_ERR_SHAPE;
     int32_t rc = check_ws(workspace, workspace_bytes, T, E, k);
     if (rc) return rc;
-    if (max_rounds <= 0) max_rounds = 1000;
+    if (max_rounds < 0) max_rounds = 1000;
     return iter_run(q, T, E, k, C, max_rounds, assign, total, flow, rounds, (char *)workspace, (hipStream_t)stream);
 }
 

@@ -25,8 +25,8 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def check(ms, q, k, C, max_rounds=0):
-    ref = oracle.iter_reroute(q, k, C, max_rounds=max_rounds if max_rounds > 0 else None)
+def check(ms, q, k, C, max_rounds=-1):
+    ref = oracle.iter_reroute(q, k, C, max_rounds=max_rounds if max_rounds >= 0 else None)
     out = ms.assign_iter_i32(dev(q.astype(np.int32)), k, C, max_rounds=max_rounds, allow_not_converged=True)
     got = out["assign"].cpu().numpy()
     assert np.array_equal(got, ref["assign"])
@@ -96,6 +96,10 @@ def test_round_limit(ms):
     assert out["rc"] != 0 and ref["rounds"] == 2        # proposals were still pending
     ref, out = check(ms, q, 2, 375, max_rounds=full["rounds"] + 1)
     assert out["rc"] == 0
+    # no rerouting at all: plain top-k with capacity, the dropped pairs stay holes
+    ref, out = check(ms, q, 2, 375, max_rounds=0)
+    assert out["rc"] == 0 and out["rounds"] == 0 and np.array_equal(out["assign"].cpu().numpy(), full["stage1"])
+    assert out["flow"] < 2 * 3000
 
 
 def test_gates_and_dispatch_accept_the_result(ms):
