@@ -158,7 +158,9 @@ def main():
     torch.cuda.synchronize()
     iter_path_ms = (time.perf_counter() - t0) / 10 * 1e3
     del out_i
-    iter_variant = {"ms": iter_ms, "whole_path_ms_per_call": iter_path_ms,
+    drop0 = ms.assign_iter_i32(out["q"], k, C, max_rounds=0)     # plain top-k with capacity: what gets dropped
+    iter_variant = {"ms": iter_ms, "topk_drop_rate": 1.0 - drop0["flow"] / float(T * k),
+                    "topk_score_over_exact_optimum": drop0["total"] / max(stats["total_score_q"], 1), "whole_path_ms_per_call": iter_path_ms,
                     "whole_path_tokens_per_s": T / (iter_path_ms * 1e-3), "rounds": it["rounds"], "flow": it["flow"], "max_flow": stats["flow_value"],
                     "score_over_exact_optimum": it["total"] / max(stats["total_score_q"], 1)}
 

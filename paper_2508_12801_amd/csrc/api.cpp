@@ -20,7 +20,7 @@ WorkspaceLayout workspace_layout(int T, int E, int k, int d)
     L.wcnt_off = off; off = align_up(off + sizeof(int) * (size_t)E * L.max_wg, 256);
     L.wmoves_off = off; off = align_up(off + sizeof(int) * (size_t)L.max_wg, 256);
     L.cand_off = off; off = align_up(off + sizeof(long long) * (size_t)kMaxE * (kCand + 2), 256);
-    L.n_tiles = (int)(((size_t)T * k + 1023) / 1024);
+    L.n_tiles = (int)(((size_t)T * k + kDispTile - 1) / kDispTile);
     L.tiles_off = off; off = align_up(off + sizeof(int) * ((size_t)L.n_tiles * E + kMaxE), 256);
     L.cap_off = off; off = align_up(off + sizeof(int) * (size_t)kMaxE, 256);     // per-expert capacities
     L.aux_off = off; off = align_up(off + sizeof(int) * 2 * (size_t)T, 256);     // two token-long lists

@@ -9,6 +9,10 @@
 namespace maxscore {
 
 constexpr int kMaxE = 1024;
+#ifndef MS_DISP_TILE
+#define MS_DISP_TILE 1024
+#endif
+constexpr int kDispTile = MS_DISP_TILE;   // slots of the pair list owned by one wavefront in the dispatch kernels
 constexpr int kMaxK = 64;
 constexpr int kMaxTBits = 21;
 constexpr int64_t kBidBig = (int64_t)1 << 40;   // bid of a token that has no alternative left
@@ -72,7 +76,7 @@ int32_t dispatch_run(const int32_t *assign, const float *gates, int T, int E, in
                      int32_t *disp_token, float *disp_gate, int32_t *token_pos, char *ws, hipStream_t s);
 // Stable position of every entry of `list` (n expert ids, -1 = none) among the entries of the same expert, and
 // the exclusive prefix sums of the per-expert counts; disp_token / disp_gate may be null.  `tiles` needs
-// n_tiles*E + kMaxE ints with n_tiles = ceil(n / 1024).
+// n_tiles*E + kMaxE ints with n_tiles = ceil(n / kDispTile).
 int32_t dispatch_core(const int32_t *list, const float *gates, size_t n, int E, int k, int32_t *offsets,
                       int32_t *disp_token, float *disp_gate, int32_t *token_pos, int *tiles, int n_tiles,
                       hipStream_t s);

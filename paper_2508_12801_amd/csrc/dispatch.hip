@@ -10,7 +10,7 @@
 namespace maxscore {
 namespace {
 
-constexpr int kTile = 1024;      // slots per wavefront tile
+constexpr int kTile = kDispTile;  // slots per wavefront tile
 constexpr int kWavesPerWg = 4;
 
 __global__ __launch_bounds__(256) void k_tile_hist(const int32_t *__restrict__ assign, size_t n, int E,
