@@ -18,6 +18,7 @@ Everything is fp64 / int64 and written to be checked against the paper by eye:
   gates_backward     derivative of the selected scores (and of Eq. 9) with respect to the logits
   max_score_assignment_caps   the exact assignment with one capacity per expert
   top1_then_residual Algorithm 1 steps 4-8 with the residual problem solved exactly
+  sinkhorn_plan, top1_then_sinkhorn   Algorithm 1 with Sinkhorn on the residual problem (a stated reading)
   iter_reroute       Section 2.3 iterative rerouting: top-k with capacity, then greedy re-proposal rounds
                      (a heuristic; the processing orders are a stated reading, parity with the
                      authors' code is unpinned)
@@ -553,3 +554,51 @@ def itertopk(L: np.ndarray, k: int) -> np.ndarray:
         w = 1.0 - y
         y = y + w * ex / (w * ex).sum(axis=1, keepdims=True)
     return y
+
+
+# ------------------------------------------------------------------------------------------------
+# Algorithm 1, step 9 as the paper does it: Sinkhorn on the residual problem
+
+def sinkhorn_plan(a_res, caps, tau: float, n_iter: int) -> dict:
+    """Matrix scaling for the residual problem of Algorithm 1 (row sums k_i = 1, column sums
+    proportional to the residual capacities).  The paper names the algorithm only; the regulariser,
+    the iteration count and the rounding are this build's reading:
+
+      K_ij = exp(a_ij / tau) on experts with caps_j > 0, else 0   (rows are max-shifted first,
+                                                                   which the row scaling absorbs)
+      m_j  = caps_j * T / sum(caps)                                (column targets, total T)
+      v = 1;  n_iter times:  u_i = 1 / sum_j K_ij v_j ;  v_j = m_j / sum_i K_ij u_i
+      plan_ij = u_i K_ij v_j   (u = 1 when n_iter = 0)
+      second_i = argmax_j plan_ij (ties to the lower expert id), -1 if the row is all zero."""
+    a = np.asarray(a_res, dtype=np.float64)
+    T, E = a.shape
+    caps = np.asarray(caps, dtype=np.float64)
+    live = caps > 0
+    K = np.exp((a - a.max(axis=1, keepdims=True)) / tau) * live[None, :]
+    m = caps * (T / caps.sum()) if caps.sum() > 0 else caps
+    u = np.ones(T)
+    v = np.ones(E)
+    for _ in range(n_iter):
+        u = 1.0 / (K @ v)
+        v = np.where(live, m / np.maximum(K.T @ u, 1e-300), 0.0)
+    plan = u[:, None] * K * v[None, :]
+    second = np.where(plan.max(axis=1) > 0, plan.argmax(axis=1), -1)
+    return dict(plan=plan, second=second, u=u, v=v, targets=m)
+
+
+def top1_then_sinkhorn(A, C: int, tau: float, n_iter: int) -> dict:
+    """Algorithm 1 on the affinity scores A: steps 4-8 as in top1_then_residual (on the scores
+    themselves), step 9 by sinkhorn_plan.  Returns assign [T, 2], the residual capacities, the plan
+    and the per-expert load of the second choices."""
+    A = np.asarray(A, dtype=np.float64)
+    T, E = A.shape
+    top1 = np.argmax(A, axis=1)
+    load = np.bincount(top1, minlength=E)
+    caps = np.maximum(0, C - load)
+    a_res = A.copy()
+    a_res[np.arange(T), top1] = 0.0
+    sk = sinkhorn_plan(a_res, caps, tau, n_iter)
+    second = sk["second"]
+    assign = np.stack([top1, second], axis=1).astype(np.int64)
+    load2 = np.bincount(second[second >= 0], minlength=E)
+    return dict(assign=assign, caps=caps, plan=sk["plan"], load2=load2, a_res=a_res, v=sk["v"], u=sk["u"])
