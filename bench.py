@@ -186,14 +186,21 @@ def main():
     from workloads import CONFIGS, make_logits
     c2 = CONFIGS["cfg2"]
     L2 = torch.from_numpy(make_logits("cfg2", 0)).to(dev)
-    _, q2 = ms.softtopk(L2, c2["k"], c2["t"])
+    sc2, q2 = ms.softtopk(L2, c2["k"], c2["t"])
     a1 = ms.assign_top1_residual_i32(q2, c2["C"])
     ex2 = ms.assign_i32(q2, c2["k"], c2["C"])
     it2 = ms.assign_iter_i32(q2, c2["k"], c2["C"])
     a1_ms = timed(lambda: ms.assign_top1_residual_i32(q2, c2["C"]), n=5)
     ex2_ms = timed(lambda: ms.assign_i32(q2, c2["k"], c2["C"]), n=5)
     load2 = torch.bincount(a1["assign"].flatten().clamp(min=0), minlength=c2["E"]).max().item()
-    algorithm1 = {"workload": f"cfg2: T={c2['T']} E={c2['E']} k=2 C={c2['C']}", "ms": a1_ms, "exact_top2_ms": ex2_ms,
+    sk = ms.assign_top1_sinkhorn(sc2, c2["C"], 0.05, 20)
+    sk_ms = timed(lambda: ms.assign_top1_sinkhorn(sc2, c2["C"], 0.05, 20), n=5)
+    ska = sk["assign"].long()
+    sk_total = (q2.long().gather(1, ska.clamp(min=0)) * (ska >= 0)).sum().item()     # reporting only
+    sk_load = torch.bincount(ska.flatten().clamp(min=0), minlength=c2["E"]).max().item()
+    algorithm1 = {"sinkhorn": {"tau": 0.05, "n_iter": 20, "ms": sk_ms, "max_expert_load": sk_load,
+                               "score_over_exact_top2": sk_total / max(ex2["stats"]["total_score_q"], 1)},
+                  "workload": f"cfg2: T={c2['T']} E={c2['E']} k=2 C={c2['C']}", "ms": a1_ms, "exact_top2_ms": ex2_ms,
                   "score_over_exact_top2": a1["total"] / max(ex2["stats"]["total_score_q"], 1),
                   "iter_score_over_exact_top2": it2["total"] / max(ex2["stats"]["total_score_q"], 1),
                   "max_expert_load": load2, "C": c2["C"]}

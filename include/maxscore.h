@@ -188,6 +188,22 @@ int32_t maxscore_assign_top1_residual_i32(const int32_t *q, int32_t T, int32_t E
                                           maxscore_stats *stats, void *workspace, size_t workspace_bytes,
                                           void *stream);
 
+/* Algorithm 1 with its last step done by Sinkhorn, as in the paper.  The paper names the algorithm only; the
+ * regulariser tau, the iteration count n_iter and the rounding are this library's reading:
+ *   top-1 per token on scores[T, E] (ties to the lower expert id); residual capacities max(0, C - load_j);
+ *   residual affinities a' = scores with the top-1 entry set to 0;
+ *   K_ij = exp((a'_ij - max_j a'_ij) / tau) on experts with residual capacity, else 0;
+ *   column targets m_j = cap_j * T / sum(cap);  v = 1;  n_iter times: u_i = 1 / sum_j K_ij v_j,
+ *   v_j = m_j / sum_i K_ij u_i;  plan_ij = u_i K_ij v_j (u = 1 when n_iter = 0);
+ *   second expert = arg-max_j plan_ij (ties to the lower id), -1 when the row is all zero.
+ * assign[T, 2] device out; plan[T, E] device out or NULL; residual_capacity[E] HOST out or NULL (the call then
+ * synchronises the stream, otherwise it only enqueues).  tau > 0, 0 <= n_iter <= 100000, E >= 2.  The rounded
+ * second choices follow the capacities only approximately.  fp32 arithmetic; column sums are added in a fixed
+ * order, so results are reproducible for a given shape. */
+int32_t maxscore_assign_top1_sinkhorn(const float *scores, int32_t T, int32_t E, int32_t C, float tau,
+                                      int32_t n_iter, int32_t *assign, float *plan, int32_t *residual_capacity,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
 /* Iterative rerouting (Section 2.3, the second stage drawn in Figure 1(c); the assignment step of the
  * "-I" variants of Section 4): a fast greedy alternative to maxscore_assign_i32 on the same integer rewards.
  * Stage 1 keeps, per expert, the first C of the tokens' top-k choices taken in the order (choice rank, token

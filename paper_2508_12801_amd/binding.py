@@ -54,6 +54,8 @@ _SIGS = {
                                  [ctypes.c_size_t, ctypes.c_void_p]),
     "maxscore_assign_top1_residual_i32": (ctypes.c_int32, [ctypes.c_void_p] + [ctypes.c_int32] * 3 +
                                           [ctypes.c_void_p] * 8 + [ctypes.c_size_t, ctypes.c_void_p]),
+    "maxscore_assign_top1_sinkhorn": (ctypes.c_int32, [ctypes.c_void_p] + [ctypes.c_int32] * 3 + [ctypes.c_float,
+                                      ctypes.c_int32] + [ctypes.c_void_p] * 4 + [ctypes.c_size_t, ctypes.c_void_p]),
     "maxscore_softtopk": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.c_float, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                            ctypes.c_void_p]),
@@ -332,6 +334,22 @@ def assign_top1_residual_i32(q, C: int, max_rounds: int = 200000, eps_div: int =
     _check(rc, "maxscore_assign_top1_residual_i32")
     return dict(assign=assign, q_residual=q2, caps=list(caps), total=total.value, flow=flow.value,
                 stats=stats.as_dict(), rc=rc)
+
+
+def assign_top1_sinkhorn(scores, C: int, tau: float, n_iter: int, want_plan: bool = False):
+    """Algorithm 1 with Sinkhorn on the residual problem.  Returns dict(assign[T,2], plan or None, caps)."""
+    torch = _torch()
+    T, E = scores.shape
+    assert scores.dtype == torch.float32 and scores.is_contiguous()
+    assign = torch.empty((T, 2), dtype=torch.int32, device=scores.device)
+    plan = torch.empty_like(scores) if want_plan else None
+    caps = (ctypes.c_int32 * E)()
+    ws, need = _workspace(T, E, 2, C, scores.device)
+    rc = load_library().maxscore_assign_top1_sinkhorn(_ptr(scores), T, E, C, float(tau), int(n_iter), _ptr(assign),
+                                                      _ptr(plan), ctypes.addressof(caps), _ptr(ws), need,
+                                                      _stream())
+    _check(rc, "maxscore_assign_top1_sinkhorn")
+    return dict(assign=assign, plan=plan, caps=list(caps))
 
 
 def gates(scores, assign):

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmaxscore.so")
-SOURCES = ["api.cpp", "solver.hip", "softtopk.hip", "dispatch.hip", "movement.hip", "iter.hip", "training.hip", "operators.hip", "alg1.hip", "gemm.hip"]
+SOURCES = ["api.cpp", "solver.hip", "softtopk.hip", "dispatch.hip", "movement.hip", "iter.hip", "training.hip", "operators.hip", "alg1.hip", "sinkhorn.hip", "gemm.hip"]
 
 
 def build(verbose: bool = False) -> str:

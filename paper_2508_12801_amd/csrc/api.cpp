@@ -180,6 +180,18 @@ int32_t maxscore_assign_top1_residual_i32(const int32_t *q, int32_t T, int32_t E
                     (hipStream_t)stream);
 }
 
+int32_t maxscore_assign_top1_sinkhorn(const float *scores, int32_t T, int32_t E, int32_t C, float tau,
+                                      int32_t n_iter, int32_t *assign, float *plan, int32_t *residual_capacity,
+                                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!scores || !assign) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, 2, C) || !(tau > 0.f) || n_iter < 0 || n_iter > 100000) return MAXSCORE_ERR_SHAPE;
+    int32_t rc = check_ws(workspace, workspace_bytes, T, E, 2);
+    if (rc) return rc;
+    return sinkhorn_run(scores, T, E, C, tau, n_iter, assign, plan, residual_capacity, (char *)workspace,
+                        (hipStream_t)stream);
+}
+
 int32_t maxscore_gates(const float *scores, const int32_t *assign, int32_t T, int32_t E, int32_t k, float *gates,
                        void *stream)
 {

@@ -96,6 +96,9 @@ int32_t caps_to_device(const int32_t *caps_host, int T, int E, int k, char *ws, 
 int32_t alg1_run(const int32_t *q, int T, int E, int C, const maxscore_opts &o, int32_t *q_residual,
                  int32_t *assign, int32_t *caps_out, int64_t *total, int32_t *flow, maxscore_stats *stats, char *ws,
                  hipStream_t s);
+// --- sinkhorn.hip
+int32_t sinkhorn_run(const float *scores, int T, int E, int C, float tau, int n_iter, int32_t *assign, float *plan,
+                     int32_t *caps_host, char *ws, hipStream_t s);
 // --- training.hip
 int32_t aux_loss_run(const float *scores, const int32_t *offsets, int T, int E, float lam, float *loss,
                      float *mean_scores, float *dscores_col, char *ws, hipStream_t s);
