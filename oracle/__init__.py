@@ -7,4 +7,4 @@ from .reference import (build, router_logits, softmax_rows, descending_rank, sof
                         assign_literal_graph, assign_contracted, max_score_assignment,
                         max_score_assignment_caps, top1_then_residual, sinkhorn_plan, top1_then_sinkhorn,
                         max_flow_value, assignment_matrix, check_feasible, verify_optimal, gates,
-                        dispatch, dispatch_tokens, combine, iter_reroute, sigmoid_scores, softkmax, itertopk, aux_loss, gates_backward, route, route_from_logits)
+                        dispatch, dispatch_tokens, combine, iter_reroute, sigmoid_scores, softkmax, itertopk, gradtopk, aux_loss, gates_backward, route, route_from_logits)

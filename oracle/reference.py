@@ -13,7 +13,7 @@ Everything is fp64 / int64 and written to be checked against the paper by eye:
   gates              Eq. 2: the affinity of each selected (token, expert) pair, not renormalised
   dispatch           per-expert buffers (Section 2.3 capacity layout): stable sort by expert
   verify_optimal     independent optimality proof for any assignment (no negative residual cycle)
-  sigmoid_scores, softkmax, itertopk   other operators of Table 2 (base cases are a stated reading)
+  sigmoid_scores, softkmax, itertopk, gradtopk   other operators of Table 2 (base cases are a stated reading)
   aux_loss           Eq. 9 load-balance loss and its derivative with respect to the scores
   gates_backward     derivative of the selected scores (and of Eq. 9) with respect to the logits
   max_score_assignment_caps   the exact assignment with one capacity per expert
@@ -602,3 +602,19 @@ def top1_then_sinkhorn(A, C: int, tau: float, n_iter: int) -> dict:
     assign = np.stack([top1, second], axis=1).astype(np.int64)
     load2 = np.bincount(second[second >= 0], minlength=E)
     return dict(assign=assign, caps=caps, plan=sk["plan"], load2=load2, a_res=a_res, v=sk["v"], u=sk["u"])
+
+
+def gradtopk(L: np.ndarray, k: int) -> np.ndarray:
+    """Table 2, GradTopk, level by level as printed:
+        g^(m) = x + log(e^{z^(m-1)} - e^{g^(m-1)}),  z^(m) = log sum_j e^{g^(m)_j} - log m,  y^(m) = e^{g^(m) - z^(m)}.
+    The table gives no base case; reading: e^{z^(0)} - e^{g^(0)} = 1, i.e. g^(1) = x, so that level 1 is
+    Softmax(x).  Where a level-(m-1) value reaches 1 the logarithm has no real value: NaN, as printed."""
+    x = np.asarray(L, dtype=np.float64)
+    g = x.copy()
+    with np.errstate(invalid="ignore", divide="ignore"):
+        for m in range(1, k + 1):
+            if m > 1:
+                g = x + np.log(np.exp(z) - np.exp(g))
+            gm = np.where(np.isnan(g), -np.inf, g).max(axis=1, keepdims=True)
+            z = gm + np.log(np.exp(g - gm).sum(axis=1, keepdims=True)) - np.log(m)
+        return np.exp(g - z)

@@ -53,3 +53,25 @@ def test_itertopk_is_shift_invariant_and_softkmax_is_not():
     L = logits(4)
     assert np.allclose(oracle.itertopk(L + 3.0, 3), oracle.itertopk(L, 3), rtol=1e-12)
     assert not np.allclose(oracle.softkmax(L + 3.0, 3), oracle.softkmax(L, 3), rtol=1e-6)   # g multiplies x
+
+
+def test_gradtopk_level_one_row_sums_and_the_level_two_closed_form():
+    L = logits(5, T=40, E=9)
+    p = softmax(L, axis=1)
+    assert np.allclose(oracle.gradtopk(L, 1), p, rtol=1e-13)
+    for k in (2, 3, 4):
+        y = oracle.gradtopk(L, k)
+        assert np.isfinite(y).all() and np.allclose(y.sum(axis=1), k, rtol=1e-12)
+    # level 2 by hand: e^{g2} = e^x (S - e^x), so y2 = 2 p (1 - p) / sum p (1 - p)
+    w = p * (1 - p)
+    assert np.allclose(oracle.gradtopk(L, 2), 2 * w / w.sum(axis=1, keepdims=True), rtol=1e-12)
+    assert np.allclose(oracle.gradtopk(np.full((2, 8), -0.3), 3), 3 / 8)
+    # p = (0.6, 0.3, 0.1): p(1-p) = (0.24, 0.21, 0.09), sum 0.54 -> y2 = (8/9, 7/9, 1/3)
+    L3 = np.log(np.array([[0.6, 0.3, 0.1]]))
+    assert np.allclose(oracle.gradtopk(L3, 2), [[8 / 9, 7 / 9, 1 / 3]], rtol=1e-13)
+
+
+def test_gradtopk_leaves_its_domain_for_two_equal_experts():
+    y2 = oracle.gradtopk(np.zeros((1, 2)), 2)
+    assert np.allclose(y2, 1.0)                          # both values reach 1 ...
+    assert not np.isfinite(oracle.gradtopk(np.zeros((1, 2)), 3)).any()   # ... and level 3 takes log(0)
