@@ -176,7 +176,7 @@ def main():
 
     # the other operators of Table 2 as alternative score kernels (same rows, 12*T*E bytes each)
     operators = {}
-    for op, levels in (("sigmoid", 1), ("softkmax", k), ("itertopk", 2)):
+    for op, levels in (("sigmoid", 1), ("softkmax", k), ("itertopk", 2), ("gradtopk", 2)):
         op_ms = timed(lambda: ms.scores_op(logits, levels, op))
         operators[op] = {"levels": levels, "ms": op_ms,
                          "hbm_frac": 12 * T * E / (op_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}

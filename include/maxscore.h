@@ -133,12 +133,16 @@ int32_t maxscore_dispatch(const int32_t *assign, const float *gates, int32_t T, 
  *   MAXSCORE_OP_SIGMOID   y = 1 / (1 + e^-x)
  *   MAXSCORE_OP_SOFTKMAX  y^(m) = y^(m-1) + Softmax((1 - y^(m-1)) * x), m = 1..k
  *   MAXSCORE_OP_ITERTOPK  y^(m) = y^(m-1) + w e^x / sum_j w_j e^x_j with w = 1 - y^(m-1), m = 1..k
- * The table gives no base case: y^(0) = 0 is used (level 1 is Softmax).  IterTopk is evaluated as printed
+ *   MAXSCORE_OP_GRADTOPK  g^(m) = x + log(e^{z^(m-1)} - e^{g^(m-1)}), z^(m) = logsumexp(g^(m)) - log m,
+ *                         y^(m) = e^{g^(m) - z^(m)}, evaluated in the equal form y^(m) = m w e^x / sum_j w_j e^x_j;
+ *                         a row in which some level-(m-1) value exceeds 1 turns NaN (the logarithm has no value)
+ * The table gives no base case: y^(0) = 0 (GradTopk: g^(1) = x) is used, so level 1 is Softmax.  IterTopk is evaluated as printed
  * (its weights may turn negative from level 3 on; a row whose weighted sum reaches 0 gives non-finite
  * values).  The integer rewards are only meaningful when score * 2^quant_shift fits 32 bits.  Only enqueues. */
 #define MAXSCORE_OP_SIGMOID 1
 #define MAXSCORE_OP_SOFTKMAX 2
 #define MAXSCORE_OP_ITERTOPK 3
+#define MAXSCORE_OP_GRADTOPK 4
 int32_t maxscore_scores_op(const float *logits, int32_t T, int32_t E, int32_t k, int32_t op, int32_t quant_shift,
                            float *scores, int32_t *q, void *stream);
 

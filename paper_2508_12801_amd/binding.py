@@ -214,7 +214,7 @@ def softtopk(logits, k: int, t: float, quant_shift: int = 20):
     return scores, q
 
 
-OPS = {"sigmoid": 1, "softkmax": 2, "itertopk": 3}
+OPS = {"sigmoid": 1, "softkmax": 2, "itertopk": 3, "gradtopk": 4}
 
 
 def scores_op(logits, k: int, op: str, quant_shift: int = 20):

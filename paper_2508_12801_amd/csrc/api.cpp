@@ -107,8 +107,7 @@ int32_t maxscore_scores_op(const float *logits, int32_t T, int32_t E, int32_t k,
 {
     if (!logits || (!scores && !q)) return MAXSCORE_ERR_NULL;
     if (!shape_ok(T, E, k, 1) || quant_shift < 1 || quant_shift > 24) return MAXSCORE_ERR_SHAPE;
-    if (op != MAXSCORE_OP_SIGMOID && op != MAXSCORE_OP_SOFTKMAX && op != MAXSCORE_OP_ITERTOPK)
-        return MAXSCORE_ERR_SHAPE;
+    if (op < MAXSCORE_OP_SIGMOID || op > MAXSCORE_OP_GRADTOPK) return MAXSCORE_ERR_SHAPE;
     return scores_op_run(logits, T, E, k, op, quant_shift, scores, q, (hipStream_t)stream);
 }
 

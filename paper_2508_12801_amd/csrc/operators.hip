@@ -1,6 +1,6 @@
 // Other routing operators of Table 2 (Section 3.1) as alternatives to SoftTopk for the affinity scores:
-// Sigmoid, SoftKmax and IterTopk.  The table gives the recursions without a base case; y^(0) = 0 is used, so
-// that level 1 of both recursions is Softmax(x).  One wavefront per token row; lane l holds experts l, l+64, ...
+// Sigmoid, SoftKmax, IterTopk and GradTopk.  The table gives the recursions without a base case; y^(0) = 0 is
+// used (for GradTopk: g^(1) = x), so that level 1 of every recursion is Softmax(x).  One wavefront per token row; lane l holds experts l, l+64, ...
 #include "common.h"
 
 namespace maxscore {
@@ -58,6 +58,30 @@ __global__ __launch_bounds__(256) void k_scores_op(const float *__restrict__ log
                 const float inv = 1.f / wave_sum_f(z);
 #pragma unroll
                 for (int c = 0; c < EPL; ++c) y[c] += g[c] * inv;
+            }
+        } else if (op == MAXSCORE_OP_GRADTOPK) {
+            // g^(m) = x + log(e^{z^(m-1)} - e^{g^(m-1)}) and y = e^{g - z} with z = logsumexp(g) - log m give
+            // y^(m) = m * w e^x / sum_j w_j e^{x_j}, w = 1 - y^(m-1) (w = 1 at level 1); the logarithm has no
+            // value for w < 0: the row turns NaN as in the printed form
+            float mx = -INFINITY;
+#pragma unroll
+            for (int c = 0; c < EPL; ++c) mx = fmaxf(mx, in[c] ? x[c] : -INFINITY);
+            mx = wave_max_f(mx);
+            float ex[EPL];
+#pragma unroll
+            for (int c = 0; c < EPL; ++c) ex[c] = in[c] ? expf(x[c] - mx) : 0.f;
+            for (int m = 1; m <= k; ++m) {
+                float term[EPL];
+                float z = 0.f;
+#pragma unroll
+                for (int c = 0; c < EPL; ++c) {
+                    const float w = m == 1 ? 1.f : 1.f - y[c];
+                    term[c] = !in[c] ? 0.f : (w > 0.f ? w * ex[c] : (w == 0.f ? 0.f : NAN));
+                    z += term[c];
+                }
+                const float scale_m = (float)m / wave_sum_f(z);
+#pragma unroll
+                for (int c = 0; c < EPL; ++c) y[c] = term[c] * scale_m;
             }
         } else {   // MAXSCORE_OP_ITERTOPK
             float mx = -INFINITY;

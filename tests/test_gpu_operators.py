@@ -9,7 +9,8 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
-REF = {"sigmoid": lambda L, k: oracle.sigmoid_scores(L), "softkmax": oracle.softkmax, "itertopk": oracle.itertopk}
+REF = {"sigmoid": lambda L, k: oracle.sigmoid_scores(L), "softkmax": oracle.softkmax, "itertopk": oracle.itertopk,
+       "gradtopk": oracle.gradtopk}
 
 
 @pytest.fixture(scope="module")
@@ -25,14 +26,14 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-@pytest.mark.parametrize("op", ["sigmoid", "softkmax", "itertopk"])
+@pytest.mark.parametrize("op", ["sigmoid", "softkmax", "itertopk", "gradtopk"])
 @pytest.mark.parametrize("T,E,k", [(300, 8, 2), (1000, 16, 4), (4099, 64, 2), (257, 7, 3), (2048, 128, 8),
                                    (700, 300, 6), (130, 1024, 2), (65, 5, 1)])
 def test_scores_match_the_checker(ms, op, T, E, k):
     print(f"operator {op} T={T} E={E} k={k}", flush=True)
     rng = np.random.default_rng(T + E + k)
     L = (rng.normal(size=(T, E)) + 1.0 * rng.normal(size=(1, E))).astype(np.float32)
-    kk = min(k, 2) if op == "itertopk" else k            # levels 1-2 keep IterTopk's weights positive
+    kk = min(k, 2) if op in ("itertopk", "gradtopk") else k   # levels 1-2 stay inside the domain on peaked rows
     sc, q = ms.scores_op(dev(L), kk, op)
     ref = REF[op](L.astype(np.float64), kk)
     got = sc.cpu().numpy()
@@ -40,6 +41,21 @@ def test_scores_match_the_checker(ms, op, T, E, k):
     # the integer is decided in the kernel's own precision
     assert np.array_equal(q.cpu().numpy(), np.rint(got.astype(np.float32) * np.float32(1 << 20)).astype(np.int64))
     assert np.abs(q.cpu().numpy() - oracle.quantise(ref)).max() <= max(2, 2e-5 * oracle.quantise(ref).max())
+
+
+def test_gradtopk_deeper_levels_and_the_edge_of_its_domain(ms):
+    print("gradtopk k=4", flush=True)
+    rng = np.random.default_rng(13)
+    L = (0.3 * rng.normal(size=(2000, 64))).astype(np.float32)     # flat rows: every level stays below 1
+    sc, _ = ms.scores_op(dev(L), 4, "gradtopk")
+    ref = oracle.gradtopk(L.astype(np.float64), 4)
+    assert np.isfinite(ref).all()
+    assert np.allclose(sc.cpu().numpy(), ref, rtol=1e-5, atol=1e-7)
+    # the edge of the domain that the size checks (k <= E) leave reachable: two equally likely experts reach
+    # exactly 1 at level 2
+    L2 = np.zeros((4, 2), dtype=np.float32)
+    assert np.allclose(ms.scores_op(dev(L2), 2, "gradtopk")[0].cpu().numpy(), 1.0)
+    assert np.allclose(oracle.gradtopk(L2.astype(np.float64), 2), 1.0)
 
 
 def test_itertopk_deeper_levels_away_from_the_pole(ms):

@@ -104,4 +104,4 @@ def test_rejected_sizes(ms):
     with pytest.raises(ms.MaxScoreError):
         ms.assign_top1_residual_i32(dev(np.zeros((4, 1), dtype=np.int32)), 8)   # top-2 needs two experts
     with pytest.raises(KeyError):
-        ms.scores_op(dev(np.zeros((4, 4), dtype=np.float32)), 2, "gradtopk")
+        ms.scores_op(dev(np.zeros((4, 4), dtype=np.float32)), 2, "no such operator")
