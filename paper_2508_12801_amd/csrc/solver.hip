@@ -575,7 +575,9 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
     __shared__ long long s_ikey[kTailIns];
     __shared__ int s_qrow[kTailThreads / 64][kTailMaxE];
     __shared__ int s_nv2[2], s_ni2[2], s_over2[2];     // per-iteration counters, double-buffered by iteration parity
-    __shared__ int s_stop, s_moves, s_changed, s_sink;
+    // stop requests: s_stop1 is written in step 1 and read after the barrier that ends it, s_stop2 likewise for
+    // step 2, so a flag is never written between a barrier and the reads that follow that barrier
+    __shared__ int s_stop1, s_stop2, s_moves, s_changed, s_sink;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const long long eps = st->eps, qmin = st->qmin;
@@ -600,7 +602,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         s_capv[e] = cap ? cap[e] : Ce;
     }
     if (tid == 0) {
-        s_stop = 0; s_moves = 0; s_changed = 0;
+        s_stop1 = 0; s_stop2 = 0; s_moves = 0; s_changed = 0;
         s_nv2[0] = s_nv2[1] = 0; s_ni2[0] = s_ni2[1] = 0; s_over2[0] = s_over2[1] = 0;
     }
     __syncthreads();
@@ -613,26 +615,67 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
 #endif
     int it = 0, over_last = 0;
     for (; it < max_iters; ++it) {
-        // the counters of this iteration were cleared during the previous one; clear the next ones
+        // the counters are double-buffered by iteration parity: this iteration's were cleared during the last one
         const int pi = it & 1;
         int &s_nv = s_nv2[pi], &s_ni = s_ni2[pi], &s_over = s_over2[pi];
-        if (tid == 0) { s_nv2[pi ^ 1] = 0; s_ni2[pi ^ 1] = 0; s_over2[pi ^ 1] = 0; }
         // rows of the first entry each expert pops are requested here, one load per cache line, so that
         // the evaluation after the barrier finds them close by
         int pfv[kTailMaxE / 32 + 1];
         bool pf_live = false;
-        // 1. every over-full expert drops its lowest candidates and raises its threshold
-        for (int e = tid; e < E; e += kTailThreads) {
+        // 0. the keys requested in the previous iteration enter the lists in request order; wavefront w serves
+        //    the experts e with e mod 16 = w (its first kCand lanes hold one list entry each) and, right after,
+        //    runs step 1 for the same experts, so no workgroup barrier is needed between the two
+        if (it > 0) {
+            const int ni_prev = s_ni2[pi ^ 1];
+            const int ni = ni_prev < kTailIns ? ni_prev : kTailIns;
+            for (int r = 0; r < ni; ++r) {
+                const int e = __builtin_amdgcn_readfirstlane(s_iexp[r]);
+                if ((e & (kTailThreads / 64 - 1)) != wv) continue;
+                const long long key = s_ikey[r];
+                long long *ce = s_cand + e * kCand;
+                int cn = s_cn[e];
+                long long val = (lane < cn && lane < kCand) ? ce[lane] : -1;
+                bool skip = false;
+                if (cn == kCand) {
+                    const long long top = ce[0];                 // largest listed key
+                    if (key > top) {
+                        if (lane == 0 && key < s_bound[e]) s_bound[e] = key;   // stays off the list
+                        skip = true;
+                    } else {
+                        if (lane == 0) s_bound[e] = top;         // the largest listed key leaves the list
+                        val = (lane + 1 < cn) ? ce[lane + 1] : -1;
+                        --cn;
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+                if (!skip) {
+                    const bool above = lane < cn && val > key;
+                    const int pos = __popcll(__ballot(above));
+                    if (lane < cn) ce[above ? lane : lane + 1] = val;
+                    if (lane == 0) {
+                        ce[pos] = key;
+                        s_cn[e] = cn + 1;
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+        }
+        MS_TP(c_p3)
+        // 1. every over-full expert drops its lowest candidates and raises its threshold (expert e: lane e/16 of
+        //    wavefront e mod 16)
+        for (int e = wv + (kTailThreads / 64) * lane; e < E; e += kTailThreads) {
             const int m = s_n[e] - s_capv[e];
             if (m > 0) {
                 s_over = 1;
                 const int cn = s_cn[e];
                 if (cn < m) {
-                    s_stop = 1;                        // list exhausted: the select pass has to rebuild it
+                    s_stop1 = 1;                       // list exhausted: the select pass has to rebuild it
                 } else {
                     const int b = atomicAdd(&s_nv, m);
                     if (b + m > kTailVict) {
-                        s_stop = 1;
+                        s_stop1 = 1;
                     } else {
                         const long long *ce = s_cand + e * kCand;
                         for (int i = 0; i < m; ++i) {
@@ -660,8 +703,10 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         }
         __syncthreads();
         MS_TP(c_p1)
+        // the counters of the other parity were last read in step 0 above; the next iteration starts from zero
+        if (tid == 0) { s_nv2[pi ^ 1] = 0; s_ni2[pi ^ 1] = 0; s_over2[pi ^ 1] = 0; }
         over_last = s_over;
-        if (s_stop || !s_over) break;
+        if (s_stop1 || !s_over) break;
         // 2. one wavefront per dropped token: the bid pass's row evaluation
         const int nv = s_nv < kTailVict ? s_nv : kTailVict;
         for (int vi = wv; vi < nv; vi += kTailThreads / 64) {
@@ -734,7 +779,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                         s_iexp[slot] = e;
                         s_ikey[slot] = key;
                     } else {
-                        s_stop = 1;
+                        s_stop2 = 1;
                     }
                 }
             };
@@ -882,47 +927,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
             for (int c = 0; c <= kTailMaxE / 32; ++c) acc ^= pfv[c];
             s_sink = acc;
         }
-        // 3. the new keys enter the lists in request order; wavefront w serves the experts e with
-        //    e mod 16 = w, its first kCand lanes hold one list entry each
-        {
-            const int ni = s_ni < kTailIns ? s_ni : kTailIns;
-            for (int r = 0; r < ni; ++r) {
-                const int e = __builtin_amdgcn_readfirstlane(s_iexp[r]);
-                if ((e & (kTailThreads / 64 - 1)) != wv) continue;
-                const long long key = s_ikey[r];
-                long long *ce = s_cand + e * kCand;
-                int cn = s_cn[e];
-                long long val = (lane < cn && lane < kCand) ? ce[lane] : -1;
-                bool skip = false;
-                if (cn == kCand) {
-                    const long long top = ce[0];                 // largest listed key
-                    if (key > top) {
-                        if (lane == 0 && key < s_bound[e]) s_bound[e] = key;   // stays off the list
-                        skip = true;
-                    } else {
-                        if (lane == 0) s_bound[e] = top;         // the largest listed key leaves the list
-                        val = (lane + 1 < cn) ? ce[lane + 1] : -1;
-                        --cn;
-                    }
-                }
-                __builtin_amdgcn_wave_barrier();
-                if (!skip) {
-                    const bool above = lane < cn && val > key;
-                    const int pos = __popcll(__ballot(above));
-                    if (lane < cn) ce[above ? lane : lane + 1] = val;
-                    if (lane == 0) {
-                        ce[pos] = key;
-                        s_cn[e] = cn + 1;
-                    }
-                }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            }
-        }
-        __syncthreads();
-        MS_TP(c_p3)
-        if (s_stop) break;
+        if (s_stop2) break;
     }
     for (int e = tid; e < E; e += kTailThreads) {
         theta[e] = s_theta[e];
@@ -932,7 +937,8 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         // Ended with nothing over capacity: every hold is valid, the phase is quiescent.  Without slack
         // there is no price lowering to decide, so the next round starts the next phase right away
         // (the last phase still gets its full check by a bid pass).
-        if (!s_stop && !over_last && !st->slack && st->eps > 1) {
+        const int stopped = s_stop1 | s_stop2;
+        if (!stopped && !over_last && !st->slack && st->eps > 1) {
             if (st->phases <= 28) st->phase_round[st->phases - 1] = st->round;
             st->eps_prev = st->eps;
             const long long ne = st->eps / st->eps_div;
@@ -941,7 +947,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
             st->moves = T;
         }
         st->after_tail = (s_changed || s_moves) ? 1 : 0;
-        st->tail_block = s_stop;
+        st->tail_block = stopped;
         st->tail_go = 0;
         st->tail_runs += 1;
         st->tail_iters += it;
