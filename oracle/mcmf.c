@@ -17,6 +17,9 @@
  *                    reduced costs non-negative so a dense Dijkstra finds each path.  Needs
  *                    T*k <= E*min(C,T) (every token is then forced to ship k units, so paths
  *                    may start from the tokens in any order).
+ * Both also exist with one k per token and one capacity per expert (the vectors k and c of
+ * Eq. 7): in Table 1 the arc Source -> Token_i then gets capacity k[i] and Expert_j -> Sink
+ * capacity c[j].
  *
  * Shares no code with the GPU library.
  */
@@ -47,11 +50,13 @@ static void g_add(graph_t *g, int a, int b, int cap, int64_t cost)
 
 /* Returns 0 on success.  P[T*E] receives the assignment, *flow the flow value, *total the
  * reward sum, *n_arcs the number of arcs of Table 1 that were built (without twins). */
-/* caps[j] is the capacity of the arc Expert_j -> Sink (the capacity vector c of Eq. 7). */
-int mcmf_literal_caps(const int64_t *q, int T, int E, int k, const int *caps, uint8_t *P, int64_t *flow,
-                      int64_t *total, int64_t *n_arcs)
+/* kvec[i] is the capacity of the arc Source -> Token_i and caps[j] that of Expert_j -> Sink (the
+ * vectors k and c of Eq. 7). */
+int mcmf_literal_kc(const int64_t *q, int T, int E, const int *kvec, const int *caps, uint8_t *P, int64_t *flow,
+                    int64_t *total, int64_t *n_arcs)
 {
-    if (T <= 0 || E <= 0 || k < 0 || !caps) return 1;
+    if (T <= 0 || E <= 0 || !kvec || !caps) return 1;
+    for (int i = 0; i < T; i++) if (kvec[i] < 0) return 1;
     for (int j = 0; j < E; j++) if (caps[j] < 0) return 1;
     int S = 0, Z = T + E + 1, n = T + E + 2;
     int64_t arcs = (int64_t)T + E + (int64_t)T * E;
@@ -66,7 +71,7 @@ int mcmf_literal_caps(const int64_t *q, int T, int E, int k, const int *caps, ui
     int *par = malloc(sizeof(int) * n), *queue = malloc(sizeof(int) * n);
     uint8_t *inq = malloc(n);
     for (int v = 0; v < n; v++) g.head[v] = -1;
-    for (int i = 0; i < T; i++) g_add(&g, S, 1 + i, k, 0);                  /* Source -> Token_i  */
+    for (int i = 0; i < T; i++) g_add(&g, S, 1 + i, kvec[i], 0);            /* Source -> Token_i  */
     for (int j = 0; j < E; j++) g_add(&g, 1 + T + j, Z, caps[j], 0);        /* Expert_j -> Sink   */
     int first_te = g.m;
     for (int i = 0; i < T; i++)                                             /* Token_i -> Expert_j */
@@ -107,6 +112,18 @@ int mcmf_literal_caps(const int64_t *q, int T, int E, int k, const int *caps, ui
     free(g.head); free(g.nxt); free(g.to); free(g.cap); free(g.cost);
     free(dist); free(par); free(queue); free(inq);
     return 0;
+}
+
+/* The same k for every token, caps[j] on the arc Expert_j -> Sink. */
+int mcmf_literal_caps(const int64_t *q, int T, int E, int k, const int *caps, uint8_t *P, int64_t *flow,
+                      int64_t *total, int64_t *n_arcs)
+{
+    if (T <= 0 || k < 0) return 1;
+    int *kvec = malloc(sizeof(int) * T);
+    for (int i = 0; i < T; i++) kvec[i] = k;
+    int rc = mcmf_literal_kc(q, T, E, kvec, caps, P, flow, total, n_arcs);
+    free(kvec);
+    return rc;
 }
 
 /* Uniform capacity C on every expert (Table 1 as printed). */
@@ -186,15 +203,23 @@ static void c_remove(cstate_t *s, int u, int j)
     }
 }
 
-/* Per-expert capacities caps[j] (clamped to T); the precondition is T*k <= sum_j min(caps[j], T).
+/* Per-token kvec[i] <= E and per-expert capacities caps[j] (clamped to T); the precondition is
+ * sum_i kvec[i] <= sum_j min(caps[j], T).
  * Returns 0 on success, 1 bad arguments, 2 precondition violated, 3 internal
- * invariant (negative reduced cost) violated.  prices[E] receives expert prices p_j >= 0 with
- * p_j = 0 on every expert left with spare capacity, such that every token holds k experts of
+ * invariant (negative reduced cost) violated, 4 a token cannot ship all its units although the
+ * precondition holds (unequal capacities can leave fewer experts with room than a token needs:
+ * the literal graph then gives the answer).  prices[E] receives expert prices p_j >= 0 with
+ * p_j = 0 on every expert left with spare capacity, such that every token i holds kvec[i] experts of
  * largest q_ij - p_j (a dual optimum).  *n_paths = augmentations, *n_hops = expert hops. */
-int mcmf_contracted_caps(const int64_t *q, int T, int E, int k, const int *caps, uint8_t *P, int64_t *prices,
-                         int64_t *flow, int64_t *total, int64_t *n_paths, int64_t *n_hops)
+int mcmf_contracted_kc(const int64_t *q, int T, int E, const int *kvec, const int *caps, uint8_t *P,
+                       int64_t *prices, int64_t *flow, int64_t *total, int64_t *n_paths, int64_t *n_hops)
 {
-    if (T <= 0 || E <= 0 || k < 0 || !caps || k > E) return 1;
+    if (T <= 0 || E <= 0 || !kvec || !caps) return 1;
+    int64_t demand = 0;
+    for (int i = 0; i < T; i++) {
+        if (kvec[i] < 0 || kvec[i] > E) return 1;
+        demand += kvec[i];
+    }
     int *cap = malloc(sizeof(int) * E);
     int64_t room = 0;
     for (int j = 0; j < E; j++) {
@@ -202,7 +227,7 @@ int mcmf_contracted_caps(const int64_t *q, int T, int E, int k, const int *caps,
         cap[j] = caps[j] < T ? caps[j] : T;
         room += cap[j];
     }
-    if ((int64_t)T * k > room) { free(cap); return 2; }
+    if (demand > room) { free(cap); return 2; }
     cstate_t s;
     s.T = T; s.E = E; s.q = q;
     s.held = calloc((size_t)T * E, 1);
@@ -221,7 +246,7 @@ int mcmf_contracted_caps(const int64_t *q, int T, int E, int k, const int *caps,
     int64_t paths = 0, hops = 0;
 
     for (int i = 0; i < T && !rc; i++) {
-        for (int rep = 0; rep < k && !rc; rep++) {
+        for (int rep = 0; rep < kvec[i] && !rc; rep++) {
             /* dense Dijkstra over experts + sink on reduced costs c + phi[a] - phi[b], phi[sink] = 0 */
             const int64_t *qi = q + (int64_t)i * E;
             for (int j = 0; j < E; j++) {
@@ -250,7 +275,7 @@ int mcmf_contracted_caps(const int64_t *q, int T, int E, int k, const int *caps,
                 if (rc) break;
             }
             if (rc) break;
-            if (parZ < 0) { rc = 3; break; }      /* cannot happen under the precondition */
+            if (parZ < 0) { rc = 4; break; }      /* this unit cannot be shipped (possible only with unequal capacities) */
             for (int j = 0; j < E; j++) phi[j] += (d[j] < dZ ? d[j] : dZ) - dZ;
             int len = 0;
             for (int j = parZ; j >= 0; j = par[j]) path[len++] = j;   /* sink side first */
@@ -270,6 +295,18 @@ int mcmf_contracted_caps(const int64_t *q, int T, int E, int k, const int *caps,
     for (int j = 0; j < E; j++) free(s.mem[j]);
     free(s.held); free(s.pos); free(s.mem); free(s.load); free(s.L); free(s.arg); free(s.dirty);
     free(phi); free(d); free(par); free(partok); free(path); free(done); free(cap);
+    return rc;
+}
+
+/* The same k for every token. */
+int mcmf_contracted_caps(const int64_t *q, int T, int E, int k, const int *caps, uint8_t *P, int64_t *prices,
+                         int64_t *flow, int64_t *total, int64_t *n_paths, int64_t *n_hops)
+{
+    if (T <= 0 || k < 0) return 1;
+    int *kvec = malloc(sizeof(int) * T);
+    for (int i = 0; i < T; i++) kvec[i] = k;
+    int rc = mcmf_contracted_kc(q, T, E, kvec, caps, P, prices, flow, total, n_paths, n_hops);
+    free(kvec);
     return rc;
 }
 

@@ -17,6 +17,7 @@ Everything is fp64 / int64 and written to be checked against the paper by eye:
   aux_loss           Eq. 9 load-balance loss and its derivative with respect to the scores
   gates_backward     derivative of the selected scores (and of Eq. 9) with respect to the logits
   max_score_assignment_caps   the exact assignment with one capacity per expert
+  max_score_assignment_kvec   the exact assignment with one k per token (and one capacity per expert)
   top1_then_residual Algorithm 1 steps 4-8 with the residual problem solved exactly
   sinkhorn_plan, top1_then_sinkhorn   Algorithm 1 with Sinkhorn on the residual problem (a stated reading)
   iter_reroute       Section 2.3 iterative rerouting: top-k with capacity, then greedy re-proposal rounds
@@ -64,6 +65,11 @@ def _load():
         _lib.mcmf_contracted_caps.argtypes = [i64p, ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p,
                                               u8p, i64p, i64p, i64p, i64p, i64p]
         _lib.mcmf_contracted_caps.restype = ctypes.c_int
+        _lib.mcmf_literal_kc.argtypes = [i64p, ctypes.c_int, ctypes.c_int, i32p, i32p, u8p, i64p, i64p, i64p]
+        _lib.mcmf_literal_kc.restype = ctypes.c_int
+        _lib.mcmf_contracted_kc.argtypes = [i64p, ctypes.c_int, ctypes.c_int, i32p, i32p,
+                                            u8p, i64p, i64p, i64p, i64p, i64p]
+        _lib.mcmf_contracted_kc.restype = ctypes.c_int
     return _lib
 
 
@@ -202,6 +208,41 @@ def max_score_assignment_caps(q, k: int, caps) -> dict:
     return dict(P=P, flow=flow.value, total=total.value)
 
 
+def max_score_assignment_kvec(q, kvec, C, solver: str = "auto") -> dict:
+    """The same optimum with a k of its own for every token (the vector k of Eq. 7; Table 1's Source -> Token_i
+    arc gets capacity kvec[i]) and C either one capacity for all experts or one per expert.  Contracted solver
+    when every kvec[i] <= E and sum_i kvec[i] <= sum_j min(C_j, T) (with one capacity for all experts every
+    token then ships all its units: a deficient expert set J would need more than C tokens with more than
+    E - |J| units each, i.e. more than E*C units in total; with unequal capacities the contracted solver can
+    report that a token cannot ship all its units, and the literal graph takes over); literal graph otherwise.  `solver` = "literal" or
+    "contracted" forces one of them."""
+    q = _as_q(q)
+    T, E = q.shape
+    kvec = np.ascontiguousarray(kvec, dtype=np.int32)
+    caps = np.ascontiguousarray(np.broadcast_to(np.asarray(C, dtype=np.int32), (E,)))
+    assert kvec.shape == (T,) and (kvec >= 0).all() and (caps >= 0).all()
+    P = np.zeros((T, E), dtype=np.uint8)
+    i32p, i64p = ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int64)
+    qp, kp, cp = q.ctypes.data_as(i64p), kvec.ctypes.data_as(i32p), caps.ctypes.data_as(i32p)
+    Pp = P.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+    fits = int(kvec.max(initial=0)) <= E and int(kvec.sum()) <= int(np.minimum(caps, T).sum())
+    if solver == "contracted" or (solver == "auto" and fits):
+        prices = np.zeros(E, dtype=np.int64)
+        flow, total, paths, hops = (ctypes.c_int64() for _ in range(4))
+        rc = _load().mcmf_contracted_kc(qp, T, E, kp, cp, Pp, prices.ctypes.data_as(i64p), ctypes.byref(flow),
+                                        ctypes.byref(total), ctypes.byref(paths), ctypes.byref(hops))
+        if rc == 0:
+            return dict(P=P, prices=prices, flow=flow.value, total=total.value)
+        if rc != 4 or solver == "contracted":
+            raise ValueError(f"mcmf_contracted_kc failed rc={rc}")
+        P[:] = 0          # some token cannot ship all its units: the literal graph decides who ships what
+    flow, total, arcs = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    rc = _load().mcmf_literal_kc(qp, T, E, kp, cp, Pp, ctypes.byref(flow), ctypes.byref(total), ctypes.byref(arcs))
+    if rc:
+        raise ValueError(f"mcmf_literal_kc failed rc={rc}")
+    return dict(P=P, flow=flow.value, total=total.value)
+
+
 def max_flow_value(T: int, E: int, k: int, C: int) -> int:
     """Flow value of the complete bipartite network of Table 1 when k <= E."""
     return min(T * k, E * min(C, T))
@@ -234,8 +275,9 @@ def check_feasible(P: np.ndarray, k: int, C: int) -> Tuple[bool, str]:
     return True, ""
 
 
-def verify_optimal(q, P, k: int, C) -> dict:
-    """C is one capacity for all experts or an array with one capacity per expert.
+def verify_optimal(q, P, k, C) -> dict:
+    """C is one capacity for all experts or an array with one capacity per expert; k is one number for all
+    tokens or an array with one k per token.
     Proof of optimality for a feasible maximum-flow P when T*k <= E*min(C,T), independent of
     how P was found: the residual network, with tokens contracted, has experts and the sink as
     nodes; arc j->j' costs min over tokens on j and not on j' of q_uj - q_uj'; j->sink costs 0
@@ -247,7 +289,8 @@ def verify_optimal(q, P, k: int, C) -> dict:
     P = np.asarray(P).astype(bool)
     T, E = q.shape
     Ce = np.minimum(np.broadcast_to(np.asarray(C, dtype=np.int64), (E,)), T)
-    assert T * k <= int(Ce.sum())
+    kv = np.broadcast_to(np.asarray(k, dtype=np.int64), (T,))
+    assert int(kv.sum()) <= int(Ce.sum())
     load = P.sum(axis=0)
     INF = np.int64(1) << 60
     Lm = np.full((E + 1, E + 1), INF, dtype=np.int64)      # node E = sink
@@ -279,7 +322,7 @@ def verify_optimal(q, P, k: int, C) -> dict:
         held_min = np.where(P, net, INF).min(axis=1)
         unheld_max = np.where(P, -INF, net).max(axis=1)
         ok_cs = bool((held_min >= unheld_max).all() and (prices >= 0).all()
-                     and (prices[load < Ce] == 0).all() and (P.sum(axis=1) == k).all())
+                     and (prices[load < Ce] == 0).all() and (P.sum(axis=1) == kv).all())
     return dict(optimal=optimal and ok_cs, prices=prices, total=int(q[P].sum()))
 
 
