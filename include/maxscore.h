@@ -175,6 +175,23 @@ int32_t maxscore_assign_caps_i32(const int32_t *q, int32_t T, int32_t E, int32_t
                                  const maxscore_opts *opts, int32_t *assign, int64_t *prices, int64_t *price_scale,
                                  maxscore_stats *stats, void *workspace, size_t workspace_bytes, void *stream);
 
+/* a4 with one k per token (the vector k of Eq. 7; in Table 1 the arc Source -> Token_i gets capacity kvec[i]).
+ * kvec is a DEVICE array of T values in 0..k; k is the row width of assign (k <= E, k <= 64).  Token i ends with
+ * exactly kvec[i] distinct experts in assign[i, 0..kvec[i]-1]; the remaining slots of its row hold -1, so
+ * maxscore_gates, maxscore_dispatch and the movement calls take the result as it is.  Capacities: C for every
+ * expert (capacity == NULL), or the HOST array capacity[E] as in maxscore_assign_caps_i32 (C is then ignored).
+ * The capacities must sum to at least sum_i kvec[i] (MAXSCORE_ERR_OVERSUBSCRIBED otherwise; with one C for all
+ * experts every token can then ship all its units, with unequal capacities that is the caller's business as in
+ * maxscore_assign_caps_i32); an entry of kvec outside 0..k gives MAXSCORE_ERR_SHAPE.  The call reads kvec back
+ * once to check it (it synchronises the stream before the solve as well as after).  Optimality is the same
+ * statement as for maxscore_assign_i32: with the returned prices every token holds its kvec[i] best experts by
+ * price_scale*q_ij - price_j up to 1 unit, which is below the resolution of the integer rewards.  Everything
+ * else as maxscore_assign_i32. */
+int32_t maxscore_assign_kvec_i32(const int32_t *q, int32_t T, int32_t E, int32_t k, const int32_t *kvec, int32_t C,
+                                 const int32_t *capacity, const maxscore_opts *opts, int32_t *assign,
+                                 int64_t *prices, int64_t *price_scale, maxscore_stats *stats, void *workspace,
+                                 size_t workspace_bytes, void *stream);
+
 /* Algorithm 1 (Section 3.2, top-2 routing) with its residual problem solved exactly: every token takes its
  * highest-reward expert whatever the load (ties to the lower id); that entry of the reward matrix is set to 0
  * (q_residual[T, E], device, out: the caller provides the storage); the capacities become max(0, C - load_j)

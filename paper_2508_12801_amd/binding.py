@@ -52,6 +52,8 @@ _SIGS = {
     "maxscore_scores_op": (ctypes.c_int32, [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p] * 3),
     "maxscore_assign_caps_i32": (ctypes.c_int32, [ctypes.c_void_p] + [ctypes.c_int32] * 3 + [ctypes.c_void_p] * 7 +
                                  [ctypes.c_size_t, ctypes.c_void_p]),
+    "maxscore_assign_kvec_i32": (ctypes.c_int32, [ctypes.c_void_p] + [ctypes.c_int32] * 3 + [ctypes.c_void_p,
+                                 ctypes.c_int32] + [ctypes.c_void_p] * 7 + [ctypes.c_size_t, ctypes.c_void_p]),
     "maxscore_assign_top1_residual_i32": (ctypes.c_int32, [ctypes.c_void_p] + [ctypes.c_int32] * 3 +
                                           [ctypes.c_void_p] * 8 + [ctypes.c_size_t, ctypes.c_void_p]),
     "maxscore_assign_top1_sinkhorn": (ctypes.c_int32, [ctypes.c_void_p] + [ctypes.c_int32] * 3 + [ctypes.c_float,
@@ -311,6 +313,29 @@ def assign_caps_i32(q, k: int, caps, max_rounds: int = 200000, eps_div: int = 12
                                                  _ptr(assign), _ptr(prices), _ptr(scale), ctypes.byref(stats),
                                                  _ptr(ws), need, _stream())
     _check(rc, "maxscore_assign_caps_i32", allow=(ERR_NOT_CONVERGED,) if allow_not_converged else ())
+    return dict(assign=assign, prices=prices, price_scale=int(scale.item()), stats=stats.as_dict(), rc=rc)
+
+
+def assign_kvec_i32(q, k: int, kvec, C: int = 0, caps=None, max_rounds: int = 200000, eps_div: int = 12,
+                    allow_not_converged=False):
+    """a4 with one k per token: kvec is an int32 device tensor of T values in 0..k, k the row width of the result;
+    capacities are C for all experts or the host sequence caps.  Returns dict(assign, prices, price_scale, stats)."""
+    torch = _torch()
+    T, E = q.shape
+    assert q.dtype == torch.int32 and q.is_contiguous()
+    assert kvec.dtype == torch.int32 and kvec.is_contiguous() and kvec.numel() == T and kvec.device == q.device
+    caps_arr = (ctypes.c_int32 * E)(*[int(c) for c in caps]) if caps is not None else None
+    assign = torch.empty((T, k), dtype=torch.int32, device=q.device)
+    prices = torch.empty(E, dtype=torch.int64, device=q.device)
+    scale = torch.empty(1, dtype=torch.int64, device=q.device)
+    stats = Stats()
+    ws, need = _workspace(T, E, k, 1, q.device)
+    o = _opts(max_rounds=max_rounds, eps_div=eps_div)
+    rc = load_library().maxscore_assign_kvec_i32(_ptr(q), T, E, k, _ptr(kvec), int(C),
+                                                 ctypes.addressof(caps_arr) if caps_arr is not None else None,
+                                                 ctypes.byref(o), _ptr(assign), _ptr(prices), _ptr(scale),
+                                                 ctypes.byref(stats), _ptr(ws), need, _stream())
+    _check(rc, "maxscore_assign_kvec_i32", allow=(ERR_NOT_CONVERGED,) if allow_not_converged else ())
     return dict(assign=assign, prices=prices, price_scale=int(scale.item()), stats=stats.as_dict(), rc=rc)
 
 

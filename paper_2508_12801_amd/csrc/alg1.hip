@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void k_pair(const int32_t *__restrict__ top1, 
 }  // namespace
 
 int32_t caps_to_device(const int32_t *caps_host, int T, int E, int k, char *ws, const int32_t **cap_dev,
-                       long long *room, int *cmax, hipStream_t s)
+                       long long *room, int *cmax, hipStream_t s, long long demand)
 {
     WorkspaceLayout L = workspace_layout(T, E, k);
     std::vector<int32_t> eff(E);
@@ -47,7 +47,7 @@ int32_t caps_to_device(const int32_t *caps_host, int T, int E, int k, char *ws, 
         sum += eff[j];
         mx = eff[j] > mx ? eff[j] : mx;
     }
-    if ((long long)T * k > sum) return MAXSCORE_ERR_OVERSUBSCRIBED;
+    if ((demand < 0 ? (long long)T * k : demand) > sum) return MAXSCORE_ERR_OVERSUBSCRIBED;
     int32_t *dst = (int32_t *)(ws + L.cap_off);
     MS_HIP(hipMemcpyAsync(dst, eff.data(), sizeof(int32_t) * E, hipMemcpyHostToDevice, s));
     MS_HIP(hipStreamSynchronize(s));          // the host vector goes out of scope

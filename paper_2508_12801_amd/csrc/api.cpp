@@ -163,6 +163,35 @@ int32_t maxscore_assign_caps_i32(const int32_t *q, int32_t T, int32_t E, int32_t
                       cap_dev, room);
 }
 
+int32_t maxscore_assign_kvec_i32(const int32_t *q, int32_t T, int32_t E, int32_t k, const int32_t *kvec, int32_t C,
+                                 const int32_t *capacity, const maxscore_opts *opts, int32_t *assign,
+                                 int64_t *prices, int64_t *price_scale, maxscore_stats *stats, void *workspace,
+                                 size_t workspace_bytes, void *stream)
+{
+    if (!q || !assign || !kvec) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, k, capacity ? 1 : C)) return MAXSCORE_ERR_SHAPE;
+    int32_t rc = check_ws(workspace, workspace_bytes, T, E, k);
+    if (rc) return rc;
+    maxscore_opts o = resolve(opts);
+    if (stats) std::memset(stats, 0, sizeof(*stats));
+    long long demand = 0;
+    rc = kvec_check(kvec, T, E, k, (char *)workspace, &demand, (hipStream_t)stream);
+    if (rc) return rc;
+    if (capacity) {
+        const int32_t *cap_dev = nullptr;
+        long long room = 0;
+        int cmax = 1;
+        rc = caps_to_device(capacity, T, E, k, (char *)workspace, &cap_dev, &room, &cmax, (hipStream_t)stream, demand);
+        if (rc) return rc;
+        return solver_run(q, T, E, k, cmax, o, assign, prices, price_scale, stats, (char *)workspace,
+                          (hipStream_t)stream, cap_dev, room, kvec, demand);
+    }
+    const int Ce = C < T ? C : T;
+    if (demand > (long long)E * Ce) return MAXSCORE_ERR_OVERSUBSCRIBED;
+    return solver_run(q, T, E, k, Ce, o, assign, prices, price_scale, stats, (char *)workspace, (hipStream_t)stream,
+                      nullptr, 0, kvec, demand);
+}
+
 int32_t maxscore_assign_top1_residual_i32(const int32_t *q, int32_t T, int32_t E, int32_t C,
                                           const maxscore_opts *opts, int32_t *q_residual, int32_t *assign,
                                           int32_t *residual_capacity, int64_t *total, int32_t *flow,

@@ -64,9 +64,13 @@ inline bool hip_ok(hipError_t e) { return e == hipSuccess; }
 
 // --- solver.hip
 // cap: optional device array of E per-expert capacities (each <= T) with sum `room`; NULL = Ce for all.
+// kvec: optional device array of T per-token k (each 0..k) with sum `demand`; NULL = k for all.
 int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore_opts &o, int32_t *assign,
                    int64_t *prices, int64_t *price_scale, maxscore_stats *stats, char *ws, hipStream_t s,
-                   const int32_t *cap = nullptr, long long room = 0);
+                   const int32_t *cap = nullptr, long long room = 0, const int32_t *kvec = nullptr,
+                   long long demand = 0);
+// Checks a device array of T per-token k (each 0..k) and returns its sum in *demand (synchronises the stream).
+int32_t kvec_check(const int32_t *kvec, int T, int E, int k, char *ws, long long *demand, hipStream_t s);
 // --- softtopk.hip
 int32_t softtopk_run(const float *logits, int T, int E, int k, float t, int shift, float *scores, int32_t *q,
                      hipStream_t s);
@@ -90,9 +94,10 @@ int32_t top1_run(const int32_t *q, int T, int E, int32_t *top1, hipStream_t s);
 int32_t assign_total_run(const int32_t *q, const int32_t *assign, int T, int E, int k, void *state16, int64_t *total,
                          int32_t *flow, hipStream_t s);
 // --- alg1.hip
-// Validates a host capacity vector (each >= 0, clamped to T, sum >= T*k) and copies it into the workspace.
+// Validates a host capacity vector (each >= 0, clamped to T, sum >= demand; demand < 0 stands for T*k) and
+// copies it into the workspace.
 int32_t caps_to_device(const int32_t *caps_host, int T, int E, int k, char *ws, const int32_t **cap_dev,
-                       long long *room, int *cmax, hipStream_t s);
+                       long long *room, int *cmax, hipStream_t s, long long demand = -1);
 int32_t alg1_run(const int32_t *q, int T, int E, int C, const maxscore_opts &o, int32_t *q_residual,
                  int32_t *assign, int32_t *caps_out, int64_t *total, int32_t *flow, maxscore_stats *stats, char *ws,
                  hipStream_t s);

@@ -188,14 +188,13 @@ __global__ __launch_bounds__(kMinmaxBlocks) void k_setup(SolverState *st, const 
 // experts l*EPL .. l*EPL+EPL-1 and slot l of the token (k <= G).  A wavefront therefore works on
 // 64/G rows at once and its loads of consecutive rows are contiguous.  The next row of each group
 // is prefetched into registers while the current one is evaluated.
-template <int G, int EPL, bool VEC>
+template <int G, int EPL, bool VEC, bool KV>
 __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, int32_t *__restrict__ assign,
                                              const long long *__restrict__ theta, const SolverState *__restrict__ st,
                                              long long *__restrict__ klist, int *__restrict__ wcnt,
                                              int *__restrict__ wmoves, int *__restrict__ errflag, int T, int E, int k,
-                                             int rows_per_wg)
+                                             int rows_per_wg, const int32_t *__restrict__ kvec)
 {
-    if (st->done) return;
     constexpr int EP = G * EPL;
     constexpr int NG = 256 / G;
     constexpr int LOGP = EPL == 1 ? 0 : EPL == 2 ? 1 : EPL == 4 ? 2 : EPL == 8 ? 3 : 4;
@@ -244,20 +243,36 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
             for (int m = 0; m < EPL; ++m) qn[m] = (lg * EPL + m < E) ? qr[m] : 0;
         }
         an = (lg < k) ? assign[(size_t)row * k + lg] : -2;
+        // with one k per token (KV), the slots from kvec[row] on do not exist for this row: they read as -2
+        // like the lanes beyond k, are never filled and emit no key (both loads are issued unconditionally)
+        if (KV) an = (lg < kvec[row]) ? an : -2;
     };
-    // thresholds and state are requested first (the barrier below waits for them), then the first row
-    // of every group
+    // The first row of every group and the thresholds are requested before the state is looked at:
+    // the exit test below then waits for the scalar loads of the state only, while the vector loads
+    // are already on their way (rows and thresholds are valid memory whether or not the solve is over).
+    if (row0 + grp < T && grp < rows_per_wg) load_row(row0 + grp);
+    long long th0[(EP + 255) / 256];
+#pragma unroll
+    for (int i = 0; i < (EP + 255) / 256; ++i) {
+        const int e = tid + i * 256;
+        th0[i] = e < E ? theta[e] : 0;
+    }
+    const int over = st->done;
     const long long eps = st->eps, qmin = st->qmin;
     const int sb = st->sbits, tb = st->tbits;
-    for (int e = tid; e < EP; e += 256) {
-        s_theta[e] = e < E ? theta[e] : 0;
-        s_cnt[e] = 0;
+    if (over) return;
+#pragma unroll
+    for (int i = 0; i < (EP + 255) / 256; ++i) {
+        const int e = tid + i * 256;
+        if (e < EP) {
+            s_theta[e] = th0[i];
+            s_cnt[e] = 0;
+        }
     }
     if (tid == 0) {
         s_moves = 0;
         s_nq = 0;
     }
-    if (row0 + grp < T && grp < rows_per_wg) load_row(row0 + grp);
     __syncthreads();
 
     long long p[EPL];
@@ -366,14 +381,18 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
             if (lg < k && my_e != was_e) assign[(size_t)row * k + lg] = my_e;
         }
         if (lg < k) {
-            long long bid = has_alt ? my_sq - a + eps : kBidBig;
-            bid = bid < kBidBig ? bid : kBidBig;
-            long long key = bid * ((long long)1 << tb) + row;
-            int pos = atomicAdd(&s_cnt[my_e], 1);
-            int idx = lr * k + lg;
-            s_key[idx] = key;
-            s_exp[idx] = (short)my_e;
-            s_pos[idx] = (short)pos;
+            const int idx = lr * k + lg;
+            if (!KV || my_e >= 0) {
+                long long bid = has_alt ? my_sq - a + eps : kBidBig;
+                bid = bid < kBidBig ? bid : kBidBig;
+                long long key = bid * ((long long)1 << tb) + row;
+                int pos = atomicAdd(&s_cnt[my_e], 1);
+                s_key[idx] = key;
+                s_exp[idx] = (short)my_e;
+                s_pos[idx] = (short)pos;
+            } else {
+                s_exp[idx] = -1;           // a slot this token does not have
+            }
         }
     };
 
@@ -417,7 +436,7 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
             }
             bool bad = false;
             long long qkey = 0;
-            if (lg < k) {
+            if (KV ? my_e != -2 : lg < k) {      // a slot lane of this row
                 bad = my_e < 0;
                 if (!bad) {
                     long long bid = ((long long)my_u << sb) - (long long)bv + eps;
@@ -428,11 +447,15 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
             }
             if ((__ballot(bad) & gmask) == 0) {
                 if (lg < k) {
-                    int pos = atomicAdd(&s_cnt[my_e], 1);
-                    int idx = lr * k + lg;
-                    s_key[idx] = qkey;
-                    s_exp[idx] = (short)my_e;
-                    s_pos[idx] = (short)pos;
+                    const int idx = lr * k + lg;
+                    if (!KV || my_e >= 0) {
+                        int pos = atomicAdd(&s_cnt[my_e], 1);
+                        s_key[idx] = qkey;
+                        s_exp[idx] = (short)my_e;
+                        s_pos[idx] = (short)pos;
+                    } else {
+                        s_exp[idx] = -1;   // a slot this token does not have
+                    }
                 }
             } else if (lg == 0) {
                 s_queue[atomicAdd(&s_nq, 1)] = (short)lr;
@@ -505,7 +528,7 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
     long long *s_sorted = (long long *)s_q;
     for (int idx = tid; idx < nslots; idx += 256) {
         const int e = s_exp[idx];
-        s_sorted[s_off[e] + s_pos[idx]] = s_key[idx];
+        if (!KV || e >= 0) s_sorted[s_off[e] + s_pos[idx]] = s_key[idx];
     }
     __syncthreads();
     for (int idx = tid; idx < nslots; idx += 256) blk[idx] = s_sorted[idx];
@@ -557,7 +580,7 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
 __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t *assign, long long *theta2,
                                           int *gcount2, SolverState *st2, const long long *cand, int *errflag,
                                           int par, int T, int E, int k, int Ce, const int *__restrict__ cap,
-                                          int max_iters)
+                                          int max_iters, const int32_t *__restrict__ kvec)
 {
     SolverState *st = st2 + (par ^ 1);          // the state the next bid pass will read
     long long *theta = theta2 + (par ^ 1) * kMaxE;
@@ -718,6 +741,8 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
             int my_e = lane < k ? __hip_atomic_load(&assign[(size_t)tok * k + lane], __ATOMIC_RELAXED,
                                                     __HIP_MEMORY_SCOPE_WORKGROUP)
                                 : -2;
+            const int k_tok = kvec ? kvec[tok] : k;       // slots from k_tok on do not exist for this token
+            my_e = lane < k_tok ? my_e : -2;
             int qv[kTailEPL];
 #pragma unroll
             for (int m = 0; m < kTailEPL; ++m) qv[m] = (m < eplt && lane + 64 * m < E) ? qr[lane + 64 * m] : 0;
@@ -986,7 +1011,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                                                         int32_t *assign, int *ready, int *host_done, int par, int T, int E, int k,
                                                         int Ce, const int *__restrict__ cap, int n_wg,
                                                         int rows_per_wg, int tail_on, int tail_moves,
-                                                        int tail_iters)
+                                                        int tail_iters, const int32_t *__restrict__ kvec)
 {
     const SolverState *st = st2 + par;
     SolverState *st_out = st2 + (par ^ 1);
@@ -1150,7 +1175,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             if (tid == 0) *errflag = 1;       // reported as MAXSCORE_ERR_HIP by the next select pass
             return;
         }
-        tail_pass(q, assign, theta2, gcount2, st2, cand, errflag, par, T, E, k, Ce, cap, tail_iters);
+        tail_pass(q, assign, theta2, gcount2, st2, cand, errflag, par, T, E, k, Ce, cap, tail_iters, kvec);
         return;
     }
     long long new_theta = base;
@@ -1420,26 +1445,65 @@ __global__ __launch_bounds__(kFinalBlocks) void k_finalize2(const long long *__r
         for (int e = threadIdx.x; e < E; e += blockDim.x) prices[e] = theta[e] >> tb;
 }
 
+// Sum of a per-token k vector and a flag for entries outside 0..k: out[0] = sum, out[1] = number of bad entries.
+// One workgroup; T is at most 2^21, so this is a few microseconds.
+__global__ __launch_bounds__(1024) void k_kvec_check(const int32_t *__restrict__ kvec, int T, int k,
+                                                     long long *__restrict__ out)
+{
+    __shared__ long long s_sum[16];
+    __shared__ int s_bad[16];
+    long long sum = 0;
+    int bad = 0;
+    for (int i = threadIdx.x; i < T; i += 1024) {
+        const int v = kvec[i];
+        bad += (v < 0 || v > k);
+        sum += v;
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        sum += (long long)shfl_xor_u64((unsigned long long)sum, off);
+        bad += __shfl_xor(bad, off);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        s_sum[threadIdx.x >> 6] = sum;
+        s_bad[threadIdx.x >> 6] = bad;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long ts = 0, tb = 0;
+        for (int w = 0; w < 16; ++w) {
+            ts += s_sum[w];
+            tb += s_bad[w];
+        }
+        out[0] = ts;
+        out[1] = tb;
+    }
+}
+
 template <int G, int EPL>
 void launch_bid(bool vec, const int32_t *q, int32_t *assign, const long long *theta, const SolverState *st,
                 long long *klist, int *wcnt, int *wmoves, int *errflag, int T, int E, int k, int rows_per_wg,
-                hipStream_t s)
+                const int32_t *kvec, hipStream_t s)
 {
     int grid = (T + rows_per_wg - 1) / rows_per_wg;
-    if (vec)
-        hipLaunchKernelGGL((k_bid<G, EPL, true>), dim3(grid), dim3(256), 0, s, q, assign, theta, st, klist, wcnt,
-                           wmoves, errflag, T, E, k, rows_per_wg);
-    else
-        hipLaunchKernelGGL((k_bid<G, EPL, false>), dim3(grid), dim3(256), 0, s, q, assign, theta, st, klist,
-                           wcnt, wmoves, errflag, T, E, k, rows_per_wg);
+#define MS_BK(VV, KK)                                                                                        \
+    hipLaunchKernelGGL((k_bid<G, EPL, VV, KK>), dim3(grid), dim3(256), 0, s, q, assign, theta, st, klist, wcnt, \
+                       wmoves, errflag, T, E, k, rows_per_wg, kvec)
+    if (kvec) {
+        if (vec) MS_BK(true, true);
+        else MS_BK(false, true);
+    } else {
+        if (vec) MS_BK(true, false);
+        else MS_BK(false, false);
+    }
+#undef MS_BK
 }
 
 template <int G>
 void launch_bid_g(int EPL, bool vec, const int32_t *q, int32_t *assign, const long long *theta,
                   const SolverState *st, long long *klist, int *wcnt, int *wmoves, int *errflag, int T, int E, int k,
-                  int rows_per_wg, hipStream_t s)
+                  int rows_per_wg, const int32_t *kvec, hipStream_t s)
 {
-#define MS_B(PP) launch_bid<G, PP>(vec, q, assign, theta, st, klist, wcnt, wmoves, errflag, T, E, k, rows_per_wg, s)
+#define MS_B(PP) launch_bid<G, PP>(vec, q, assign, theta, st, klist, wcnt, wmoves, errflag, T, E, k, rows_per_wg, kvec, s)
     if (EPL == 1) MS_B(1);
     else if (EPL == 2) MS_B(2);
     else if (EPL == 4) MS_B(4);
@@ -1450,9 +1514,23 @@ void launch_bid_g(int EPL, bool vec, const int32_t *q, int32_t *assign, const lo
 
 }  // namespace
 
+int32_t kvec_check(const int32_t *kvec, int T, int E, int k, char *ws, long long *demand, hipStream_t s)
+{
+    WorkspaceLayout L = workspace_layout(T, E, k);
+    long long *out = (long long *)(ws + L.cand_off);       // the candidate lists are not in use before a solve
+    hipLaunchKernelGGL(k_kvec_check, dim3(1), dim3(1024), 0, s, kvec, T, k, out);
+    long long h[2] = {0, 0};
+    MS_HIP(hipMemcpyAsync(h, out, sizeof(h), hipMemcpyDeviceToHost, s));
+    MS_HIP(hipStreamSynchronize(s));
+    MS_HIP(hipGetLastError());
+    if (h[1] != 0) return MAXSCORE_ERR_SHAPE;
+    *demand = h[0];
+    return MAXSCORE_OK;
+}
+
 int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore_opts &o, int32_t *assign,
                    int64_t *prices, int64_t *price_scale, maxscore_stats *stats, char *ws, hipStream_t s,
-                   const int32_t *cap, long long room)
+                   const int32_t *cap, long long room, const int32_t *kvec, long long demand)
 {
     WorkspaceLayout L = workspace_layout(T, E, k);
     SolverState *st = (SolverState *)(ws + L.state_off);
@@ -1489,7 +1567,9 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     if (n_wg > L.max_wg) return MAXSCORE_ERR_WORKSPACE;
 
     // room = total capacity (sum of the vector, or E*Ce)
-    const int slack = ((cap ? room : (long long)E * Ce) - (long long)T * k) > 0 ? 1 : 0;
+    // demand = number of pairs to place (sum of the per-token k, or T*k)
+    const long long want = kvec ? demand : (long long)T * k;
+    const int slack = ((cap ? room : (long long)E * Ce) - want) > 0 ? 1 : 0;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     MS_HIP(hipEventCreate(&ev0));
     MS_HIP(hipEventCreate(&ev1));
@@ -1543,7 +1623,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             }
 #define MS_BID(GG)                                                                                   \
     launch_bid_g<GG>(EPL, vec, q, assign, theta + par * kMaxE, st + par, klist, wcnt, wmoves, qmm + 2, T, E, k, \
-                     rows, s)
+                     rows, kvec, s)
             if (G == 8) MS_BID(8);
             else if (G == 16) MS_BID(16);
             else if (G == 32) MS_BID(32);
@@ -1552,7 +1632,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             if (g_kernel_timing) MS_HIP(hipEventRecord(tev.back(), s));
             hipLaunchKernelGGL(k_select, dim3(E + tail_on), dim3(kSelThreads), 0, s, klist, wcnt, wmoves, gcount, theta,
                                st, qmm + 2, cand, q, assign, qmm + 3, tl_flag_dev, par, T, E, k, Ce, cap, n_wg, rows, tail_on,
-                               tail_moves, tail_iters);
+                               tail_moves, tail_iters, kvec);
             ++launched;
         }
         MS_HIP(hipEventRecord(evb[slot], s));
