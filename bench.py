@@ -205,6 +205,14 @@ def main():
                   "iter_score_over_exact_top2": it2["total"] / max(ex2["stats"]["total_score_q"], 1),
                   "max_expert_load": load2, "C": c2["C"]}
 
+    # the exact assignment with one k per token (the vector k of Eq. 7) at the same shape: k_i ~ Poisson(5)
+    # clipped to 0..k, on the same rewards
+    kv = torch.from_numpy(np.clip(np.random.default_rng(11).poisson(5.0, T), 0, k).astype(np.int32)).to(dev)
+    kv_out = ms.assign_kvec_i32(out["q"], k, kv, C)
+    kv_ms = timed(lambda: ms.assign_kvec_i32(out["q"], k, kv, C), n=5)
+    per_token_k = {"ms": kv_ms, "pairs": int(kv.sum().item()), "rounds": kv_out["stats"]["rounds"],
+                   "k_vector": "Poisson(5) clipped to 0..k"}
+
     line = {
         "metric": "routed tokens/sec", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -232,6 +240,7 @@ def main():
         "training_side": training_side,
         "table2_operators": operators,
         "algorithm1_top2": algorithm1,
+        "per_token_k": per_token_k,
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(args.config, min(args.cpu_sample, T))
