@@ -68,6 +68,40 @@ __device__ __forceinline__ unsigned long long group_max(unsigned long long v)
     return v;
 }
 
+#ifdef MS_BID_PROF
+// timing of the bid pass by round (100 MHz wall clock): earliest start and latest end over the workgroups, and
+// the sums over the workgroups of the time spent up to the first barrier, in the row loop, in the scan and in
+// the sort-and-store epilogue
+__device__ unsigned long long g_bidmin[256], g_bidmax[256], g_bidph[256][4];
+#endif
+
+// Maximum of a 32-bit value over the G lanes of a group, result in every lane of the group.  Groups of 8 and 16
+// lanes lie inside one 16-lane row, where data-parallel-primitive lane swaps do it without going through the LDS
+// crossbar: inside each quad, then the mirrored half row (lane i <-> 7-i pairs the two quads), then the
+// mirrored row (lane i <-> 15-i pairs the two halves).
+template <int G>
+__device__ __forceinline__ int group_max_i32(int v)
+{
+    if constexpr (G == 8 || G == 16) {
+        // every lane of a full wavefront is a valid source for these swaps, so the value read for an invalid
+        // source never matters (that lets the compiler fold the swap into the max instruction)
+        int o;
+        o = __builtin_amdgcn_mov_dpp(v, 0xB1, 0xf, 0xf, true); v = o > v ? o : v;   // quad_perm [1,0,3,2]
+        o = __builtin_amdgcn_mov_dpp(v, 0x4E, 0xf, 0xf, true); v = o > v ? o : v;   // quad_perm [2,3,0,1]
+        o = __builtin_amdgcn_mov_dpp(v, 0x141, 0xf, 0xf, true); v = o > v ? o : v;  // row_half_mirror
+        if constexpr (G == 16) {
+            o = __builtin_amdgcn_mov_dpp(v, 0x140, 0xf, 0xf, true); v = o > v ? o : v;  // row_mirror
+        }
+    } else {
+#pragma unroll
+        for (int off = G / 2; off > 0; off >>= 1) {
+            const int o = __shfl_xor(v, off);
+            v = o > v ? o : v;
+        }
+    }
+    return v;
+}
+
 __global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm, int32_t *assign, int T, int E,
                        int k, int eps_div, int max_rounds, int slack)
 {
@@ -78,6 +112,13 @@ __global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm,
         theta[i] = 0;
         gcount[i] = 0;
     }
+#ifdef MS_BID_PROF
+    if (i < 256) {
+        g_bidmin[i] = ~0ull;
+        g_bidmax[i] = 0;
+        for (int a = 0; a < 4; ++a) g_bidph[i][a] = 0;
+    }
+#endif
     if (i == 0) {
         qmm[0] = 0x7fffffff;
         qmm[1] = -0x7fffffff - 1;
@@ -217,13 +258,16 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
     const int lane = tid & 63, lg = lane & (G - 1), gbase = lane & ~(G - 1);
     const int grp = tid / G;
     const int row0 = blockIdx.x * rows_per_wg;
-    const unsigned long long gmask = (G == 64) ? ~0ull : (((1ull << G) - 1) << gbase);
+    // the bits of a wavefront ballot that belong to this lane's group, moved down to bit 0
+    auto group_bits = [&](unsigned long long b) {
+        return G == 64 ? b : (b >> gbase) & ((1ull << (G & 63)) - 1);
+    };
     int *sq = s_q + grp * SQ_ROW;
     auto sq_at = [&](int e) { return e + (e >> LOGP); };
 
     int qn[EPL];
     int an = -2;
-    auto load_row = [&](int row) {
+    auto load_row_to = [&](int row, int(&qn)[EPL], int &an) {
         const int32_t *qr = q + (size_t)row * E + lg * EPL;
         if (VEC) {
             if (EPL >= 4) {
@@ -247,6 +291,10 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
         // like the lanes beyond k, are never filled and emit no key (both loads are issued unconditionally)
         if (KV) an = (lg < kvec[row]) ? an : -2;
     };
+    auto load_row = [&](int row) { load_row_to(row, qn, an); };
+#ifdef MS_BID_PROF
+    const unsigned long long bp0 = wall_clock64();
+#endif
     // The first row of every group and the thresholds are requested before the state is looked at:
     // the exit test below then waits for the scalar loads of the state only, while the vector loads
     // are already on their way (rows and thresholds are valid memory whether or not the solve is over).
@@ -274,15 +322,19 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
         s_nq = 0;
     }
     __syncthreads();
+#ifdef MS_BID_PROF
+    const unsigned long long bp1 = wall_clock64();
+#endif
 
-    long long p[EPL];
+    // The prices of this lane's experts are read from the LDS copy of the thresholds where they are needed:
+    // keeping the 64-bit values in registers through both kinds of pass costs more registers than a wavefront
+    // has to spare, and a spilled row costs a memory round trip at the head of the kernel.
     unsigned validm = 0;
     bool high = false;
 #pragma unroll
     for (int m = 0; m < EPL; ++m) {
         int e = lg * EPL + m;
-        p[m] = s_theta[e] >> tb;
-        high |= p[m] >= kNarrowPrice;
+        high |= (s_theta[e] >> tb) >= kNarrowPrice;
         if (e < E) validm |= 1u << m;
     }
     // Quick check of a row (most rows of most rounds): when rewards and prices are small enough for
@@ -303,7 +355,7 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
 
         long long v[EPL];
 #pragma unroll
-        for (int m = 0; m < EPL; ++m) v[m] = (((long long)qc[m] - qmin) << sb) - p[m];
+        for (int m = 0; m < EPL; ++m) v[m] = (((long long)qc[m] - qmin) << sb) - (s_theta[lg * EPL + m] >> tb);
         unsigned heldm = 0;
         for (int s = 0; s < k; ++s) {
             int es = __shfl(my_e, s, G);
@@ -348,10 +400,10 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
                 my_e = -1;
             }
         }
-        const unsigned long long gfb = (__ballot(my_e == -1) & gmask) >> gbase;
+        const unsigned long long gfb = group_bits(__ballot(my_e == -1));
         const int f = __popcll(gfb);
         if (f > 0) {
-            const bool any_drop = ((__ballot(dropped) & gmask) != 0);
+            const bool any_drop = group_bits(__ballot(dropped)) != 0;
             if (any_drop) {
                 heldm = 0;
                 for (int s = 0; s < k; ++s) {
@@ -397,43 +449,39 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
     };
 
     if (quick) {
-        // pass 1: value-only check of every row; rows with a hold to drop or a slot to fill are queued
-        for (int lr = grp; lr < rows_per_wg; lr += NG) {
+        // pass 1: value-only check of every row; rows with a hold to drop or a slot to fill are queued.
+        // The raw rewards are staged; slot lanes fetch the reward of their expert and then blank it, so that
+        // the re-read row holds only experts not held.  Values are (q - qmin)*S - price in 32 bits, computed
+        // as (q << sb) + np with np = -(price + (qmin << sb)) (wrap-around arithmetic; the true value fits).
+        constexpr int kBlank = -(1 << 30);        // (blank value) - price stays above -2^31
+        const unsigned qmin_s = (unsigned)qmin32 << sb;
+        const int blank_q = (int)((unsigned)qmin32 + (unsigned)(kBlank >> sb));
+        unsigned np[EPL];
+#pragma unroll
+        for (int m = 0; m < EPL; ++m) np[m] = 0u - ((unsigned)(s_theta[lg * EPL + m] >> tb) + qmin_s);
+        auto quick_row = [&](const int lr, const int(&qc)[EPL], const int my_e) {
             const int row = row0 + lr;
-            if (row >= T) break;
-            int qc[EPL];
 #pragma unroll
-            for (int m = 0; m < EPL; ++m) qc[m] = qn[m];
-            const int my_e = an;
-            if (lr + NG < rows_per_wg && row + NG < T) load_row(row + NG);
-            // u = q - qmin (>= 0, < 2^28 / S) is staged; slot lanes fetch the u of their expert and
-            // then blank it, so that the re-read row holds only experts not held
-            constexpr int kBlank = -(1 << 30);
-#pragma unroll
-            for (int m = 0; m < EPL; ++m) sq[lg * (EPL + 1) + m] = qc[m] - qmin32;
+            for (int m = 0; m < EPL; ++m) sq[lg * (EPL + 1) + m] = qc[m];
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             int my_u = 0;
-            if (my_e >= 0) my_u = sq[sq_at(my_e)];
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            if (my_e >= 0) sq[sq_at(my_e)] = kBlank >> sb;      // (blank << sb) - price stays above -2^31
+            if (my_e >= 0) {
+                my_u = sq[sq_at(my_e)] - qmin32;       // u = q - qmin (>= 0, < 2^28 / S)
+                sq[sq_at(my_e)] = blank_q;             // same lane, same word: read, then overwritten
+            }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             int bv = -0x7fffffff - 1;
 #pragma unroll
             for (int m = 0; m < EPL; ++m) {
-                const int vv = (int)((unsigned)sq[lg * (EPL + 1) + m] << sb) - (int)p[m];   // E == EP: no padding experts
+                int vv;     // (q << sb) + np in one instruction; E == EP: no padding experts
+                asm("v_lshl_add_u32 %0, %1, %2, %3" : "=v"(vv) : "v"(sq[lg * (EPL + 1) + m]), "s"(sb), "v"(np[m]));
                 bv = vv > bv ? vv : bv;
             }
-#pragma unroll
-            for (int off = G / 2; off > 0; off >>= 1) {
-                const int o = __shfl_xor(bv, off);
-                bv = o > bv ? o : bv;
-            }
+            bv = group_max_i32<G>(bv);
             bool bad = false;
             long long qkey = 0;
             if (KV ? my_e != -2 : lg < k) {      // a slot lane of this row
@@ -445,7 +493,7 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
                     bad = qkey < s_theta[my_e];
                 }
             }
-            if ((__ballot(bad) & gmask) == 0) {
+            if (group_bits(__ballot(bad)) == 0) {
                 if (lg < k) {
                     const int idx = lr * k + lg;
                     if (!KV || my_e >= 0) {
@@ -461,6 +509,20 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
                 s_queue[atomicAdd(&s_nq, 1)] = (short)lr;
             }
             __builtin_amdgcn_wave_barrier();   // the next row reuses this group's staging buffer
+        };
+        // two register sets take turns: while one row is checked, the next one of the group is on its way
+        // into the other set
+        int qb[EPL];
+        int ab = -2;
+        for (int lr = grp; lr < rows_per_wg; lr += 2 * NG) {
+            const int row = row0 + lr;
+            if (row >= T) break;
+            const bool has_b = lr + NG < rows_per_wg && row + NG < T;
+            if (has_b) load_row_to(row + NG, qb, ab);
+            quick_row(lr, qn, an);
+            if (!has_b) break;
+            if (lr + 2 * NG < rows_per_wg && row + 2 * NG < T) load_row_to(row + 2 * NG, qn, an);
+            quick_row(lr + NG, qb, ab);
         }
         __syncthreads();
         // pass 2: the queued rows, compacted over the groups, get the full evaluation
@@ -468,10 +530,7 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
         for (int qi = grp; qi < nq; qi += NG) {
             const int lr = s_queue[qi];
             load_row(row0 + lr);
-            int qc[EPL];
-#pragma unroll
-            for (int m = 0; m < EPL; ++m) qc[m] = qn[m];
-            full_row(lr, qc, an);
+            full_row(lr, qn, an);
             __builtin_amdgcn_wave_barrier();   // the next row reuses this group's staging buffer
         }
     } else {
@@ -488,6 +547,9 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
         }
     }
     __syncthreads();
+#ifdef MS_BID_PROF
+    const unsigned long long bp2 = wall_clock64();
+#endif
     // The keys of this workgroup are stored sorted by expert in one contiguous block of the key
     // buffer (block w starts at w*rows_per_wg*k), with (offset << 16 | count) per expert beside it:
     // full cache lines are written and no global atomics are needed.
@@ -520,6 +582,9 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
     }
     if (tid == 0) wmoves[blockIdx.x] = s_moves;
     __syncthreads();
+#ifdef MS_BID_PROF
+    const unsigned long long bp3 = wall_clock64();
+#endif
     int rows_here = T - row0;
     rows_here = rows_here < rows_per_wg ? rows_here : rows_per_wg;
     const int nslots = rows_here * k;
@@ -532,6 +597,19 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
     }
     __syncthreads();
     for (int idx = tid; idx < nslots; idx += 256) blk[idx] = s_sorted[idx];
+#ifdef MS_BID_PROF
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned long long bp4 = wall_clock64();
+        const int r = st->round & 255;
+        atomicMin(&g_bidmin[r], bp0);
+        atomicMax(&g_bidmax[r], bp4);
+        atomicAdd(&g_bidph[r][0], bp1 - bp0);
+        atomicAdd(&g_bidph[r][1], bp2 - bp1);
+        atomicAdd(&g_bidph[r][2], bp3 - bp2);
+        atomicAdd(&g_bidph[r][3], bp4 - bp3);
+    }
+#endif
 }
 
 // Tail pass: when a bid pass moved only a few slots, one workgroup continues the same auction on the
@@ -1716,6 +1794,18 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         (void)hipMemcpyFromSymbol(hr, HIP_SYMBOL(g_selround), sizeof(hr));
         for (int a = 0; a < 90; ++a) fprintf(stderr, "[selround] %d cyc %llu n %llu fl %llu\n", a, hr[a] >> 32, (hr[a] >> 8) & 0xffffff, hr[a] & 3);
         fprintf(stderr, "[selprof] block 0: wall ticks (100 MHz) %lld, clock64 ticks %lld\n", hw[0], hw[1]);
+    }
+#endif
+#ifdef MS_BID_PROF
+    {
+        static unsigned long long hmin[256], hmax[256], hph[256][4];
+        (void)hipMemcpyFromSymbol(hmin, HIP_SYMBOL(g_bidmin), sizeof(hmin));
+        (void)hipMemcpyFromSymbol(hmax, HIP_SYMBOL(g_bidmax), sizeof(hmax));
+        (void)hipMemcpyFromSymbol(hph, HIP_SYMBOL(g_bidph), sizeof(hph));
+        for (int r = 0; r < h.round && r < 256; ++r)
+            fprintf(stderr, "[bidprof] round %d span %.2f us; mean per workgroup: to first barrier %.2f, rows %.2f, scan %.2f, store %.2f us\n",
+                    r, (hmax[r] - hmin[r]) * 0.01, hph[r][0] * 0.01 / n_wg, hph[r][1] * 0.01 / n_wg,
+                    hph[r][2] * 0.01 / n_wg, hph[r][3] * 0.01 / n_wg);
     }
 #endif
 #ifdef MS_TAIL_PROF
