@@ -1633,7 +1633,9 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     while (G * EPL < E) EPL *= 2;
     const int ngrp = 256 / G;
     int rows = ngrp * 2;
-    while (rows * 2 * k <= 1024 && (T + rows - 1) / rows > 4096) rows *= 2;
+    // more rows per workgroup as long as two workgroups per compute unit remain: fewer, longer key blocks for the
+    // select pass, and the loads of a group's later rows overlap with the evaluation of its earlier ones
+    while (rows * 2 * k <= 1024 && (T + 2 * rows - 1) / (2 * rows) >= 512) rows *= 2;
     if (rows * k > 1024) rows = ngrp;
     if (rows * k > 1024) return MAXSCORE_ERR_SHAPE;
     if (const char *ev = getenv("MAXSCORE_ROWS")) {   // tuning override (debug)
