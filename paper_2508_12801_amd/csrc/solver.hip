@@ -1523,16 +1523,18 @@ __global__ __launch_bounds__(kFinalBlocks) void k_finalize2(const long long *__r
         for (int e = threadIdx.x; e < E; e += blockDim.x) prices[e] = theta[e] >> tb;
 }
 
-// Sum of a per-token k vector and a flag for entries outside 0..k: out[0] = sum, out[1] = number of bad entries.
-// One workgroup; T is at most 2^21, so this is a few microseconds.
-__global__ __launch_bounds__(1024) void k_kvec_check(const int32_t *__restrict__ kvec, int T, int k,
-                                                     long long *__restrict__ out)
+// Sum of a per-token k vector and the number of entries outside 0..k: workgroup b leaves its partial results in
+// out[2*b], out[2*b+1] (no atomics, nothing to clear); the host adds the kKvecBlocks pairs.
+constexpr int kKvecBlocks = 64;
+
+__global__ __launch_bounds__(256) void k_kvec_check(const int32_t *__restrict__ kvec, int T, int k,
+                                                    long long *__restrict__ out)
 {
-    __shared__ long long s_sum[16];
-    __shared__ int s_bad[16];
+    __shared__ long long s_sum[4];
+    __shared__ int s_bad[4];
     long long sum = 0;
     int bad = 0;
-    for (int i = threadIdx.x; i < T; i += 1024) {
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < T; i += kKvecBlocks * 256) {
         const int v = kvec[i];
         bad += (v < 0 || v > k);
         sum += v;
@@ -1547,13 +1549,8 @@ __global__ __launch_bounds__(1024) void k_kvec_check(const int32_t *__restrict__
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        long long ts = 0, tb = 0;
-        for (int w = 0; w < 16; ++w) {
-            ts += s_sum[w];
-            tb += s_bad[w];
-        }
-        out[0] = ts;
-        out[1] = tb;
+        out[2 * blockIdx.x] = s_sum[0] + s_sum[1] + s_sum[2] + s_sum[3];
+        out[2 * blockIdx.x + 1] = s_bad[0] + s_bad[1] + s_bad[2] + s_bad[3];
     }
 }
 
@@ -1596,13 +1593,18 @@ int32_t kvec_check(const int32_t *kvec, int T, int E, int k, char *ws, long long
 {
     WorkspaceLayout L = workspace_layout(T, E, k);
     long long *out = (long long *)(ws + L.cand_off);       // the candidate lists are not in use before a solve
-    hipLaunchKernelGGL(k_kvec_check, dim3(1), dim3(1024), 0, s, kvec, T, k, out);
-    long long h[2] = {0, 0};
+    hipLaunchKernelGGL(k_kvec_check, dim3(kKvecBlocks), dim3(256), 0, s, kvec, T, k, out);
+    long long h[2 * kKvecBlocks];
     MS_HIP(hipMemcpyAsync(h, out, sizeof(h), hipMemcpyDeviceToHost, s));
     MS_HIP(hipStreamSynchronize(s));
     MS_HIP(hipGetLastError());
-    if (h[1] != 0) return MAXSCORE_ERR_SHAPE;
-    *demand = h[0];
+    long long sum = 0, bad = 0;
+    for (int b = 0; b < kKvecBlocks; ++b) {
+        sum += h[2 * b];
+        bad += h[2 * b + 1];
+    }
+    if (bad != 0) return MAXSCORE_ERR_SHAPE;
+    *demand = sum;
     return MAXSCORE_OK;
 }
 
