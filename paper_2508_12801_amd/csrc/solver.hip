@@ -678,7 +678,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
     __shared__ int s_nv2[2], s_ni2[2], s_over2[2];     // per-iteration counters, double-buffered by iteration parity
     // stop requests: s_stop1 is written in step 1 and read after the barrier that ends it, s_stop2 likewise for
     // step 2, so a flag is never written between a barrier and the reads that follow that barrier
-    __shared__ int s_stop1, s_stop2, s_moves, s_changed, s_sink;
+    __shared__ int s_stop1, s_stop2, s_moves, s_changed;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const long long eps = st->eps, qmin = st->qmin;
@@ -719,10 +719,6 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         // the counters are double-buffered by iteration parity: this iteration's were cleared during the last one
         const int pi = it & 1;
         int &s_nv = s_nv2[pi], &s_ni = s_ni2[pi], &s_over = s_over2[pi];
-        // rows of the first entry each expert pops are requested here, one load per cache line, so that
-        // the evaluation after the barrier finds them close by
-        int pfv[kTailMaxE / 32 + 1];
-        bool pf_live = false;
         // 0. the keys requested in the previous iteration enter the lists in request order; wavefront w serves
         //    the experts e with e mod 16 = w (its first kCand lanes hold one list entry each) and, right after,
         //    runs step 1 for the same experts, so no workgroup barrier is needed between the two
@@ -790,14 +786,6 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                         s_cn[e] = cn - m;
                         s_changed = 1;
                         if (nt > s_theta[e] && nt < kKeyInf) s_theta[e] = nt;
-                        {
-                            const int t0 = (int)(ce[cn - 1] & tmask);
-                            const int32_t *pr = q + (size_t)t0 * E;
-#pragma unroll
-                            for (int c = 0; c < kTailMaxE / 32; ++c) pfv[c] = c * 32 < E ? pr[c * 32] : 0;
-                            pfv[kTailMaxE / 32] = assign[(size_t)t0 * k];
-                            pf_live = true;
-                        }
                     }
                 }
             }
@@ -1024,12 +1012,6 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         c_y += clock64() - c_d;
 #endif
         MS_TP(c_p2)
-        if (pf_live) {          // the requested lines have long arrived; this only keeps the loads alive
-            int acc = 0;
-#pragma unroll
-            for (int c = 0; c <= kTailMaxE / 32; ++c) acc ^= pfv[c];
-            s_sink = acc;
-        }
         if (s_stop2) break;
     }
     for (int e = tid; e < E; e += kTailThreads) {
