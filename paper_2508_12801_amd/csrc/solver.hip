@@ -269,14 +269,14 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
     int an = -2;
     auto load_row_to = [&](int row, int(&qn)[EPL], int &an) {
         const int32_t *qr = q + (size_t)row * E + lg * EPL;
-        if (VEC) {
-            if (EPL >= 4) {
+        if constexpr (VEC) {
+            if constexpr (EPL >= 4) {
 #pragma unroll
                 for (int m = 0; m < EPL; m += 4) {
                     int4 t4 = *(const int4 *)(qr + m);
                     qn[m] = t4.x; qn[m + 1] = t4.y; qn[m + 2] = t4.z; qn[m + 3] = t4.w;
                 }
-            } else if (EPL == 2) {
+            } else if constexpr (EPL == 2) {
                 int2 t2 = *(const int2 *)qr;
                 qn[0] = t2.x; qn[1] = t2.y;
             } else {
@@ -655,6 +655,35 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
 
 // Runs in the extra workgroup of the select pass (all kTailThreads threads), after the other
 // workgroups have published their candidate lists.
+// LDS of the tail pass, in a function of its own so that the instantiations of tail_pass share one copy.
+struct TailShared {
+    // candidate lists are kept in DESCENDING order: the lowest keys sit at the end and leave by
+    // shortening the list
+    long long cand[kTailMaxE * kCand];
+    long long theta[kTailMaxE];
+    long long bound[kTailMaxE];
+    long long ikey[kTailIns];
+    int n[kTailMaxE];
+    int capv[kTailMaxE];     // capacity of every expert (uniform Ce unless a vector was given)
+    int cn[kTailMaxE];
+    int vtok[kTailVict], vexp[kTailVict];
+    int iexp[kTailIns];
+    int qrow[kTailThreads / 64][kTailMaxE];
+    int nv2[2], ni2[2], over2[2];     // per-iteration counters, double-buffered by iteration parity
+    // stop requests: stop1 is written in step 1 and read after the barrier that ends it, stop2 likewise for
+    // step 2, so a flag is never written between a barrier and the reads that follow that barrier
+    int stop1, stop2, moves, changed;
+};
+
+__device__ __forceinline__ TailShared *tail_shared()
+{
+    __shared__ TailShared s;
+    return &s;
+}
+
+// TEPL = expert slots per lane (ceil(E / 64) <= TEPL): 1 and 2 serve E <= 64 and E <= 128 without the dead work
+// of 4 (the pass is bound by the number of instructions one wavefront has to get through per hop).
+template <int TEPL>
 __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t *assign, long long *theta2,
                                           int *gcount2, SolverState *st2, const long long *cand, int *errflag,
                                           int par, int T, int E, int k, int Ce, const int *__restrict__ cap,
@@ -663,22 +692,22 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
     SolverState *st = st2 + (par ^ 1);          // the state the next bid pass will read
     long long *theta = theta2 + (par ^ 1) * kMaxE;
     int *gcur = gcount2 + par * kMaxE;
-    // candidate lists are kept in DESCENDING order: the lowest keys sit at the end and leave by
-    // shortening the list
-    __shared__ long long s_cand[kTailMaxE * kCand];
-    __shared__ long long s_theta[kTailMaxE];
-    __shared__ long long s_bound[kTailMaxE];
-    __shared__ int s_n[kTailMaxE];
-    __shared__ int s_capv[kTailMaxE];     // capacity of every expert (uniform Ce unless a vector was given)
-    __shared__ int s_cn[kTailMaxE];
-    __shared__ int s_vtok[kTailVict], s_vexp[kTailVict];
-    __shared__ int s_iexp[kTailIns];
-    __shared__ long long s_ikey[kTailIns];
-    __shared__ int s_qrow[kTailThreads / 64][kTailMaxE];
-    __shared__ int s_nv2[2], s_ni2[2], s_over2[2];     // per-iteration counters, double-buffered by iteration parity
-    // stop requests: s_stop1 is written in step 1 and read after the barrier that ends it, s_stop2 likewise for
-    // step 2, so a flag is never written between a barrier and the reads that follow that barrier
-    __shared__ int s_stop1, s_stop2, s_moves, s_changed;
+    TailShared &sh = *tail_shared();
+    auto &s_cand = sh.cand;
+    auto &s_theta = sh.theta;
+    auto &s_bound = sh.bound;
+    auto &s_n = sh.n;
+    auto &s_capv = sh.capv;
+    auto &s_cn = sh.cn;
+    auto &s_vtok = sh.vtok;
+    auto &s_vexp = sh.vexp;
+    auto &s_iexp = sh.iexp;
+    auto &s_ikey = sh.ikey;
+    auto &s_qrow = sh.qrow;
+    auto &s_nv2 = sh.nv2;
+    auto &s_ni2 = sh.ni2;
+    auto &s_over2 = sh.over2;
+    int &s_stop1 = sh.stop1, &s_stop2 = sh.stop2, &s_moves = sh.moves, &s_changed = sh.changed;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const long long eps = st->eps, qmin = st->qmin;
@@ -809,9 +838,9 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                                 : -2;
             const int k_tok = kvec ? kvec[tok] : k;       // slots from k_tok on do not exist for this token
             my_e = lane < k_tok ? my_e : -2;
-            int qv[kTailEPL];
+            int qv[TEPL];
 #pragma unroll
-            for (int m = 0; m < kTailEPL; ++m) qv[m] = (m < eplt && lane + 64 * m < E) ? qr[lane + 64 * m] : 0;
+            for (int m = 0; m < TEPL; ++m) qv[m] = (m < eplt && lane + 64 * m < E) ? qr[lane + 64 * m] : 0;
             // a token challenged by several experts at once is evaluated once, by its first entry
             const unsigned long long twins = __ballot(lane < nv && lane != vi && s_vtok[lane] == tok);
             if (twins & ((1ull << vi) - 1)) continue;
@@ -819,10 +848,10 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
 #ifdef MS_TAIL_PROF
             long long c_a = clock64();
 #endif
-            long long v[kTailEPL];
+            long long v[TEPL];
             unsigned validm = 0, heldm = 0;
 #pragma unroll
-            for (int m = 0; m < kTailEPL; ++m) {
+            for (int m = 0; m < TEPL; ++m) {
                 v[m] = 0;
                 if (m < eplt) {
                     const int e = lane + 64 * m;
@@ -848,7 +877,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
             auto best_unheld = [&]() {
                 unsigned long long b = 0;
 #pragma unroll
-                for (int m = 0; m < kTailEPL; ++m) {
+                for (int m = 0; m < TEPL; ++m) {
                     if (m < eplt && (((validm & ~heldm) >> m) & 1u)) {
                         unsigned long long pk =
                             ((unsigned long long)(v[m] + (long long)kVB) << 10) | (unsigned)((lane + 64 * m) ^ r0);
@@ -885,7 +914,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 auto reward_of = [&](int e) {             // e is wavefront-uniform
                     int r = 0;
 #pragma unroll
-                    for (int m = 0; m < kTailEPL; ++m)
+                    for (int m = 0; m < TEPL; ++m)
                         if ((e >> 6) == m) r = __builtin_amdgcn_readlane(qv[m], e & 63);
                     return ((long long)r - qmin) << sb;
                 };
@@ -940,7 +969,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
             // several holds of the token are challenged at once: the bid pass's general evaluation
             int *qrow = s_qrow[wv];
 #pragma unroll
-            for (int m = 0; m < kTailEPL; ++m)
+            for (int m = 0; m < TEPL; ++m)
                 if (m < eplt && lane + 64 * m < E) qrow[lane + 64 * m] = qv[m];
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -1063,7 +1092,10 @@ __device__ unsigned long long g_selround[1024];
 static_assert(kSelThreads == kTailThreads, "the tail pass runs in a workgroup of the select pass");
 
 // Grid: E workgroups, one per expert, plus (when tail_on) one more that runs the tail pass on the
-// candidate lists the others publish in rounds that hand over to it.
+// candidate lists the others publish in rounds that hand over to it.  TEPL = expert slots per lane of the tail
+// pass (the host picks the smallest that covers E: the kernel then carries one copy of that pass, and a smaller
+// kernel measurably runs faster here).
+template <int TEPL>
 __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restrict__ klist,
                                                         const int *__restrict__ wcnt, const int *__restrict__ wmoves,
                                                         int *gcount2, long long *theta2, SolverState *st2,
@@ -1235,7 +1267,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             if (tid == 0) *errflag = 1;       // reported as MAXSCORE_ERR_HIP by the next select pass
             return;
         }
-        tail_pass(q, assign, theta2, gcount2, st2, cand, errflag, par, T, E, k, Ce, cap, tail_iters, kvec);
+        tail_pass<TEPL>(q, assign, theta2, gcount2, st2, cand, errflag, par, T, E, k, Ce, cap, tail_iters, kvec);
         return;
     }
     long long new_theta = base;
@@ -1694,9 +1726,14 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             else MS_BID(64);
 #undef MS_BID
             if (g_kernel_timing) MS_HIP(hipEventRecord(tev.back(), s));
-            hipLaunchKernelGGL(k_select, dim3(E + tail_on), dim3(kSelThreads), 0, s, klist, wcnt, wmoves, gcount, theta,
-                               st, qmm + 2, cand, q, assign, qmm + 3, tl_flag_dev, par, T, E, k, Ce, cap, n_wg, rows, tail_on,
-                               tail_moves, tail_iters, kvec);
+#define MS_SEL(TT)                                                                                             \
+    hipLaunchKernelGGL(k_select<TT>, dim3(E + tail_on), dim3(kSelThreads), 0, s, klist, wcnt, wmoves, gcount, theta, \
+                       st, qmm + 2, cand, q, assign, qmm + 3, tl_flag_dev, par, T, E, k, Ce, cap, n_wg, rows, tail_on, \
+                       tail_moves, tail_iters, kvec)
+            if (E <= 64) MS_SEL(1);
+            else if (E <= 128) MS_SEL(2);
+            else MS_SEL(kTailEPL);
+#undef MS_SEL
             ++launched;
         }
         MS_HIP(hipEventRecord(evb[slot], s));

@@ -64,6 +64,11 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert lib.maxscore_assign_i32(one, 8, 4, 2, 4, null, one, null, null, null, null, 1 << 20, null) == -3
     assert lib.maxscore_assign_i32(one, 8, 4, 2, 4, null, one, null, null, null, ctypes.c_void_p(260), 1 << 20, null) == -3
     assert lib.maxscore_assign_i32(one, 8, 4, 2, 4, null, one, null, null, null, one, 16, null) == -3
+    # per-token k: missing vector, k > E, capacity < 1 without a capacity vector, missing workspace
+    assert lib.maxscore_assign_kvec_i32(one, 8, 4, 2, null, 4, null, null, one, null, null, null, one, 1 << 20, null) == -1
+    assert lib.maxscore_assign_kvec_i32(one, 8, 4, 5, one, 4, null, null, one, null, null, null, one, 1 << 20, null) == -2
+    assert lib.maxscore_assign_kvec_i32(one, 8, 4, 2, one, 0, null, null, one, null, null, null, one, 1 << 20, null) == -2
+    assert lib.maxscore_assign_kvec_i32(one, 8, 4, 2, one, 4, null, null, one, null, null, null, null, 1 << 20, null) == -3
     # dtype
     assert lib.maxscore_router_logits(one, one, null, 7, 4, 4, 4, one, null, 0, null) == -4
     assert lib.maxscore_copy_bytes(one, one, 10, null) == -2
