@@ -671,6 +671,7 @@ struct TailShared {
     int vtok[kTailVict], vexp[kTailVict];
     int iexp[kTailIns];
     int qrow[kTailThreads / 64][kTailMaxE];
+    unsigned char hmark[kTailThreads / 64][kTailMaxE];   // per wavefront: 1 on the experts the token under evaluation holds
     int nv2[2], ni2[2], over2[2];     // per-iteration counters, double-buffered by iteration parity
     // stop requests: stop1 is written in step 1 and read after the barrier that ends it, stop2 likewise for
     // step 2, so a flag is never written between a barrier and the reads that follow that barrier
@@ -706,6 +707,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
     auto &s_iexp = sh.iexp;
     auto &s_ikey = sh.ikey;
     auto &s_qrow = sh.qrow;
+    auto &s_hmark = sh.hmark;
     auto &s_nv2 = sh.nv2;
     auto &s_ni2 = sh.ni2;
     auto &s_over2 = sh.over2;
@@ -733,6 +735,8 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         s_n[e] = gcur[e];
         s_capv[e] = cap ? cap[e] : Ce;
     }
+    static_assert(sizeof(sh.hmark) == 4 * kTailThreads, "one word of marks per thread");
+    ((int *)&s_hmark[0][0])[tid] = 0;
     if (tid == 0) {
         s_stop1 = 0; s_stop2 = 0; s_moves = 0; s_changed = 0;
         s_nv2[0] = s_nv2[1] = 0; s_ni2[0] = s_ni2[1] = 0; s_over2[0] = s_over2[1] = 0;
@@ -866,9 +870,21 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
 #ifdef MS_TAIL_PROF
             long long c_b = clock64();
 #endif
-            for (int s2 = 0; s2 < k; ++s2) {
-                const int es = __builtin_amdgcn_readlane(my_e, s2);
-                if (es >= 0 && (es & 63) == lane) heldm |= 1u << (es >> 6);
+            {
+                // which of this lane's experts the token holds: the slot lanes mark their expert in a byte map of the
+                // wavefront, every lane reads its own bytes, the marks are taken back (three LDS instructions where a
+                // loop over the slots needs a dozen instructions per slot)
+                unsigned char *hm = s_hmark[wv];
+                if (my_e >= 0) hm[my_e] = 1;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                for (int m = 0; m < TEPL; ++m) heldm |= (unsigned)hm[lane + 64 * m] << m;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                if (my_e >= 0) hm[my_e] = 0;
             }
 #ifdef MS_TAIL_PROF
             long long c_h = clock64();
