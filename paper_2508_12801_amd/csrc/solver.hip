@@ -628,7 +628,8 @@ __device__ int g_tailstat[8];
 constexpr int kTailMoves = 16;            // hand over to the tail pass when a bid pass moved this few slots
 constexpr long long kKeyInf = (long long)1 << 62;
 constexpr int kTailSpinMax = 1 << 20;     // polls of the tail workgroup for the candidate lists before it gives up
-constexpr int kTailVict = 64;
+constexpr int kTailVict = 64;             // dropped tokens per iteration (the list is read back one entry per lane)
+static_assert(kTailVict == 64, "the victim list is read with one entry per lane");
 constexpr int kTailIns = 256;
 constexpr int kTailEPL = kTailMaxE / 64;
 
@@ -829,12 +830,16 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         MS_TP(c_p1)
         // the counters of the other parity were last read in step 0 above; the next iteration starts from zero
         if (tid == 0) { s_nv2[pi ^ 1] = 0; s_ni2[pi ^ 1] = 0; s_over2[pi ^ 1] = 0; }
-        over_last = s_over;
-        if (s_stop1 || !s_over) break;
+        // everything this step needs from the mailboxes is asked for at once (one LDS round trip instead of five
+        // dependent ones): the flags, the count, and the whole victim list, one entry per lane
+        const int stop1_now = s_stop1, over_now = s_over, nv_now = s_nv;
+        const int vtok_l = s_vtok[lane], vexp_l = s_vexp[lane];
+        over_last = over_now;
+        if (stop1_now || !over_now) break;
         // 2. one wavefront per dropped token: the bid pass's row evaluation
-        const int nv = s_nv < kTailVict ? s_nv : kTailVict;
+        const int nv = nv_now < kTailVict ? nv_now : kTailVict;
         for (int vi = wv; vi < nv; vi += kTailThreads / 64) {
-            const int tok = __builtin_amdgcn_readfirstlane(s_vtok[vi]);
+            const int tok = __builtin_amdgcn_readlane(vtok_l, vi);
             const int32_t *qr = q + (size_t)tok * E;
             // the row is requested first, everything else is looked up while it travels.  Other
             // wavefronts of this workgroup may have rewritten the assignment row in an earlier round:
@@ -848,9 +853,9 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
 #pragma unroll
             for (int m = 0; m < TEPL; ++m) qv[m] = (m < eplt && lane + 64 * m < E) ? qr[lane + 64 * m] : 0;
             // a token challenged by several experts at once is evaluated once, by its first entry
-            const unsigned long long twins = __ballot(lane < nv && lane != vi && s_vtok[lane] == tok);
+            const unsigned long long twins = __ballot(lane < nv && lane != vi && vtok_l == tok);
             if (twins & ((1ull << vi) - 1)) continue;
-            const int ve = __builtin_amdgcn_readfirstlane(s_vexp[vi]);
+            const int ve = __builtin_amdgcn_readlane(vexp_l, vi);
 #ifdef MS_TAIL_PROF
             long long c_a = clock64();
 #endif
