@@ -856,6 +856,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
             const unsigned long long twins = __ballot(lane < nv && lane != vi && vtok_l == tok);
             if (twins & ((1ull << vi) - 1)) continue;
             const int ve = __builtin_amdgcn_readlane(vexp_l, vi);
+            const long long theta_ve = s_theta[ve];
 #ifdef MS_TAIL_PROF
             long long c_a = clock64();
 #endif
@@ -915,8 +916,9 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 bid = bid < kBidBig ? bid : kBidBig;
                 return bid * ((long long)1 << tb) + tok;
             };
-            auto request = [&](int e, long long key) {       // one lane
-                if (key < s_bound[e]) {
+            // (bounds and thresholds are only written in steps 0 and 1, so they can be read ahead of their use here)
+            auto request = [&](int e, long long key, long long bound_e) {       // one lane; bound_e = s_bound[e]
+                if (key < bound_e) {
                     const int slot = atomicAdd(&s_ni, 1);
                     if (slot < kTailIns) {
                         s_iexp[slot] = e;
@@ -943,8 +945,8 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 };
                 if (__ballot(my_e == ve) != 0) {           // still held (else there is nothing to decide)
                     const long long key = key_of(reward_of(ve), pk);
-                    if (key >= s_theta[ve]) {
-                        if (lane == 0) request(ve, key);   // survives: back on the list with its true key
+                    if (key >= theta_ve) {
+                        if (lane == 0) request(ve, key, s_bound[ve]);   // survives: back on the list with its true key
 #ifdef MS_TAIL_PROF
                         if (lane == 0) atomicAdd(&g_tailstat[nv == 1 ? 0 : 2], 1);
 #endif
@@ -955,6 +957,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                         if (pk == 0 || e1 >= E) {          // cannot happen while k <= E
                             *errflag = 1;
                         } else {
+                            const long long bound_e1 = s_bound[e1];     // on its way while the next best is found
                             if ((ve & 63) == lane) heldm &= ~(1u << (ve >> 6));
                             if ((e1 & 63) == lane) heldm |= 1u << (e1 >> 6);
 #ifdef MS_TAIL_PROF
@@ -972,7 +975,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                                 atomicAdd(&s_n[ve], -1);
                                 atomicAdd(&s_n[e1], 1);
                                 atomicAdd(&s_moves, 1);
-                                request(e1, key1);
+                                request(e1, key1, bound_e1);
 #ifdef MS_TAIL_PROF
                                 atomicAdd(&g_tailstat[nv == 1 ? 1 : 3], 1);
 #endif
@@ -1052,7 +1055,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                                        __HIP_MEMORY_SCOPE_WORKGROUP);
                     atomicAdd(&s_n[my_e], 1);
                 }
-                request(my_e, key);
+                request(my_e, key, s_bound[my_e]);
             }
             __builtin_amdgcn_wave_barrier();
         }
