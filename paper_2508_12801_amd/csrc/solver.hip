@@ -971,10 +971,14 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                             if (my_e == ve)
                                 __hip_atomic_store(&assign[(size_t)tok * k + lane], e1, __ATOMIC_RELAXED,
                                                    __HIP_MEMORY_SCOPE_WORKGROUP);
+                            // the three counters in one LDS instruction: lanes 0-2 take one each (with a
+                            // wavefront-uniform address the compiler wraps every atomic in code that counts
+                            // the active lanes first)
+                            if (lane < 3) {
+                                int *ctr = lane == 0 ? &s_n[ve] : lane == 1 ? &s_n[e1] : &s_moves;
+                                atomicAdd(ctr, lane == 0 ? -1 : 1);
+                            }
                             if (lane == 0) {
-                                atomicAdd(&s_n[ve], -1);
-                                atomicAdd(&s_n[e1], 1);
-                                atomicAdd(&s_moves, 1);
                                 request(e1, key1, bound_e1);
 #ifdef MS_TAIL_PROF
                                 atomicAdd(&g_tailstat[nv == 1 ? 1 : 3], 1);
