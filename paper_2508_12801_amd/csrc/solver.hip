@@ -656,6 +656,17 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
     return ((unsigned long long)mhi << 32) | mlo;
 }
 
+// An LDS counter address the compiler cannot see to be the same in all lanes: with a wavefront-uniform address it
+// wraps an atomic add in code that first counts and ranks the active lanes (a loop over them when the addends
+// differ); here one or two lanes are active, and the plain LDS atomic is a fraction of that code.
+__device__ __forceinline__ int *opaque_counter(int *p)
+{
+    typedef __attribute__((address_space(3))) int lds_int;
+    unsigned off = (unsigned)(unsigned long)(lds_int *)p;      // the 32-bit LDS offset (the address stays an LDS one)
+    asm volatile("" : "+v"(off));
+    return (int *)(lds_int *)(unsigned long)off;
+}
+
 // Runs in the extra workgroup of the select pass (all kTailThreads threads), after the other
 // workgroups have published their candidate lists.
 // LDS of the tail pass, in a function of its own so that the instantiations of tail_pass share one copy.
@@ -806,7 +817,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 if (cn < m) {
                     s_stop1 = 1;                       // list exhausted: the select pass has to rebuild it
                 } else {
-                    const int b = atomicAdd(&s_nv, m);
+                    const int b = atomicAdd(opaque_counter(&s_nv), m);
                     if (b + m > kTailVict) {
                         s_stop1 = 1;
                     } else {
@@ -919,7 +930,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
             // (bounds and thresholds are only written in steps 0 and 1, so they can be read ahead of their use here)
             auto request = [&](int e, long long key, long long bound_e) {       // one lane; bound_e = s_bound[e]
                 if (key < bound_e) {
-                    const int slot = atomicAdd(&s_ni, 1);
+                    const int slot = atomicAdd(opaque_counter(&s_ni), 1);
                     if (slot < kTailIns) {
                         s_iexp[slot] = e;
                         s_ikey[slot] = key;
