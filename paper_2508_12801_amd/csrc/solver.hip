@@ -57,13 +57,34 @@ __device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v,
     return ((unsigned long long)hi << 32) | lo;
 }
 
+// One step of a 64-bit maximum across lanes: both halves make the same lane swap (CTRL: a data-parallel-primitive
+// pattern inside the 16-lane row), the larger of own and swapped value stays.
+template <int CTRL>
+__device__ __forceinline__ unsigned long long max_swap_u64(unsigned long long v)
+{
+    const unsigned lo = (unsigned)__builtin_amdgcn_mov_dpp((int)(unsigned)v, CTRL, 0xf, 0xf, true);
+    const unsigned hi = (unsigned)__builtin_amdgcn_mov_dpp((int)(unsigned)(v >> 32), CTRL, 0xf, 0xf, true);
+    const unsigned long long o = ((unsigned long long)hi << 32) | lo;
+    return o > v ? o : v;
+}
+
+// Maximum of a 64-bit value over the G lanes of a group, result in every lane of the group.  Groups of 8 and 16
+// lanes use lane swaps inside the row (quad, mirrored half row, mirrored row: every lane of a full wavefront is a
+// valid source); wider groups go through the LDS crossbar.
 template <int G>
 __device__ __forceinline__ unsigned long long group_max(unsigned long long v)
 {
+    if constexpr (G == 8 || G == 16) {
+        v = max_swap_u64<0xB1>(v);      // quad_perm [1,0,3,2]
+        v = max_swap_u64<0x4E>(v);      // quad_perm [2,3,0,1]
+        v = max_swap_u64<0x141>(v);     // row_half_mirror
+        if constexpr (G == 16) v = max_swap_u64<0x140>(v);   // row_mirror
+    } else {
 #pragma unroll
-    for (int off = G / 2; off > 0; off >>= 1) {
-        unsigned long long o = shfl_xor_u64(v, off);
-        v = o > v ? o : v;
+        for (int off = G / 2; off > 0; off >>= 1) {
+            unsigned long long o = shfl_xor_u64(v, off);
+            v = o > v ? o : v;
+        }
     }
     return v;
 }
@@ -252,6 +273,7 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
     __shared__ short s_exp[1024];
     __shared__ short s_pos[1024];
     __shared__ short s_queue[1024];
+    __shared__ unsigned s_hm[256];          // per group of G lanes: G words of "held" bits, one word per lane
     __shared__ int s_moves, s_nq;
 
     const int tid = threadIdx.x;
@@ -356,11 +378,22 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
         long long v[EPL];
 #pragma unroll
         for (int m = 0; m < EPL; ++m) v[m] = (((long long)qc[m] - qmin) << sb) - (s_theta[lg * EPL + m] >> tb);
-        unsigned heldm = 0;
-        for (int s = 0; s < k; ++s) {
-            int es = __shfl(my_e, s, G);
-            if (es >= 0 && (es >> LOGP) == lg) heldm |= 1u << (es & (EPL - 1));
-        }
+        // which of this lane's experts the row holds: the slot lanes set their expert's bit in the word of the lane
+        // that owns it (three LDS instructions; a loop over the k slots costs a cross-lane read and half a dozen
+        // instructions per slot)
+        auto held_mask = [&](int e_slot) {
+            unsigned *hmg = s_hm + (tid - lg);
+            hmg[lg] = 0;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (e_slot >= 0) atomicOr(&hmg[e_slot >> LOGP], 1u << (e_slot & (EPL - 1)));
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            return hmg[lg];
+        };
+        unsigned heldm = held_mask(my_e);
         // packed candidate: value, then a per-row rotation of the lane order, then the lower expert
         const unsigned long long pbase = (kVB << 10) | ((unsigned long long)((lg + row) & (G - 1)) << 4);
         auto local_best = [&]() {
@@ -404,13 +437,7 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
         const int f = __popcll(gfb);
         if (f > 0) {
             const bool any_drop = group_bits(__ballot(dropped)) != 0;
-            if (any_drop) {
-                heldm = 0;
-                for (int s = 0; s < k; ++s) {
-                    int es = __shfl(my_e, s, G);
-                    if (es >= 0 && (es >> LOGP) == lg) heldm |= 1u << (es & (EPL - 1));
-                }
-            }
+            if (any_drop) heldm = held_mask(my_e);
             const int my_rank = (my_e == -1) ? __popcll(gfb & ((1ull << lg) - 1)) : -1;
             for (int r = 0; r < f; ++r) {
                 pk = group_max<G>(local_best());
