@@ -675,6 +675,31 @@ __device__ __forceinline__ unsigned wave_max_u32(unsigned v)
     return (unsigned)__builtin_amdgcn_readlane((int)v, 63);
 }
 
+// Inclusive prefix sum over the 64 lanes with lane moves inside the rows and row broadcasts (no LDS crossbar):
+// lanes without a source read 0.  Lane 63 ends with the total.
+__device__ __forceinline__ int wave_scan_add(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);    // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);    // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);    // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);    // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+// The same walk with OR: lane 63 ends with the OR over the wavefront.
+__device__ __forceinline__ int wave_scan_or(int v)
+{
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);
+    return v;
+}
+
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
 {
     const unsigned hi = (unsigned)(v >> 32), lo = (unsigned)v;
@@ -1230,12 +1255,10 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     const long long cur_eps = st->eps, cur_eps_prev = st->eps_prev, cur_beta = st->beta;
     const long long base = theta_in[j];
     int flags = (ov ? 2 : 0) | (vi ? 4 : 0);
-    for (int off = 32; off > 0; off >>= 1) {
-        flags |= __shfl_xor(flags, off);
-        mv += __shfl_xor(mv, off);
-        ct += __shfl_xor(ct, off);
-    }
-    if (lane == 0) {
+    flags = wave_scan_or(flags);          // lane 63 holds the wavefront's result
+    mv = wave_scan_add(mv);
+    ct = wave_scan_add(ct);
+    if (lane == 63) {
         s_redi[wv] = ct;
         s_flag[wv] = flags;
         s_mvw[wv] = mv;
@@ -1373,14 +1396,14 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                 for (int u = 0; u < 8; ++u) {
                     if (it0 + u < iters) {           // the same for the whole wavefront
                         int inc = cs[u];             // all 8 lanes of a group hold their segment's count
-                        for (int off = 8; off < 64; off <<= 1) {
-                            int o = __shfl_up(inc, off);
-                            if (lane >= off) inc += o;
-                        }
-                        const int tot = __shfl(inc, 63);
+                        // inclusive sum over the groups: the other half of the row, then the rows before
+                        inc += __builtin_amdgcn_update_dpp(0, inc, 0x118, 0xf, 0xf, true);    // row_shr:8
+                        inc += __builtin_amdgcn_update_dpp(0, inc, 0x142, 0xa, 0xf, false);   // row_bcast:15
+                        inc += __builtin_amdgcn_update_dpp(0, inc, 0x143, 0xc, 0xf, false);   // row_bcast:31
+                        const int tot = __builtin_amdgcn_readlane(inc, 63);
                         int bp = 0;
                         if (lane == 63 && tot > 0) bp = atomicAdd(&s_fill, tot);
-                        bp = __shfl(bp, 63);
+                        bp = __builtin_amdgcn_readlane(bp, 63);
                         const int gpos = bp + inc - cs[u];
                         if (sub < cs[u]) s_keys[gpos + sub] = kvv[u];
                         for (int i = sub + 8; i < cs[u]; i += 8) s_keys[gpos + i] = sp[u][i];
@@ -1419,11 +1442,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                 if (wv == 0) {
                     const int4 b4 = *(const int4 *)&s_hist[h][lane * 4];
                     const int sum = b4.x + b4.y + b4.z + b4.w;
-                    int hi = sum;
-                    for (int off = 1; off < 64; off <<= 1) {
-                        int o = __shfl_up(hi, off);
-                        if (lane >= off) hi += o;
-                    }
+                    const int hi = wave_scan_add(sum);
                     const int exc = hi - sum;
                     if (exc <= rank && rank < hi) {
                         int r = rank - exc, d = 0, m = b4.x;
