@@ -57,6 +57,31 @@ __device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v,
     return ((unsigned long long)hi << 32) | lo;
 }
 
+// Inclusive prefix sum over the 64 lanes with lane moves inside the rows and row broadcasts (no LDS crossbar):
+// lanes without a source read 0.  Lane 63 ends with the total.
+__device__ __forceinline__ int wave_scan_add(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);    // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);    // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);    // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);    // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+// The same walk with OR: lane 63 ends with the OR over the wavefront.
+__device__ __forceinline__ int wave_scan_or(int v)
+{
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);
+    return v;
+}
+
 // One step of a 64-bit maximum across lanes: both halves make the same lane swap (CTRL: a data-parallel-primitive
 // pattern inside the 16-lane row), the larger of own and swapped value stays.
 template <int CTRL>
@@ -590,11 +615,7 @@ __global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, i
             loc[i] = e < EP ? s_cnt[e] : 0;
             sum += loc[i];
         }
-        int inc = sum;
-        for (int off = 1; off < 64; off <<= 1) {
-            int o = __shfl_up(inc, off);
-            if ((tid & 63) >= off) inc += o;
-        }
+        const int inc = wave_scan_add(sum);
         if ((tid & 63) == 63) s_wtot[tid >> 6] = inc;
         __syncthreads();
         int base = inc - sum;
@@ -673,31 +694,6 @@ __device__ __forceinline__ unsigned wave_max_u32(unsigned v)
     o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false); v = o > v ? o : v;  // row_bcast:15
     o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false); v = o > v ? o : v;  // row_bcast:31
     return (unsigned)__builtin_amdgcn_readlane((int)v, 63);
-}
-
-// Inclusive prefix sum over the 64 lanes with lane moves inside the rows and row broadcasts (no LDS crossbar):
-// lanes without a source read 0.  Lane 63 ends with the total.
-__device__ __forceinline__ int wave_scan_add(int v)
-{
-    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);    // row_shr:1
-    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);    // row_shr:2
-    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);    // row_shr:4
-    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);    // row_shr:8
-    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
-    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
-    return v;
-}
-
-// The same walk with OR: lane 63 ends with the OR over the wavefront.
-__device__ __forceinline__ int wave_scan_or(int v)
-{
-    v |= __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);
-    v |= __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);
-    v |= __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);
-    v |= __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);
-    v |= __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);
-    v |= __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);
-    return v;
 }
 
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
@@ -1500,8 +1496,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                     mine = s_small[el];
                     for (int i = part; i < m; i += kParts) r += s_small[i] < mine;
                 }
-#pragma unroll
-                for (int off = 1; off < kParts; off <<= 1) r += __shfl_xor(r, off);
+                static_assert(kParts == 4, "the partial counts of a key sit in one quad of lanes");
+                r += __builtin_amdgcn_mov_dpp(r, 0xB1, 0xf, 0xf, true);     // quad_perm [1,0,3,2]
+                r += __builtin_amdgcn_mov_dpp(r, 0x4E, 0xf, 0xf, true);     // quad_perm [2,3,0,1]
                 if (el < m && part == 0 && r == rank) s_res = mine;
             }
             __syncthreads();
