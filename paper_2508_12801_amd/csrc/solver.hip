@@ -888,7 +888,8 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         __syncthreads();
         MS_TP(c_p1)
         // the counters of the other parity were last read in step 0 above; the next iteration starts from zero
-        if (tid == 0) { s_nv2[pi ^ 1] = 0; s_ni2[pi ^ 1] = 0; s_over2[pi ^ 1] = 0; }
+        // (by the last wavefront: the first ones are the ones that evaluate, and this pass is bound by what they have to issue)
+        if (tid == kTailThreads - 1) { s_nv2[pi ^ 1] = 0; s_ni2[pi ^ 1] = 0; s_over2[pi ^ 1] = 0; }
         // everything this step needs from the mailboxes is asked for at once (one LDS round trip instead of five
         // dependent ones): the flags, the count, and the whole victim list, one entry per lane
         const int stop1_now = s_stop1, over_now = s_over, nv_now = s_nv;
