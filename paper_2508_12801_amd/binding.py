@@ -100,6 +100,13 @@ def load_library():
         path = lib_path()
         if not os.path.exists(path):
             raise MaxScoreError(-5, f"{path} is missing: run `python -m paper_2508_12801_amd.build` first")
+        # torch first: it brings its own copy of the HIP runtime, and the library must bind to that copy (the device
+        # memory and the streams it is handed come from there).  Loaded the other way round, the process holds two
+        # runtimes and every launch on torch's memory fails with a HIP error.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         lib = ctypes.CDLL(path)
         for name, (res, args) in _SIGS.items():
             fn = getattr(lib, name)
