@@ -275,8 +275,9 @@ __global__ __launch_bounds__(kMinmaxBlocks) void k_setup(SolverState *st, const 
 // experts l*EPL .. l*EPL+EPL-1 and slot l of the token (k <= G).  A wavefront therefore works on
 // 64/G rows at once and its loads of consecutive rows are contiguous.  The next row of each group
 // is prefetched into registers while the current one is evaluated.
+// (four workgroups per compute unit for the narrow groups; rows of 512 and 1024 experts need more registers)
 template <int G, int EPL, bool VEC, bool KV>
-__global__ __launch_bounds__(256, 4) void k_bid(const int32_t *__restrict__ q, int32_t *__restrict__ assign,
+__global__ __launch_bounds__(256, (G * EPL > 256 ? 3 : 4)) void k_bid(const int32_t *__restrict__ q, int32_t *__restrict__ assign,
                                              const long long *__restrict__ theta, const SolverState *__restrict__ st,
                                              long long *__restrict__ klist, int *__restrict__ wcnt,
                                              int *__restrict__ wmoves, int *__restrict__ errflag, int T, int E, int k,
