@@ -1198,6 +1198,17 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
 {
     const SolverState *st = st2 + par;
     SolverState *st_out = st2 + (par ^ 1);
+    // This thread's count and move words are requested before the state is looked at (valid memory whether or not
+    // the solve is over): the exit test then waits for the scalar loads of the state only, and the first of the
+    // kernel's two dependent memory round trips has already begun.
+    int mt0 = 0, mv = 0;
+    {
+        const int jj = (int)blockIdx.x == E ? 0 : blockIdx.x;
+        if ((int)threadIdx.x < n_wg) {
+            mt0 = wcnt[(size_t)threadIdx.x * E + jj];
+            mv = wmoves[threadIdx.x];
+        }
+    }
     if (st->done) {
         if (blockIdx.x == 0 && threadIdx.x == 0) {
             *st_out = *st;
@@ -1233,12 +1244,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     long long c_sp = clock64();
     const long long c_w0 = wall_clock64(), c_c0 = c_sp;
 #endif
-    int ct = 0, mv = 0, ov = 0, vi = 0, mt0 = 0;
-    if (tid < n_wg) {
-        mt0 = meta(tid);
-        ct = mt0 & 0xffff;
-        mv = wmoves[tid];
-    }
+    int ct = mt0 & 0xffff, ov = 0, vi = 0;
     for (int w = tid + kSelThreads; w < n_wg; w += kSelThreads) {
         ct += meta(w) & 0xffff;
         mv += wmoves[w];
