@@ -858,30 +858,42 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         MS_TP(c_p3)
         // 1. every over-full expert drops its lowest candidates and raises its threshold (expert e: lane e/16 of
         //    wavefront e mod 16)
+        // (the words of an expert are asked for together, and the list entries together with the slot reservation:
+        // three LDS round trips on the path of an over-full expert instead of six)
         for (int e = wv + (kTailThreads / 64) * lane; e < E; e += kTailThreads) {
-            const int m = s_n[e] - s_capv[e];
+            const int cap_e = s_capv[e], cn = s_cn[e], n_e = s_n[e];
+            const long long theta_e = s_theta[e], bound_e = s_bound[e];
+            // (the empty statement makes the five words live here: otherwise the compiler moves each read down to
+            // its first use, one dependent round trip after the other)
+            asm volatile("" ::"v"(cap_e), "v"(cn), "v"(n_e), "v"(theta_e), "v"(bound_e));
+            const int m = n_e - cap_e;
             if (m > 0) {
                 s_over = 1;
-                const int cn = s_cn[e];
                 if (cn < m) {
                     s_stop1 = 1;                       // list exhausted: the select pass has to rebuild it
                 } else {
+                    const long long *ce = s_cand + e * kCand;
+                    const long long low0 = ce[cn - 1];                       // the first key to go
+                    const long long next_key = cn > m ? ce[cn - 1 - m] : bound_e;
+                    const long long last_out = ce[cn - m];                   // the highest key that goes
                     const int b = atomicAdd(opaque_counter(&s_nv), m);
+                    asm volatile("" ::"v"(low0), "v"(next_key), "v"(last_out), "v"(b));
                     if (b + m > kTailVict) {
                         s_stop1 = 1;
                     } else {
-                        const long long *ce = s_cand + e * kCand;
-                        for (int i = 0; i < m; ++i) {
+                        s_vtok[b] = (int)(low0 & tmask);
+                        s_vexp[b] = e;
+                        for (int i = 1; i < m; ++i) {
                             s_vtok[b + i] = (int)(ce[cn - 1 - i] & tmask);
                             s_vexp[b + i] = e;
                         }
-                        long long nt = cn > m ? ce[cn - 1 - m] : s_bound[e];
+                        long long nt = next_key;
                         // an expert without capacity that dropped every key it had: nobody may stay at or
                         // under the highest of them
-                        if (s_capv[e] == 0 && !(nt < kKeyInf)) nt = ce[cn - m] + 1;
+                        if (cap_e == 0 && !(nt < kKeyInf)) nt = last_out + 1;
                         s_cn[e] = cn - m;
                         s_changed = 1;
-                        if (nt > s_theta[e] && nt < kKeyInf) s_theta[e] = nt;
+                        if (nt > theta_e && nt < kKeyInf) s_theta[e] = nt;
                     }
                 }
             }
