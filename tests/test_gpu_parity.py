@@ -215,3 +215,44 @@ def test_route_xw_end_to_end(ms, name, T):
     assert np.array_equal(out["disp_token"].cpu().numpy(), d["disp_token"])
     assert np.array_equal(out["disp_gate"].cpu().numpy(), d["disp_gate"].astype(np.float32))
     assert np.array_equal(out["token_pos"].cpu().numpy(), d["token_pos"])
+
+
+def test_route_xw_headline_size(ms):
+    """The whole path at the benchmark's configuration and launch shape (T=65536, d=2048, E=128, k=8, C=4096, bf16):
+    logits, scores, rewards and gates against the checker on sampled rows, the assignment by the certificate
+    of optimality on the path's own rewards, the dispatch lists against the checker in full."""
+    print("route_xw cfg5 full size", flush=True)
+    r = make_inputs("cfg5")
+    xd = dev(r.x_bits.view(np.int16)).view(torch.bfloat16)
+    Wd = dev(r.W_bits.view(np.int16)).view(torch.bfloat16)
+    out = ms.route_xw(xd, Wd, dev(r.bias), r.k, r.C, t=r.t)
+    del xd
+    rows = np.random.default_rng(5).choice(r.T, 1024, replace=False)
+    rows = np.concatenate([rows, [0, 1, 63, 64, r.T - 65, r.T - 1]])
+    logits = out["logits"].cpu().numpy()
+    refL = oracle.router_logits(r.x[rows], r.W, r.bias)
+    assert (np.abs(logits[rows] - refL) / np.maximum(np.abs(refL), 1.0)).max() <= 2e-2
+    # from here on the checker follows the path's own fp32 logits
+    A = oracle.soft_topk(logits[rows].astype(np.float64), r.k, r.t)
+    scores = out["scores"].cpu().numpy()
+    assert np.all(np.abs(scores[rows] - A) <= 1e-5 * np.abs(A) + 1e-12)
+    q = out["q"].cpu().numpy().astype(np.int64)
+    # the rewards are the rounding of the path's own fp32 scores (same precision on both sides)
+    assert np.array_equal(q, oracle.quantise(scores))
+    assign = out["assign"].cpu().numpy()
+    P = oracle.assignment_matrix(assign, r.E)
+    ok, why = oracle.check_feasible(P, r.k, r.C)
+    assert ok, why
+    assert int(P.sum()) == out["stats"]["flow_value"] == r.T * r.k
+    assert int(q[P.astype(bool)].sum()) == out["stats"]["total_score_q"]
+    assert oracle.verify_optimal(q, P, r.k, r.C)["optimal"]
+    g = out["gates"].cpu().numpy()
+    gref = oracle.gates(A, assign[rows])
+    assert np.all(np.abs(g[rows] - gref) <= 1e-5 * np.abs(gref) + 1e-12)
+    # all gates are the path's own scores at the assigned experts, bit for bit
+    assert np.array_equal(g, np.take_along_axis(scores, assign.astype(np.int64), axis=1))
+    d = oracle.dispatch(assign, g, r.E)
+    assert np.array_equal(out["expert_offsets"].cpu().numpy(), d["expert_offsets"])
+    assert np.array_equal(out["disp_token"].cpu().numpy(), d["disp_token"])
+    assert np.array_equal(out["disp_gate"].cpu().numpy(), d["disp_gate"].astype(np.float32))
+    assert np.array_equal(out["token_pos"].cpu().numpy(), d["token_pos"])
