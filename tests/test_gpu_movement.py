@@ -87,6 +87,54 @@ def test_identity_experts_return_gate_sum_times_x(ms):
     assert np.allclose(y, gsum[:, None] * x, rtol=2e-6, atol=1e-7)
 
 
+def test_movement_at_the_headline_size(ms):
+    """T=65536, d=2048, E=128, k=8, C=4096, bf16 (the shapes the benchmark times): the expert input buffers of
+    sampled experts and the combined rows of sampled tokens against the checker, which gets the sub-problem of
+    exactly those experts / tokens; plus two properties over all rows (every filled slot is a bit copy of its
+    token's row; identity experts return the gate sum times x)."""
+    print("movement headline size", flush=True)
+    T, d, E, k, C = 65536, 2048, 128, 8, 4096
+    out, rng = routed_case(ms, T, E, k, C, seed=11)
+    off = out["expert_offsets"].cpu().numpy()
+    tok = out["disp_token"].cpu().numpy()
+    xb = bf16_bits(rng.standard_normal((T, d), dtype=np.float32))
+    x_dev = dev(xb.view(np.int16)).view(torch.bfloat16)
+    buf = ms.dispatch_tokens(x_dev, out["expert_offsets"], out["disp_token"], E, C)
+    assert tuple(buf.shape) == (E, C, d)
+    # sampled experts: the checker on the sub-problem made of their segments of the dispatch list
+    es = np.array([0, 1, 37, 64, 126, 127])
+    seg = [tok[off[e]:off[e + 1]] for e in es]
+    off_sub = np.concatenate([[0], np.cumsum([len(s) for s in seg])]).astype(off.dtype)
+    ref = oracle.dispatch_tokens(bf16_from_bits(xb).astype(np.float64), off_sub, np.concatenate(seg), len(es), C)
+    got = buf[torch.from_numpy(es).cuda()].float().cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, ref)
+    # all experts: filled slots are bit copies, the rest is zero
+    bits = buf.view(torch.int16)
+    for e in range(E):
+        n = int(off[e + 1] - off[e])
+        rows = torch.from_numpy(tok[off[e]:off[e + 1]].astype(np.int64)).cuda()
+        assert torch.equal(bits[e, :n], x_dev.view(torch.int16)[rows])
+        assert not bits[e, n:].any()
+
+    # expert outputs: a different scale per expert (exact in bf16: powers of two), applied on the device
+    scale = torch.from_numpy((2.0 ** rng.integers(-2, 3, E)).astype(np.float32)).cuda()
+    eo = (buf.float() * scale[:, None, None]).to(torch.bfloat16)
+    y = ms.combine(eo, out["assign"], out["token_pos"], out["gates"])
+    rows = np.concatenate([np.random.default_rng(12).choice(T, 512, replace=False), [0, 1, T - 2, T - 1]])
+    ri = torch.from_numpy(rows).cuda()
+    a_s, p_s = out["assign"][ri].long(), out["token_pos"][ri].long()
+    eo_sub = eo[a_s, p_s].float().cpu().numpy().astype(np.float64)          # [n, k, d]: one "expert" per sampled token
+    g_s = out["gates"][ri].cpu().numpy().astype(np.float64)
+    n = len(rows)
+    y_ref = oracle.combine(eo_sub, np.repeat(np.arange(n)[:, None], k, axis=1), np.tile(np.arange(k), (n, 1)), g_s)
+    bound = 1e-6 * (np.abs(g_s)[:, :, None] * np.abs(eo_sub)).sum(axis=1) + 1e-30
+    assert (np.abs(y[ri].cpu().numpy() - y_ref) <= bound).all()
+    # all rows: with identity experts the combine returns (sum of the gates) * x
+    y1 = ms.combine(buf, out["assign"], out["token_pos"], out["gates"])
+    want = out["gates"].double().sum(dim=1, keepdim=True) * x_dev.double()
+    assert torch.allclose(y1.double(), want, rtol=2e-6, atol=1e-7)
+
+
 def test_movement_argument_errors(ms):
     x = torch.zeros((4, 8), dtype=torch.float32, device="cuda")
     off = torch.zeros(3, dtype=torch.int32, device="cuda")
