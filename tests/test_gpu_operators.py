@@ -28,7 +28,7 @@ def dev(a):
 
 @pytest.mark.parametrize("op", ["sigmoid", "softkmax", "itertopk", "gradtopk"])
 @pytest.mark.parametrize("T,E,k", [(300, 8, 2), (1000, 16, 4), (4099, 64, 2), (257, 7, 3), (2048, 128, 8),
-                                   (700, 300, 6), (130, 1024, 2), (65, 5, 1)])
+                                   (700, 300, 6), (130, 1024, 2), (65, 5, 1), (65536, 128, 8)])
 def test_scores_match_the_checker(ms, op, T, E, k):
     print(f"operator {op} T={T} E={E} k={k}", flush=True)
     rng = np.random.default_rng(T + E + k)

@@ -39,7 +39,7 @@ def cfg_case(name, T=None):
 
 @pytest.mark.parametrize("T,E,k,t", [(64, 8, 2, 0.0), (300, 16, 2, 1.0), (257, 64, 8, 1.0), (1000, 128, 8, 1.0),
                                       (130, 128, 8, 4.0), (77, 5, 3, 1.0), (50, 100, 7, 0.5), (33, 200, 16, 1.0),
-                                      (9, 1000, 64, 1.0), (40, 12, 12, 2.0), (1, 8, 1, 1.0)])
+                                      (9, 1000, 64, 1.0), (40, 12, 12, 2.0), (1, 8, 1, 1.0), (65536, 128, 8, 1.0)])
 def test_softtopk(ms, T, E, k, t):
     print(f"softtopk T={T} E={E} k={k} t={t}", flush=True)
     rng = np.random.default_rng(T * 1000 + E)
