@@ -128,6 +128,18 @@ int32_t maxscore_dispatch(const int32_t *assign, const float *gates, int32_t T, 
                           int32_t *expert_offsets, int32_t *disp_token, float *disp_gate,
                           int32_t *token_pos, void *workspace, size_t workspace_bytes, void *stream);
 
+/* a6 for callers that cannot allocate or hand over scratch memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same inputs, outputs and results as maxscore_dispatch, without the
+ * workspace arguments: the per-tile expert counts live in a 1 MiB device array that is part of the library (every
+ * GPU the library runs on holds its copy until the process ends).  Limit: ceil(T*k / 1024) * E + 1024 <= 262144
+ * (T*k <= 2^21 pairs at E = 128); larger problems return MAXSCORE_ERR_WORKSPACE.  The call allocates nothing, on
+ * the host or on the device, and only enqueues work.  The device of `stream` must be the current device.  All
+ * calls on one GPU share that array: two calls that overlap in time on the same GPU (different streams) race;
+ * calls on one stream, or on different GPUs, do not. */
+int32_t maxscore_dispatch_static(const int32_t *assign, const float *gates, int32_t T, int32_t E, int32_t k,
+                                 int32_t *expert_offsets, int32_t *disp_token, float *disp_gate,
+                                 int32_t *token_pos, void *stream);
+
 /* Other routing operators of Table 2 (Section 3.1) in place of SoftTopk: scores[T, E] and/or the integer
  * rewards q = round-half-even(score * 2^quant_shift) (either output may be NULL, not both).
  *   MAXSCORE_OP_SIGMOID   y = 1 / (1 + e^-x)

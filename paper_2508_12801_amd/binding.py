@@ -70,6 +70,9 @@ _SIGS = {
     "maxscore_dispatch": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "maxscore_dispatch_static": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                                  ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                                  ctypes.c_void_p, ctypes.c_void_p]),
     "maxscore_dispatch_tokens": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                                   ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                                   ctypes.c_void_p, ctypes.c_void_p]),
@@ -409,6 +412,24 @@ def dispatch(assign, gate, E: int, C: int = 1):
                                           _ptr(disp_gate), _ptr(token_pos), _ptr(ws), need, _stream())
     _check(rc, "maxscore_dispatch")
     return dict(expert_offsets=offsets, disp_token=disp_token, disp_gate=disp_gate, token_pos=token_pos)
+
+
+def dispatch_static(assign, gate, E: int, out: Optional[dict] = None):
+    """a6 through the entry point that uses the library's built-in scratch (no workspace, nothing allocated by the
+    call itself: pass `out` to reuse output tensors)."""
+    torch = _torch()
+    T, k = assign.shape
+    dev = assign.device
+    if out is None:
+        out = dict(expert_offsets=torch.empty(E + 1, dtype=torch.int32, device=dev),
+                   disp_token=torch.full((T * k,), -1, dtype=torch.int32, device=dev),
+                   disp_gate=torch.zeros(T * k, dtype=torch.float32, device=dev) if gate is not None else None,
+                   token_pos=torch.empty((T, k), dtype=torch.int32, device=dev))
+    rc = load_library().maxscore_dispatch_static(_ptr(assign), _ptr(gate), T, E, k, _ptr(out["expert_offsets"]),
+                                                 _ptr(out["disp_token"]), _ptr(out["disp_gate"]),
+                                                 _ptr(out["token_pos"]), _stream())
+    _check(rc, "maxscore_dispatch_static")
+    return out
 
 
 def _dtype_code(t):
