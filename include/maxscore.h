@@ -52,13 +52,15 @@ enum {
     MAXSCORE_ERR_HIP = -5,            /* a HIP call or kernel launch failed */
     MAXSCORE_ERR_OVERSUBSCRIBED = -6, /* T*k > E*min(C,T): not every token can get k experts */
     MAXSCORE_ERR_RANGE = -7,          /* reward range too wide for the solver's 64-bit bids */
-    MAXSCORE_ERR_NOT_CONVERGED = -8   /* max_rounds reached; outputs hold the last state */
+    MAXSCORE_ERR_NOT_CONVERGED = -8   /* max_rounds reached: the assignment returned is feasible (<= C tokens per
+                                         expert, distinct experts per token) but neither complete nor optimal:
+                                         slots the solver still had to move are empty (-1) */
 };
 
 enum { MAXSCORE_DTYPE_BF16 = 0, MAXSCORE_DTYPE_FP32 = 1 };
 
-/* Options.  Pass NULL for the defaults {t = 1, quant_shift = 20, max_rounds = 200000,
- * eps_div = 12}. */
+/* Options.  Pass NULL for the defaults {t = 1, quant_shift = 20, max_rounds = 200000, eps_div = 12, exact
+ * assignment, no flags, no starting prices}.  Zero in a field stands for its default. */
 typedef struct {
     float t;              /* SoftTopk temperature of Eq. 6 */
     int32_t quant_shift;  /* rewards are round(A * 2^quant_shift); 1..24 */
@@ -67,9 +69,18 @@ typedef struct {
     int32_t assignment;   /* maxscore_route_* only: MAXSCORE_ASSIGN_EXACT (0, the exact solver) or
                              MAXSCORE_ASSIGN_ITER (1, iterative rerouting: prices are not written,
                              stats carry total, flow and the number of rerouting rounds) */
+    uint32_t flags;       /* MAXSCORE_FLAG_* */
+    const int64_t *prices_in; /* exact solver: NULL, or DEVICE array of E starting prices in the units of the
+                             `prices` output (1/price_scale of a q unit; price_scale depends on E only), e.g. the
+                             prices a previous call returned for a batch routed by the same W_g.  Any values >= 0 are
+                             legal: the result is the same optimum, only the number of rounds changes. */
+    int64_t eps_start;    /* with prices_in: eps of the first phase in the same units (it is rounded down to a power
+                             of eps_div; 0 = 1/144 of the cold-start value).  A phase that runs longer than 48 rounds
+                             after a start from given prices goes back up one step of the eps ladder. */
 } maxscore_opts;
 #define MAXSCORE_ASSIGN_EXACT 0
 #define MAXSCORE_ASSIGN_ITER 1
+#define MAXSCORE_FLAG_NO_TAIL_PASS 1u   /* exact solver: dense rounds only (slower; same optimum) */
 
 /* Filled on the HOST when the call returns (may be NULL). */
 typedef struct {
@@ -281,6 +292,16 @@ int32_t maxscore_route_logits(const float *logits, int32_t T, int32_t E, int32_t
                               int32_t *assign, float *gates, int32_t *expert_offsets,
                               int32_t *disp_token, float *disp_gate, int32_t *token_pos,
                               int64_t *prices, maxscore_stats *stats, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+/* a3..a6 from given scores A[T,E] (fp32; e.g. affinities produced by another operator): rewards
+ * q_out[T,E] = round_half_even(A * 2^quant_shift) (required: the working storage of a3), then the assignment on
+ * them (Eq. 7-8), gates[i,s] = A[i, assign[i,s]] (Eq. 2) and the dispatch (Section 2.3).  Algorithm 1's
+ * Require/Ensure: affinities in, P out.  Synchronises `stream`. */
+int32_t maxscore_route_scores(const float *scores, int32_t T, int32_t E, int32_t k, int32_t C,
+                              const maxscore_opts *opts, int32_t *q_out, int32_t *assign, float *gates,
+                              int32_t *expert_offsets, int32_t *disp_token, float *disp_gate,
+                              int32_t *token_pos, int64_t *prices, maxscore_stats *stats, void *workspace,
                               size_t workspace_bytes, void *stream);
 
 /* a1..a6 from x and W_g.  logits_out[T,E] is required.  Synchronises `stream`. */

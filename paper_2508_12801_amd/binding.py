@@ -21,7 +21,8 @@ class MaxScoreError(RuntimeError):
 
 class _Opts(ctypes.Structure):
     _fields_ = [("t", ctypes.c_float), ("quant_shift", ctypes.c_int32), ("max_rounds", ctypes.c_int32),
-                ("eps_div", ctypes.c_int32), ("assignment", ctypes.c_int32)]
+                ("eps_div", ctypes.c_int32), ("assignment", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("prices_in", ctypes.c_void_p), ("eps_start", ctypes.c_int64)]
 
 
 class Stats(ctypes.Structure):
@@ -81,6 +82,9 @@ _SIGS = {
                                           ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]),
     "maxscore_route_logits": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                                ctypes.c_int32, ctypes.c_void_p] + [ctypes.c_void_p] * 11 +
+                              [ctypes.c_size_t, ctypes.c_void_p]),
+    "maxscore_route_scores": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                               ctypes.c_int32, ctypes.c_void_p] + [ctypes.c_void_p] * 10 +
                               [ctypes.c_size_t, ctypes.c_void_p]),
     "maxscore_route_xw": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
                                            ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
@@ -159,7 +163,8 @@ def _workspace(T, E, k, C, device, d=0):
     need = workspace_bytes(T, d, E, k, C)
     if need == 0:
         raise MaxScoreError(-2, "workspace_bytes")
-    key = (str(device),)
+    # one buffer per device and stream: calls on different streams may overlap and must not share scratch
+    key = (str(device), torch.cuda.current_stream(device).cuda_stream)
     buf = _WS.get(key)
     if buf is None or buf.numel() < need:
         buf = torch.empty(need, dtype=torch.uint8, device=device)
@@ -170,8 +175,14 @@ def _workspace(T, E, k, C, device, d=0):
 ASSIGNMENTS = {"exact": 0, "iter": 1}
 
 
-def _opts(t=1.0, quant_shift=20, max_rounds=200000, eps_div=12, assignment="exact"):
-    return _Opts(float(t), int(quant_shift), int(max_rounds), int(eps_div), ASSIGNMENTS[assignment])
+FLAG_NO_TAIL_PASS = 1
+
+
+def _opts(t=1.0, quant_shift=20, max_rounds=200000, eps_div=12, assignment="exact", tail_pass=True, prices_in=None,
+          eps_start=0):
+    return _Opts(float(t), int(quant_shift), int(max_rounds), int(eps_div), ASSIGNMENTS[assignment],
+                 0 if tail_pass else FLAG_NO_TAIL_PASS, prices_in.data_ptr() if prices_in is not None else None,
+                 int(eps_start))
 
 
 def set_kernel_timing(on: bool) -> None:
@@ -202,7 +213,7 @@ def router_logits(x, W, bias=None, use_workspace=True):
     ws, need = (None, 0)
     if use_workspace:
         need = 2 * d * E
-        key = ("wt", str(x.device))
+        key = ("wt", str(x.device), torch.cuda.current_stream(x.device).cuda_stream)
         ws = _WS.get(key)
         if ws is None or ws.numel() < need:
             ws = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
@@ -242,17 +253,21 @@ def scores_op(logits, k: int, op: str, quant_shift: int = 20):
     return scores, q
 
 
-def assign_i32(q, k: int, C: int, max_rounds: int = 200000, eps_div: int = 12, allow_not_converged=False):
-    """a4: exact assignment on int32 rewards.  Returns dict(assign, prices, price_scale, stats)."""
+def assign_i32(q, k: int, C: int, max_rounds: int = 200000, eps_div: int = 12, allow_not_converged=False,
+               tail_pass: bool = True, prices_in=None, eps_start: int = 0):
+    """a4: exact assignment on int32 rewards.  Returns dict(assign, prices, price_scale, stats).  prices_in: int64
+    device tensor of E starting prices (the `prices` of an earlier call), eps_start: first-phase eps with them."""
     torch = _torch()
     T, E = q.shape
     assert q.dtype == torch.int32 and q.is_contiguous()
+    if prices_in is not None:
+        assert prices_in.dtype == torch.int64 and prices_in.numel() == E and prices_in.device == q.device
     assign = torch.empty((T, k), dtype=torch.int32, device=q.device)
     prices = torch.empty(E, dtype=torch.int64, device=q.device)
     scale = torch.empty(1, dtype=torch.int64, device=q.device)
     stats = Stats()
     ws, need = _workspace(T, E, k, C, q.device)
-    o = _opts(max_rounds=max_rounds, eps_div=eps_div)
+    o = _opts(max_rounds=max_rounds, eps_div=eps_div, tail_pass=tail_pass, prices_in=prices_in, eps_start=eps_start)
     rc = load_library().maxscore_assign_i32(_ptr(q), T, E, k, C, ctypes.byref(o), _ptr(assign), _ptr(prices),
                                             _ptr(scale), ctypes.byref(stats), _ptr(ws), need, _stream())
     _check(rc, "maxscore_assign_i32", allow=(ERR_NOT_CONVERGED,) if allow_not_converged else ())
@@ -482,7 +497,8 @@ def _route_outputs(T, E, k, dev):
 
 
 def route_logits(logits, k: int, C: int, t: float = 1.0, quant_shift: int = 20, max_rounds: int = 200000,
-                 eps_div: int = 12, out: Optional[dict] = None, assignment: str = "exact"):
+                 eps_div: int = 12, out: Optional[dict] = None, assignment: str = "exact",
+                 allow_not_converged: bool = False):
     """a2..a6 from logits; assignment = "exact" (the solver) or "iter" (iterative rerouting)."""
     torch = _torch()
     T, E = logits.shape
@@ -495,9 +511,32 @@ def route_logits(logits, k: int, C: int, t: float = 1.0, quant_shift: int = 20, 
         _ptr(logits), T, E, k, C, ctypes.byref(opts), _ptr(o["scores"]), _ptr(o["q"]), _ptr(o["assign"]),
         _ptr(o["gates"]), _ptr(o["expert_offsets"]), _ptr(o["disp_token"]), _ptr(o["disp_gate"]),
         _ptr(o["token_pos"]), _ptr(o["prices"]), ctypes.byref(stats), _ptr(ws), need, _stream())
-    _check(rc, "maxscore_route_logits")
+    _check(rc, "maxscore_route_logits", allow=(ERR_NOT_CONVERGED,) if allow_not_converged else ())
     o = dict(o)
     o["stats"] = stats.as_dict()
+    o["rc"] = rc
+    return o
+
+
+def route_scores(scores, k: int, C: int, quant_shift: int = 20, max_rounds: int = 200000, eps_div: int = 12,
+                 out: Optional[dict] = None, assignment: str = "exact", allow_not_converged: bool = False):
+    """a3..a6 from given fp32 scores [T, E]."""
+    torch = _torch()
+    T, E = scores.shape
+    assert scores.dtype == torch.float32 and scores.is_contiguous()
+    o = out if out is not None else _route_outputs(T, E, k, scores.device)
+    ws, need = _workspace(T, E, k, C, scores.device)
+    stats = Stats()
+    opts = _opts(1.0, quant_shift, max_rounds, eps_div, assignment)
+    rc = load_library().maxscore_route_scores(
+        _ptr(scores), T, E, k, C, ctypes.byref(opts), _ptr(o["q"]), _ptr(o["assign"]), _ptr(o["gates"]),
+        _ptr(o["expert_offsets"]), _ptr(o["disp_token"]), _ptr(o["disp_gate"]), _ptr(o["token_pos"]),
+        _ptr(o["prices"]), ctypes.byref(stats), _ptr(ws), need, _stream())
+    _check(rc, "maxscore_route_scores", allow=(ERR_NOT_CONVERGED,) if allow_not_converged else ())
+    o = dict(o)
+    o["scores"] = scores
+    o["stats"] = stats.as_dict()
+    o["rc"] = rc
     return o
 
 

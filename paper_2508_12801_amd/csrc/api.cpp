@@ -36,12 +36,13 @@ static bool shape_ok(int T, int E, int k, int C)
 
 static maxscore_opts resolve(const maxscore_opts *o)
 {
-    maxscore_opts r = {1.0f, 20, 200000, 12, MAXSCORE_ASSIGN_EXACT};
+    maxscore_opts r = {1.0f, 20, 200000, 12, MAXSCORE_ASSIGN_EXACT, 0u, nullptr, 0};
     if (o) {
         r = *o;
         if (r.quant_shift == 0) r.quant_shift = 20;
         if (r.max_rounds <= 0) r.max_rounds = 200000;
         if (r.eps_div < 2) r.eps_div = 12;
+        if (r.eps_start < 0) r.eps_start = 0;
     }
     return r;
 }
@@ -261,6 +262,69 @@ int32_t maxscore_combine(const void *expert_out, int32_t in_dtype, const int32_t
     return combine_run(expert_out, in_dtype, assign, token_pos, gates, T, d, E, k, C, y, (hipStream_t)stream);
 }
 
+// a4..a6 on scores and rewards that are already in place (the common tail of the maxscore_route_* calls).
+static int32_t route_from_rewards(const float *scores, const int32_t *q, int T, int E, int k, int C,
+                                  const maxscore_opts &o, int32_t *assign, float *gates, int32_t *expert_offsets,
+                                  int32_t *disp_token, float *disp_gate, int32_t *token_pos, int64_t *prices,
+                                  maxscore_stats *stats, char *ws, hipStream_t s)
+{
+    const int Ce = C < T ? C : T;
+    int32_t src;
+    if (o.assignment == MAXSCORE_ASSIGN_ITER) {
+        int64_t total = 0;
+        int32_t flow = 0, rounds = 0;
+        src = iter_run(q, T, E, k, C, o.max_rounds, assign, &total, &flow, &rounds, ws, s);
+        if (stats) {
+            stats->total_score_q = total;
+            stats->flow_value = flow;
+            stats->rounds = rounds;
+            stats->status = src;
+        }
+    } else {
+        src = solver_run(q, T, E, k, Ce, o, assign, prices, nullptr, stats, ws, s);
+    }
+    if (src != MAXSCORE_OK && src != MAXSCORE_ERR_NOT_CONVERGED) return src;
+    int32_t rc = gates_run(scores, assign, T, E, k, gates, s);
+    if (rc) return rc;
+    rc = dispatch_run(assign, gates, T, E, k, expert_offsets, disp_token, disp_gate, token_pos, ws, s);
+    if (rc) return rc;
+    if (hipStreamSynchronize(s) != hipSuccess) return MAXSCORE_ERR_HIP;
+    return src;
+}
+
+// Argument checks shared by the maxscore_route_* calls (everything after the scores exist).
+static int32_t route_check(int T, int E, int k, int C, const maxscore_opts &o, const void *workspace,
+                           size_t workspace_bytes)
+{
+    if (!shape_ok(T, E, k, C)) return MAXSCORE_ERR_SHAPE;
+    if (o.assignment != MAXSCORE_ASSIGN_EXACT && o.assignment != MAXSCORE_ASSIGN_ITER) return MAXSCORE_ERR_SHAPE;
+    if (o.quant_shift < 1 || o.quant_shift > 24 || !(o.t >= 0.f) || o.t > 64.f) return MAXSCORE_ERR_SHAPE;
+    const int Ce = C < T ? C : T;
+    // the exact solver needs room for every token's k experts; iterative rerouting simply leaves holes
+    if (o.assignment == MAXSCORE_ASSIGN_EXACT && (long long)T * k > (long long)E * Ce)
+        return MAXSCORE_ERR_OVERSUBSCRIBED;
+    return check_ws(workspace, workspace_bytes, T, E, k);
+}
+
+int32_t maxscore_route_scores(const float *scores, int32_t T, int32_t E, int32_t k, int32_t C,
+                              const maxscore_opts *opts, int32_t *q_out, int32_t *assign, float *gates,
+                              int32_t *expert_offsets, int32_t *disp_token, float *disp_gate, int32_t *token_pos,
+                              int64_t *prices, maxscore_stats *stats, void *workspace, size_t workspace_bytes,
+                              void *stream)
+{
+    if (!scores || !q_out || !assign || !gates || !expert_offsets || !disp_token || !disp_gate || !token_pos)
+        return MAXSCORE_ERR_NULL;
+    maxscore_opts o = resolve(opts);
+    int32_t rc = route_check(T, E, k, C, o, workspace, workspace_bytes);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    if (stats) std::memset(stats, 0, sizeof(*stats));
+    rc = quantise_run(scores, T, E, o.quant_shift, q_out, s);
+    if (rc) return rc;
+    return route_from_rewards(scores, q_out, T, E, k, C, o, assign, gates, expert_offsets, disp_token, disp_gate,
+                              token_pos, prices, stats, (char *)workspace, s);
+}
+
 int32_t maxscore_route_logits(const float *logits, int32_t T, int32_t E, int32_t k, int32_t C,
                               const maxscore_opts *opts, float *scores_out, int32_t *q_out, int32_t *assign,
                               float *gates, int32_t *expert_offsets, int32_t *disp_token, float *disp_gate,
@@ -270,41 +334,15 @@ int32_t maxscore_route_logits(const float *logits, int32_t T, int32_t E, int32_t
     if (!logits || !scores_out || !q_out || !assign || !gates || !expert_offsets || !disp_token || !disp_gate ||
         !token_pos)
         return MAXSCORE_ERR_NULL;
-    if (!shape_ok(T, E, k, C)) return MAXSCORE_ERR_SHAPE;
-    const int Ce = C < T ? C : T;
-    if ((long long)T * k > (long long)E * Ce) return MAXSCORE_ERR_OVERSUBSCRIBED;
-    int32_t rc = check_ws(workspace, workspace_bytes, T, E, k);
-    if (rc) return rc;
     maxscore_opts o = resolve(opts);
-    if (o.quant_shift < 1 || o.quant_shift > 24 || !(o.t >= 0.f) || o.t > 64.f) return MAXSCORE_ERR_SHAPE;
+    int32_t rc = route_check(T, E, k, C, o, workspace, workspace_bytes);
+    if (rc) return rc;
     hipStream_t s = (hipStream_t)stream;
     if (stats) std::memset(stats, 0, sizeof(*stats));
     rc = softtopk_run(logits, T, E, k, o.t, o.quant_shift, scores_out, q_out, s);
     if (rc) return rc;
-    int32_t src;
-    if (o.assignment == MAXSCORE_ASSIGN_ITER) {
-        int64_t total = 0;
-        int32_t flow = 0, rounds = 0;
-        src = iter_run(q_out, T, E, k, C, o.max_rounds, assign, &total, &flow, &rounds, (char *)workspace, s);
-        if (stats) {
-            stats->total_score_q = total;
-            stats->flow_value = flow;
-            stats->rounds = rounds;
-            stats->status = src;
-        }
-    } else if (o.assignment == MAXSCORE_ASSIGN_EXACT) {
-        src = solver_run(q_out, T, E, k, Ce, o, assign, prices, nullptr, stats, (char *)workspace, s);
-    } else {
-        return MAXSCORE_ERR_SHAPE;
-    }
-    if (src != MAXSCORE_OK && src != MAXSCORE_ERR_NOT_CONVERGED) return src;
-    rc = gates_run(scores_out, assign, T, E, k, gates, s);
-    if (rc) return rc;
-    rc = dispatch_run(assign, gates, T, E, k, expert_offsets, disp_token, disp_gate, token_pos, (char *)workspace,
-                      s);
-    if (rc) return rc;
-    if (hipStreamSynchronize(s) != hipSuccess) return MAXSCORE_ERR_HIP;
-    return src;
+    return route_from_rewards(scores_out, q_out, T, E, k, C, o, assign, gates, expert_offsets, disp_token,
+                              disp_gate, token_pos, prices, stats, (char *)workspace, s);
 }
 
 int32_t maxscore_route_xw(const void *x, const void *W, const float *bias, int32_t in_dtype, int32_t T, int32_t d,
@@ -320,9 +358,7 @@ int32_t maxscore_route_xw(const void *x, const void *W, const float *bias, int32
     if (!shape_ok(T, E, k, C)) return MAXSCORE_ERR_SHAPE;
     if (!scores_out || !q_out || !assign || !gates || !expert_offsets || !disp_token || !disp_gate || !token_pos)
         return MAXSCORE_ERR_NULL;
-    const int Ce = C < T ? C : T;
-    if ((long long)T * k > (long long)E * Ce) return MAXSCORE_ERR_OVERSUBSCRIBED;
-    int32_t rc = check_ws(workspace, workspace_bytes, T, E, k);
+    int32_t rc = route_check(T, E, k, C, resolve(opts), workspace, workspace_bytes);
     if (rc) return rc;
     void *wt = nullptr;
     {

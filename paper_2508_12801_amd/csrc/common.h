@@ -44,6 +44,9 @@ struct SolverState {
     int tail_block;        // the tail pass could not proceed: the next select pass must do a normal select
     int tail_gos;          // rounds so far in which the select pass handed over to the tail pass
     int tail_runs, tail_iters;   // diagnostics
+    int warm;              // 1: started from given prices (a long phase may go back up the eps ladder)
+    int phase_start;       // round at which the current phase began
+    long long eps0;        // first-phase epsilon of a cold start (upper end of the eps ladder)
     int phase_round[28];   // round index at which each phase ended (diagnostic)
 };
 
@@ -74,6 +77,7 @@ int32_t kvec_check(const int32_t *kvec, int T, int E, int k, char *ws, long long
 // --- softtopk.hip
 int32_t softtopk_run(const float *logits, int T, int E, int k, float t, int shift, float *scores, int32_t *q,
                      hipStream_t s);
+int32_t quantise_run(const float *scores, int T, int E, int shift, int32_t *q, hipStream_t s);
 int32_t gates_run(const float *scores, const int32_t *assign, int T, int E, int k, float *gates, hipStream_t s);
 // --- dispatch.hip
 int32_t dispatch_run(const int32_t *assign, const float *gates, int T, int E, int k, int32_t *offsets,

@@ -88,6 +88,8 @@ __global__ __launch_bounds__(256) void k_combine(const u32x4 *__restrict__ buf, 
                 const int e = assign[(size_t)i * k + s];
                 if (e < 0) continue;                           // empty slot (wavefront-uniform)
                 const int pos = token_pos[(size_t)i * k + s];
+                // a place outside the expert's buffer (an assignment made with another capacity) is never read
+                if (e >= E || pos < 0 || pos >= C) continue;
                 const float g = gates[(size_t)i * k + s];
                 const u32x4 *src = buf + ((size_t)e * C + pos) * vec_per_row;
                 u32x4 vals[kMaxChunks];
@@ -138,7 +140,9 @@ __global__ __launch_bounds__(256) void k_combine_elem(const void *__restrict__ b
         for (int s = 0; s < k; ++s) {
             const int e = assign[i * k + s];
             if (e < 0) continue;
-            const size_t at = ((size_t)e * C + token_pos[i * k + s]) * d + c;
+            const int pos = token_pos[i * k + s];
+            if (e >= E || pos < 0 || pos >= C) continue;      // outside the expert's buffer: never read
+            const size_t at = ((size_t)e * C + pos) * d + c;
             const float v = BF16 ? bf16_to_f32(((const unsigned short *)buf_)[at]) : ((const float *)buf_)[at];
             acc = fmaf(gates[i * k + s], v, acc);
         }

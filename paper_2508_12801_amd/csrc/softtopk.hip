@@ -127,6 +127,24 @@ __global__ __launch_bounds__(256) void k_softtopk(const float *__restrict__ logi
     }
 }
 
+// a3 alone: q = round-half-even(score * 2^shift) for scores that were computed elsewhere
+__global__ __launch_bounds__(256) void k_quantise(const float *__restrict__ scores, size_t n, float qscale,
+                                                  int32_t *__restrict__ q)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (((((uintptr_t)scores) | ((uintptr_t)q)) & 15) == 0) {
+        const size_t n4 = n / 4;
+        for (; i < n4; i += stride) {
+            const float4 v = ((const float4 *)scores)[i];
+            ((int4 *)q)[i] = make_int4(__float2int_rn(v.x * qscale), __float2int_rn(v.y * qscale),
+                                       __float2int_rn(v.z * qscale), __float2int_rn(v.w * qscale));
+        }
+        i = n4 * 4 + (size_t)blockIdx.x * blockDim.x + threadIdx.x;      // the last n % 4 values
+    }
+    for (; i < n; i += stride) q[i] = __float2int_rn(scores[i] * qscale);
+}
+
 __global__ __launch_bounds__(256) void k_gates(const float *__restrict__ scores, const int32_t *__restrict__ assign,
                                                size_t n, int E, int k, float *__restrict__ gates)
 {
@@ -173,6 +191,17 @@ int32_t softtopk_run(const float *logits, int T, int E, int k, float t, int shif
     else MS_ST(64);
 #undef MS_ST
 #undef MS_ST2
+    MS_HIP(hipGetLastError());
+    return MAXSCORE_OK;
+}
+
+int32_t quantise_run(const float *scores, int T, int E, int shift, int32_t *q, hipStream_t s)
+{
+    const size_t n = (size_t)T * E;
+    int grid = (int)((n / 4 + 255) / 256);
+    if (grid > 4096) grid = 4096;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(k_quantise, dim3(grid), dim3(256), 0, s, scores, n, (float)(1 << shift), q);
     MS_HIP(hipGetLastError());
     return MAXSCORE_OK;
 }

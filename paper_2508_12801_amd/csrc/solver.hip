@@ -33,6 +33,7 @@
 //     counts, so no block waits for another (only the tail workgroup waits, for the candidate
 //     lists, in the few rounds that hand over to it).  The host enqueues rounds ahead of the
 //     device and polls `done` from pinned memory.
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <vector>
@@ -177,6 +178,7 @@ __global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm,
         st->blocks_done = 0; st->flow = 0; st->slack = slack;
         st->wide = 0; st->tail_go = 0; st->after_tail = 0; st->tail_block = 0; st->tail_runs = 0; st->tail_gos = 0;
         st->tail_iters = 0;
+        st->warm = 0; st->phase_start = 0; st->eps0 = 1;
         for (int a = 0; a < 28; ++a) st->phase_round[a] = 0;
     }
 }
@@ -226,8 +228,15 @@ __global__ __launch_bounds__(256) void k_minmax(const int32_t *__restrict__ q, s
     }
 }
 
+// prices_in (optional): E starting prices in the units of the price output; they become the thresholds of round 0
+// and the first phase starts at eps_start (rounded down to a power of the ladder's ratio) instead of at the top.
+constexpr long long kMaxPriceIn = (long long)1 << 38;
+constexpr int kWarmPhaseCap = 48;          // rounds after which a phase started from given prices goes back up the ladder
+
 __global__ __launch_bounds__(kMinmaxBlocks) void k_setup(SolverState *st, const int *__restrict__ part, int nparts,
-                                                        int T, int E, int force_wide, int eps0_shift)
+                                                        int T, int E, int force_wide, int eps0_shift,
+                                                        long long *__restrict__ theta,
+                                                        const int64_t *__restrict__ prices_in, long long eps_start)
 {
     __shared__ int s_lo[kMinmaxBlocks / 64], s_hi[kMinmaxBlocks / 64];
     int lo = 0x7fffffff, hi = -0x7fffffff - 1;
@@ -245,6 +254,15 @@ __global__ __launch_bounds__(kMinmaxBlocks) void k_setup(SolverState *st, const 
         s_hi[threadIdx.x >> 6] = hi;
     }
     __syncthreads();
+    int tb = 1;
+    while ((1 << tb) < T) ++tb;
+    if (prices_in) {
+        for (int e = threadIdx.x; e < E; e += kMinmaxBlocks) {
+            long long p = prices_in[e];
+            p = p < 0 ? 0 : (p > kMaxPriceIn ? kMaxPriceIn : p);
+            theta[e] = p << tb;
+        }
+    }
     if (threadIdx.x != 0) return;
     for (int w = 1; w < kMinmaxBlocks / 64; ++w) {
         lo = s_lo[w] < lo ? s_lo[w] : lo;
@@ -254,8 +272,6 @@ __global__ __launch_bounds__(kMinmaxBlocks) void k_setup(SolverState *st, const 
     st->qmax = hi;
     int sb = 0;
     while ((1 << sb) < E + 1) ++sb;
-    int tb = 1;
-    while ((1 << tb) < T) ++tb;
     st->sbits = sb;
     st->tbits = tb;
     long long range = ((long long)hi - (long long)lo) << sb;
@@ -268,6 +284,13 @@ __global__ __launch_bounds__(kMinmaxBlocks) void k_setup(SolverState *st, const 
     st->wide = (range >= ((long long)1 << 28) || force_wide) ? 1 : 0;
     long long top = range >> eps0_shift, eps = 1;
     while (eps * st->eps_div <= top) eps *= st->eps_div;
+    st->eps0 = eps;
+    if (prices_in) {
+        // start lower on the same ladder (the later phases are then the ones of a cold start)
+        const long long want = eps_start > 0 ? eps_start : eps / ((long long)st->eps_div * st->eps_div);
+        while (eps > 1 && eps > want) eps /= st->eps_div;
+        st->warm = 1;
+    }
     st->eps = eps;
 }
 
@@ -1162,6 +1185,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
             st->eps = ne > 1 ? ne : 1;
             st->phases += 1;
             st->moves = T;
+            st->phase_start = st->round;
         }
         st->after_tail = (s_changed || s_moves) ? 1 : 0;
         st->tail_block = stopped;
@@ -1308,8 +1332,10 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     const long long eps_ref = cur_eps_prev > 0 ? cur_eps_prev : cur_eps;
     // few slots moved: leave the thresholds alone, publish each expert's lowest keys and let the
     // single-workgroup tail pass run the next rounds on them
+    const bool stopping = cur_round + 1 >= cur_max_rounds || *errflag != 0;
+    // (not in the last round the cap allows: that round must leave thresholds that cut every expert to capacity)
     const bool tail_go = tail_on && !quiet && !cur_tail_block && cur_round > 0 && moves <= tail_moves &&
-                         (moves > 0 || (flags & 2));
+                         (moves > 0 || (flags & 2)) && !stopping;
     int action = 0;
     long long lower = 0;
     if (redo) {
@@ -1319,12 +1345,13 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
         action = 1;
         lower = cur_beta * cur_eps;
     }
-    const bool stopping = cur_round + 1 >= cur_max_rounds || *errflag != 0;
     if (blockIdx.x == 0 && tid == 0) {
         SolverState ns = *st;
         const int round = cur_round + 1;
+        bool back_up = false;
         if (quiet) {
             if (ns.phases <= 28) ns.phase_round[ns.phases - 1] = round;
+            ns.phase_start = round;
             if (redo) {
                 ns.beta = cur_beta * 2;
                 ns.phases += 1;
@@ -1339,13 +1366,21 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
         } else if (round >= ns.max_rounds) {
             ns.status = MAXSCORE_ERR_NOT_CONVERGED;
             ns.done = 1;
+        } else if (ns.warm && round - ns.phase_start >= kWarmPhaseCap && cur_eps * ns.eps_div <= ns.eps0) {
+            // The given prices were further off than the starting eps assumed: one step back up the ladder.  Every
+            // hold that is valid at an eps is valid at a larger one, so this is legal at any time; the phases below
+            // it run again afterwards.
+            ns.eps = cur_eps * ns.eps_div;
+            ns.phases += 1;
+            ns.phase_start = round;
+            back_up = true;
         }
         if (*errflag) {
             ns.status = MAXSCORE_ERR_HIP;
             ns.done = 1;
         }
         ns.round = round;
-        ns.moves = quiet ? T : moves;        // a new phase starts with many moves: no quick checks in its first round
+        ns.moves = (quiet || back_up) ? T : moves;   // a new phase starts with many moves: no quick checks in its first round
         ns.tail_go = tail_go ? 1 : 0;
         ns.tail_gos = cur_tail_gos + (tail_go ? 1 : 0);
         ns.after_tail = 0;
@@ -1611,10 +1646,38 @@ __global__ __launch_bounds__(256) void k_finalize(const int32_t *__restrict__ q,
     }
 }
 
+// At the round cap the last select pass has raised the thresholds so that every expert keeps its capacity, but the
+// bid pass that would drop the holds under them never runs.  This pass drops them: every key of the last bid pass
+// that lies under its expert's final threshold gives up its slot (-1), which leaves a feasible, incomplete
+// assignment.  One workgroup per key block; exits at once unless the solve ended at the cap.
+__global__ __launch_bounds__(256) void k_trim(const SolverState *__restrict__ st, const long long *__restrict__ theta2,
+                                              const long long *__restrict__ klist, const int *__restrict__ wcnt,
+                                              int32_t *__restrict__ assign, int E, int k, int rows_per_wg)
+{
+    if (st->status != MAXSCORE_ERR_NOT_CONVERGED) return;
+    const long long *theta = theta2 + (st->round & 1) * kMaxE;      // what the last select pass wrote
+    const long long tmask = ((long long)1 << st->tbits) - 1;
+    const long long *blk = klist + (size_t)blockIdx.x * rows_per_wg * k;
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+        const int mt = wcnt[(size_t)blockIdx.x * E + e];
+        const int off = mt >> 16, cnt = mt & 0xffff;
+        const long long th = theta[e];
+        for (int i = 0; i < cnt; ++i) {
+            const long long key = blk[off + i];
+            if (key < th) {
+                const size_t tok = (size_t)(key & tmask);
+                for (int sl = 0; sl < k; ++sl)
+                    if (assign[tok * k + sl] == e) assign[tok * k + sl] = -1;
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(kFinalBlocks) void k_finalize2(const long long *__restrict__ part,
-                                                           const long long *__restrict__ theta, SolverState *st,
+                                                           const long long *__restrict__ theta2, SolverState *st,
                                                            int64_t *prices, int64_t *price_scale, int E)
 {
+    const long long *theta = theta2 + (st->round & 1) * kMaxE;      // what the last select pass wrote
     __shared__ long long s_sum[kFinalBlocks / 64], s_cnt[kFinalBlocks / 64];
     long long sum = part[2 * threadIdx.x], cnt = part[2 * threadIdx.x + 1];
     for (int off = 32; off > 0; off >>= 1) {
@@ -1726,6 +1789,51 @@ int32_t kvec_check(const int32_t *kvec, int T, int E, int k, char *ws, long long
     return MAXSCORE_OK;
 }
 
+// Per-host-thread objects of the solver that outlive a call: the pinned flag the select pass writes `done` into,
+// and the events (created once, reused by every solve of the thread, never destroyed: a few handles per thread).
+struct SolverHost {
+    int *flag = nullptr;        // pinned and mapped
+    int *flag_dev = nullptr;    // the same word as the device sees it
+    hipEvent_t ev0 = nullptr, ev1 = nullptr, evb[2] = {nullptr, nullptr};
+    std::vector<hipEvent_t> tev;      // pool of per-launch timing events (kernel timing only)
+    int device = -1;
+};
+
+static int32_t solver_host(SolverHost **out)
+{
+    static thread_local SolverHost tl[8];      // one per device the thread has solved on (up to 8 devices)
+    int dev = 0;
+    MS_HIP(hipGetDevice(&dev));
+    SolverHost *h = nullptr;
+    for (auto &c : tl)
+        if (c.device == dev || c.device < 0) {
+            h = &c;
+            break;
+        }
+    if (!h) return MAXSCORE_ERR_HIP;
+    if (h->device < 0) {
+        MS_HIP(hipHostMalloc((void **)&h->flag, 64, hipHostMallocMapped));
+        MS_HIP(hipHostGetDevicePointer((void **)&h->flag_dev, h->flag, 0));
+        MS_HIP(hipEventCreate(&h->ev0));
+        MS_HIP(hipEventCreate(&h->ev1));
+        MS_HIP(hipEventCreateWithFlags(&h->evb[0], hipEventDisableTiming));
+        MS_HIP(hipEventCreateWithFlags(&h->evb[1], hipEventDisableTiming));
+        h->device = dev;
+    }
+    *out = h;
+    return MAXSCORE_OK;
+}
+
+// On an error after work has been queued the stream is drained before returning, so that nothing of this solve
+// is still running on the caller's buffers.
+#define MS_HIP_SYNC(call)                        \
+    do {                                         \
+        if ((call) != hipSuccess) {              \
+            (void)hipStreamSynchronize(s);       \
+            return MAXSCORE_ERR_HIP;             \
+        }                                        \
+    } while (0)
+
 int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore_opts &o, int32_t *assign,
                    int64_t *prices, int64_t *price_scale, maxscore_stats *stats, char *ws, hipStream_t s,
                    const int32_t *cap, long long room, const int32_t *kvec, long long demand)
@@ -1739,12 +1847,9 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     int *wcnt = (int *)(ws + L.wcnt_off);
     int *wmoves = (int *)(ws + L.wmoves_off);
     long long *cand = (long long *)(ws + L.cand_off);
-    int tail_on = E <= kTailMaxE ? 1 : 0, tail_iters = 64, tail_moves = kTailMoves;
-    if (const char *ev = getenv("MAXSCORE_TAIL_MOVES")) tail_moves = atoi(ev);   // tuning override (debug)
-    if (const char *ev = getenv("MAXSCORE_TAIL")) {   // tuning override (debug): 0 disables the tail pass
-        tail_iters = atoi(ev);
-        if (tail_iters <= 0) tail_on = 0;
-    }
+    int tail_on = (E <= kTailMaxE && !(o.flags & MAXSCORE_FLAG_NO_TAIL_PASS)) ? 1 : 0;
+    int tail_iters = 64, tail_moves = kTailMoves;
+    int eps0_shift = kEps0Shift;
 
     // lanes per token row (G >= k) and consecutive experts per lane
     int G = 8, EPL = 1;
@@ -1758,22 +1863,33 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     while (rows * 2 * k <= 1024 && (T + 2 * rows - 1) / (2 * rows) >= 512) rows *= 2;
     if (rows * k > 1024) rows = ngrp;
     if (rows * k > 1024) return MAXSCORE_ERR_SHAPE;
-    if (const char *ev = getenv("MAXSCORE_ROWS")) {   // tuning override (debug)
+#ifdef MAXSCORE_DEBUG_ENV
+    // tuning overrides of a development build (not compiled into the library otherwise); values are clamped
+    if (const char *ev = getenv("MAXSCORE_TAIL_MOVES")) tail_moves = std::max(0, std::min(atoi(ev), kTailVict));
+    if (const char *ev = getenv("MAXSCORE_TAIL")) {
+        tail_iters = std::max(0, std::min(atoi(ev), 4096));
+        if (tail_iters <= 0) tail_on = 0;
+    }
+    if (const char *ev = getenv("MAXSCORE_ROWS")) {
         int r = atoi(ev);
         if (r >= ngrp && r % ngrp == 0 && r * k <= 1024) rows = r;
     }
+    if (const char *ev = getenv("MAXSCORE_EPS0_SHIFT")) eps0_shift = std::max(0, std::min(atoi(ev), 30));
+#endif
     const bool vec = (E == G * EPL) && (((uintptr_t)q) % 16 == 0);
     const int n_wg = (T + rows - 1) / rows;
     if (n_wg > L.max_wg) return MAXSCORE_ERR_WORKSPACE;
 
+    SolverHost *hs = nullptr;
+    {
+        int32_t rc = solver_host(&hs);
+        if (rc) return rc;
+    }
     // room = total capacity (sum of the vector, or E*Ce)
     // demand = number of pairs to place (sum of the per-token k, or T*k)
     const long long want = kvec ? demand : (long long)T * k;
     const int slack = ((cap ? room : (long long)E * Ce) - want) > 0 ? 1 : 0;
-    hipEvent_t ev0 = nullptr, ev1 = nullptr;
-    MS_HIP(hipEventCreate(&ev0));
-    MS_HIP(hipEventCreate(&ev1));
-    MS_HIP(hipEventRecord(ev0, s));
+    MS_HIP(hipEventRecord(hs->ev0, s));
     {
         size_t n = (size_t)T * k;
         int grid = (int)((n + 255) / 256);
@@ -1787,39 +1903,29 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         if (g2 < 1) g2 = 1;
         int *part = (int *)cand;                 // the candidate lists are not in use yet
         hipLaunchKernelGGL(k_minmax, dim3(g2), dim3(256), 0, s, q, nq, part);
-        int eps0_shift = kEps0Shift;
-        if (const char *ev = getenv("MAXSCORE_EPS0_SHIFT")) eps0_shift = atoi(ev);   // tuning override (debug)
         hipLaunchKernelGGL(k_setup, dim3(1), dim3(kMinmaxBlocks), 0, s, st, part, g2, T, E, k == E ? 1 : 0,
-                           eps0_shift);
+                           eps0_shift, theta, o.prices_in, (long long)o.eps_start);
     }
 
     // Rounds are enqueued in batches; the select pass writes `done` straight into pinned host memory.
     // The next batch is always enqueued BEFORE the host waits for the flag of the current one, so the
     // device never idles during the host round trip; once the solve is over the rounds still in the
     // queue exit at once.
-    static thread_local int *tl_flag = nullptr;      // pinned and mapped; lives until the process ends
-    static thread_local int *tl_flag_dev = nullptr;  // the same word as the device sees it
-    if (!tl_flag) {
-        MS_HIP(hipHostMalloc((void **)&tl_flag, 64, hipHostMallocMapped));
-        MS_HIP(hipHostGetDevicePointer((void **)&tl_flag_dev, tl_flag, 0));
-    }
-    *(volatile int *)tl_flag = 0;
-    std::vector<hipEvent_t> tev;
+    *(volatile int *)hs->flag = 0;
+    std::vector<hipEvent_t> &tev = hs->tev;
+    size_t tev_used = 0;
     const int batch = 4;
     int launched = 0;
-    hipEvent_t evb[2] = {nullptr, nullptr};
-    MS_HIP(hipEventCreateWithFlags(&evb[0], hipEventDisableTiming));
-    MS_HIP(hipEventCreateWithFlags(&evb[1], hipEventDisableTiming));
     auto enqueue_batch = [&](int slot) -> int32_t {
         for (int b = 0; b < batch; ++b) {
             const int par = launched & 1;
             if (g_kernel_timing) {
-                hipEvent_t e0, e1;
-                MS_HIP(hipEventCreate(&e0));
-                MS_HIP(hipEventCreate(&e1));
-                tev.push_back(e0);
-                tev.push_back(e1);
-                MS_HIP(hipEventRecord(e0, s));
+                while (tev.size() < tev_used + 2) {
+                    hipEvent_t e = nullptr;
+                    MS_HIP(hipEventCreate(&e));
+                    tev.push_back(e);
+                }
+                MS_HIP(hipEventRecord(tev[tev_used], s));
             }
 #define MS_BID(GG)                                                                                   \
     launch_bid_g<GG>(EPL, vec, q, assign, theta + par * kMaxE, st + par, klist, wcnt, wmoves, qmm + 2, T, E, k, \
@@ -1829,10 +1935,13 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             else if (G == 32) MS_BID(32);
             else MS_BID(64);
 #undef MS_BID
-            if (g_kernel_timing) MS_HIP(hipEventRecord(tev.back(), s));
+            if (g_kernel_timing) {
+                MS_HIP(hipEventRecord(tev[tev_used + 1], s));
+                tev_used += 2;
+            }
 #define MS_SEL(TT)                                                                                             \
     hipLaunchKernelGGL(k_select<TT>, dim3(E + tail_on), dim3(kSelThreads), 0, s, klist, wcnt, wmoves, gcount, theta, \
-                       st, qmm + 2, cand, q, assign, qmm + 3, tl_flag_dev, par, T, E, k, Ce, cap, n_wg, rows, tail_on, \
+                       st, qmm + 2, cand, q, assign, qmm + 3, hs->flag_dev, par, T, E, k, Ce, cap, n_wg, rows, tail_on, \
                        tail_moves, tail_iters, kvec)
             if (E <= 64) MS_SEL(1);
             else if (E <= 128) MS_SEL(2);
@@ -1840,7 +1949,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
 #undef MS_SEL
             ++launched;
         }
-        MS_HIP(hipEventRecord(evb[slot], s));
+        MS_HIP(hipEventRecord(hs->evb[slot], s));
         return MAXSCORE_OK;
     };
     {
@@ -1850,32 +1959,37 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             const int launched_cur = launched;
             rc = enqueue_batch(cur ^ 1);
             if (rc != MAXSCORE_OK) break;
-            MS_HIP(hipEventSynchronize(evb[cur]));
-            if (*(volatile int *)tl_flag || launched_cur > o.max_rounds + 64) break;
+            MS_HIP_SYNC(hipEventSynchronize(hs->evb[cur]));
+            if (*(volatile int *)hs->flag || launched_cur > o.max_rounds + 64) break;
             cur ^= 1;
         }
-        (void)hipEventDestroy(evb[0]);
-        (void)hipEventDestroy(evb[1]);
-        if (rc != MAXSCORE_OK) return rc;
+        if (rc != MAXSCORE_OK) {
+            (void)hipStreamSynchronize(s);
+            return rc;
+        }
     }
-    const int fpar = launched & 1;
+    const int fpar = launched & 1;       // every launch after the end copied the final state on: both copies hold it
+    hipLaunchKernelGGL(k_trim, dim3(n_wg), dim3(256), 0, s, st + fpar, theta, klist, wcnt, assign, E, k, rows);
     hipLaunchKernelGGL(k_finalize, dim3(kFinalBlocks), dim3(256), 0, s, q, assign, cand, T, E, k);   // lists are free again
-    hipLaunchKernelGGL(k_finalize2, dim3(1), dim3(kFinalBlocks), 0, s, cand, theta + fpar * kMaxE, st + fpar, prices,
-                       price_scale, E);
-    MS_HIP(hipEventRecord(ev1, s));
+    hipLaunchKernelGGL(k_finalize2, dim3(1), dim3(kFinalBlocks), 0, s, cand, theta, st + fpar, prices, price_scale, E);
+    MS_HIP_SYNC(hipEventRecord(hs->ev1, s));
     SolverState h;
-    MS_HIP(hipMemcpyAsync(&h, st + fpar, sizeof(h), hipMemcpyDeviceToHost, s));
+    MS_HIP_SYNC(hipMemcpyAsync(&h, st + fpar, sizeof(h), hipMemcpyDeviceToHost, s));
     MS_HIP(hipStreamSynchronize(s));
     MS_HIP(hipGetLastError());
     float ms = 0.f, bid_ms = 0.f;
-    (void)hipEventElapsedTime(&ms, ev0, ev1);
+    (void)hipEventElapsedTime(&ms, hs->ev0, hs->ev1);
     int timed = 0;
-    if (!tev.empty()) {
+    if (tev_used > 0) {
         // what a pair of event records costs with nothing between them is taken off every launch time
         float empty_ms = 0.f;
         const int n_cal = 16;
-        hipEvent_t ce[2 * n_cal];
-        for (int i = 0; i < 2 * n_cal; ++i) MS_HIP(hipEventCreate(&ce[i]));
+        while (tev.size() < tev_used + 2 * n_cal) {
+            hipEvent_t e = nullptr;
+            MS_HIP(hipEventCreate(&e));
+            tev.push_back(e);
+        }
+        hipEvent_t *ce = tev.data() + tev_used;
         for (int i = 0; i < n_cal; ++i) {
             MS_HIP(hipEventRecord(ce[2 * i], s));
             MS_HIP(hipEventRecord(ce[2 * i + 1], s));
@@ -1886,8 +2000,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             (void)hipEventElapsedTime(&t, ce[2 * i], ce[2 * i + 1]);
             empty_ms += t / n_cal;
         }
-        for (int i = 0; i < 2 * n_cal; ++i) (void)hipEventDestroy(ce[i]);
-        for (size_t i = 0; i + 1 < tev.size(); i += 2) {
+        for (size_t i = 0; i + 1 < tev_used; i += 2) {
             if ((int)(i / 2) < h.round) {
                 float t = 0.f;
                 (void)hipEventElapsedTime(&t, tev[i], tev[i + 1]);
@@ -1895,12 +2008,8 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
                 bid_ms += t > 0.f ? t : 0.f;
                 ++timed;
             }
-            (void)hipEventDestroy(tev[i]);
-            (void)hipEventDestroy(tev[i + 1]);
         }
     }
-    (void)hipEventDestroy(ev0);
-    (void)hipEventDestroy(ev1);
 #ifdef MS_SEL_PROF
     {
         static long long hp[kMaxE * 8];
@@ -1942,6 +2051,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         fprintf(stderr, "[tailstat] cumulative: single-victim iterations survive %d drop %d; multi-victim survive %d drop %d\n", hs[0], hs[1], hs[2], hs[3]);
     }
 #endif
+#ifdef MAXSCORE_DEBUG_ENV
     if (getenv("MAXSCORE_DEBUG")) {
         fprintf(stderr, "[maxscore] phase end rounds:");
         for (int a = 0; a < 28 && a < h.phases; ++a) fprintf(stderr, " %d", h.phase_round[a]);
@@ -1951,6 +2061,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         fprintf(stderr, "  eval detail (fast path, cyc/64): held marks %d, first best %d, decision %d, second best %d, commit %d\n",
                 h.phase_round[14], h.phase_round[15], h.phase_round[16], h.phase_round[17], h.phase_round[18]);
     }
+#endif
     if (stats) {
         stats->total_score_q = h.total;
         stats->flow_value = h.flow;

@@ -1,8 +1,6 @@
 """GPU parity of the assignment step (a4) on the solver's different code paths: 32-bit quick checks and
 64-bit full evaluation, with and without the tail pass, zero slack and slack capacity, several seeds,
 and the error statuses.  Every optimum is compared bit for bit with the CPU checker's."""
-import os
-
 import numpy as np
 import pytest
 
@@ -100,12 +98,35 @@ def test_eps_schedule_does_not_change_the_optimum(ms, eps_div):
 
 
 def test_round_cap_reports_not_converged(ms):
+    """At the round cap the call reports it and still returns a feasible (incomplete) assignment: at most C tokens
+    per expert, distinct experts per token, empty slots where the solver still had to move somebody."""
     print("round_cap", flush=True)
-    q = skewed_rewards(np.random.default_rng(11), 4096, 64, 20)
-    out = ms.assign_i32(dev(q.astype(np.int32)), 8, 512, max_rounds=3, allow_not_converged=True)
-    assert out["rc"] == -8 and out["stats"]["status"] == -8 and out["stats"]["rounds"] <= 3
+    T, E, k, C = 4096, 64, 8, 512
+    q = skewed_rewards(np.random.default_rng(11), T, E, 20)
+    for cap_rounds in (1, 2, 3, 7):
+        out = ms.assign_i32(dev(q.astype(np.int32)), k, C, max_rounds=cap_rounds, allow_not_converged=True)
+        assert out["rc"] == -8 and out["stats"]["status"] == -8 and out["stats"]["rounds"] <= cap_rounds
+        a = out["assign"].cpu().numpy()
+        P = oracle.assignment_matrix(a, E)
+        assert P.max() <= 1 and P.sum(axis=1).max() <= k and P.sum(axis=0).max() <= C, cap_rounds
+        assert int(P.sum()) == out["stats"]["flow_value"] == int((a >= 0).sum())     # distinct experts per token
+        assert int(P.sum()) < T * k                                                  # incomplete, as reported
+        assert out["stats"]["total_score_q"] == int(q[P.astype(bool)].sum())
     with pytest.raises(ms.MaxScoreError):
-        ms.assign_i32(dev(q.astype(np.int32)), 8, 512, max_rounds=3)
+        ms.assign_i32(dev(q.astype(np.int32)), k, C, max_rounds=3)
+    # through the routing entry: every position lies inside its expert's buffer of C places
+    L = np.random.default_rng(12).standard_normal((T, E)).astype(np.float32) * 2
+    r = ms.route_logits(dev(L), k, C, max_rounds=2, allow_not_converged=True)
+    assert r["rc"] == -8
+    a = r["assign"].cpu().numpy()
+    pos = r["token_pos"].cpu().numpy()
+    assert pos[a >= 0].max() < C and (pos[a < 0] == -1).all()
+    d = oracle.dispatch(a, r["gates"].cpu().numpy(), E)
+    assert np.array_equal(r["expert_offsets"].cpu().numpy(), d["expert_offsets"])
+    assert np.diff(d["expert_offsets"]).max() <= C
+    n = int(d["expert_offsets"][-1])
+    assert np.array_equal(r["disp_token"].cpu().numpy()[:n], d["disp_token"])
+    assert np.array_equal(pos, d["token_pos"])
 
 
 def test_reward_range_too_wide_is_an_error(ms):
@@ -118,20 +139,53 @@ def test_reward_range_too_wide_is_an_error(ms):
 
 
 def test_tail_pass_switch_gives_the_same_optimum(ms):
-    """The debug switch that turns the tail pass off must not change the total (different, equally optimal
-    assignments are allowed)."""
+    """Switching the tail pass off (MAXSCORE_FLAG_NO_TAIL_PASS) must not change the total (different, equally
+    optimal assignments are allowed)."""
     print("tail_switch", flush=True)
     q = skewed_rewards(np.random.default_rng(13), 4096, 64, 20)
     qd = dev(q.astype(np.int32))
     with_tail = ms.assign_i32(qd, 8, 512)
-    os.environ["MAXSCORE_TAIL"] = "0"
-    try:
-        without = ms.assign_i32(qd, 8, 512)
-    finally:
-        del os.environ["MAXSCORE_TAIL"]
+    without = ms.assign_i32(qd, 8, 512, tail_pass=False)
     assert with_tail["stats"]["total_score_q"] == without["stats"]["total_score_q"]
+    assert without["stats"]["rounds"] > with_tail["stats"]["rounds"]       # the switch did switch something
     ref = oracle.max_score_assignment(q, 8, 512)["total"]
     assert with_tail["stats"]["total_score_q"] == ref
+
+
+@pytest.mark.parametrize("name,T,slack", [("cfg5", 8192, False), ("cfg3", 4096, False), ("cfg4a", 4096, True)])
+def test_starting_prices_do_not_change_the_optimum(ms, name, T, slack):
+    """Starting prices (the prices another batch of the same router ended with, or arbitrary ones) only change the
+    number of rounds: totals equal the checker's optimum, and the returned prices certify it."""
+    print(f"starting_prices {name} T={T}", flush=True)
+    cfg = CONFIGS[name]
+    E, k = cfg["E"], cfg["k"]
+    C = capacity(T, E, k, cfg["C"] * E / (cfg["T"] * k))
+    qs = [oracle.quantise(oracle.soft_topk(make_logits(name, seed=sd, T=T), k, cfg["t"])) for sd in (0, 1)]
+    other = ms.assign_i32(dev(qs[1].astype(np.int32)), k, C)          # another batch, same expert popularity
+    cold = solve_and_check(ms, qs[0], k, C)
+    rng = np.random.default_rng(3)
+    S = other["price_scale"]
+    starts = [("other batch", other["prices"], 0), ("other batch, eps 1", other["prices"], 1),
+              ("other batch, large eps", other["prices"], 1 << 40),
+              ("own prices", cold["prices"], 1),
+              ("random", dev(rng.integers(0, (1 << 20) * S, E).astype(np.int64)), 0),
+              ("random, eps 1", dev(rng.integers(0, (1 << 16) * S, E).astype(np.int64)), 1),
+              ("zeros", dev(np.zeros(E, dtype=np.int64)), 0)]
+    for label, p_in, eps_start in starts:
+        out = solve_and_check(ms, qs[0], k, C, prices_in=p_in, eps_start=eps_start)
+        print(f"  {label}: rounds {out['stats']['rounds']} (cold {cold['stats']['rounds']}), phases "
+              f"{out['stats']['phases']}", flush=True)
+        # eps = 1 complementary slackness of the returned prices, price 0 on unfilled experts
+        a = out["assign"].cpu().numpy()
+        P = oracle.assignment_matrix(a, E).astype(bool)
+        p = out["prices"].cpu().numpy()
+        load = P.sum(axis=0)
+        assert (p >= 0).all() and (p[load < min(C, T)] == 0).all()
+        net = qs[0] * S - p[None, :]
+        big = np.int64(1) << 60
+        assert (np.where(P, net, big).min(axis=1) >= np.where(P, -big, net).max(axis=1) - 1).all()
+    own = solve_and_check(ms, qs[0], k, C, prices_in=cold["prices"], eps_start=1)
+    assert own["stats"]["rounds"] < cold["stats"]["rounds"]        # its own final prices: little left to do
 
 
 def test_large_batch_certified_by_its_prices(ms):
