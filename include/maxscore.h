@@ -73,10 +73,13 @@ typedef struct {
     const int64_t *prices_in; /* exact solver: NULL, or DEVICE array of E starting prices in the units of the
                              `prices` output (1/price_scale of a q unit; price_scale depends on E only), e.g. the
                              prices a previous call returned for a batch routed by the same W_g.  Any values >= 0 are
-                             legal: the result is the same optimum, only the number of rounds changes. */
+                             legal: the result is the same optimum, only the number of rounds changes.  (A forward
+                             auction only raises prices, so a start that is too high on some experts makes all the
+                             others climb: measured on successive batches of one router it saves nothing.) */
     int64_t eps_start;    /* with prices_in: eps of the first phase in the same units (it is rounded down to a power
-                             of eps_div; 0 = 1/144 of the cold-start value).  A phase that runs longer than 48 rounds
-                             after a start from given prices goes back up one step of the eps ladder. */
+                             of eps_div; 0 = one step below the cold-start value).  A phase that runs longer than 48 rounds
+                             after a start from given prices goes back up one step of the eps ladder (at most as many
+                             steps in all as the start skipped). */
 } maxscore_opts;
 #define MAXSCORE_ASSIGN_EXACT 0
 #define MAXSCORE_ASSIGN_ITER 1
@@ -93,7 +96,8 @@ typedef struct {
     float bid_ms;          /* summed device time of the bid-pass launches inside a4 (0 unless
                               timing was switched on with maxscore_set_kernel_timing) */
     int32_t bid_launches;  /* bid-pass launches that did work (0 unless timing is on) */
-    int32_t reserved;
+    float select_ms;       /* summed device time of the select-pass launches of the same rounds, the tail pass
+                              that runs inside some of them included (0 unless timing is on) */
 } maxscore_stats;
 
 /* Bytes of device scratch the calls below need for these sizes (0 on invalid sizes). */
@@ -313,8 +317,8 @@ int32_t maxscore_route_xw(const void *x, const void *W, const float *bias, int32
                           int64_t *prices, maxscore_stats *stats, void *workspace,
                           size_t workspace_bytes, void *stream);
 
-/* Switch per-launch HIP-event timing of the solver's bid pass on (1) or off (0, default).
- * Timing adds two event records per round; it is meant for benchmarks. */
+/* Switch per-launch HIP-event timing of the solver's bid and select passes on (1) or off (0, default).
+ * Timing adds three event records per round; it is meant for benchmarks. */
 void maxscore_set_kernel_timing(int32_t on);
 
 /* Plain device-to-device copy kernel of `bytes` bytes (multiple of 16), used by the benchmark to

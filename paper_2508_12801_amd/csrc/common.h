@@ -44,7 +44,7 @@ struct SolverState {
     int tail_block;        // the tail pass could not proceed: the next select pass must do a normal select
     int tail_gos;          // rounds so far in which the select pass handed over to the tail pass
     int tail_runs, tail_iters;   // diagnostics
-    int warm;              // 1: started from given prices (a long phase may go back up the eps ladder)
+    int warm;              // after a start from given prices: how many steps back up the eps ladder are still allowed
     int phase_start;       // round at which the current phase began
     long long eps0;        // first-phase epsilon of a cold start (upper end of the eps ladder)
     int phase_round[28];   // round index at which each phase ended (diagnostic)

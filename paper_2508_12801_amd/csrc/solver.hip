@@ -287,9 +287,13 @@ __global__ __launch_bounds__(kMinmaxBlocks) void k_setup(SolverState *st, const 
     st->eps0 = eps;
     if (prices_in) {
         // start lower on the same ladder (the later phases are then the ones of a cold start)
-        const long long want = eps_start > 0 ? eps_start : eps / ((long long)st->eps_div * st->eps_div);
-        while (eps > 1 && eps > want) eps /= st->eps_div;
-        st->warm = 1;
+        const long long want = eps_start > 0 ? eps_start : eps / st->eps_div;
+        int rungs = 0;
+        while (eps > 1 && eps > want) {
+            eps /= st->eps_div;
+            ++rungs;
+        }
+        st->warm = rungs;          // steps back up the ladder that are still allowed
     }
     st->eps = eps;
 }
@@ -1366,13 +1370,14 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
         } else if (round >= ns.max_rounds) {
             ns.status = MAXSCORE_ERR_NOT_CONVERGED;
             ns.done = 1;
-        } else if (ns.warm && round - ns.phase_start >= kWarmPhaseCap && cur_eps * ns.eps_div <= ns.eps0) {
+        } else if (ns.warm > 0 && round - ns.phase_start >= kWarmPhaseCap && cur_eps * ns.eps_div <= ns.eps0) {
             // The given prices were further off than the starting eps assumed: one step back up the ladder.  Every
             // hold that is valid at an eps is valid at a larger one, so this is legal at any time; the phases below
             // it run again afterwards.
             ns.eps = cur_eps * ns.eps_div;
             ns.phases += 1;
             ns.phase_start = round;
+            ns.warm -= 1;              // at most as many steps up as the start skipped: no ping-pong
             back_up = true;
         }
         if (*errflag) {
@@ -1920,7 +1925,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         for (int b = 0; b < batch; ++b) {
             const int par = launched & 1;
             if (g_kernel_timing) {
-                while (tev.size() < tev_used + 2) {
+                while (tev.size() < tev_used + 3) {
                     hipEvent_t e = nullptr;
                     MS_HIP(hipEventCreate(&e));
                     tev.push_back(e);
@@ -1935,10 +1940,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             else if (G == 32) MS_BID(32);
             else MS_BID(64);
 #undef MS_BID
-            if (g_kernel_timing) {
-                MS_HIP(hipEventRecord(tev[tev_used + 1], s));
-                tev_used += 2;
-            }
+            if (g_kernel_timing) MS_HIP(hipEventRecord(tev[tev_used + 1], s));
 #define MS_SEL(TT)                                                                                             \
     hipLaunchKernelGGL(k_select<TT>, dim3(E + tail_on), dim3(kSelThreads), 0, s, klist, wcnt, wmoves, gcount, theta, \
                        st, qmm + 2, cand, q, assign, qmm + 3, hs->flag_dev, par, T, E, k, Ce, cap, n_wg, rows, tail_on, \
@@ -1947,6 +1949,10 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             else if (E <= 128) MS_SEL(2);
             else MS_SEL(kTailEPL);
 #undef MS_SEL
+            if (g_kernel_timing) {
+                MS_HIP(hipEventRecord(tev[tev_used + 2], s));
+                tev_used += 3;
+            }
             ++launched;
         }
         MS_HIP(hipEventRecord(hs->evb[slot], s));
@@ -1977,7 +1983,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     MS_HIP_SYNC(hipMemcpyAsync(&h, st + fpar, sizeof(h), hipMemcpyDeviceToHost, s));
     MS_HIP(hipStreamSynchronize(s));
     MS_HIP(hipGetLastError());
-    float ms = 0.f, bid_ms = 0.f;
+    float ms = 0.f, bid_ms = 0.f, select_ms = 0.f;
     (void)hipEventElapsedTime(&ms, hs->ev0, hs->ev1);
     int timed = 0;
     if (tev_used > 0) {
@@ -2000,12 +2006,15 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             (void)hipEventElapsedTime(&t, ce[2 * i], ce[2 * i + 1]);
             empty_ms += t / n_cal;
         }
-        for (size_t i = 0; i + 1 < tev_used; i += 2) {
-            if ((int)(i / 2) < h.round) {
+        for (size_t i = 0; i + 2 < tev_used; i += 3) {
+            if ((int)(i / 3) < h.round) {
                 float t = 0.f;
                 (void)hipEventElapsedTime(&t, tev[i], tev[i + 1]);
                 t -= empty_ms;
                 bid_ms += t > 0.f ? t : 0.f;
+                (void)hipEventElapsedTime(&t, tev[i + 1], tev[i + 2]);
+                t -= empty_ms;
+                select_ms += t > 0.f ? t : 0.f;
                 ++timed;
             }
         }
@@ -2071,7 +2080,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         stats->solver_ms = ms;
         stats->bid_ms = bid_ms;
         stats->bid_launches = timed;
-        stats->reserved = 0;
+        stats->select_ms = select_ms;
     }
     return h.status;
 }

@@ -160,8 +160,8 @@ def test_starting_prices_do_not_change_the_optimum(ms, name, T, slack):
     cfg = CONFIGS[name]
     E, k = cfg["E"], cfg["k"]
     C = capacity(T, E, k, cfg["C"] * E / (cfg["T"] * k))
-    qs = [oracle.quantise(oracle.soft_topk(make_logits(name, seed=sd, T=T), k, cfg["t"])) for sd in (0, 1)]
-    other = ms.assign_i32(dev(qs[1].astype(np.int32)), k, C)          # another batch, same expert popularity
+    qs = [oracle.quantise(oracle.soft_topk(make_logits(name, T=T, batch=b), k, cfg["t"])) for b in (0, 1)]
+    other = ms.assign_i32(dev(qs[1].astype(np.int32)), k, C)          # another batch of the same router
     cold = solve_and_check(ms, qs[0], k, C)
     rng = np.random.default_rng(3)
     S = other["price_scale"]

@@ -115,16 +115,20 @@ def make_inputs(name: str, seed: int = 0, T: Optional[int] = None) -> RouterInpu
                         x=x, W=W, bias=bias, x_bits=x_bits, W_bits=W_bits)
 
 
-def make_logits(name: str, seed: int = 0, T: Optional[int] = None) -> np.ndarray:
+def make_logits(name: str, seed: int = 0, T: Optional[int] = None, batch: int = 0) -> np.ndarray:
     """fp32 router logits with the distribution x.W + bias has for the named config, drawn
     directly (x ~ N(0,1), W ~ N(0,1/d) give unit-variance logits) so that cases which do not
-    exercise the projection need not generate x.  Duplicate-row variants are honoured."""
+    exercise the projection need not generate x.  Duplicate-row variants are honoured.
+    `batch` > 0 gives another batch of tokens for the SAME router (same seed: same expert bias),
+    as successive training steps see it."""
     cfg = dict(CONFIGS[name])
     idx = list(CONFIGS).index(name)
     rng = np.random.default_rng([seed, idx, 7])
     E = cfg["E"]
     T = cfg["T"] if T is None else T
     bias = _expert_bias(rng, E, cfg["bias"])
+    if batch > 0:
+        rng = np.random.default_rng([seed, idx, 7, batch])
     L = rng.standard_normal((T, E), dtype=np.float32)
     dup = cfg.get("dup")
     if dup is not None:
