@@ -1,0 +1,98 @@
+// Host-only stand-ins for the kernel launchers behind the C ABI: every one reports success without touching a GPU.
+// Linked with api.cpp under -fsanitize=address,undefined so that the argument validation and workspace carving of
+// the boundary run on the CPU under the sanitizers.
+#include "common.h"
+
+namespace maxscore {
+
+int g_kernel_timing = 0;
+
+int32_t solver_run(const int32_t *, int, int, int, int, const maxscore_opts &, int32_t *, int64_t *, int64_t *,
+                   maxscore_stats *, char *, hipStream_t, const int32_t *, long long, const int32_t *, long long)
+{
+    return MAXSCORE_OK;
+}
+int32_t kvec_check(const int32_t *, int, int, int, char *, long long *demand, hipStream_t)
+{
+    *demand = 0;
+    return MAXSCORE_OK;
+}
+int32_t softtopk_run(const float *, int, int, int, float, int, float *, int32_t *, hipStream_t) { return MAXSCORE_OK; }
+int32_t quantise_run(const float *, int, int, int, int32_t *, hipStream_t) { return MAXSCORE_OK; }
+int32_t gates_run(const float *, const int32_t *, int, int, int, float *, hipStream_t) { return MAXSCORE_OK; }
+int32_t dispatch_run(const int32_t *, const float *, int, int, int, int32_t *, int32_t *, float *, int32_t *, char *,
+                     hipStream_t)
+{
+    return MAXSCORE_OK;
+}
+int32_t dispatch_core(const int32_t *, const float *, size_t, int, int, int32_t *, int32_t *, float *, int32_t *,
+                      int *, int, hipStream_t)
+{
+    return MAXSCORE_OK;
+}
+int32_t iter_run(const int32_t *, int, int, int, int, int, int32_t *, int64_t *, int32_t *, int32_t *, char *,
+                 hipStream_t)
+{
+    return MAXSCORE_OK;
+}
+int32_t scores_op_run(const float *, int, int, int, int, int, float *, int32_t *, hipStream_t) { return MAXSCORE_OK; }
+int32_t top1_run(const int32_t *, int, int, int32_t *, hipStream_t) { return MAXSCORE_OK; }
+int32_t assign_total_run(const int32_t *, const int32_t *, int, int, int, void *, int64_t *, int32_t *, hipStream_t)
+{
+    return MAXSCORE_OK;
+}
+int32_t caps_to_device(const int32_t *caps_host, int T, int E, int k, char *, const int32_t **cap_dev, long long *room,
+                       int *cmax, hipStream_t, long long demand)
+{
+    long long sum = 0;
+    int mx = 0;
+    for (int j = 0; j < E; ++j) {          // reads the caller's host array, as the real one does
+        if (caps_host[j] < 0) return MAXSCORE_ERR_SHAPE;
+        const int c = caps_host[j] < T ? caps_host[j] : T;
+        sum += c;
+        mx = c > mx ? c : mx;
+    }
+    if ((demand < 0 ? (long long)T * k : demand) > sum) return MAXSCORE_ERR_OVERSUBSCRIBED;
+    *cap_dev = nullptr;
+    *room = sum;
+    *cmax = mx > 0 ? mx : 1;
+    return MAXSCORE_OK;
+}
+int32_t alg1_run(const int32_t *, int, int, int, const maxscore_opts &, int32_t *, int32_t *, int32_t *, int64_t *,
+                 int32_t *, maxscore_stats *, char *, hipStream_t)
+{
+    return MAXSCORE_OK;
+}
+int32_t sinkhorn_run(const float *, int, int, int, float, int, int32_t *, float *, int32_t *, char *, hipStream_t)
+{
+    return MAXSCORE_OK;
+}
+int32_t aux_loss_run(const float *, const int32_t *, int, int, float, float *, float *, float *, char *, hipStream_t)
+{
+    return MAXSCORE_OK;
+}
+int32_t gates_backward_run(const float *, const float *, const int32_t *, const float *, const float *, int, int, int,
+                           float *, hipStream_t)
+{
+    return MAXSCORE_OK;
+}
+int32_t dispatch_tokens_run(const void *, int, const int32_t *, const int32_t *, int, int, int, int, void *,
+                            hipStream_t)
+{
+    return MAXSCORE_OK;
+}
+int32_t combine_run(const void *, int, const int32_t *, const int32_t *, const float *, int, int, int, int, int,
+                    float *, hipStream_t)
+{
+    return MAXSCORE_OK;
+}
+int32_t gemm_run(const void *, const void *, const float *, int, int, int, int, float *, void *, hipStream_t)
+{
+    return MAXSCORE_OK;
+}
+int32_t copy_run(const void *, void *, size_t, hipStream_t) { return MAXSCORE_OK; }
+
+}  // namespace maxscore
+
+// the one HIP call api.cpp makes itself (after its launchers): nothing is queued in this build
+extern "C" hipError_t hipStreamSynchronize(hipStream_t) { return hipSuccess; }
