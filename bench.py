@@ -138,7 +138,10 @@ def main():
     sel_bytes = T * k * 8 + n_wg * E * 4
     gd_bytes = T * k * (4 + 4 + 4) + T * k * (4 + 4) + T * k * 12 + 4 * (E + 1)
     pass_bytes = st["rounds"] * (bid_bytes + sel_bytes) + gd_bytes
-    pass_ms = solve_ms + gates_ms + disp_ms
+    # gates + dispatch as the routing calls run them: from the solver's final key blocks, two launches (the separate
+    # maxscore_gates / maxscore_dispatch entry points are timed above)
+    gd_ms = sorted(ms.route_scores(out["scores"], k, C)["stats"]["gates_dispatch_ms"] for _ in range(5))[2]
+    pass_ms = solve_ms + gd_ms
     pass_gbs = pass_bytes / (pass_ms * 1e-3) / 1e9
     floor_bytes = 4 * T * E + 4 * T * k + 8 * E
     # plain copy kernel of the same footprint: achievable-bandwidth reference
@@ -280,13 +283,13 @@ def main():
                                       "share_of_solver_time": st["select_ms"] / max(st["solver_ms"], 1e-9),
                                       "note": "mean over all rounds; the tail pass runs inside some of these "
                                               "launches (one workgroup, latency-bound)"},
-                         "gates_dispatch": {"bytes": gd_bytes, "us": (gates_ms + disp_ms) * 1e3,
-                                            "frac": gd_bytes / ((gates_ms + disp_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS}},
+                         "gates_dispatch": {"bytes": gd_bytes, "us": gd_ms * 1e3,
+                                            "frac": gd_bytes / (gd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}},
                      "copy_kernel_GBs": copy_gbs,
                      "note": "frac is below the 0.5 target: the passes are bound by launch and chain latency, "
                              "not by bytes (DESIGN.md section 8)"},
         "stages_ms": {"router_gemm": gemm_ms, "softtopk_quantise": soft_ms, "assignment": solve_ms,
-                      "gates": gates_ms, "dispatch": disp_ms,
+                      "gates_dispatch_in_route": gd_ms, "gates_entry": gates_ms, "dispatch_entry": disp_ms,
                       "gemm_hbm_frac": (T * d * 2 + d * E * 2 + T * E * 4) / (gemm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                       "gemm_tflops": 2.0 * T * d * E / (gemm_ms * 1e-3) / 1e12},
         "tie_heavy_solve": tie,

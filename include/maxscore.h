@@ -98,6 +98,7 @@ typedef struct {
     int32_t bid_launches;  /* bid-pass launches that did work (0 unless timing is on) */
     float select_ms;       /* summed device time of the select-pass launches of the same rounds, the tail pass
                               that runs inside some of them included (0 unless timing is on) */
+    float gates_dispatch_ms; /* maxscore_route_* only: device time of a5 + a6 between two events on `stream` */
 } maxscore_stats;
 
 /* Bytes of device scratch the calls below need for these sizes (0 on invalid sizes). */

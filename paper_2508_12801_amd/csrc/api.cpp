@@ -24,6 +24,7 @@ WorkspaceLayout workspace_layout(int T, int E, int k, int d)
     L.tiles_off = off; off = align_up(off + sizeof(int) * ((size_t)L.n_tiles * E + kMaxE), 256);
     L.cap_off = off; off = align_up(off + sizeof(int) * (size_t)kMaxE, 256);     // per-expert capacities
     L.aux_off = off; off = align_up(off + sizeof(int) * 2 * (size_t)T, 256);     // two token-long lists
+    L.dbase_off = off; off = align_up(off + sizeof(int) * ((size_t)E * L.max_wg + kMaxE), 256);   // dispatch from key blocks
     L.wt_off = off; off = align_up(off + sizeof(unsigned short) * (size_t)E * (d > 0 ? d : 0), 256);
     L.total = off;
     return L;
@@ -262,6 +263,23 @@ int32_t maxscore_combine(const void *expert_out, int32_t in_dtype, const int32_t
     return combine_run(expert_out, in_dtype, assign, token_pos, gates, T, d, E, k, C, y, (hipStream_t)stream);
 }
 
+// A pair of events per host thread for the a5 + a6 time of the routing calls (created once, kept).
+static int32_t route_events(hipEvent_t *a, hipEvent_t *b)
+{
+    static thread_local hipEvent_t ev[2] = {nullptr, nullptr};
+    static thread_local int ev_dev = -1;
+    int dev = 0;
+    MS_HIP(hipGetDevice(&dev));
+    if (ev_dev != dev) {                 // first call of the thread (or the thread moved to another device)
+        MS_HIP(hipEventCreate(&ev[0]));
+        MS_HIP(hipEventCreate(&ev[1]));
+        ev_dev = dev;
+    }
+    *a = ev[0];
+    *b = ev[1];
+    return MAXSCORE_OK;
+}
+
 // a4..a6 on scores and rewards that are already in place (the common tail of the maxscore_route_* calls).
 static int32_t route_from_rewards(const float *scores, const int32_t *q, int T, int E, int k, int C,
                                   const maxscore_opts &o, int32_t *assign, float *gates, int32_t *expert_offsets,
@@ -270,6 +288,17 @@ static int32_t route_from_rewards(const float *scores, const int32_t *q, int T, 
 {
     const int Ce = C < T ? C : T;
     int32_t src;
+    hipEvent_t ev_a = nullptr, ev_b = nullptr;
+    {
+        int32_t rc = route_events(&ev_a, &ev_b);
+        if (rc) return rc;
+    }
+    auto finish = [&](int32_t status) -> int32_t {       // end of a5 + a6: wait for the stream, report their time
+        if (hipEventRecord(ev_b, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return MAXSCORE_ERR_HIP;
+        float t = 0.f;
+        if (stats && hipEventElapsedTime(&t, ev_a, ev_b) == hipSuccess) stats->gates_dispatch_ms = t;
+        return status;
+    };
     if (o.assignment == MAXSCORE_ASSIGN_ITER) {
         int64_t total = 0;
         int32_t flow = 0, rounds = 0;
@@ -281,15 +310,24 @@ static int32_t route_from_rewards(const float *scores, const int32_t *q, int T, 
             stats->status = src;
         }
     } else {
-        src = solver_run(q, T, E, k, Ce, o, assign, prices, nullptr, stats, ws, s);
+        SolverGeometry geom = {0, 0, 0};
+        src = solver_run(q, T, E, k, Ce, o, assign, prices, nullptr, stats, ws, s, nullptr, 0, nullptr, 0, &geom);
+        if (src == MAXSCORE_OK && geom.n_wg > 0) {
+            // converged: the final bid pass left every pair as a key, sorted by expert inside each block of rows
+            MS_HIP(hipEventRecord(ev_a, s));
+            int32_t rc = dispatch_from_keys(geom, scores, assign, T, E, k, gates, expert_offsets, disp_token,
+                                            disp_gate, token_pos, ws, s);
+            if (rc) return rc;
+            return finish(src);
+        }
     }
     if (src != MAXSCORE_OK && src != MAXSCORE_ERR_NOT_CONVERGED) return src;
+    MS_HIP(hipEventRecord(ev_a, s));
     int32_t rc = gates_run(scores, assign, T, E, k, gates, s);
     if (rc) return rc;
     rc = dispatch_run(assign, gates, T, E, k, expert_offsets, disp_token, disp_gate, token_pos, ws, s);
     if (rc) return rc;
-    if (hipStreamSynchronize(s) != hipSuccess) return MAXSCORE_ERR_HIP;
-    return src;
+    return finish(src);
 }
 
 // Argument checks shared by the maxscore_route_* calls (everything after the scores exist).

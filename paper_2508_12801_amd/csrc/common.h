@@ -52,8 +52,16 @@ struct SolverState {
 
 struct WorkspaceLayout {
     size_t state_off, theta_off, gcount_off, klist_off, wcnt_off, wmoves_off, cand_off, tiles_off, cap_off, aux_off,
-        wt_off, total;
+        wt_off, dbase_off, total;
     int n_tiles, max_wg;
+};
+
+// How the last solve laid out its bid keys (what the dispatch needs to read them): the key blocks of the final bid
+// pass hold one key per (token, expert) pair, sorted by expert inside each block of `rows` consecutive tokens.
+struct SolverGeometry {
+    int rows;        // token rows per bid workgroup = per key block
+    int n_wg;        // number of key blocks
+    int tbits;       // the token id sits in the low tbits bits of a key
 };
 
 WorkspaceLayout workspace_layout(int T, int E, int k, int d = 0);
@@ -71,7 +79,7 @@ inline bool hip_ok(hipError_t e) { return e == hipSuccess; }
 int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore_opts &o, int32_t *assign,
                    int64_t *prices, int64_t *price_scale, maxscore_stats *stats, char *ws, hipStream_t s,
                    const int32_t *cap = nullptr, long long room = 0, const int32_t *kvec = nullptr,
-                   long long demand = 0);
+                   long long demand = 0, SolverGeometry *geom = nullptr);
 // Checks a device array of T per-token k (each 0..k) and returns its sum in *demand (synchronises the stream).
 int32_t kvec_check(const int32_t *kvec, int T, int E, int k, char *ws, long long *demand, hipStream_t s);
 // --- softtopk.hip
@@ -85,6 +93,11 @@ int32_t dispatch_run(const int32_t *assign, const float *gates, int T, int E, in
 // Stable position of every entry of `list` (n expert ids, -1 = none) among the entries of the same expert, and
 // the exclusive prefix sums of the per-expert counts; disp_token / disp_gate may be null.  `tiles` needs
 // n_tiles*E + kMaxE ints with n_tiles = ceil(n / kDispTile).
+// a5 + a6 straight from the key blocks of a converged solve in the same workspace (every token holds k experts):
+// gates, expert offsets, both dispatch lists and the positions, in two launches.
+int32_t dispatch_from_keys(const SolverGeometry &g, const float *scores, const int32_t *assign, int T, int E, int k,
+                           float *gates, int32_t *offsets, int32_t *disp_token, float *disp_gate, int32_t *token_pos,
+                           char *ws, hipStream_t s);
 int32_t dispatch_core(const int32_t *list, const float *gates, size_t n, int E, int k, int32_t *offsets,
                       int32_t *disp_token, float *disp_gate, int32_t *token_pos, int *tiles, int n_tiles,
                       hipStream_t s);

@@ -1841,7 +1841,7 @@ static int32_t solver_host(SolverHost **out)
 
 int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore_opts &o, int32_t *assign,
                    int64_t *prices, int64_t *price_scale, maxscore_stats *stats, char *ws, hipStream_t s,
-                   const int32_t *cap, long long room, const int32_t *kvec, long long demand)
+                   const int32_t *cap, long long room, const int32_t *kvec, long long demand, SolverGeometry *geom)
 {
     WorkspaceLayout L = workspace_layout(T, E, k);
     SolverState *st = (SolverState *)(ws + L.state_off);
@@ -2071,6 +2071,11 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
                 h.phase_round[14], h.phase_round[15], h.phase_round[16], h.phase_round[17], h.phase_round[18]);
     }
 #endif
+    if (geom) {
+        geom->rows = rows;
+        geom->n_wg = n_wg;
+        geom->tbits = h.tbits;
+    }
     if (stats) {
         stats->total_score_q = h.total;
         stats->flow_value = h.flow;

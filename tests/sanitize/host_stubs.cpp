@@ -8,7 +8,13 @@ namespace maxscore {
 int g_kernel_timing = 0;
 
 int32_t solver_run(const int32_t *, int, int, int, int, const maxscore_opts &, int32_t *, int64_t *, int64_t *,
-                   maxscore_stats *, char *, hipStream_t, const int32_t *, long long, const int32_t *, long long)
+                   maxscore_stats *, char *, hipStream_t, const int32_t *, long long, const int32_t *, long long,
+                   SolverGeometry *)
+{
+    return MAXSCORE_OK;
+}
+int32_t dispatch_from_keys(const SolverGeometry &, const float *, const int32_t *, int, int, int, float *, int32_t *,
+                           int32_t *, float *, int32_t *, char *, hipStream_t)
 {
     return MAXSCORE_OK;
 }
@@ -94,5 +100,9 @@ int32_t copy_run(const void *, void *, size_t, hipStream_t) { return MAXSCORE_OK
 
 }  // namespace maxscore
 
-// the one HIP call api.cpp makes itself (after its launchers): nothing is queued in this build
+// the HIP calls api.cpp makes itself (around its launchers): nothing is queued in this build
 extern "C" hipError_t hipStreamSynchronize(hipStream_t) { return hipSuccess; }
+extern "C" hipError_t hipGetDevice(int *d) { *d = 0; return hipSuccess; }
+extern "C" hipError_t hipEventCreate(hipEvent_t *e) { *e = nullptr; return hipSuccess; }
+extern "C" hipError_t hipEventRecord(hipEvent_t, hipStream_t) { return hipSuccess; }
+extern "C" hipError_t hipEventElapsedTime(float *ms, hipEvent_t, hipEvent_t) { *ms = 0.f; return hipSuccess; }
