@@ -84,6 +84,8 @@ typedef struct {
 #define MAXSCORE_ASSIGN_EXACT 0
 #define MAXSCORE_ASSIGN_ITER 1
 #define MAXSCORE_FLAG_NO_TAIL_PASS 1u   /* exact solver: dense rounds only (slower; same optimum) */
+#define MAXSCORE_FLAG_NO_FINISHER 2u    /* exact solver: the auction runs down to eps = 1 itself instead of handing
+                                           its last phases to the cycle-cancelling finisher (slower; same optimum) */
 
 /* Filled on the HOST when the call returns (may be NULL). */
 typedef struct {

@@ -177,13 +177,14 @@ ASSIGNMENTS = {"exact": 0, "iter": 1}
 
 
 FLAG_NO_TAIL_PASS = 1
+FLAG_NO_FINISHER = 2
 
 
 def _opts(t=1.0, quant_shift=20, max_rounds=200000, eps_div=12, assignment="exact", tail_pass=True, prices_in=None,
-          eps_start=0):
-    return _Opts(float(t), int(quant_shift), int(max_rounds), int(eps_div), ASSIGNMENTS[assignment],
-                 0 if tail_pass else FLAG_NO_TAIL_PASS, prices_in.data_ptr() if prices_in is not None else None,
-                 int(eps_start))
+          eps_start=0, finisher=True):
+    flags = (0 if tail_pass else FLAG_NO_TAIL_PASS) | (0 if finisher else FLAG_NO_FINISHER)
+    return _Opts(float(t), int(quant_shift), int(max_rounds), int(eps_div), ASSIGNMENTS[assignment], flags,
+                 prices_in.data_ptr() if prices_in is not None else None, int(eps_start))
 
 
 def set_kernel_timing(on: bool) -> None:
@@ -255,7 +256,7 @@ def scores_op(logits, k: int, op: str, quant_shift: int = 20):
 
 
 def assign_i32(q, k: int, C: int, max_rounds: int = 200000, eps_div: int = 12, allow_not_converged=False,
-               tail_pass: bool = True, prices_in=None, eps_start: int = 0):
+               tail_pass: bool = True, prices_in=None, eps_start: int = 0, finisher: bool = True):
     """a4: exact assignment on int32 rewards.  Returns dict(assign, prices, price_scale, stats).  prices_in: int64
     device tensor of E starting prices (the `prices` of an earlier call), eps_start: first-phase eps with them."""
     torch = _torch()
@@ -268,7 +269,8 @@ def assign_i32(q, k: int, C: int, max_rounds: int = 200000, eps_div: int = 12, a
     scale = torch.empty(1, dtype=torch.int64, device=q.device)
     stats = Stats()
     ws, need = _workspace(T, E, k, C, q.device)
-    o = _opts(max_rounds=max_rounds, eps_div=eps_div, tail_pass=tail_pass, prices_in=prices_in, eps_start=eps_start)
+    o = _opts(max_rounds=max_rounds, eps_div=eps_div, tail_pass=tail_pass, prices_in=prices_in, eps_start=eps_start,
+              finisher=finisher)
     rc = load_library().maxscore_assign_i32(_ptr(q), T, E, k, C, ctypes.byref(o), _ptr(assign), _ptr(prices),
                                             _ptr(scale), ctypes.byref(stats), _ptr(ws), need, _stream())
     _check(rc, "maxscore_assign_i32", allow=(ERR_NOT_CONVERGED,) if allow_not_converged else ())

@@ -47,12 +47,19 @@ struct SolverState {
     int warm;              // after a start from given prices: how many steps back up the eps ladder are still allowed
     int phase_start;       // round at which the current phase began
     long long eps0;        // first-phase epsilon of a cold start (upper end of the eps ladder)
+    long long stop_eps;    // the phase with eps <= stop_eps is the last one of the auction (1: it runs to the optimum
+                           // itself; above 1 the cycle-cancelling finisher takes over from there)
+    long long fin_bound;   // finisher: arcs whose reduced cost is at or above this are left out of the arc matrix
+    int fin;               // finisher: 0 not in use, 1 pending (more passes needed), 2 optimum certified, 3 gave up
+    int fin_passes;        // arc-matrix passes so far
+    int fin_cycles;        // negative cycles cancelled so far
+    int fin_dirty;         // cycles cancelled since the arc matrix was last rebuilt
     int phase_round[28];   // round index at which each phase ended (diagnostic)
 };
 
 struct WorkspaceLayout {
     size_t state_off, theta_off, gcount_off, klist_off, wcnt_off, wmoves_off, cand_off, tiles_off, cap_off, aux_off,
-        wt_off, dbase_off, total;
+        wt_off, dbase_off, fin_off, total;
     int n_tiles, max_wg;
 };
 
@@ -82,6 +89,16 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
                    long long demand = 0, SolverGeometry *geom = nullptr);
 // Checks a device array of T per-token k (each 0..k) and returns its sum in *demand (synchronises the stream).
 int32_t kvec_check(const int32_t *kvec, int T, int E, int k, char *ws, long long *demand, hipStream_t s);
+// --- finish.hip
+// Exact finish from a quiescent auction state at a coarse eps (every token holds its experts): cancels the negative
+// cycles of the expert graph until none is left and replaces the prices by exact ones.  `passes` pairs of (arc
+// matrix, Bellman-Ford + cancelling) are enqueued; each exits at once unless st->fin is 1.  Supports E <= kFinMaxE.
+constexpr int kFinMaxE = 128;
+constexpr int kFinMovedCap = 4096;        // tokens the finisher may move in one solve (more: the auction goes on)
+int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long long *theta2, const int *loads2,
+                       const int *cap, int Ce, int T, int E, int k, char *ws, int rows, int n_wg, int passes,
+                       long long bound_mult, int *host_words, hipStream_t s);
+size_t finish_area_bytes(int T);          // bytes of WorkspaceLayout::fin_off's region
 // --- softtopk.hip
 int32_t softtopk_run(const float *logits, int T, int E, int k, float t, int shift, float *scores, int32_t *q,
                      hipStream_t s);

@@ -150,7 +150,7 @@ __device__ __forceinline__ int group_max_i32(int v)
 }
 
 __global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm, int32_t *assign, int T, int E,
-                       int k, int eps_div, int max_rounds, int slack)
+                       int k, int eps_div, int max_rounds, int slack, long long stop_eps)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t n = (size_t)T * k;
@@ -178,7 +178,8 @@ __global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm,
         st->blocks_done = 0; st->flow = 0; st->slack = slack;
         st->wide = 0; st->tail_go = 0; st->after_tail = 0; st->tail_block = 0; st->tail_runs = 0; st->tail_gos = 0;
         st->tail_iters = 0;
-        st->warm = 0; st->phase_start = 0; st->eps0 = 1;
+        st->warm = 0; st->phase_start = 0; st->eps0 = 1; st->stop_eps = stop_eps;
+        st->fin = 0; st->fin_passes = 0; st->fin_cycles = 0; st->fin_dirty = 0; st->fin_bound = 0;
         for (int a = 0; a < 28; ++a) st->phase_round[a] = 0;
     }
 }
@@ -231,12 +232,16 @@ __global__ __launch_bounds__(256) void k_minmax(const int32_t *__restrict__ q, s
 // prices_in (optional): E starting prices in the units of the price output; they become the thresholds of round 0
 // and the first phase starts at eps_start (rounded down to a power of the ladder's ratio) instead of at the top.
 constexpr long long kMaxPriceIn = (long long)1 << 38;
+constexpr long long kFinLimitQ = 8;        // the finisher takes over at the first eps rung at or under 8 reward units
+constexpr int kFinPasses = 8;              // finisher passes enqueued per solve
+constexpr long long kFinBoundMult = 32;    // arcs with a reduced cost of 32 eps or more stay out of the finisher's arc matrix
 constexpr int kWarmPhaseCap = 48;          // rounds after which a phase started from given prices goes back up the ladder
 
 __global__ __launch_bounds__(kMinmaxBlocks) void k_setup(SolverState *st, const int *__restrict__ part, int nparts,
                                                         int T, int E, int force_wide, int eps0_shift,
                                                         long long *__restrict__ theta,
-                                                        const int64_t *__restrict__ prices_in, long long eps_start)
+                                                        const int64_t *__restrict__ prices_in, long long eps_start,
+                                                        long long fin_limit_q)
 {
     __shared__ int s_lo[kMinmaxBlocks / 64], s_hi[kMinmaxBlocks / 64];
     int lo = 0x7fffffff, hi = -0x7fffffff - 1;
@@ -296,6 +301,14 @@ __global__ __launch_bounds__(kMinmaxBlocks) void k_setup(SolverState *st, const 
         st->warm = rungs;          // steps back up the ladder that are still allowed
     }
     st->eps = eps;
+    if (fin_limit_q > 0) {
+        // the auction stops at the first rung of its ladder that is at or under fin_limit_q reward units; the
+        // cycle-cancelling finisher takes over from there
+        const long long limit = fin_limit_q << sb;
+        long long r = st->eps0;
+        while (r > 1 && r > limit) r /= st->eps_div;
+        st->stop_eps = r > 1 ? r : 1;
+    }
 }
 
 // Bid pass.  A group of G lanes owns one token row; lane l of the group owns the EPL consecutive
@@ -308,7 +321,7 @@ __global__ __launch_bounds__(256, (G * EPL > 256 ? 3 : 4)) void k_bid(const int3
                                              const long long *__restrict__ theta, const SolverState *__restrict__ st,
                                              long long *__restrict__ klist, int *__restrict__ wcnt,
                                              int *__restrict__ wmoves, int *__restrict__ errflag, int T, int E, int k,
-                                             int rows_per_wg, const int32_t *__restrict__ kvec)
+                                             int rows_per_wg, const int32_t *__restrict__ kvec, int force)
 {
     constexpr int EP = G * EPL;
     constexpr int NG = 256 / G;
@@ -383,7 +396,7 @@ __global__ __launch_bounds__(256, (G * EPL > 256 ? 3 : 4)) void k_bid(const int3
     const int over = st->done;
     const long long eps = st->eps, qmin = st->qmin;
     const int sb = st->sbits, tb = st->tbits;
-    if (over) return;
+    if (over && !force) return;       // (force: one more pass after the end, which only rewrites the key blocks)
 #pragma unroll
     for (int i = 0; i < (EP + 255) / 256; ++i) {
         const int e = tid + i * 256;
@@ -1182,7 +1195,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         // there is no price lowering to decide, so the next round starts the next phase right away
         // (the last phase still gets its full check by a bid pass).
         const int stopped = s_stop1 | s_stop2;
-        if (!stopped && !over_last && !st->slack && st->eps > 1) {
+        if (!stopped && !over_last && !st->slack && st->eps > st->stop_eps) {
             if (st->phases <= 28) st->phase_round[st->phases - 1] = st->round;
             st->eps_prev = st->eps;
             const long long ne = st->eps / st->eps_div;
@@ -1345,7 +1358,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     if (redo) {
         action = 1;                          // an unfilled expert kept a positive price: redo the phase lower
         lower = cur_beta * 2 * eps_ref;
-    } else if (quiet && cur_eps != 1 && cur_slack) {
+    } else if (quiet && cur_eps > st->stop_eps && cur_slack) {
         action = 1;
         lower = cur_beta * cur_eps;
     }
@@ -1359,8 +1372,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             if (redo) {
                 ns.beta = cur_beta * 2;
                 ns.phases += 1;
-            } else if (cur_eps == 1) {
+            } else if (cur_eps <= ns.stop_eps) {
                 ns.done = 1;
+                ns.fin = ns.stop_eps > 1 ? 1 : 0;      // stopped above eps = 1: the finisher has to take over
             } else {
                 ns.eps_prev = cur_eps;
                 long long ne = cur_eps / ns.eps_div;
@@ -1743,12 +1757,12 @@ __global__ __launch_bounds__(256) void k_kvec_check(const int32_t *__restrict__ 
 template <int G, int EPL>
 void launch_bid(bool vec, const int32_t *q, int32_t *assign, const long long *theta, const SolverState *st,
                 long long *klist, int *wcnt, int *wmoves, int *errflag, int T, int E, int k, int rows_per_wg,
-                const int32_t *kvec, hipStream_t s)
+                const int32_t *kvec, int force, hipStream_t s)
 {
     int grid = (T + rows_per_wg - 1) / rows_per_wg;
 #define MS_BK(VV, KK)                                                                                        \
     hipLaunchKernelGGL((k_bid<G, EPL, VV, KK>), dim3(grid), dim3(256), 0, s, q, assign, theta, st, klist, wcnt, \
-                       wmoves, errflag, T, E, k, rows_per_wg, kvec)
+                       wmoves, errflag, T, E, k, rows_per_wg, kvec, force)
     if (kvec) {
         if (vec) MS_BK(true, true);
         else MS_BK(false, true);
@@ -1762,9 +1776,9 @@ void launch_bid(bool vec, const int32_t *q, int32_t *assign, const long long *th
 template <int G>
 void launch_bid_g(int EPL, bool vec, const int32_t *q, int32_t *assign, const long long *theta,
                   const SolverState *st, long long *klist, int *wcnt, int *wmoves, int *errflag, int T, int E, int k,
-                  int rows_per_wg, const int32_t *kvec, hipStream_t s)
+                  int rows_per_wg, const int32_t *kvec, int force, hipStream_t s)
 {
-#define MS_B(PP) launch_bid<G, PP>(vec, q, assign, theta, st, klist, wcnt, wmoves, errflag, T, E, k, rows_per_wg, kvec, s)
+#define MS_B(PP) launch_bid<G, PP>(vec, q, assign, theta, st, klist, wcnt, wmoves, errflag, T, E, k, rows_per_wg, kvec, force, s)
     if (EPL == 1) MS_B(1);
     else if (EPL == 2) MS_B(2);
     else if (EPL == 4) MS_B(4);
@@ -1855,6 +1869,12 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     int tail_on = (E <= kTailMaxE && !(o.flags & MAXSCORE_FLAG_NO_TAIL_PASS)) ? 1 : 0;
     int tail_iters = 64, tail_moves = kTailMoves;
     int eps0_shift = kEps0Shift;
+    long long stop_eps = 1;
+    // The cycle-cancelling finisher takes over from the auction at the first rung of the eps ladder at or under
+    // this many reward units (0: the auction runs down to eps = 1 itself).
+    long long fin_limit_q = (E <= kFinMaxE && !(o.flags & MAXSCORE_FLAG_NO_FINISHER)) ? kFinLimitQ : 0;
+    int fin_passes = kFinPasses;
+    long long fin_bound_mult = kFinBoundMult;
 
     // lanes per token row (G >= k) and consecutive experts per lane
     int G = 8, EPL = 1;
@@ -1880,6 +1900,10 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         if (r >= ngrp && r % ngrp == 0 && r * k <= 1024) rows = r;
     }
     if (const char *ev = getenv("MAXSCORE_EPS0_SHIFT")) eps0_shift = std::max(0, std::min(atoi(ev), 30));
+    if (const char *ev = getenv("MAXSCORE_STOP_EPS")) stop_eps = std::max(1ll, atoll(ev));   // ends early: NOT optimal
+    if (const char *ev = getenv("MAXSCORE_FIN_Q")) fin_limit_q = E <= kFinMaxE ? std::max(0ll, atoll(ev)) : 0;
+    if (const char *ev = getenv("MAXSCORE_FIN_PASSES")) fin_passes = std::max(1, std::min(atoi(ev), 64));
+    if (const char *ev = getenv("MAXSCORE_FIN_BMULT")) fin_bound_mult = std::max(1ll, atoll(ev));
 #endif
     const bool vec = (E == G * EPL) && (((uintptr_t)q) % 16 == 0);
     const int n_wg = (T + rows - 1) / rows;
@@ -1901,7 +1925,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         if (grid < 4) grid = 4;
         if (grid > 4096) grid = 4096;
         hipLaunchKernelGGL(k_init, dim3(grid), dim3(256), 0, s, st, theta, gcount, qmm, assign, T, E, k,
-                           o.eps_div, o.max_rounds, slack);
+                           o.eps_div, o.max_rounds, slack, stop_eps);
         size_t nq = (size_t)T * E;
         int g2 = (int)((nq + 256 * 16 - 1) / (256 * 16));
         if (g2 > kMinmaxBlocks) g2 = kMinmaxBlocks;
@@ -1909,7 +1933,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         int *part = (int *)cand;                 // the candidate lists are not in use yet
         hipLaunchKernelGGL(k_minmax, dim3(g2), dim3(256), 0, s, q, nq, part);
         hipLaunchKernelGGL(k_setup, dim3(1), dim3(kMinmaxBlocks), 0, s, st, part, g2, T, E, k == E ? 1 : 0,
-                           eps0_shift, theta, o.prices_in, (long long)o.eps_start);
+                           eps0_shift, theta, o.prices_in, (long long)o.eps_start, fin_limit_q);
     }
 
     // Rounds are enqueued in batches; the select pass writes `done` straight into pinned host memory.
@@ -1934,7 +1958,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             }
 #define MS_BID(GG)                                                                                   \
     launch_bid_g<GG>(EPL, vec, q, assign, theta + par * kMaxE, st + par, klist, wcnt, wmoves, qmm + 2, T, E, k, \
-                     rows, kvec, s)
+                     rows, kvec, 0, s)
             if (G == 8) MS_BID(8);
             else if (G == 16) MS_BID(16);
             else if (G == 32) MS_BID(32);
@@ -1958,20 +1982,62 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         MS_HIP(hipEventRecord(hs->evb[slot], s));
         return MAXSCORE_OK;
     };
-    {
+    auto run_rounds = [&]() -> int32_t {
         int cur = 0;
+        const int launched0 = launched;
         int32_t rc = enqueue_batch(cur);
         while (rc == MAXSCORE_OK) {
             const int launched_cur = launched;
             rc = enqueue_batch(cur ^ 1);
             if (rc != MAXSCORE_OK) break;
             MS_HIP_SYNC(hipEventSynchronize(hs->evb[cur]));
-            if (*(volatile int *)hs->flag || launched_cur > o.max_rounds + 64) break;
+            if (*(volatile int *)hs->flag || launched_cur - launched0 > o.max_rounds + 64) break;
             cur ^= 1;
         }
+        if (rc != MAXSCORE_OK) (void)hipStreamSynchronize(s);
+        return rc;
+    };
+    {
+        int32_t rc = run_rounds();
+        if (rc != MAXSCORE_OK) return rc;
+    }
+    int fin_cycles = 0, fin_state = 0;
+    if (fin_limit_q > 0) {
+        // The auction has stopped at a coarse eps (or ended for another reason, then every finisher launch exits at
+        // once).  A fixed number of finisher passes is enqueued; the last kernel reports through pinned memory
+        // whether the optimum is certified or the auction has been set going again (one step down its ladder).
+        volatile int *words = (volatile int *)hs->flag;
+        words[4] = 0;
+        const int fp = launched & 1;
+        int32_t rc = finish_enqueue(q, assign, st + fp, theta, gcount, cap, Ce, T, E, k, ws, rows, n_wg, fin_passes,
+                                    fin_bound_mult, hs->flag_dev + 4, s);
         if (rc != MAXSCORE_OK) {
             (void)hipStreamSynchronize(s);
             return rc;
+        }
+        MS_HIP_SYNC(hipEventRecord(hs->evb[0], s));
+        MS_HIP_SYNC(hipEventSynchronize(hs->evb[0]));
+        fin_cycles = words[5];
+        fin_state = words[6];
+        if (words[4] == 2) {
+            // not certified: the second copy of the state follows the first, and the rounds go on to eps = 1
+            MS_HIP_SYNC(hipMemcpyAsync(st + (fp ^ 1), st + fp, sizeof(SolverState), hipMemcpyDeviceToDevice, s));
+            words[0] = 0;
+            launched = words[7];          // rounds done so far: thresholds and loads alternate with the round number
+            rc = run_rounds();
+            if (rc != MAXSCORE_OK) return rc;
+        } else if (fin_cycles > 0 && geom) {
+            // the caller reads the key blocks of the last bid pass: one more pass rewrites them for the final
+            // assignment (every hold is valid under the exact prices, so the pass moves nothing)
+            const int par = launched & 1;
+#define MS_BIDF(GG) \
+    launch_bid_g<GG>(EPL, vec, q, assign, theta + par * kMaxE, st + par, klist, wcnt, wmoves, qmm + 2, T, E, k, rows, \
+                     kvec, 1, s)
+            if (G == 8) MS_BIDF(8);
+            else if (G == 16) MS_BIDF(16);
+            else if (G == 32) MS_BIDF(32);
+            else MS_BIDF(64);
+#undef MS_BIDF
         }
     }
     const int fpar = launched & 1;       // every launch after the end copied the final state on: both copies hold it
@@ -2061,6 +2127,9 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     }
 #endif
 #ifdef MAXSCORE_DEBUG_ENV
+    if (getenv("MAXSCORE_DEBUG"))
+        fprintf(stderr, "[maxscore] finisher: stop_eps %lld state %d passes %d cycles %d (host saw state %d cycles %d)\n",
+                (long long)h.stop_eps, h.fin, h.fin_passes, h.fin_cycles, fin_state, fin_cycles);
     if (getenv("MAXSCORE_DEBUG")) {
         fprintf(stderr, "[maxscore] phase end rounds:");
         for (int a = 0; a < 28 && a < h.phases; ++a) fprintf(stderr, " %d", h.phase_round[a]);

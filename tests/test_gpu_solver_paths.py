@@ -152,6 +152,60 @@ def test_tail_pass_switch_gives_the_same_optimum(ms):
     assert with_tail["stats"]["total_score_q"] == ref
 
 
+def certified(q64, out, k, C):
+    """eps = 1 complementary slackness of the returned prices, price 0 on unfilled experts."""
+    T, E = q64.shape
+    P = oracle.assignment_matrix(out["assign"].cpu().numpy(), E).astype(bool)
+    p, S = out["prices"].cpu().numpy(), out["price_scale"]
+    load = P.sum(axis=0)
+    if not ((p >= 0).all() and (p[load < min(C, T)] == 0).all()):
+        return False
+    net = q64 * S - p[None, :]
+    big = np.int64(1) << 60
+    return bool((np.where(P, net, big).min(axis=1) >= np.where(P, -big, net).max(axis=1) - 1).all())
+
+
+@pytest.mark.parametrize("name,T,seed", [("cfg5", 8192, 0), ("cfg5", 16384, 1), ("cfg3", 4096, 2), ("cfg4a", 4096, 0),
+                                         ("cfg4b_exact", 4096, 0), ("cfg4b_near", 4096, 1), ("cfg2", None, 3)])
+def test_finisher_and_auction_reach_the_same_optimum(ms, name, T, seed):
+    """The last phases of the eps ladder are replaced by cancelling negative cycles (the default) or run by the
+    auction itself (MAXSCORE_FLAG_NO_FINISHER): same total as the checker either way, prices that certify it, and
+    fewer auction rounds with the finisher."""
+    print(f"finisher {name} T={T} seed={seed}", flush=True)
+    cfg = CONFIGS[name]
+    L = make_logits(name, seed=seed, T=T)
+    T = L.shape[0]
+    E, k = cfg["E"], cfg["k"]
+    C = capacity(T, E, k, cfg["C"] * E / (cfg["T"] * k))
+    q = oracle.quantise(oracle.soft_topk(L, k, cfg["t"]))
+    fin = solve_and_check(ms, q, k, C)
+    auc = solve_and_check(ms, q, k, C, finisher=False)
+    assert certified(q, fin, k, C) and certified(q, auc, k, C)
+    assert fin["stats"]["rounds"] <= auc["stats"]["rounds"]
+    again = ms.assign_i32(dev(q.astype(np.int32)), k, C)
+    assert again["stats"]["total_score_q"] == fin["stats"]["total_score_q"]
+    if name != "cfg4b_exact":        # (among thousands of identical rows the auction's own tie order varies from run to run)
+        assert torch.equal(again["assign"], fin["assign"]) and torch.equal(again["prices"], fin["prices"])
+
+
+def test_finisher_with_k_vector_and_capacity_vector(ms):
+    """Per-token k (with zeros) and unequal capacities through the finisher: checker's optimum, valid rows."""
+    print("finisher kvec+caps", flush=True)
+    rng = np.random.default_rng(31)
+    T, E, k = 3000, 48, 6
+    q = skewed_rewards(rng, T, E, 20)
+    kvec = rng.integers(0, k + 1, T).astype(np.int32)
+    caps = rng.integers(200, 500, E).astype(np.int32)
+    caps[3] = 0
+    assert caps.sum() >= kvec.sum()
+    out = ms.assign_kvec_i32(dev(q.astype(np.int32)), k, dev(kvec), caps=list(caps))
+    a = out["assign"].cpu().numpy()
+    ref = oracle.max_score_assignment_kvec(q, kvec, caps)
+    P = oracle.assignment_matrix(a, E)
+    assert (P.sum(axis=1) == kvec).all() and (P.sum(axis=0) <= caps).all()
+    assert int(q[P.astype(bool)].sum()) == ref["total"] == out["stats"]["total_score_q"]
+
+
 @pytest.mark.parametrize("name,T,slack", [("cfg5", 8192, False), ("cfg3", 4096, False), ("cfg4a", 4096, True)])
 def test_starting_prices_do_not_change_the_optimum(ms, name, T, slack):
     """Starting prices (the prices another batch of the same router ended with, or arbitrary ones) only change the
