@@ -137,7 +137,10 @@ def main():
     bid_bytes = T * E * 4 + T * k * 4 + T * k * 8
     sel_bytes = T * k * 8 + n_wg * E * 4
     gd_bytes = T * k * (4 + 4 + 4) + T * k * (4 + 4) + T * k * 12 + 4 * (E + 1)
-    pass_bytes = st["rounds"] * (bid_bytes + sel_bytes) + gd_bytes
+    # finisher: every pass scans the bid keys and the per-block counts and reads and clears the arc matrix; the
+    # rows it reads beyond that are a few thousand (not counted)
+    fin_bytes = st["finish_passes"] * (T * k * 8 + n_wg * E * 4 + 2 * E * E * 8)
+    pass_bytes = st["rounds"] * (bid_bytes + sel_bytes) + fin_bytes + gd_bytes
     # gates + dispatch as the routing calls run them: from the solver's final key blocks, two launches (the separate
     # maxscore_gates / maxscore_dispatch entry points are timed above)
     gd_ms = sorted(ms.route_scores(out["scores"], k, C)["stats"]["gates_dispatch_ms"] for _ in range(5))[2]
@@ -150,6 +153,11 @@ def main():
     copy_ms = timed(lambda: ms.copy_bytes(src, dst))
     copy_gbs = 2 * src.numel() / (copy_ms * 1e-3) / 1e9
     del src, dst
+
+    # the same solve with the auction running down to eps = 1 itself (no finisher), for comparison
+    auction_only = ms.assign_i32(out["q"], k, C, finisher=False)["stats"]
+    auction_only = {"solver_ms": sorted(ms.assign_i32(out["q"], k, C, finisher=False)["stats"]["solver_ms"]
+                                       for _ in range(3))[1], "rounds": auction_only["rounds"]}
 
     # the tie-heavy variant of the fourth configuration (a quarter of the rows identical): exact solve only
     from workloads import CONFIGS, make_logits
@@ -268,6 +276,7 @@ def main():
                      "traffic": profile_value("pass_cfg5_pmc_traffic.txt", "pass_traffic_bytes")
                      if args.config == "cfg5" else None,
                      "bytes": pass_bytes, "ms": pass_ms, "rounds": st["rounds"],
+                     "finisher_passes": st["finish_passes"], "finisher_cycles": st["finish_cycles"],
                      "fraction_floor": floor_bytes / (pass_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "floor_bytes": floor_bytes,
                      "kernels": {
@@ -293,6 +302,7 @@ def main():
                       "gemm_hbm_frac": (T * d * 2 + d * E * 2 + T * E * 4) / (gemm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                       "gemm_tflops": 2.0 * T * d * E / (gemm_ms * 1e-3) / 1e12},
         "tie_heavy_solve": tie,
+        "auction_without_finisher": auction_only,
         "activation_movement": movement,
         "iterative_rerouting": iter_variant,
         "training_side": training_side,

@@ -91,7 +91,7 @@ typedef struct {
 typedef struct {
     int64_t total_score_q; /* sum of q over the chosen pairs */
     int32_t flow_value;    /* number of chosen pairs */
-    int32_t rounds;        /* solver rounds executed */
+    int32_t rounds;        /* solver rounds executed (auction rounds: bid pass + select pass) */
     int32_t phases;        /* eps-scaling phases executed (restarts included) */
     int32_t status;        /* MAXSCORE_OK, MAXSCORE_ERR_RANGE or MAXSCORE_ERR_NOT_CONVERGED */
     float solver_ms;       /* device time of a4 between two events on `stream` */
@@ -101,6 +101,8 @@ typedef struct {
     float select_ms;       /* summed device time of the select-pass launches of the same rounds, the tail pass
                               that runs inside some of them included (0 unless timing is on) */
     float gates_dispatch_ms; /* maxscore_route_* only: device time of a5 + a6 between two events on `stream` */
+    int32_t finish_passes; /* passes of the cycle-cancelling finisher (0: the auction ran to eps = 1 itself) */
+    int32_t finish_cycles; /* negative cycles it cancelled */
 } maxscore_stats;
 
 /* Bytes of device scratch the calls below need for these sizes (0 on invalid sizes). */

@@ -29,7 +29,8 @@ class Stats(ctypes.Structure):
     _fields_ = [("total_score_q", ctypes.c_int64), ("flow_value", ctypes.c_int32), ("rounds", ctypes.c_int32),
                 ("phases", ctypes.c_int32), ("status", ctypes.c_int32), ("solver_ms", ctypes.c_float),
                 ("bid_ms", ctypes.c_float), ("bid_launches", ctypes.c_int32), ("select_ms", ctypes.c_float),
-                ("gates_dispatch_ms", ctypes.c_float)]
+                ("gates_dispatch_ms", ctypes.c_float), ("finish_passes", ctypes.c_int32),
+                ("finish_cycles", ctypes.c_int32)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

@@ -354,7 +354,7 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
     __syncthreads();
     const int n_arcs = sh.n_arcs;
 
-    bool converged = false;
+    bool converged = false, from_zero = first_pass;
     int cur = 0;
     const int max_sweeps = 8 * (E + 2) + 16 * kFinMaxCyclesPerPass;
 #ifdef MS_FIN_PROF
@@ -396,6 +396,28 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
         cur ^= 1;
         MS_FP(c_sweep)
         if (!sh.changed[it % 3]) {
+            // Stopped relaxing.  If nothing was cancelled this pass can certify, provided the potentials spread
+            // less than the bound; potentials carried over from earlier passes can spread more than needed, so
+            // in that case the sweeps run once more from zero (no cycle is left: they converge).
+            if (sh.dirty == 0 && !from_zero) {
+                long long lo = kDistInf, hi = -kDistInf;
+                for (int v = 0; v <= Z; ++v) {
+                    const long long dv = (long long)(sh.key[cur][v] >> kIdxBits);
+                    lo = dv < lo ? dv : lo;
+                    hi = dv > hi ? dv : hi;
+                }
+                if (hi - lo >= B) {            // the same for every thread
+                    __syncthreads();
+                    for (int v = tid; v < kFinMaxE + 2; v += kFinThreads) {
+                        const unsigned long long k0 = ((unsigned long long)kKeyBias << kIdxBits) | kIdxRoot;
+                        sh.key[0][v] = k0;
+                        sh.key[1][v] = k0;
+                    }
+                    from_zero = true;
+                    __syncthreads();
+                    continue;
+                }
+            }
             converged = true;
             break;
         }

@@ -232,7 +232,7 @@ __global__ __launch_bounds__(256) void k_minmax(const int32_t *__restrict__ q, s
 // prices_in (optional): E starting prices in the units of the price output; they become the thresholds of round 0
 // and the first phase starts at eps_start (rounded down to a power of the ladder's ratio) instead of at the top.
 constexpr long long kMaxPriceIn = (long long)1 << 38;
-constexpr long long kFinLimitQ = 8;        // the finisher takes over at the first eps rung at or under 8 reward units
+constexpr long long kFinPairBudget = 8000000;   // the finisher takes over at the first eps rung with pairs * eps (in reward units) under this
 constexpr int kFinPasses = 8;              // finisher passes enqueued per solve
 constexpr long long kFinBoundMult = 32;    // arcs with a reduced cost of 32 eps or more stay out of the finisher's arc matrix
 constexpr int kWarmPhaseCap = 48;          // rounds after which a phase started from given prices goes back up the ladder
@@ -1871,8 +1871,14 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     int eps0_shift = kEps0Shift;
     long long stop_eps = 1;
     // The cycle-cancelling finisher takes over from the auction at the first rung of the eps ladder at or under
-    // this many reward units (0: the auction runs down to eps = 1 itself).
-    long long fin_limit_q = (E <= kFinMaxE && !(o.flags & MAXSCORE_FLAG_NO_FINISHER)) ? kFinLimitQ : 0;
+    // fin_limit_q reward units (0: the auction runs down to eps = 1 itself).
+    // (the number of cycles left to cancel grows with the number of pairs and with eps: the switch point keeps
+    // pairs * eps, in reward units, under a budget that leaves a few dozen cycles at most)
+    long long fin_limit_q = 0;
+    if (E <= kFinMaxE && !(o.flags & MAXSCORE_FLAG_NO_FINISHER)) {
+        fin_limit_q = kFinPairBudget / ((long long)T * k);
+        fin_limit_q = fin_limit_q < 1 ? 1 : fin_limit_q;
+    }
     int fin_passes = kFinPasses;
     long long fin_bound_mult = kFinBoundMult;
 
@@ -2155,6 +2161,8 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         stats->bid_ms = bid_ms;
         stats->bid_launches = timed;
         stats->select_ms = select_ms;
+        stats->finish_passes = h.fin_passes;
+        stats->finish_cycles = h.fin_cycles;
     }
     return h.status;
 }
