@@ -44,7 +44,9 @@ struct SolverState {
     int tail_block;        // the tail pass could not proceed: the next select pass must do a normal select
     int tail_gos;          // rounds so far in which the select pass handed over to the tail pass
     int tail_runs, tail_iters;   // diagnostics
-    int warm;              // after a start from given prices: how many steps back up the eps ladder are still allowed
+    int warm;              // how many steps back up the eps ladder are still allowed (a start from given prices, or
+                           // phases that were ended early, may have left the prices further off than their eps assumes)
+    int early_off;         // set once the ladder has been climbed back up: from then on no phase ends early
     int phase_start;       // round at which the current phase began
     long long eps0;        // first-phase epsilon of a cold start (upper end of the eps ladder)
     long long stop_eps;    // the phase with eps <= stop_eps is the last one of the auction (1: it runs to the optimum
@@ -91,13 +93,15 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
 int32_t kvec_check(const int32_t *kvec, int T, int E, int k, char *ws, long long *demand, hipStream_t s);
 // --- finish.hip
 // Exact finish from a quiescent auction state at a coarse eps (every token holds its experts): cancels the negative
-// cycles of the expert graph until none is left and replaces the prices by exact ones.  `passes` pairs of (arc
-// matrix, Bellman-Ford + cancelling) are enqueued; each exits at once unless st->fin is 1.  Supports E <= kFinMaxE.
+// cycles of the expert graph until none is left and replaces the prices by exact ones.  One call enqueues the passes
+// first_pass .. first_pass + passes - 1 of total_passes, each a pair of (arc matrix, Bellman-Ford + cancelling) that
+// exits at once unless st->fin is 1, and a last kernel that reports to host_words[0..3]: {1 certified | 2 the auction
+// goes on | 3 not finished, passes left; cycles cancelled so far; st->fin; round}.  Supports E <= kFinMaxE.
 constexpr int kFinMaxE = 128;
 constexpr int kFinMovedCap = 4096;        // tokens the finisher may move in one solve (more: the auction goes on)
 int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long long *theta2, const int *loads2,
-                       const int *cap, int Ce, int T, int E, int k, char *ws, int rows, int n_wg, int passes,
-                       long long bound_mult, int *host_words, hipStream_t s);
+                       const int *cap, int Ce, int T, int E, int k, char *ws, int rows, int n_wg, int first_pass,
+                       int passes, int total_passes, long long bound_mult, int *host_words, hipStream_t s);
 size_t finish_area_bytes(int T);          // bytes of WorkspaceLayout::fin_off's region
 // --- softtopk.hip
 int32_t softtopk_run(const float *logits, int T, int E, int k, float t, int shift, float *scores, int32_t *q,

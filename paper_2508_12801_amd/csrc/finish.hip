@@ -616,12 +616,20 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
     for (int v = tid; v <= E; v += kFinThreads) fa.pot[v] = (long long)(sh.key[cur][v] >> kIdxBits) - kKeyBias;
 }
 
-// After the last pass: if the optimum is not certified the auction goes on one step further down its ladder, to
-// eps = 1, from the state the finisher left (its exchanges only improved the assignment).
-__global__ void k_fin_end(SolverState *st, int T, int *host_words)
+// After a group of passes: the host learns where the finisher stands (word 0: 1 = certified, 2 = the auction goes
+// on, 3 = passes are left and the work is not finished).  After the last pass, or when the finisher gave up, an
+// optimum that is not certified sends the auction one step further down its ladder, to eps = 1, from the state the
+// finisher left (its exchanges only improved the assignment).
+__global__ void k_fin_end(SolverState *st, int T, int *host_words, int final)
 {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     int resumed = 0;
+    if (st->fin == 1 && !final) {
+        __hip_atomic_store(&host_words[1], st->fin_cycles, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        __hip_atomic_store(&host_words[2], st->fin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        __hip_atomic_store(&host_words[0], 3, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        return;
+    }
     if (st->fin == 1 || st->fin == 3) {
         st->done = 0;
         st->eps_prev = st->eps;
@@ -648,10 +656,12 @@ size_t finish_area_bytes(int T)
 }
 
 int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long long *theta2, const int *loads2,
-                       const int *cap, int Ce, int T, int E, int k, char *ws, int rows, int n_wg, int passes,
-                       long long bound_mult, int *host_words, hipStream_t s)
+                       const int *cap, int Ce, int T, int E, int k, char *ws, int rows, int n_wg, int first_pass,
+                       int passes, int total_passes, long long bound_mult, int *host_words, hipStream_t s)
 {
-    if (E > kFinMaxE || passes < 1 || bound_mult < 1 || rows * k > 1024 || n_wg < 1) return MAXSCORE_ERR_SHAPE;
+    if (E > kFinMaxE || passes < 1 || first_pass < 0 || first_pass + passes > total_passes || bound_mult < 1 ||
+        rows * k > 1024 || n_wg < 1)
+        return MAXSCORE_ERR_SHAPE;
     WorkspaceLayout L = workspace_layout(T, E, k);
     unsigned long long *M = (unsigned long long *)(ws + L.cand_off);      // E*E*8 <= 128 KB of the 278 KB there
     static_assert(sizeof(unsigned long long) * kFinMaxE * kFinMaxE <= sizeof(long long) * (size_t)kMaxE * (kCand + 2),
@@ -660,8 +670,9 @@ int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long 
     if (finish_area_bytes(T) > L.wt_off - L.fin_off) return MAXSCORE_ERR_WORKSPACE;      // layout and area must agree
     const long long *klist = (const long long *)(ws + L.klist_off);
     const int *wcnt = (const int *)(ws + L.wcnt_off);
-    hipLaunchKernelGGL(k_fin_begin, dim3(1), dim3(kFinThreads), 0, s, st, M, fin_base, T, E, bound_mult);
-    for (int pass = 0; pass < passes; ++pass) {
+    if (first_pass == 0)
+        hipLaunchKernelGGL(k_fin_begin, dim3(1), dim3(kFinThreads), 0, s, st, M, fin_base, T, E, bound_mult);
+    for (int pass = first_pass; pass < first_pass + passes; ++pass) {
         if (E <= 64)
             hipLaunchKernelGGL(k_fin_arcs<1>, dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
                                fin_base, T, E, k, rows);
@@ -669,9 +680,10 @@ int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long 
             hipLaunchKernelGGL(k_fin_arcs<2>, dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
                                fin_base, T, E, k, rows);
         hipLaunchKernelGGL(k_fin_cycles, dim3(1), dim3(kFinThreads), 0, s, st, M, assign, theta2, loads2, fin_base, cap,
-                           Ce, T, E, k, pass == passes - 1 ? 1 : 0);
+                           Ce, T, E, k, pass == total_passes - 1 ? 1 : 0);
     }
-    hipLaunchKernelGGL(k_fin_end, dim3(1), dim3(64), 0, s, st, T, host_words);
+    hipLaunchKernelGGL(k_fin_end, dim3(1), dim3(64), 0, s, st, T, host_words,
+                       first_pass + passes == total_passes ? 1 : 0);
     MS_HIP(hipGetLastError());
     return MAXSCORE_OK;
 }

@@ -178,7 +178,7 @@ __global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm,
         st->blocks_done = 0; st->flow = 0; st->slack = slack;
         st->wide = 0; st->tail_go = 0; st->after_tail = 0; st->tail_block = 0; st->tail_runs = 0; st->tail_gos = 0;
         st->tail_iters = 0;
-        st->warm = 0; st->phase_start = 0; st->eps0 = 1; st->stop_eps = stop_eps;
+        st->warm = 0; st->early_off = 0; st->phase_start = 0; st->eps0 = 1; st->stop_eps = stop_eps;
         st->fin = 0; st->fin_passes = 0; st->fin_cycles = 0; st->fin_dirty = 0; st->fin_bound = 0;
         for (int a = 0; a < 28; ++a) st->phase_round[a] = 0;
     }
@@ -233,7 +233,8 @@ __global__ __launch_bounds__(256) void k_minmax(const int32_t *__restrict__ q, s
 // and the first phase starts at eps_start (rounded down to a power of the ladder's ratio) instead of at the top.
 constexpr long long kMaxPriceIn = (long long)1 << 38;
 constexpr long long kFinPairBudget = 8000000;   // the finisher takes over at the first eps rung with pairs * eps (in reward units) under this
-constexpr int kFinPasses = 8;              // finisher passes enqueued per solve
+constexpr int kFinPasses = 8;              // finisher passes per solve at most
+constexpr int kFinGroup = 4;               // passes enqueued at a time
 constexpr long long kFinBoundMult = 32;    // arcs with a reduced cost of 32 eps or more stay out of the finisher's arc matrix
 constexpr int kWarmPhaseCap = 48;          // rounds after which a phase started from given prices goes back up the ladder
 
@@ -715,6 +716,7 @@ constexpr int kTailThreads = 1024;
 __device__ int g_tailstat[8];
 #endif
 constexpr int kTailMoves = 16;            // hand over to the tail pass when a bid pass moved this few slots
+constexpr int kEarlyMoves = 16;           // a phase before the last one ends when a bid pass moved this few slots
 constexpr long long kKeyInf = (long long)1 << 62;
 constexpr int kTailSpinMax = 1 << 20;     // polls of the tail workgroup for the candidate lists before it gives up
 constexpr int kTailVict = 64;             // dropped tokens per iteration (the list is read back one entry per lane)
@@ -1246,7 +1248,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                                                         int *errflag, long long *cand, const int32_t *__restrict__ q,
                                                         int32_t *assign, int *ready, int *host_done, int par, int T, int E, int k,
                                                         int Ce, const int *__restrict__ cap, int n_wg,
-                                                        int rows_per_wg, int tail_on, int tail_moves,
+                                                        int rows_per_wg, int tail_on, int tail_moves, int early_moves,
                                                         int tail_iters, const int32_t *__restrict__ kvec)
 {
     const SolverState *st = st2 + par;
@@ -1351,8 +1353,18 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     // single-workgroup tail pass run the next rounds on them
     const bool stopping = cur_round + 1 >= cur_max_rounds || *errflag != 0;
     // (not in the last round the cap allows: that round must leave thresholds that cut every expert to capacity)
+    // A phase that is not the auction's last one only has to bring the prices near their values at its eps:
+    // the holds it leaves are checked again under the next eps anyway.  Such a phase therefore ends as soon as a
+    // round moves only a few slots, instead of settling its last tokens one by one; they go on bidding under the
+    // smaller eps.  (Only where supply equals demand: with spare capacity a phase change also lowers prices, which
+    // needs the quiescent state.)  The last phase runs to the end: it has to leave a complete assignment.
+    // The tokens left over may still have long chains of displacements ahead of them, which a smaller eps makes
+    // longer: every early end therefore allows one step back up the ladder should a later phase drag on, and after
+    // such a step every phase runs to its end.
+    const bool early_end = early_moves > 0 && !quiet && moves <= early_moves && !cur_slack && !st->early_off &&
+                           cur_eps > st->stop_eps && !stopping && cur_round - st->phase_start >= 2;
     const bool tail_go = tail_on && !quiet && !cur_tail_block && cur_round > 0 && moves <= tail_moves &&
-                         (moves > 0 || (flags & 2)) && !stopping;
+                         (moves > 0 || (flags & 2)) && !stopping && !early_end;
     int action = 0;
     long long lower = 0;
     if (redo) {
@@ -1365,7 +1377,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     if (blockIdx.x == 0 && tid == 0) {
         SolverState ns = *st;
         const int round = cur_round + 1;
-        bool back_up = false;
+        bool new_phase = false;      // eps changed without a quiescent round
         if (quiet) {
             if (ns.phases <= 28) ns.phase_round[ns.phases - 1] = round;
             ns.phase_start = round;
@@ -1384,6 +1396,15 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
         } else if (round >= ns.max_rounds) {
             ns.status = MAXSCORE_ERR_NOT_CONVERGED;
             ns.done = 1;
+        } else if (early_end) {
+            if (ns.phases <= 28) ns.phase_round[ns.phases - 1] = round;
+            ns.phase_start = round;
+            ns.eps_prev = cur_eps;
+            long long ne = cur_eps / ns.eps_div;
+            ns.eps = ne > 1 ? ne : 1;
+            ns.phases += 1;
+            ns.warm += 1;
+            new_phase = true;
         } else if (ns.warm > 0 && round - ns.phase_start >= kWarmPhaseCap && cur_eps * ns.eps_div <= ns.eps0) {
             // The given prices were further off than the starting eps assumed: one step back up the ladder.  Every
             // hold that is valid at an eps is valid at a larger one, so this is legal at any time; the phases below
@@ -1391,15 +1412,16 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             ns.eps = cur_eps * ns.eps_div;
             ns.phases += 1;
             ns.phase_start = round;
-            ns.warm -= 1;              // at most as many steps up as the start skipped: no ping-pong
-            back_up = true;
+            ns.warm -= 1;              // at most as many steps up as were skipped or cut short: no ping-pong
+            ns.early_off = 1;
+            new_phase = true;
         }
         if (*errflag) {
             ns.status = MAXSCORE_ERR_HIP;
             ns.done = 1;
         }
         ns.round = round;
-        ns.moves = (quiet || back_up) ? T : moves;   // a new phase starts with many moves: no quick checks in its first round
+        ns.moves = (quiet || new_phase) ? T : moves;   // a new phase starts with many moves: no quick checks in its first round
         ns.tail_go = tail_go ? 1 : 0;
         ns.tail_gos = cur_tail_gos + (tail_go ? 1 : 0);
         ns.after_tail = 0;
@@ -1867,7 +1889,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     int *wmoves = (int *)(ws + L.wmoves_off);
     long long *cand = (long long *)(ws + L.cand_off);
     int tail_on = (E <= kTailMaxE && !(o.flags & MAXSCORE_FLAG_NO_TAIL_PASS)) ? 1 : 0;
-    int tail_iters = 64, tail_moves = kTailMoves;
+    int tail_iters = 64, tail_moves = kTailMoves, early_moves = kEarlyMoves;
     int eps0_shift = kEps0Shift;
     long long stop_eps = 1;
     // The cycle-cancelling finisher takes over from the auction at the first rung of the eps ladder at or under
@@ -1897,6 +1919,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
 #ifdef MAXSCORE_DEBUG_ENV
     // tuning overrides of a development build (not compiled into the library otherwise); values are clamped
     if (const char *ev = getenv("MAXSCORE_TAIL_MOVES")) tail_moves = std::max(0, std::min(atoi(ev), kTailVict));
+    if (const char *ev = getenv("MAXSCORE_EARLY")) early_moves = std::max(0, atoi(ev));
     if (const char *ev = getenv("MAXSCORE_TAIL")) {
         tail_iters = std::max(0, std::min(atoi(ev), 4096));
         if (tail_iters <= 0) tail_on = 0;
@@ -1974,7 +1997,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
 #define MS_SEL(TT)                                                                                             \
     hipLaunchKernelGGL(k_select<TT>, dim3(E + tail_on), dim3(kSelThreads), 0, s, klist, wcnt, wmoves, gcount, theta, \
                        st, qmm + 2, cand, q, assign, qmm + 3, hs->flag_dev, par, T, E, k, Ce, cap, n_wg, rows, tail_on, \
-                       tail_moves, tail_iters, kvec)
+                       tail_moves, early_moves, tail_iters, kvec)
             if (E <= 64) MS_SEL(1);
             else if (E <= 128) MS_SEL(2);
             else MS_SEL(kTailEPL);
@@ -2015,14 +2038,20 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         volatile int *words = (volatile int *)hs->flag;
         words[4] = 0;
         const int fp = launched & 1;
-        int32_t rc = finish_enqueue(q, assign, st + fp, theta, gcount, cap, Ce, T, E, k, ws, rows, n_wg, fin_passes,
-                                    fin_bound_mult, hs->flag_dev + 4, s);
-        if (rc != MAXSCORE_OK) {
-            (void)hipStreamSynchronize(s);
-            return rc;
+        // the passes are enqueued a few at a time (most solves are certified within the first group, and a pass
+        // that finds the work done still costs two launches)
+        int32_t rc = MAXSCORE_OK;
+        for (int p0 = 0; p0 < fin_passes; p0 += kFinGroup) {
+            rc = finish_enqueue(q, assign, st + fp, theta, gcount, cap, Ce, T, E, k, ws, rows, n_wg, p0,
+                                std::min(kFinGroup, fin_passes - p0), fin_passes, fin_bound_mult, hs->flag_dev + 4, s);
+            if (rc != MAXSCORE_OK) {
+                (void)hipStreamSynchronize(s);
+                return rc;
+            }
+            MS_HIP_SYNC(hipEventRecord(hs->evb[0], s));
+            MS_HIP_SYNC(hipEventSynchronize(hs->evb[0]));
+            if (words[4] != 3) break;
         }
-        MS_HIP_SYNC(hipEventRecord(hs->evb[0], s));
-        MS_HIP_SYNC(hipEventSynchronize(hs->evb[0]));
         fin_cycles = words[5];
         fin_state = words[6];
         if (words[4] == 2) {
