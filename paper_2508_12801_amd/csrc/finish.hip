@@ -224,11 +224,13 @@ struct FinShared {
     int jump[2][kFinMaxE + 2];
     int load[kFinMaxE], capv[kFinMaxE];
     int cyc[kFinMaxE + 2];                    // nodes of the cycle being cancelled
+    int pred[kFinMaxE + 2];                   // predecessor of every node at the last check
+    int cycflag[kFinMaxE + 2], cyclist[kFinMaxE + 2];     // smallest node of every cycle found by the check
     int moved[kFinMaxE + 2];
-    int scan[16][kFinThreads / 64];           // arcs per (chunk of the matrix, wavefront) while the list is built
+    int scan[kFinMaxE * kFinMaxE / kFinThreads][kFinThreads / 64];           // arcs per (chunk of the matrix, wavefront) while the list is built
     int moved_all[kFinMovedCap / 8];          // tokens moved in this pass, for the list in memory
     int changed[3];       // one flag per sweep, three in rotation (a flag is cleared two sweeps after its last read)
-    int n_arcs, cyc_node, n_cyc, n_moved, n_moved_all, give_up, dirty, cycles, bad;
+    int n_arcs, n_found, n_cyc, n_moved, n_moved_all, give_up, dirty, cycles, bad;
     long long cyc_sum;
 };
 
@@ -354,6 +356,18 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
     __syncthreads();
     const int n_arcs = sh.n_arcs;
 
+    // The first kRegArcs arcs of every thread (arc tid + j * kFinThreads) are kept in registers between sweeps, so
+    // that a sweep issues all its label reads at once; they are read again whenever arcs have been withdrawn.
+    constexpr int kRegArcs = 4;
+    unsigned long long wreg[kRegArcs];
+    auto load_arcs = [&]() {
+#pragma unroll
+        for (int j = 0; j < kRegArcs; ++j) {
+            const int i = tid + j * kFinThreads;
+            wreg[j] = i < n_arcs ? sh.arc[i] : arc_pack(kCostInf, 0, 0);
+        }
+    };
+    load_arcs();
     bool converged = false, from_zero = first_pass;
     int cur = 0;
     const int max_sweeps = 8 * (E + 2) + 16 * kFinMaxCyclesPerPass;
@@ -376,8 +390,25 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
             // the copy to be lowered is two sweeps old (labels never rise): it first catches up with the current one
             for (int v = tid; v <= Z; v += kFinThreads) atomicMin(&kn[v], kc[v]);
             bool any = false;
-#pragma unroll 4
-            for (int i = tid; i < n_arcs; i += kFinThreads) {
+            {
+                long long da[kRegArcs], db[kRegArcs];
+#pragma unroll
+                for (int j = 0; j < kRegArcs; ++j) {
+                    da[j] = (long long)(kc[arc_from(wreg[j])] >> kIdxBits);
+                    db[j] = (long long)(kc[arc_to(wreg[j])] >> kIdxBits);
+                }
+#pragma unroll
+                for (int j = 0; j < kRegArcs; ++j) {
+                    const int c = arc_cost(wreg[j]);
+                    const long long cand = da[j] + c;
+                    if (c < kCostInf && cand < db[j]) {
+                        atomicMin(&kn[arc_to(wreg[j])],
+                                  ((unsigned long long)cand << kIdxBits) | (unsigned)(tid + j * kFinThreads));
+                        any = true;
+                    }
+                }
+            }
+            for (int i = tid + kRegArcs * kFinThreads; i < n_arcs; i += kFinThreads) {
                 const unsigned long long w = sh.arc[i];
                 const int c = arc_cost(w);
                 if (c >= kCostInf) continue;
@@ -425,8 +456,9 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
 #ifdef MS_FIN_PROF
         ++n_checks;
 #endif
-        // a cycle of the predecessor graph: follow the predecessors 256 steps by pointer doubling; a node that does
-        // not end at the root has landed on a cycle (wavefront 0, three nodes per lane; the others wait)
+        // cycles of the predecessor graph: follow the predecessors 256 steps by pointer doubling; a node that does
+        // not end at the root has landed on a cycle.  Every node has one predecessor, so the cycles are disjoint;
+        // each is named by its smallest node (wavefront 0, three nodes per lane; the others wait)
         if (wv == 0) {
             for (int v = lane; v <= R; v += 64) {
                 int pv = R;
@@ -435,6 +467,8 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
                     if (idx != kIdxRoot) pv = arc_from(sh.arc[idx]);
                 }
                 sh.jump[0][v] = pv;
+                sh.pred[v] = pv;
+                sh.cycflag[v] = 0;
             }
             int jb = 0;
             for (int rep = 0; rep < 8; ++rep) {
@@ -447,103 +481,139 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            int best = R;
             for (int v = lane; v <= Z; v += 64) {
                 const int l = sh.jump[jb][v];
-                best = l < best ? l : best;
+                if (l == R) continue;
+                int m = l, x = sh.pred[l];
+                for (int step = 0; step <= E + 1 && x != l && x != R; ++step) {
+                    m = x < m ? x : m;
+                    x = sh.pred[x];
+                }
+                if (x == l) sh.cycflag[m] = 1;
             }
-            for (int off = 32; off > 0; off >>= 1) {
-                const int o = __shfl_xor(best, off);
-                best = o < best ? o : best;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            // the flagged nodes in ascending order (the order in which the cycles are cancelled is fixed)
+            int n_found = 0;
+            for (int v0 = 0; v0 <= Z; v0 += 64) {
+                const int v = v0 + lane;
+                const bool f = v <= Z && sh.cycflag[v] != 0;
+                const unsigned long long bal = __ballot(f);
+                if (f) sh.cyclist[n_found + __popcll(bal & ((1ull << lane) - 1))] = v;
+                n_found += __popcll(bal);
             }
-            if (lane == 0) sh.cyc_node = best;
+            if (lane == 0) sh.n_found = n_found;
         }
         __syncthreads();
         MS_FP(c_check)
-        if (sh.cyc_node == R) continue;
-        if (sh.cycles >= kFinMaxCyclesPerPass) break;
-        // ---- cancel the cycle through sh.cyc_node ----
-        if (tid == 0) {
-            // walking the predecessors lists the nodes x of the cycle; the arc into x is the one in its label
-            int n = 0, x = sh.cyc_node;
-            long long sum = 0;
-            bool ok = true;
-            do {
-                sh.cyc[n++] = x;
-                const unsigned idx = (unsigned)(sh.key[cur][x] & kIdxRoot);
-                if (idx == kIdxRoot || arc_cost(sh.arc[idx]) >= kCostInf) {
-                    ok = false;
-                    break;
+        const int n_found = sh.n_found;
+        if (n_found == 0) continue;
+        bool stop = false;
+        int done_here = 0;
+        for (int ci = 0; ci < n_found; ++ci) {
+            if (sh.cycles >= kFinMaxCyclesPerPass) {
+                stop = true;
+                break;
+            }
+            // ---- cancel the cycle through sh.cyclist[ci] ----
+            if (tid == 0) {
+                // walking the predecessors lists the nodes x of the cycle; the arc into x is the one in its label.
+                // An earlier cancellation of this round may have withdrawn one of its arcs: then it is left alone.
+                const int c0 = sh.cyclist[ci];
+                int n = 0, x = c0;
+                long long sum = 0;
+                bool ok = true;
+                do {
+                    sh.cyc[n++] = x;
+                    const unsigned idx = (unsigned)(sh.key[cur][x] & kIdxRoot);
+                    if (idx == kIdxRoot || arc_cost(sh.arc[idx]) >= kCostInf) {
+                        ok = false;
+                        break;
+                    }
+                    sum += arc_cost(sh.arc[idx]);
+                    x = arc_from(sh.arc[idx]);
+                } while (x != c0 && n <= E + 1);
+                sh.n_cyc = (ok && x == c0 && sum < 0) ? n : 0;
+                sh.cyc_sum = sum;
+                sh.bad = 0;
+                sh.n_moved = 0;
+            }
+            __syncthreads();
+            const int n = sh.n_cyc;
+            if (n == 0) {                                             // the same for every thread
+                __syncthreads();                                      // (the next walk writes sh.n_cyc again)
+                continue;
+            }
+            // every token move is checked before anything is changed: wavefront w takes the arcs w, w + 16, ...
+            for (int i = wv; i < n; i += kFinThreads / 64) {
+                const unsigned idx = (unsigned)(sh.key[cur][sh.cyc[i]] & kIdxRoot);
+                const int u = sh.atok[idx];
+                if (u < 0) continue;                                  // an arc of Z: no token moves
+                const int a = arc_from(sh.arc[idx]), x = arc_to(sh.arc[idx]);
+                const int sl = (lane < k && u < T) ? assign[(size_t)u * k + lane] : -1;
+                const int n_a = __popcll(__ballot(lane < k && sl == a));
+                const int n_x = __popcll(__ballot(lane < k && sl == x));
+                if (lane == 0 && (u >= T || n_a != 1 || n_x != 0)) sh.bad = 1;
+            }
+            __syncthreads();
+            if (sh.bad) {
+                // a recorded arc that the assignment does not bear out: the finisher hands back to the auction
+                if (tid == 0) sh.give_up = 1;
+                stop = true;
+                break;
+            }
+            for (int i = wv; i < n; i += kFinThreads / 64) {
+                const unsigned idx = (unsigned)(sh.key[cur][sh.cyc[i]] & kIdxRoot);
+                const int u = sh.atok[idx];
+                const int a = arc_from(sh.arc[idx]), x = arc_to(sh.arc[idx]);
+                if (u >= 0) {
+                    if (lane < k && assign[(size_t)u * k + lane] == a) assign[(size_t)u * k + lane] = x;
+                    if (lane == 0) {
+                        sh.moved[atomicAdd(&sh.n_moved, 1)] = u;
+                        // marked for the arc passes to come (its bid keys no longer describe it) and listed; a token
+                        // listed twice is only evaluated twice
+                        atomicOr(&fa.bits[u >> 5], 1u << (u & 31));
+                        const int pos = atomicAdd(&sh.n_moved_all, 1);
+                        if (pos < kFinMovedCap / 8) sh.moved_all[pos] = u;
+                        else sh.give_up = 1;
+                    }
+                } else if (lane == 0) {
+                    if (x == Z) atomicAdd(&sh.load[a], 1);            // a keeps the token it received
+                    else atomicAdd(&sh.load[x], -1);                  // x gives one away without getting one back
                 }
-                sum += arc_cost(sh.arc[idx]);
-                x = arc_from(sh.arc[idx]);
-            } while (x != sh.cyc_node && n <= E + 1);
-            sh.n_cyc = (ok && x == sh.cyc_node) ? n : 0;
-            sh.cyc_sum = sum;
-            sh.bad = (sh.n_cyc == 0 || sum >= 0) ? 1 : 0;
-            sh.n_moved = 0;
+            }
+            if (tid == 0) {
+                sh.dirty += 1;
+                sh.cycles += 1;
+            }
+            ++done_here;
+            __syncthreads();
+            // arcs realised by a token that has moved are no longer known: they are withdrawn until the next pass
+            {
+                const int nm = sh.n_moved;
+                for (int i = 2 * E + tid; i < n_arcs; i += kFinThreads) {
+                    const int u = sh.atok[i];
+                    bool hit = false;
+                    for (int m = 0; m < nm; ++m) hit |= (sh.moved[m] == u);
+                    if (hit) sh.arc[i] = arc_pack(kCostInf, 0, 0);
+                }
+                set_z_arcs();
+            }
+            __syncthreads();
         }
-        __syncthreads();
-        const int n = sh.n_cyc;
-        // every token move is checked before anything is changed: wavefront w takes the arcs w, w + 16, ...
-        for (int i = wv; i < n; i += kFinThreads / 64) {
-            const unsigned idx = (unsigned)(sh.key[cur][sh.cyc[i]] & kIdxRoot);
-            const int u = sh.atok[idx];
-            if (u < 0) continue;                                  // an arc of Z: no token moves
-            const int a = arc_from(sh.arc[idx]), x = arc_to(sh.arc[idx]);
-            const int sl = (lane < k && u < T) ? assign[(size_t)u * k + lane] : -1;
-            const int n_a = __popcll(__ballot(lane < k && sl == a));
-            const int n_x = __popcll(__ballot(lane < k && sl == x));
-            if (lane == 0 && (u >= T || n_a != 1 || n_x != 0)) sh.bad = 1;
-        }
-        __syncthreads();
-        if (sh.bad) {
-            if (tid == 0) sh.give_up = 1;
+        if (stop) {
             __syncthreads();
             break;
         }
-        for (int i = wv; i < n; i += kFinThreads / 64) {
-            const unsigned idx = (unsigned)(sh.key[cur][sh.cyc[i]] & kIdxRoot);
-            const int u = sh.atok[idx];
-            const int a = arc_from(sh.arc[idx]), x = arc_to(sh.arc[idx]);
-            if (u >= 0) {
-                if (lane < k && assign[(size_t)u * k + lane] == a) assign[(size_t)u * k + lane] = x;
-                if (lane == 0) {
-                    sh.moved[atomicAdd(&sh.n_moved, 1)] = u;
-                    // marked for the arc passes to come (its bid keys no longer describe it) and listed; a token
-                    // listed twice is only evaluated twice
-                    atomicOr(&fa.bits[u >> 5], 1u << (u & 31));
-                    const int pos = atomicAdd(&sh.n_moved_all, 1);
-                    if (pos < kFinMovedCap / 8) sh.moved_all[pos] = u;
-                    else sh.give_up = 1;
-                }
-            } else if (lane == 0) {
-                if (x == Z) atomicAdd(&sh.load[a], 1);            // a keeps the token it received
-                else atomicAdd(&sh.load[x], -1);                  // x gives one away without getting one back
-            }
-        }
-        if (tid == 0) {
-            sh.dirty += 1;
-            sh.cycles += 1;
+        // The potentials stay; the predecessor arcs start again (an arc that is gone must not be followed, and what
+        // is left of the other cycles shows again as soon as their nodes are lowered).
+        for (int v = tid; v <= R; v += kFinThreads) {
+            sh.key[0][v] |= kIdxRoot;
+            sh.key[1][v] |= kIdxRoot;
         }
         __syncthreads();
-        // arcs realised by a token that has moved are no longer known: they are withdrawn until the next pass.
-        // The potentials stay; the predecessor arcs start again (an arc that is gone must not be followed).
-        {
-            const int nm = sh.n_moved;
-            for (int i = 2 * E + tid; i < n_arcs; i += kFinThreads) {
-                const int u = sh.atok[i];
-                bool hit = false;
-                for (int m = 0; m < nm; ++m) hit |= (sh.moved[m] == u);
-                if (hit) sh.arc[i] = arc_pack(kCostInf, 0, 0);
-            }
-            for (int v = tid; v <= R; v += kFinThreads) {
-                sh.key[0][v] |= kIdxRoot;
-                sh.key[1][v] |= kIdxRoot;
-            }
-            set_z_arcs();
-        }
-        __syncthreads();
+        if (done_here > 0) load_arcs();
         MS_FP(c_cancel)
     }
 #ifdef MS_FIN_PROF
