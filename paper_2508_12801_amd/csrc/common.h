@@ -61,7 +61,7 @@ struct SolverState {
 
 struct WorkspaceLayout {
     size_t state_off, theta_off, gcount_off, klist_off, wcnt_off, wmoves_off, cand_off, tiles_off, cap_off, aux_off,
-        wt_off, dbase_off, fin_off, total;
+        wt_off, dbase_off, fin_off, tri_off, total;
     int n_tiles, max_wg;
 };
 
@@ -103,6 +103,14 @@ int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long 
                        const int *cap, int Ce, int T, int E, int k, char *ws, int rows, int n_wg, int first_pass,
                        int passes, int total_passes, long long bound_mult, int *host_words, hipStream_t s);
 size_t finish_area_bytes(int T);          // bytes of WorkspaceLayout::fin_off's region
+// Arc lists of the finisher's first pass: key block w owns fin_seg_cap(rows, k) consecutive entries; the region
+// holds fin_tri_entries() of them (enough for every geometry the solver picks: rows * k <= 1024 per block).
+inline int fin_seg_cap(int rows, int k)
+{
+    const int c = rows * k / 16;
+    return c < 8 ? 8 : c;
+}
+inline size_t fin_tri_entries(int T, int k, int max_wg) { return ((size_t)T + 1024) * k / 16 + 8 * (size_t)max_wg + 8; }
 // --- softtopk.hip
 int32_t softtopk_run(const float *logits, int T, int E, int k, float t, int shift, float *scores, int32_t *q,
                      hipStream_t s);

@@ -31,6 +31,10 @@ constexpr long long kDistInf = (long long)1 << 60;
 constexpr int kFinThreads = 1024;
 constexpr int kFinMaxCyclesPerPass = 256;
 
+#ifdef MS_FIN_PROF
+__device__ int g_fin_triples[4];
+#endif
+
 __device__ __forceinline__ long long shfl_xor_i64(long long v, int off)
 {
     unsigned lo = (unsigned)v, hi = (unsigned)((unsigned long long)v >> 32);
@@ -91,14 +95,27 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_begin(SolverState *st, unsi
 }
 
 // The arcs that token u offers: for the expert `only` it holds (or every expert it holds when only < 0) and every
-// expert e it does not hold, the loss of moving it there in reduced form; arcs under the bound go into the matrix
-// (smallest loss wins, then the lower token id).  One wavefront; lane l owns experts l and l + 64.
-template <int TEPL>
-__device__ __forceinline__ void token_arcs(const int32_t *__restrict__ q, const int32_t *__restrict__ assign,
-                                           const long long (&p)[TEPL], int sb, int u, int only, long long B,
-                                           unsigned long long *M, int E, int k, int lane)
+// expert e it does not hold, the loss of moving it there in reduced form; arcs under the bound count.  With MIN they
+// go into the matrix (smallest loss wins, then the lower token id); with an output list they are also written there
+// in a fixed order (slot of the hold, then expert), the j-th of them at out_base + j while that is below out_end.
+// Returns their number (the same in every lane).  One wavefront; lane l owns experts l and l + 64.  The assignment
+// row is read at device scope: the Bellman-Ford workgroup calls this for tokens it has just moved.
+__device__ __forceinline__ unsigned long long arc_pack(int cost, int a, int b)
 {
-    const int a = lane < k ? assign[(size_t)u * k + lane] : -1;
+    return ((unsigned long long)(unsigned)cost << 32) | (unsigned)((a << 8) | b);
+}
+__device__ __forceinline__ int arc_cost(unsigned long long w) { return (int)(unsigned)(w >> 32); }
+__device__ __forceinline__ int arc_from(unsigned long long w) { return (int)((w >> 8) & 255); }
+__device__ __forceinline__ int arc_to(unsigned long long w) { return (int)(w & 255); }
+
+template <int TEPL, bool MIN>
+__device__ __forceinline__ int token_arcs(const int32_t *__restrict__ q, const int32_t *assign,
+                                          const long long (&p)[TEPL], int sb, int u, int only, long long B,
+                                          unsigned long long *M, int E, int k, int lane, unsigned long long *out_arc,
+                                          int *out_tok, int out_base, int out_end)
+{
+    const int a = lane < k ? __hip_atomic_load(&assign[(size_t)u * k + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                           : -1;
     long long v[TEPL];
 #pragma unroll
     for (int m = 0; m < TEPL; ++m) {
@@ -111,6 +128,7 @@ __device__ __forceinline__ void token_arcs(const int32_t *__restrict__ q, const 
         const int h = __builtin_amdgcn_readlane(a, s);
         if (h >= 0 && (h & 63) == lane) heldm |= 1u << (h >> 6);
     }
+    int cnt = 0;
     for (int s = 0; s < k; ++s) {
         const int h = __builtin_amdgcn_readlane(a, s);
         if (h < 0 || (only >= 0 && h != only)) continue;
@@ -119,40 +137,61 @@ __device__ __forceinline__ void token_arcs(const int32_t *__restrict__ q, const 
 #pragma unroll
         for (int m = 0; m < TEPL; ++m) {
             const int e = lane + 64 * m;
-            if (e < E && !((heldm >> m) & 1u)) {
-                const long long rc = vh - v[m];
-                if (rc < B && rc > -kRcBias) {
+            const long long rc = vh - v[m];
+            const bool ok = e < E && !((heldm >> m) & 1u) && rc < B && rc > -kRcBias;
+            const unsigned long long bal = __ballot(ok);
+            if (ok) {
+                if (MIN) {
+#ifdef MS_FIN_PROF
+                    atomicAdd(&g_fin_triples[0], 1);
+#endif
                     const unsigned long long pk =
                         ((unsigned long long)(rc + kRcBias) << kTokBits) | (unsigned long long)u;
                     atomicMin(&M[(size_t)h * E + e], pk);
                 }
+                if (out_arc) {
+                    const int pos = out_base + cnt + __popcll(bal & ((1ull << lane) - 1));
+                    if (pos < out_end) {
+                        out_arc[pos] = arc_pack((int)rc, h, e);
+                        out_tok[pos] = u;
+                    }
+                }
             }
+            cnt += __popcll(bal);
         }
     }
+    return cnt;
 }
 
-// Arc matrix of one pass.  The bid keys of the auction's last round already hold, for every (token, expert) hold,
-// how far the hold is above the token's best alternative: key >> tbits = S*q - best alternative + eps.  Only holds
+// Arcs of one pass.  The bid keys of the auction's last round already hold, for every (token, expert) hold, how
+// far the hold is above the token's best alternative: key >> tbits = S*q - best alternative + eps.  Only holds
 // whose margin is under the bound can offer an arc under the bound, and they are few; so the key blocks are
 // scanned (8 bytes per hold) and only the rows of those holds are read.  Tokens that a cancelled cycle has moved
 // are taken from the list instead (their keys are out of date): all their holds are evaluated.
+// Every arc goes into the matrix (smallest loss per expert pair).  The first pass also writes ALL arcs under the
+// bound as a list, block w into its own segment of seg_cap entries in a fixed order (holds by their place in the
+// key block, then by expert), with their number in tri_cnt[w] (-1: the segment is too small).  With the complete
+// list the Bellman-Ford workgroup can keep the arcs up to date itself while it moves tokens, so one pass is enough.
 // Grid: one workgroup per key block (n_wg), 256 threads.
 template <int TEPL>
-__global__ __launch_bounds__(256) void k_fin_arcs(const int32_t *__restrict__ q, const int32_t *__restrict__ assign,
+__global__ __launch_bounds__(256) void k_fin_arcs(const int32_t *__restrict__ q, const int32_t *assign,
                                                   const long long *__restrict__ theta2,
                                                   const SolverState *__restrict__ st,
                                                   const long long *__restrict__ klist, const int *__restrict__ wcnt,
                                                   unsigned long long *M, char *fin_base, int T, int E, int k,
-                                                  int rows)
+                                                  int rows, unsigned long long *tri_arc, int *tri_tok, int *tri_cnt,
+                                                  int seg_cap)
 {
     if (st->fin != 1) return;
     __shared__ short s_e[1024];
     __shared__ short s_list[1024];
+    __shared__ int s_cnt[1024];
     __shared__ long long s_p[kFinMaxE];
-    __shared__ int s_n;
+    __shared__ int s_wn[4], s_total;
     const FinArea fa = fin_area(fin_base, T);
     const long long B = st->fin_bound, eps = st->eps;
     const int sb = st->sbits, tb = st->tbits;
+    const bool want_list = st->fin_passes == 0;
     const long long tmask = ((long long)1 << tb) - 1;
     const long long *theta = theta2 + (st->round & 1) * kMaxE;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, w = blockIdx.x;
@@ -162,7 +201,6 @@ __global__ __launch_bounds__(256) void k_fin_arcs(const int32_t *__restrict__ q,
     const int nslots = rows_here * k;
     for (int e = tid; e < E; e += 256) s_p[e] = theta[e] >> tb;
     for (int i = tid; i < nslots; i += 256) s_e[i] = -1;
-    if (tid == 0) s_n = 0;
     __syncthreads();
     for (int e = tid; e < E; e += 256) {
         const int mt = wcnt[(size_t)w * E + e];
@@ -172,30 +210,75 @@ __global__ __launch_bounds__(256) void k_fin_arcs(const int32_t *__restrict__ q,
     }
     __syncthreads();
     const long long *blk = klist + (size_t)w * rows * k;
-    for (int idx = tid; idx < nslots; idx += 256) {
-        const int e = s_e[idx];
-        if (e < 0) continue;
-        const long long key = blk[idx];
-        const long long margin = (key >> tb) - eps - s_p[e];       // the hold's value minus the best alternative's
-        if (margin >= B) continue;
-        const int u = (int)(key & tmask);
-        if (u < row0 || u >= row0 + rows_here) continue;           // never with keys of this block
-        if (fa.bits[u >> 5] & (1u << (u & 31))) continue;          // moved since: taken from the list
-        s_list[atomicAdd(&s_n, 1)] = (short)idx;
+    // the holds under the bound, in the order of their places in the key block
+    int n = 0;
+    for (int i0 = 0; i0 < nslots; i0 += 256) {
+        const int idx = i0 + tid;
+        bool take = false;
+        if (idx < nslots) {
+            const int e = s_e[idx];
+            if (e >= 0) {
+                const long long key = blk[idx];
+                const long long margin = (key >> tb) - eps - s_p[e];   // the hold's value minus the best alternative's
+                const int u = (int)(key & tmask);
+                take = margin < B && u >= row0 && u < row0 + rows_here &&     // (never outside with keys of this block)
+                       !(fa.bits[u >> 5] & (1u << (u & 31)));                // moved since: taken from the list
+            }
+        }
+        const unsigned long long bal = __ballot(take);
+        if (lane == 0) s_wn[wv] = __popcll(bal);
+        __syncthreads();
+        int before = n;
+        for (int x = 0; x < wv; ++x) before += s_wn[x];
+        if (take) s_list[before + __popcll(bal & ((1ull << lane) - 1))] = (short)idx;
+        n += s_wn[0] + s_wn[1] + s_wn[2] + s_wn[3];
+        __syncthreads();
     }
-    __syncthreads();
     long long p[TEPL];
 #pragma unroll
     for (int m = 0; m < TEPL; ++m) p[m] = lane + 64 * m < E ? s_p[lane + 64 * m] : 0;
-    const int n = s_n;
     for (int i = wv; i < n; i += 4) {
         const int idx = s_list[i];
         const int u = (int)(blk[idx] & tmask);
-        token_arcs<TEPL>(q, assign, p, sb, u, s_e[idx], B, M, E, k, lane);
+        const int c = token_arcs<TEPL, true>(q, assign, p, sb, u, s_e[idx], B, M, E, k, lane, nullptr, nullptr, 0, 0);
+        if (lane == 0) s_cnt[i] = c;
+    }
+    if (want_list) {
+        __syncthreads();
+        if (wv == 0) {
+            // exclusive prefix sums of the per-hold counts (one wavefront, chunks of 64 holds)
+            int run = 0;
+            for (int i0 = 0; i0 < n; i0 += 64) {
+                const int c = i0 + lane < n ? s_cnt[i0 + lane] : 0;
+                int inc = c;
+                for (int off = 1; off < 64; off <<= 1) {
+                    const int o = __shfl_up(inc, off);
+                    if (lane >= off) inc += o;
+                }
+                if (i0 + lane < n) s_cnt[i0 + lane] = run + inc - c;
+                run += __shfl(inc, 63);
+            }
+            if (lane == 0) {
+                s_total = run;
+                tri_cnt[w] = run <= seg_cap ? run : -1;
+            }
+        }
+        __syncthreads();
+        const int total = s_total;
+        if (total > 0 && total <= seg_cap) {
+            const int base = w * seg_cap;
+            for (int i = wv; i < n; i += 4) {
+                const int idx = s_list[i];
+                const int u = (int)(blk[idx] & tmask);
+                (void)token_arcs<TEPL, false>(q, assign, p, sb, u, s_e[idx], B, M, E, k, lane, tri_arc, tri_tok,
+                                              base + s_cnt[i], base + seg_cap);
+            }
+        }
     }
     // the moved tokens, spread over all wavefronts of the grid
     const int nm = fa.n_moved[0] < kFinMovedCap ? fa.n_moved[0] : kFinMovedCap;
-    for (int i = w * 4 + wv; i < nm; i += gridDim.x * 4) token_arcs<TEPL>(q, assign, p, sb, fa.list[i], -1, B, M, E, k, lane);
+    for (int i = w * 4 + wv; i < nm; i += gridDim.x * 4)
+        (void)token_arcs<TEPL, true>(q, assign, p, sb, fa.list[i], -1, B, M, E, k, lane, nullptr, nullptr, 0, 0);
 }
 
 constexpr int kFinArcs = 12288;               // arcs the Bellman-Ford workgroup can hold (more: the auction goes on)
@@ -204,13 +287,6 @@ constexpr int kIdxBits = 14;
 constexpr unsigned kIdxRoot = (1u << kIdxBits) - 1;  // "no predecessor arc"
 constexpr long long kZCostMax = (long long)1 << 30;  // prices must stay under this for the spare-capacity arcs
 
-__device__ __forceinline__ unsigned long long arc_pack(int cost, int a, int b)
-{
-    return ((unsigned long long)(unsigned)cost << 32) | (unsigned)((a << 8) | b);
-}
-__device__ __forceinline__ int arc_cost(unsigned long long w) { return (int)(unsigned)(w >> 32); }
-__device__ __forceinline__ int arc_from(unsigned long long w) { return (int)((w >> 8) & 255); }
-__device__ __forceinline__ int arc_to(unsigned long long w) { return (int)(w & 255); }
 
 struct FinShared {
     // arc i: reduced cost (signed, kCostInf = slot empty or arc withdrawn) in the high word, from << 8 | to in the
@@ -230,7 +306,10 @@ struct FinShared {
     int scan[kFinMaxE * kFinMaxE / kFinThreads][kFinThreads / 64];           // arcs per (chunk of the matrix, wavefront) while the list is built
     int moved_all[kFinMovedCap / 8];          // tokens moved in this pass, for the list in memory
     int changed[3];       // one flag per sweep, three in rotation (a flag is cleared two sweeps after its last read)
+    int newcnt[kFinMaxE + 2];                 // arcs that every token moved by the current cycle offers anew
+    int wsum[kFinThreads / 64];
     int n_arcs, n_found, n_cyc, n_moved, n_moved_all, give_up, dirty, cycles, bad;
+    int complete;         // the arc list holds EVERY arc under the bound (kept so while tokens move): one pass can certify
     long long cyc_sum;
 };
 
@@ -246,7 +325,11 @@ struct FinShared {
 __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, unsigned long long *M, int32_t *assign,
                                                             long long *theta2, const int *__restrict__ loads2,
                                                             char *fin_base, const int *__restrict__ cap, int Ce,
-                                                            int T, int E, int k, int last_pass)
+                                                            int T, int E, int k, int last_pass,
+                                                            const int32_t *__restrict__ q,
+                                                            const unsigned long long *__restrict__ tri_arc,
+                                                            const int *__restrict__ tri_tok,
+                                                            const int *__restrict__ tri_cnt, int seg_cap, int n_wg)
 {
     if (st->fin != 1) return;
     __shared__ FinShared sh;
@@ -295,6 +378,52 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
     };
     set_z_arcs();
     {
+        // First pass: the arc kernel has left every arc under the bound in per-block segments.  If no segment ran
+        // over and all of them fit the list, they are taken in block order (a fixed order) and the list is complete.
+        int mine = 0, bad_seg = 0;
+        const int per = (n_wg + kFinThreads - 1) / kFinThreads, w0 = tid * per;
+        if (first_pass) {
+            for (int w = w0; w < w0 + per && w < n_wg; ++w) {
+                const int c = tri_cnt[w];
+                bad_seg |= c < 0;
+                mine += c > 0 ? c : 0;
+            }
+        }
+        int inc = mine;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(inc, off);
+            if (lane >= off) inc += o;
+        }
+        if (lane == 63) sh.wsum[wv] = inc;
+        const int any_bad = __syncthreads_or(bad_seg);
+        int before = inc - mine, total = 0;
+        for (int x = 0; x < kFinThreads / 64; ++x) {
+            const int t = sh.wsum[x];
+            before += x < wv ? t : 0;
+            total += t;
+        }
+        const bool complete = first_pass && !any_bad && 2 * E + total <= kFinArcs;
+        if (complete) {
+            int pos = 2 * E + before;
+            for (int w = w0; w < w0 + per && w < n_wg; ++w) {
+                const int c = tri_cnt[w];
+                for (int j = 0; j < c; ++j) {
+                    sh.arc[pos] = tri_arc[(size_t)w * seg_cap + j];
+                    sh.atok[pos] = tri_tok[(size_t)w * seg_cap + j];
+                    ++pos;
+                }
+            }
+        }
+        if (tid == 0) {
+            sh.complete = complete ? 1 : 0;
+            if (complete) sh.n_arcs = 2 * E + total;
+#ifdef MS_FIN_PROF
+            printf("[fin] arc list: %d arcs in %d segments of %d, complete %d\n", total, n_wg, seg_cap, (int)complete);
+#endif
+        }
+        __syncthreads();
+    }
+    if (!sh.complete) {
         // the matrix is read in chunks of kFinThreads consecutive entries (all loads are issued at once); an arc's
         // place in the list follows from the number of arcs before it in matrix order
         const int n = E * E;
@@ -349,12 +478,13 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
             sh.n_arcs = na < kFinArcs ? na : kFinArcs;
             if (na > kFinArcs) sh.give_up = 1;          // more arcs than the list holds
 #ifdef MS_FIN_PROF
-            printf("[fin] arcs under the bound: %d (+ %d for Z)\n", total, 2 * E);
+            printf("[fin] arcs under the bound: %d (+ %d for Z); triples so far: %d (< B/2: %d, < B/4: %d, < B/8: %d)\n", total, 2 * E, g_fin_triples[0], g_fin_triples[1], g_fin_triples[2], g_fin_triples[3]);
+            g_fin_triples[0] = g_fin_triples[1] = g_fin_triples[2] = g_fin_triples[3] = 0;
 #endif
         }
     }
     __syncthreads();
-    const int n_arcs = sh.n_arcs;
+    int n_arcs = sh.n_arcs;
 
     // The first kRegArcs arcs of every thread (arc tid + j * kFinThreads) are kept in registers between sweeps, so
     // that a sweep issues all its label reads at once; they are read again whenever arcs have been withdrawn.
@@ -368,7 +498,7 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
         }
     };
     load_arcs();
-    bool converged = false, from_zero = first_pass;
+    bool converged = false, fresh = first_pass;     // fresh: the potentials started from zero and nothing was cancelled since
     int cur = 0;
     const int max_sweeps = 8 * (E + 2) + 16 * kFinMaxCyclesPerPass;
 #ifdef MS_FIN_PROF
@@ -430,7 +560,7 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
             // Stopped relaxing.  If nothing was cancelled this pass can certify, provided the potentials spread
             // less than the bound; potentials carried over from earlier passes can spread more than needed, so
             // in that case the sweeps run once more from zero (no cycle is left: they converge).
-            if (sh.dirty == 0 && !from_zero) {
+            if ((sh.dirty == 0 || sh.complete) && !fresh) {
                 long long lo = kDistInf, hi = -kDistInf;
                 for (int v = 0; v <= Z; ++v) {
                     const long long dv = (long long)(sh.key[cur][v] >> kIdxBits);
@@ -444,7 +574,7 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
                         sh.key[0][v] = k0;
                         sh.key[1][v] = k0;
                     }
-                    from_zero = true;
+                    fresh = true;
                     __syncthreads();
                     continue;
                 }
@@ -537,7 +667,7 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
                 sh.n_cyc = (ok && x == c0 && sum < 0) ? n : 0;
                 sh.cyc_sum = sum;
                 sh.bad = 0;
-                sh.n_moved = 0;
+                sh.n_moved = sh.n_cyc;            // moved[i] = the token on arc i of the cycle (-1: an arc of Z)
             }
             __syncthreads();
             const int n = sh.n_cyc;
@@ -551,7 +681,9 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
                 const int u = sh.atok[idx];
                 if (u < 0) continue;                                  // an arc of Z: no token moves
                 const int a = arc_from(sh.arc[idx]), x = arc_to(sh.arc[idx]);
-                const int sl = (lane < k && u < T) ? assign[(size_t)u * k + lane] : -1;
+                const int sl = (lane < k && u < T) ? __hip_atomic_load(&assign[(size_t)u * k + lane], __ATOMIC_RELAXED,
+                                                                       __HIP_MEMORY_SCOPE_AGENT)
+                                                   : -1;
                 const int n_a = __popcll(__ballot(lane < k && sl == a));
                 const int n_x = __popcll(__ballot(lane < k && sl == x));
                 if (lane == 0 && (u >= T || n_a != 1 || n_x != 0)) sh.bad = 1;
@@ -568,9 +700,11 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
                 const int u = sh.atok[idx];
                 const int a = arc_from(sh.arc[idx]), x = arc_to(sh.arc[idx]);
                 if (u >= 0) {
-                    if (lane < k && assign[(size_t)u * k + lane] == a) assign[(size_t)u * k + lane] = x;
+                    if (lane < k && __hip_atomic_load(&assign[(size_t)u * k + lane], __ATOMIC_RELAXED,
+                                                      __HIP_MEMORY_SCOPE_AGENT) == a)
+                        __hip_atomic_store(&assign[(size_t)u * k + lane], x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     if (lane == 0) {
-                        sh.moved[atomicAdd(&sh.n_moved, 1)] = u;
+                        sh.moved[i] = u;
                         // marked for the arc passes to come (its bid keys no longer describe it) and listed; a token
                         // listed twice is only evaluated twice
                         atomicOr(&fa.bits[u >> 5], 1u << (u & 31));
@@ -579,6 +713,7 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
                         else sh.give_up = 1;
                     }
                 } else if (lane == 0) {
+                    sh.moved[i] = -1;
                     if (x == Z) atomicAdd(&sh.load[a], 1);            // a keeps the token it received
                     else atomicAdd(&sh.load[x], -1);                  // x gives one away without getting one back
                 }
@@ -601,6 +736,44 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
                 set_z_arcs();
             }
             __syncthreads();
+            if (sh.complete) {
+                // ... and, with a complete list, the arcs the moved tokens offer from where they are now join it
+                // (counted first, then written behind the list in the order of the cycle), so the list stays complete
+                const int nm = sh.n_moved;
+                long long pp[2];
+                pp[0] = lane < E ? sh.p[lane] : 0;
+                pp[1] = lane + 64 < E ? sh.p[lane + 64] : 0;
+                const int sbq = st->sbits;
+                for (int i = wv; i < nm; i += kFinThreads / 64) {
+                    const int u = sh.moved[i];
+                    bool skip = u < 0;
+                    for (int j = 0; j < i; ++j) skip |= sh.moved[j] == u;      // a token on two arcs is taken once
+                    const int c = skip ? 0
+                                       : token_arcs<2, false>(q, assign, pp, sbq, u, -1, B, M, E, k, lane, nullptr,
+                                                              nullptr, 0, 0);
+                    if (lane == 0) sh.newcnt[i] = skip ? -1 : c;
+                }
+                __syncthreads();
+                if (tid == 0) {
+                    int run = n_arcs;
+                    for (int i = 0; i < nm; ++i) {
+                        const int c = sh.newcnt[i];
+                        sh.newcnt[i] = c < 0 ? -1 : run;
+                        run += c < 0 ? 0 : c;
+                    }
+                    if (run > kFinArcs) sh.complete = 0;        // no room: from here on as without the list
+                    else sh.n_arcs = run;
+                }
+                __syncthreads();
+                if (sh.complete) {
+                    for (int i = wv; i < nm; i += kFinThreads / 64)
+                        if (sh.newcnt[i] >= 0)
+                            (void)token_arcs<2, false>(q, assign, pp, sbq, sh.moved[i], -1, B, M, E, k, lane, sh.arc,
+                                                       sh.atok, sh.newcnt[i], kFinArcs);
+                    n_arcs = sh.n_arcs;
+                }
+                __syncthreads();
+            }
         }
         if (stop) {
             __syncthreads();
@@ -613,7 +786,10 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
             sh.key[1][v] |= kIdxRoot;
         }
         __syncthreads();
-        if (done_here > 0) load_arcs();
+        if (done_here > 0) {
+            load_arcs();
+            fresh = false;
+        }
         MS_FP(c_cancel)
     }
 #ifdef MS_FIN_PROF
@@ -631,7 +807,7 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
     }
     if (sh.give_up || !converged) {
         if (tid == 0) st->fin = (sh.give_up || last_pass) ? 3 : 1;
-    } else if (sh.dirty > 0) {
+    } else if (sh.dirty > 0 && !sh.complete) {
         if (tid == 0 && last_pass) st->fin = 3;               // still pending and no pass left
     } else {
         // nothing was cancelled and the potentials stopped relaxing: no negative cycle among the recorded arcs.
@@ -740,17 +916,23 @@ int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long 
     if (finish_area_bytes(T) > L.wt_off - L.fin_off) return MAXSCORE_ERR_WORKSPACE;      // layout and area must agree
     const long long *klist = (const long long *)(ws + L.klist_off);
     const int *wcnt = (const int *)(ws + L.wcnt_off);
+    const int seg_cap = fin_seg_cap(rows, k);
+    const size_t tri_n = fin_tri_entries(T, k, L.max_wg);
+    if ((size_t)n_wg * seg_cap > tri_n || n_wg > L.max_wg) return MAXSCORE_ERR_WORKSPACE;
+    unsigned long long *tri_arc = (unsigned long long *)(ws + L.tri_off);
+    int *tri_tok = (int *)(ws + L.tri_off + 8 * tri_n);
+    int *tri_cnt = tri_tok + tri_n;
     if (first_pass == 0)
         hipLaunchKernelGGL(k_fin_begin, dim3(1), dim3(kFinThreads), 0, s, st, M, fin_base, T, E, bound_mult);
     for (int pass = first_pass; pass < first_pass + passes; ++pass) {
         if (E <= 64)
             hipLaunchKernelGGL(k_fin_arcs<1>, dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
-                               fin_base, T, E, k, rows);
+                               fin_base, T, E, k, rows, tri_arc, tri_tok, tri_cnt, seg_cap);
         else
             hipLaunchKernelGGL(k_fin_arcs<2>, dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
-                               fin_base, T, E, k, rows);
+                               fin_base, T, E, k, rows, tri_arc, tri_tok, tri_cnt, seg_cap);
         hipLaunchKernelGGL(k_fin_cycles, dim3(1), dim3(kFinThreads), 0, s, st, M, assign, theta2, loads2, fin_base, cap,
-                           Ce, T, E, k, pass == total_passes - 1 ? 1 : 0);
+                           Ce, T, E, k, pass == total_passes - 1 ? 1 : 0, q, tri_arc, tri_tok, tri_cnt, seg_cap, n_wg);
     }
     hipLaunchKernelGGL(k_fin_end, dim3(1), dim3(64), 0, s, st, T, host_words,
                        first_pass + passes == total_passes ? 1 : 0);

@@ -235,6 +235,7 @@ constexpr long long kMaxPriceIn = (long long)1 << 38;
 constexpr long long kFinPairBudget = 8000000;   // the finisher takes over at the first eps rung with pairs * eps (in reward units) under this
 constexpr int kFinPasses = 8;              // finisher passes per solve at most
 constexpr int kFinGroup = 4;               // passes enqueued at a time
+constexpr int kFinFirstGroup = 2;          // ... the first time (the first pass usually certifies: it keeps its arc list complete)
 constexpr long long kFinBoundMult = 32;    // arcs with a reduced cost of 32 eps or more stay out of the finisher's arc matrix
 constexpr int kWarmPhaseCap = 48;          // rounds after which a phase started from given prices goes back up the ladder
 
@@ -715,6 +716,10 @@ constexpr int kTailThreads = 1024;
 #ifdef MS_TAIL_PROF
 __device__ int g_tailstat[8];
 #endif
+#ifdef MAXSCORE_DEBUG_ENV
+__device__ int g_tailtrace[256 * 8];      // per tail run: round, iterations, victims, stop1, stop2, over_last, wall ticks
+__device__ int g_tailruns;
+#endif
 constexpr int kTailMoves = 16;            // hand over to the tail pass when a bid pass moved this few slots
 constexpr int kEarlyMoves = 16;           // a phase before the last one ends when a bid pass moved this few slots
 constexpr long long kKeyInf = (long long)1 << 62;
@@ -852,6 +857,10 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
 #else
 #define MS_TP(var)
 #endif
+#ifdef MAXSCORE_DEBUG_ENV
+    int dbg_vict = 0;
+    const long long dbg_t0 = wall_clock64();
+#endif
     int it = 0, over_last = 0;
     for (; it < max_iters; ++it) {
         // the counters are double-buffered by iteration parity: this iteration's were cleared during the last one
@@ -950,6 +959,9 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         const int stop1_now = s_stop1, over_now = s_over, nv_now = s_nv;
         const int vtok_l = s_vtok[lane], vexp_l = s_vexp[lane];
         over_last = over_now;
+#ifdef MAXSCORE_DEBUG_ENV
+        dbg_vict += nv_now;
+#endif
         if (stop1_now || !over_now) break;
         // 2. one wavefront per dropped token: the bid pass's row evaluation
         const int nv = nv_now < kTailVict ? nv_now : kTailVict;
@@ -1209,6 +1221,15 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         st->after_tail = (s_changed || s_moves) ? 1 : 0;
         st->tail_block = stopped;
         st->tail_go = 0;
+#ifdef MAXSCORE_DEBUG_ENV
+        {
+            const int r = g_tailruns < 255 ? g_tailruns : 255;
+            g_tailtrace[r * 8 + 0] = st->round; g_tailtrace[r * 8 + 1] = it; g_tailtrace[r * 8 + 2] = dbg_vict;
+            g_tailtrace[r * 8 + 3] = s_stop1; g_tailtrace[r * 8 + 4] = s_stop2; g_tailtrace[r * 8 + 5] = over_last;
+            g_tailtrace[r * 8 + 6] = (int)(wall_clock64() - dbg_t0); g_tailtrace[r * 8 + 7] = s_moves;
+            g_tailruns = r + 1;
+        }
+#endif
         st->tail_runs += 1;
         st->tail_iters += it;
 #ifdef MS_TAIL_PROF
@@ -1241,6 +1262,9 @@ static_assert(kSelThreads == kTailThreads, "the tail pass runs in a workgroup of
 // candidate lists the others publish in rounds that hand over to it.  TEPL = expert slots per lane of the tail
 // pass (the host picks the smallest that covers E: the kernel then carries one copy of that pass, and a smaller
 // kernel measurably runs faster here).
+#ifdef MAXSCORE_DEBUG_ENV
+__device__ long long g_roundtrace[2048 * 2];      // per round: moves | flags << 32, eps
+#endif
 template <int TEPL>
 __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restrict__ klist,
                                                         const int *__restrict__ wcnt, const int *__restrict__ wmoves,
@@ -1420,6 +1444,12 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             ns.status = MAXSCORE_ERR_HIP;
             ns.done = 1;
         }
+#ifdef MAXSCORE_DEBUG_ENV
+        if (cur_round < 2048) {
+            g_roundtrace[2 * cur_round] = (long long)moves | ((long long)(flags | (tail_go ? 8 : 0) | (early_end ? 16 : 0) | (quiet ? 32 : 0)) << 32);
+            g_roundtrace[2 * cur_round + 1] = cur_eps;
+        }
+#endif
         ns.round = round;
         ns.moves = (quiet || new_phase) ? T : moves;   // a new phase starts with many moves: no quick checks in its first round
         ns.tail_go = tail_go ? 1 : 0;
@@ -2038,12 +2068,13 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         volatile int *words = (volatile int *)hs->flag;
         words[4] = 0;
         const int fp = launched & 1;
-        // the passes are enqueued a few at a time (most solves are certified within the first group, and a pass
-        // that finds the work done still costs two launches)
+        // the passes are enqueued a few at a time (most solves are certified by the first pass, and a pass that
+        // finds the work done still costs two launches)
         int32_t rc = MAXSCORE_OK;
-        for (int p0 = 0; p0 < fin_passes; p0 += kFinGroup) {
-            rc = finish_enqueue(q, assign, st + fp, theta, gcount, cap, Ce, T, E, k, ws, rows, n_wg, p0,
-                                std::min(kFinGroup, fin_passes - p0), fin_passes, fin_bound_mult, hs->flag_dev + 4, s);
+        for (int p0 = 0, grp = kFinFirstGroup; p0 < fin_passes; p0 += grp, grp = kFinGroup) {
+            grp = std::min(grp, fin_passes - p0);
+            rc = finish_enqueue(q, assign, st + fp, theta, gcount, cap, Ce, T, E, k, ws, rows, n_wg, p0, grp, fin_passes,
+                                fin_bound_mult, hs->flag_dev + 4, s);
             if (rc != MAXSCORE_OK) {
                 (void)hipStreamSynchronize(s);
                 return rc;
@@ -2165,6 +2196,20 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     if (getenv("MAXSCORE_DEBUG"))
         fprintf(stderr, "[maxscore] finisher: stop_eps %lld state %d passes %d cycles %d (host saw state %d cycles %d)\n",
                 (long long)h.stop_eps, h.fin, h.fin_passes, h.fin_cycles, fin_state, fin_cycles);
+    if (getenv("MAXSCORE_TRACE")) {
+        static int tt[256 * 8];
+        int nr = 0, zero = 0;
+        (void)hipMemcpyFromSymbol(tt, HIP_SYMBOL(g_tailtrace), sizeof(tt));
+        (void)hipMemcpyFromSymbol(&nr, HIP_SYMBOL(g_tailruns), sizeof(nr));
+        (void)hipMemcpyToSymbol(HIP_SYMBOL(g_tailruns), &zero, sizeof(zero));
+        for (int r = 0; r < nr; ++r)
+            fprintf(stderr, "[tail] after round %d: iters %d victims %d stop1 %d stop2 %d over_last %d us %.1f moves %d\n", tt[r * 8], tt[r * 8 + 1],
+                    tt[r * 8 + 2], tt[r * 8 + 3], tt[r * 8 + 4], tt[r * 8 + 5], tt[r * 8 + 6] * 0.01, tt[r * 8 + 7]);
+        static long long tr[4096];
+        (void)hipMemcpyFromSymbol(tr, HIP_SYMBOL(g_roundtrace), sizeof(tr));
+        for (int r = 0; r < h.round && r < 2048; ++r)
+            fprintf(stderr, "[trace] round %d eps %lld moves %lld flags %lld\n", r, tr[2 * r + 1], tr[2 * r] & 0xffffffffll, tr[2 * r] >> 32);
+    }
     if (getenv("MAXSCORE_DEBUG")) {
         fprintf(stderr, "[maxscore] phase end rounds:");
         for (int a = 0; a < 28 && a < h.phases; ++a) fprintf(stderr, " %d", h.phase_round[a]);

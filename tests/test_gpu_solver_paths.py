@@ -188,6 +188,28 @@ def test_finisher_and_auction_reach_the_same_optimum(ms, name, T, seed):
         assert torch.equal(again["assign"], fin["assign"]) and torch.equal(again["prices"], fin["prices"])
 
 
+@pytest.mark.parametrize("name,seed", [("cfg5", 0), ("cfg5", 1), ("cfg3", 1)])
+def test_finisher_certifies_in_one_pass_at_full_size(ms, name, seed):
+    """At the benchmark's sizes the first finisher pass holds every arc under its bound and keeps that list complete
+    while it moves tokens (the arcs of a moved token are replaced on the spot), so it cancels all cycles and
+    certifies without a second pass.  Same total as the auction alone, prices that certify it."""
+    print(f"finisher one pass {name} seed={seed}", flush=True)
+    cfg = CONFIGS[name]
+    E, k, C = cfg["E"], cfg["k"], cfg["C"]
+    q = oracle.quantise(oracle.soft_topk(make_logits(name, seed=seed), k, cfg["t"]))
+    qd = dev(q.astype(np.int32))
+    fin = ms.assign_i32(qd, k, C)
+    auc = ms.assign_i32(qd, k, C, finisher=False)
+    assert fin["stats"]["status"] == 0 and fin["stats"]["total_score_q"] == auc["stats"]["total_score_q"]
+    assert certified(q, fin, k, C)
+    assert fin["stats"]["finish_cycles"] > 0 and fin["stats"]["finish_passes"] == 1, fin["stats"]
+    a = fin["assign"].cpu().numpy()
+    P = oracle.assignment_matrix(a, E)
+    ok, why = oracle.check_feasible(P, k, C)
+    assert ok, why
+    assert int(q[P.astype(bool)].sum()) == fin["stats"]["total_score_q"]
+
+
 def test_finisher_with_k_vector_and_capacity_vector(ms):
     """Per-token k (with zeros) and unequal capacities through the finisher: checker's optimum, valid rows."""
     print("finisher kvec+caps", flush=True)
