@@ -30,8 +30,14 @@
  *     of pinned host memory that the first such call of a host thread allocates and keeps until the
  *     process ends (one solve at a time per host thread; different threads may solve concurrently on
  *     different streams with different workspaces).
- *   - Supported sizes: 1 <= k <= E <= 1024, k <= 64, 1 <= T <= 2^21, C >= 1 (C > T acts as T),
- *     and T*k <= E*min(C,T) (true for every capacity c' = c_f*k*n/e with c_f >= 1, Section 2.3).
+ *   - Supported sizes: 1 <= k <= E <= 1024, k <= 64, 1 <= T <= 2^21, C >= 1 (C > T acts as T).
+ *   - More demand than capacity, T*k > E*min(C,T) (never with a capacity c' = c_f*k*n/e, c_f >= 1, of Section 2.3):
+ *     Eq. 7's equalities cannot all hold then; with the capacities of Table 1 the problem is still a flow problem
+ *     (Section 3.2), and the exact assignment is its solution: every expert ends full (E*min(C,T) pairs, the
+ *     maximum flow) and the placed pairs have the maximum score.  Rows come back with their experts first and -1
+ *     in the slots left empty; gates are 0 there and the dispatch lists hold the placed pairs only.  It is solved
+ *     with k padding experts, so it needs E + k <= 1024 (MAXSCORE_ERR_OVERSUBSCRIBED otherwise) and the larger
+ *     workspace that maxscore_workspace_bytes reports for such T, E, k, C.
  */
 #ifndef MAXSCORE_H
 #define MAXSCORE_H
@@ -50,7 +56,8 @@ enum {
     MAXSCORE_ERR_WORKSPACE = -3,      /* workspace NULL, misaligned or too small */
     MAXSCORE_ERR_DTYPE = -4,          /* unknown input dtype code */
     MAXSCORE_ERR_HIP = -5,            /* a HIP call or kernel launch failed */
-    MAXSCORE_ERR_OVERSUBSCRIBED = -6, /* T*k > E*min(C,T): not every token can get k experts */
+    MAXSCORE_ERR_OVERSUBSCRIBED = -6, /* more demand than capacity in a form that is not solved: T*k > E*min(C,T) with
+                                         E + k > 1024, or a capacity vector whose sum is below the demand */
     MAXSCORE_ERR_RANGE = -7,          /* reward range too wide for the solver's 64-bit bids */
     MAXSCORE_ERR_NOT_CONVERGED = -8   /* max_rounds reached: the assignment returned is feasible (<= C tokens per
                                          expert, distinct experts per token) but neither complete nor optimal:
@@ -122,8 +129,10 @@ int32_t maxscore_router_logits(const void *x, const void *W, const float *bias, 
 int32_t maxscore_softtopk(const float *logits, int32_t T, int32_t E, int32_t k, float t,
                           int32_t quant_shift, float *scores, int32_t *q, void *stream);
 
-/* a4.  Exact assignment on integer rewards q[T,E].
- *   assign[T,k] : expert ids per token, distinct, ascending slot order is arbitrary.
+/* a4.  Exact assignment on integer rewards q[T,E] (Eq. 7-8, Table 1: maximum flow, then maximum score).
+ *   assign[T,k] : expert ids per token, distinct, ascending slot order is arbitrary.  With more demand than
+ *                 capacity (see above) a row holds fewer than k experts, first in the row, then -1; the prices
+ *                 then belong to the padded problem and certify nothing by themselves.
  *   prices[E]   : (may be NULL) int64 expert prices in units of 1/price_scale of a q unit;
  *                 every token holds k experts whose price_scale*q_ij - price_j is within 1 of
  *                 its best alternatives, and unfilled experts have price 0 (the dual side of

@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(ROOT, "_build", "maxscore")
 LIB = os.path.join(HERE, "libmaxscore.so")
 SOURCES = ["api.cpp", "solver.hip", "softtopk.hip", "dispatch.hip", "movement.hip", "iter.hip", "training.hip",
-           "operators.hip", "alg1.hip", "sinkhorn.hip", "gemm.hip", "noalloc.hip", "finish.hip"]
+           "operators.hip", "alg1.hip", "sinkhorn.hip", "gemm.hip", "noalloc.hip", "finish.hip", "oversub.hip"]
 
 
 def _flags():

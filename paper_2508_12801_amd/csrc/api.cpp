@@ -68,7 +68,13 @@ extern "C" {
 size_t maxscore_workspace_bytes(int32_t T, int32_t d, int32_t E, int32_t k, int32_t C)
 {
     if (!shape_ok(T, E, k, C) || d < 0) return 0;
-    return workspace_layout(T, E, k, d).total;
+    size_t need = workspace_layout(T, E, k, d).total;
+    const int Ce = C < T ? C : T;
+    if ((long long)T * k > (long long)E * Ce) {       // the exact solver then works on a padded copy of the rewards
+        const size_t os = oversub_workspace_bytes(T, E, k);
+        need = os > need ? os : need;
+    }
+    return need;
 }
 
 int32_t maxscore_router_logits(const void *x, const void *W, const float *bias, int32_t in_dtype, int32_t T,
@@ -99,11 +105,13 @@ int32_t maxscore_assign_i32(const int32_t *q, int32_t T, int32_t E, int32_t k, i
     if (!q || !assign) return MAXSCORE_ERR_NULL;
     if (!shape_ok(T, E, k, C)) return MAXSCORE_ERR_SHAPE;
     const int Ce = C < T ? C : T;
-    if ((long long)T * k > (long long)E * Ce) return MAXSCORE_ERR_OVERSUBSCRIBED;
     int32_t rc = check_ws(workspace, workspace_bytes, T, E, k);
     if (rc) return rc;
     maxscore_opts o = resolve(opts);
     if (stats) std::memset(stats, 0, sizeof(*stats));
+    if ((long long)T * k > (long long)E * Ce)
+        return oversub_run(q, T, E, k, Ce, o, assign, prices, price_scale, stats, (char *)workspace, workspace_bytes,
+                           (hipStream_t)stream);
     return solver_run(q, T, E, k, Ce, o, assign, prices, price_scale, stats, (char *)workspace,
                       (hipStream_t)stream);
 }
@@ -288,7 +296,7 @@ static int32_t route_events(hipEvent_t *a, hipEvent_t *b)
 static int32_t route_from_rewards(const float *scores, const int32_t *q, int T, int E, int k, int C,
                                   const maxscore_opts &o, int32_t *assign, float *gates, int32_t *expert_offsets,
                                   int32_t *disp_token, float *disp_gate, int32_t *token_pos, int64_t *prices,
-                                  maxscore_stats *stats, char *ws, hipStream_t s)
+                                  maxscore_stats *stats, char *ws, size_t ws_bytes, hipStream_t s)
 {
     const int Ce = C < T ? C : T;
     int32_t src;
@@ -313,6 +321,9 @@ static int32_t route_from_rewards(const float *scores, const int32_t *q, int T, 
             stats->rounds = rounds;
             stats->status = src;
         }
+    } else if ((long long)T * k > (long long)E * Ce) {
+        // more demand than capacity: every expert ends full, rows come back with empty slots (-1) at their end
+        src = oversub_run(q, T, E, k, Ce, o, assign, prices, nullptr, stats, ws, ws_bytes, s);
     } else {
         SolverGeometry geom = {0, 0, 0};
         src = solver_run(q, T, E, k, Ce, o, assign, prices, nullptr, stats, ws, s, nullptr, 0, nullptr, 0, &geom);
@@ -342,8 +353,9 @@ static int32_t route_check(int T, int E, int k, int C, const maxscore_opts &o, c
     if (o.assignment != MAXSCORE_ASSIGN_EXACT && o.assignment != MAXSCORE_ASSIGN_ITER) return MAXSCORE_ERR_SHAPE;
     if (o.quant_shift < 1 || o.quant_shift > 24 || !(o.t >= 0.f) || o.t > 64.f) return MAXSCORE_ERR_SHAPE;
     const int Ce = C < T ? C : T;
-    // the exact solver needs room for every token's k experts; iterative rerouting simply leaves holes
-    if (o.assignment == MAXSCORE_ASSIGN_EXACT && (long long)T * k > (long long)E * Ce)
+    // with more demand than capacity both kinds of assignment leave empty slots; the exact solver then pads the
+    // problem with k more experts
+    if (o.assignment == MAXSCORE_ASSIGN_EXACT && (long long)T * k > (long long)E * Ce && E + k > kMaxE)
         return MAXSCORE_ERR_OVERSUBSCRIBED;
     return check_ws(workspace, workspace_bytes, T, E, k);
 }
@@ -364,7 +376,7 @@ int32_t maxscore_route_scores(const float *scores, int32_t T, int32_t E, int32_t
     rc = quantise_run(scores, T, E, o.quant_shift, q_out, s);
     if (rc) return rc;
     return route_from_rewards(scores, q_out, T, E, k, C, o, assign, gates, expert_offsets, disp_token, disp_gate,
-                              token_pos, prices, stats, (char *)workspace, s);
+                              token_pos, prices, stats, (char *)workspace, workspace_bytes, s);
 }
 
 int32_t maxscore_route_logits(const float *logits, int32_t T, int32_t E, int32_t k, int32_t C,
@@ -384,7 +396,7 @@ int32_t maxscore_route_logits(const float *logits, int32_t T, int32_t E, int32_t
     rc = softtopk_run(logits, T, E, k, o.t, o.quant_shift, scores_out, q_out, s);
     if (rc) return rc;
     return route_from_rewards(scores_out, q_out, T, E, k, C, o, assign, gates, expert_offsets, disp_token,
-                              disp_gate, token_pos, prices, stats, (char *)workspace, s);
+                              disp_gate, token_pos, prices, stats, (char *)workspace, workspace_bytes, s);
 }
 
 int32_t maxscore_route_xw(const void *x, const void *W, const float *bias, int32_t in_dtype, int32_t T, int32_t d,

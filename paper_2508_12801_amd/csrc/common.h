@@ -107,10 +107,18 @@ size_t finish_area_bytes(int T);          // bytes of WorkspaceLayout::fin_off's
 // holds fin_tri_entries() of them (enough for every geometry the solver picks: rows * k <= 1024 per block).
 inline int fin_seg_cap(int rows, int k)
 {
-    const int c = rows * k / 16;
+    const int c = rows * k / 8;
     return c < 8 ? 8 : c;
 }
-inline size_t fin_tri_entries(int T, int k, int max_wg) { return ((size_t)T + 1024) * k / 16 + 8 * (size_t)max_wg + 8; }
+inline size_t fin_tri_entries(int T, int k, int max_wg) { return ((size_t)T + 1024) * k / 8 + 8 * (size_t)max_wg + 8; }
+// --- oversub.hip
+// Exact assignment with more demand than capacity (T*k > E*Ce): every expert ends full, the placed pairs have the
+// maximum score, rows come back with their experts first and -1 in the slots left empty.  Needs E + k <= kMaxE and
+// oversub_workspace_bytes() of workspace (0: not supported for these sizes).  Synchronises the stream.
+size_t oversub_workspace_bytes(int T, int E, int k);
+int32_t oversub_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore_opts &o, int32_t *assign,
+                    int64_t *prices, int64_t *price_scale, maxscore_stats *stats, char *ws, size_t ws_bytes,
+                    hipStream_t s);
 // --- softtopk.hip
 int32_t softtopk_run(const float *logits, int T, int E, int k, float t, int shift, float *scores, int32_t *q,
                      hipStream_t s);

@@ -28,7 +28,17 @@ int main()
     // a4
     CHECK(maxscore_assign_i32(nullptr, T, E, k, C, &o, (int32_t *)one, nullptr, nullptr, &st, one, ws, nullptr) == MAXSCORE_ERR_NULL);
     CHECK(maxscore_assign_i32((int32_t *)one, T, E, E + 1, C, &o, (int32_t *)one, nullptr, nullptr, &st, one, ws, nullptr) == MAXSCORE_ERR_SHAPE);
-    CHECK(maxscore_assign_i32((int32_t *)one, T, E, k, 10, &o, (int32_t *)one, nullptr, nullptr, &st, one, ws, nullptr) == MAXSCORE_ERR_OVERSUBSCRIBED);
+    // more demand than capacity: solved on a padded copy of the rewards, which needs the larger workspace that
+    // maxscore_workspace_bytes reports for that capacity; refused only when E + k padding experts do not fit
+    const size_t ws10 = maxscore_workspace_bytes(T, d, E, k, 10);
+    CHECK(ws10 > ws);
+    CHECK(maxscore_assign_i32((int32_t *)one, T, E, k, 10, &o, (int32_t *)one, nullptr, nullptr, &st, one, ws, nullptr) == MAXSCORE_ERR_WORKSPACE);
+    CHECK(maxscore_assign_i32((int32_t *)one, T, E, k, 10, &o, (int32_t *)one, nullptr, nullptr, &st, one, ws10, nullptr) == MAXSCORE_OK);
+    {
+        const size_t wsb = maxscore_workspace_bytes(T, 0, 1000, 30, 1);
+        CHECK(wsb > 0);
+        CHECK(maxscore_assign_i32((int32_t *)one, T, 1000, 30, 1, &o, (int32_t *)one, nullptr, nullptr, &st, one, wsb, nullptr) == MAXSCORE_ERR_OVERSUBSCRIBED);
+    }
     const size_t ws0 = maxscore_workspace_bytes(T, 0, E, k, C);     // without the scratch of the projection
     CHECK(ws0 > 0 && ws0 <= ws);
     CHECK(maxscore_assign_i32((int32_t *)one, T, E, k, C, &o, (int32_t *)one, nullptr, nullptr, &st, one, ws0 - 1, nullptr) == MAXSCORE_ERR_WORKSPACE);
@@ -51,11 +61,12 @@ int main()
     CHECK(maxscore_gates((float *)one, nullptr, T, E, k, (float *)one, nullptr) == MAXSCORE_ERR_NULL);
     CHECK(maxscore_dispatch((int32_t *)one, (float *)one, T, E, k, (int32_t *)one, (int32_t *)one, nullptr, (int32_t *)one, one, ws, nullptr) == MAXSCORE_ERR_NULL);
     CHECK(maxscore_dispatch((int32_t *)one, (float *)one, T, E, k, (int32_t *)one, (int32_t *)one, (float *)one, (int32_t *)one, one, ws, nullptr) == MAXSCORE_OK);
-    // routing entries: exact refuses short capacity, iterative rerouting takes it
+    // routing entries: both kinds of assignment take short capacity (empty slots)
     float *f = (float *)one;
     int32_t *i = (int32_t *)one;
     CHECK(maxscore_route_scores(f, T, E, k, C, &o, i, i, f, i, i, f, i, nullptr, &st, one, ws, nullptr) == MAXSCORE_OK);
-    CHECK(maxscore_route_logits(f, T, E, k, 10, &o, f, i, i, f, i, i, f, i, nullptr, &st, one, ws, nullptr) == MAXSCORE_ERR_OVERSUBSCRIBED);
+    CHECK(maxscore_route_logits(f, T, E, k, 10, &o, f, i, i, f, i, i, f, i, nullptr, &st, one, ws10, nullptr) == MAXSCORE_OK);
+    CHECK(maxscore_route_logits(f, T, 1000, 30, 1, &o, f, i, i, f, i, i, f, i, nullptr, &st, one, maxscore_workspace_bytes(T, 0, 1000, 30, 1), nullptr) == MAXSCORE_ERR_OVERSUBSCRIBED);
     o.assignment = MAXSCORE_ASSIGN_ITER;
     CHECK(maxscore_route_logits(f, T, E, k, 10, &o, f, i, i, f, i, i, f, i, nullptr, &st, one, ws, nullptr) == MAXSCORE_OK);
     o.assignment = 5;

@@ -13,6 +13,18 @@ int32_t solver_run(const int32_t *, int, int, int, int, const maxscore_opts &, i
 {
     return MAXSCORE_OK;
 }
+size_t oversub_workspace_bytes(int T, int E, int k)
+{
+    if (E + k > kMaxE) return 0;
+    return workspace_layout(T, E + k, k).total + sizeof(int32_t) * (size_t)T * (E + k) + sizeof(int64_t) * (E + k) + 1024;
+}
+int32_t oversub_run(const int32_t *, int T, int E, int k, int, const maxscore_opts &, int32_t *, int64_t *, int64_t *,
+                    maxscore_stats *, char *, size_t ws_bytes, hipStream_t)
+{
+    if (E + k > kMaxE) return MAXSCORE_ERR_OVERSUBSCRIBED;
+    if (ws_bytes < oversub_workspace_bytes(T, E, k)) return MAXSCORE_ERR_WORKSPACE;
+    return MAXSCORE_OK;
+}
 int32_t dispatch_from_keys(const SolverGeometry &, const float *, const int32_t *, int, int, int, float *, int32_t *,
                            int32_t *, float *, int32_t *, char *, hipStream_t)
 {

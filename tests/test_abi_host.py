@@ -58,8 +58,12 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert lib.maxscore_assign_i32(one, 4, 4, 2, 0, null, one, null, null, null, one, 1 << 20, null) == -2   # C < 1
     assert lib.maxscore_softtopk(one, 4, 4, 2, -1.0, 20, one, one, null) == -2                                  # t < 0
     assert lib.maxscore_softtopk(one, 4, 4, 2, 1.0, 40, one, one, null) == -2                                   # shift
-    # capacity too small for every token to get k experts
-    assert lib.maxscore_assign_i32(one, 10, 4, 2, 4, null, one, null, null, null, one, 1 << 20, null) == -6
+    # capacity too small for every token to get k experts is solved with k padding experts; refused when E + k of them
+    # do not fit, and with the workspace of the plain problem
+    assert lib.maxscore_assign_i32(one, 40, 1000, 30, 1, null, one, null, null, null, one, 1 << 30, null) == -6
+    plain = lib.maxscore_workspace_bytes(10, 0, 4, 2, 5)
+    assert lib.maxscore_workspace_bytes(10, 0, 4, 2, 4) > plain
+    assert lib.maxscore_assign_i32(one, 10, 4, 2, 4, null, one, null, null, null, one, plain, null) == -3
     # workspace: missing, misaligned, too small
     assert lib.maxscore_assign_i32(one, 8, 4, 2, 4, null, one, null, null, null, null, 1 << 20, null) == -3
     assert lib.maxscore_assign_i32(one, 8, 4, 2, 4, null, one, null, null, null, ctypes.c_void_p(260), 1 << 20, null) == -3

@@ -1,0 +1,143 @@
+"""GPU parity of the exact assignment when demand exceeds capacity (T*k > E*C): maximum flow first, then maximum
+score (Section 3.2, Eq. 7-8 read with the capacities of Table 1).  The checker is the successive-cheapest-path
+solver on the literal graph of Table 1, itself pinned by enumeration over every capacity (tests/test_oracle_assignment.py)."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from workloads import CONFIGS, make_logits
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.fixture(scope="module")
+def ms():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2508_12801_amd as m
+    m.load_library()
+    return m
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check_rows(a, E, k, C):
+    """Real experts first, -1 after them, distinct experts per row, at most C tokens per expert."""
+    T = a.shape[0]
+    filled = a >= 0
+    assert (a < E).all()
+    assert (filled[:, :-1] >= filled[:, 1:]).all()            # no expert after an empty slot
+    srt = np.sort(np.where(filled, a, -1 - np.arange(k)[None, :]), axis=1)
+    assert (srt[:, 1:] != srt[:, :-1]).all()
+    load = np.bincount(a[filled], minlength=E)
+    assert load.max() <= min(C, T)
+    return load
+
+
+def solve_and_check(ms, q, k, C):
+    T, E = q.shape
+    out = ms.assign_i32(dev(q.astype(np.int32)), k, C)
+    a = out["assign"].cpu().numpy()
+    load = check_rows(a, E, k, C)
+    ref = oracle.assign_literal_graph(q, k, C)
+    flow = int((a >= 0).sum())
+    total = int(np.take_along_axis(q, np.where(a >= 0, a, 0).astype(np.int64), axis=1)[a >= 0].sum())
+    assert flow == ref["flow"] == oracle.max_flow_value(T, E, k, C) == out["stats"]["flow_value"]
+    assert total == ref["total"] == out["stats"]["total_score_q"], (total, ref["total"], out["stats"])
+    assert out["stats"]["status"] == 0
+    return out, load
+
+
+def test_flow_first_fixture_with_less_capacity(ms):
+    """The fixture's rewards with capacity 1: three pairs can be placed, and the best three are 100 + 100 + 10."""
+    print("oversubscribed fixture", flush=True)
+    q = np.loadtxt(os.path.join(GOLD, "flow_first_example.txt"), comments="#", dtype=np.int64)
+    out, load = solve_and_check(ms, q, 2, 1)
+    assert out["stats"]["flow_value"] == 3 and out["stats"]["total_score_q"] == 210 and (load == 1).all()
+
+
+@pytest.mark.parametrize("kind", ["uniform", "ties", "rows_equal", "signed", "skewed"])
+def test_small_random_cases(ms, kind):
+    print(f"oversubscribed small {kind}", flush=True)
+    rng = np.random.default_rng(abs(hash(kind)) % 1000)
+    n = 0
+    for T, E, k in [(7, 3, 2), (12, 4, 3), (30, 5, 5), (40, 8, 3), (65, 16, 4), (130, 9, 2), (200, 20, 8)]:
+        for C in sorted({1, max(1, T * k // (2 * E)), max(1, (T * k - 1) // E)}):
+            if T * k <= E * min(C, T):
+                continue
+            if kind == "uniform":
+                q = rng.integers(0, 1 << 20, (T, E))
+            elif kind == "ties":
+                q = rng.integers(0, 4, (T, E))
+            elif kind == "rows_equal":
+                q = np.tile(rng.integers(0, 50, (1, E)), (T, 1))
+            elif kind == "signed":
+                q = rng.integers(-2000, 2000, (T, E))
+            else:
+                L = rng.normal(size=(T, E)) + 2.0 * rng.normal(size=(1, E))
+                p = np.exp(L - L.max(axis=1, keepdims=True))
+                q = np.rint(p / p.sum(axis=1, keepdims=True) * ((1 << 20) - 1)).astype(np.int64)
+            solve_and_check(ms, q.astype(np.int64), k, C)
+            n += 1
+    assert n >= 10
+
+
+def test_route_logits_with_short_capacity(ms):
+    """The whole path after the logits with 60 % of the capacity the tokens ask for: every expert full, total equal
+    to the checker's flow-first optimum on the path's own rewards, gates 0 in the empty slots, dispatch lists equal
+    to the checker's."""
+    print("oversubscribed route_logits", flush=True)
+    cfg = CONFIGS["cfg2"]
+    E, k, t = cfg["E"], cfg["k"], cfg["t"]
+    T = 600
+    L = make_logits("cfg2", seed=4, T=T).astype(np.float32)
+    C = int(0.6 * T * k / E)
+    out = ms.route_logits(dev(L), k, C, t=t)
+    q = out["q"].cpu().numpy().astype(np.int64)
+    a = out["assign"].cpu().numpy()
+    load = check_rows(a, E, k, C)
+    assert (load == C).all()
+    ref = oracle.assign_literal_graph(q, k, C)
+    total = int(np.take_along_axis(q, np.where(a >= 0, a, 0).astype(np.int64), axis=1)[a >= 0].sum())
+    assert (int((a >= 0).sum()), total) == (ref["flow"], ref["total"]) == (E * C, out["stats"]["total_score_q"])
+    scores = out["scores"].cpu().numpy()
+    g = out["gates"].cpu().numpy()
+    want = np.where(a >= 0, np.take_along_axis(scores, np.where(a >= 0, a, 0).astype(np.int64), axis=1), 0.0)
+    assert np.array_equal(g, want.astype(np.float32))
+    d = oracle.dispatch(a, g, E)
+    assert np.array_equal(out["expert_offsets"].cpu().numpy(), d["expert_offsets"])
+    n = int(d["expert_offsets"][-1])                       # the lists hold the placed pairs; the rest of the buffers is unused
+    assert n == E * C == len(d["disp_token"])
+    assert np.array_equal(out["disp_token"].cpu().numpy()[:n], d["disp_token"])
+    assert np.array_equal(out["disp_gate"].cpu().numpy()[:n], d["disp_gate"].astype(np.float32))
+    pos = out["token_pos"].cpu().numpy()
+    assert np.array_equal(pos, d["token_pos"]) and pos[a >= 0].max() < C
+
+
+def test_larger_batch_against_bounds(ms):
+    """cfg3's rewards (T = 16384, E = 64, k = 8) with three quarters of the capacity: too large for the literal graph
+    in a test, so the result is checked by what must hold: every expert full, and the total between the optimum of
+    the same capacity with k lowered to what fits (a feasible sub-problem the checker can solve: every token ships all
+    of its k' units) and the sum of every expert's C best rewards (capacity alone)."""
+    print("oversubscribed cfg3", flush=True)
+    cfg = CONFIGS["cfg3"]
+    E, k, T = cfg["E"], cfg["k"], cfg["T"]
+    C = 3 * cfg["C"] // 4
+    q = oracle.quantise(oracle.soft_topk(make_logits("cfg3", seed=1), k, cfg["t"]))
+    out = ms.assign_i32(dev(q.astype(np.int32)), k, C)
+    a = out["assign"].cpu().numpy()
+    load = check_rows(a, E, k, C)
+    assert (load == C).all() and out["stats"]["flow_value"] == E * C
+    total = int(np.take_along_axis(q, np.where(a >= 0, a, 0).astype(np.int64), axis=1)[a >= 0].sum())
+    assert total == out["stats"]["total_score_q"]
+    upper = int(np.sort(q, axis=0)[-C:, :].sum())
+    k_fit = (E * C) // T                                  # 6: every token can ship k_fit units within the capacity
+    lower = oracle.max_score_assignment(q, k_fit, C)["total"]
+    assert lower <= total <= upper, (lower, total, upper)

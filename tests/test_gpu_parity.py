@@ -255,14 +255,11 @@ def test_route_scores_end_to_end(ms, name, T):
 
 
 def test_route_with_token_dropping_when_capacity_is_short(ms):
-    """T*k > E*C: the exact solver refuses (every token must be able to get k experts), iterative rerouting routes
-    with holes (Section 2.3, Figure 1(b)/(c)) and matches the checker element by element."""
+    """T*k > E*C: iterative rerouting routes with holes (Section 2.3, Figure 1(b)/(c)) and matches the checker
+    element by element (the exact solver's answer to the same case is in test_gpu_oversubscribed.py)."""
     print("route iter oversubscribed", flush=True)
     L, E, k, _, t = cfg_case("cfg3", 2000)
     C = 200                                           # 2000*8 = 16000 > 64*200 = 12800
-    with pytest.raises(ms.MaxScoreError) as e:
-        ms.route_logits(dev(L), k, C, t=t)
-    assert e.value.code == -6
     out = ms.route_logits(dev(L), k, C, t=t, assignment="iter")
     q = out["q"].cpu().numpy().astype(np.int64)
     ref = oracle.iter_reroute(q, k, C)
