@@ -122,6 +122,40 @@ def soft_topk(L: np.ndarray, k: int, t: float) -> np.ndarray:
     return A
 
 
+def soft_topk_reading(L: np.ndarray, k: int, t: float, reading: str) -> np.ndarray:
+    """Eq. 6 under the other readings its print admits (it gives no base case, and its SE term does not depend
+    on the recursion level as printed).  Each is the recursion SoftTopk^(m) = SoftTopk^(m-1) + SE written out:
+
+    "A"   the reading of soft_topk(): level 1 is Softmax(a), level m = 2..k masks the m-1 largest entries;
+    "A1"  level 0 is Softmax(a), level m = 1..k masks the m largest entries (one level more, masks shifted by one);
+    "B"   the mask as printed, the k largest entries at every level: level 1 is Softmax(a), levels 2..k each add
+          t*Softmax(a) outside the top k and nothing inside it;
+    "C"   as "A", with SE renormalised over the entries it is added to (t * p_i / sum of the unmasked p), in the
+          manner of the iterated operators of Table 2: every level adds a distribution scaled by t.
+    Ranks as in soft_topk (equal logits: lower index first)."""
+    L = np.asarray(L, dtype=np.float64)
+    p = softmax_rows(L)
+    rank = descending_rank(L)
+    A = p.copy()
+    if reading == "A":
+        return soft_topk(L, k, t)
+    if reading == "A1":
+        for m in range(1, k + 1):
+            A = A + np.where(rank <= m, 0.0, t * p)
+        return A
+    if reading == "B":
+        for m in range(2, k + 1):
+            A = A + np.where(rank <= k, 0.0, t * p)
+        return A
+    if reading == "C":
+        for m in range(2, k + 1):
+            free = rank > m - 1
+            mass = np.where(free, p, 0.0).sum(axis=1, keepdims=True)
+            A = A + np.where(free, t * p / mass, 0.0)
+        return A
+    raise ValueError(reading)
+
+
 # ------------------------------------------------------------------------------------------------
 # a3  integer rewards
 

@@ -106,6 +106,64 @@ def test_softtopk_tie_order_and_overtaking():
     assert np.allclose(A, [0.4, 1.75, 1.25])             # runner-up may overtake the leader
 
 
+# ---- a2, the other readings of Eq. 6 -------------------------------------------------------------
+
+def _brute_rank(L):
+    E = L.shape[1]
+    idx = np.arange(E)
+    beats = (L[:, None, :] > L[:, :, None]) | ((L[:, None, :] == L[:, :, None]) & (idx[None, None, :] < idx[None, :, None]))
+    return 1 + beats.sum(axis=2)
+
+
+def test_softtopk_readings_limits():
+    """Every reading is Softmax at t = 0; A, B and C are Softmax at k = 1 (no level is added), A1 is not (its first
+    level already lifts everything but the largest entry); reading "A" is soft_topk itself."""
+    L = make_logits("cfg3", T=40).astype(np.float64)
+    ref = scipy.special.softmax(L, axis=1)
+    for rd in ("A", "A1", "B", "C"):
+        assert np.allclose(oracle.soft_topk_reading(L, 8, 0.0, rd), ref, rtol=1e-13, atol=0)
+    for rd in ("A", "B", "C"):
+        assert np.allclose(oracle.soft_topk_reading(L, 1, 3.0, rd), ref, rtol=1e-13, atol=0)
+    rank = _brute_rank(L)
+    assert np.allclose(oracle.soft_topk_reading(L, 1, 3.0, "A1"), ref * np.where(rank == 1, 1.0, 4.0), rtol=1e-13)
+    assert np.array_equal(oracle.soft_topk_reading(L, 5, 2.0, "A"), oracle.soft_topk(L, 5, 2.0))
+
+
+def test_softtopk_readings_closed_forms_and_row_sums():
+    """Closed forms with ranks counted by brute force, and what every row must sum to: A1 adds t times the mass
+    outside the m largest entries at level m = 1..k; B adds t times the mass outside the k largest, k - 1 times;
+    C adds exactly t per level (a distribution scaled by t)."""
+    L = make_logits("cfg5", T=30).astype(np.float64)
+    p = scipy.special.softmax(L, axis=1)
+    rank = _brute_rank(L)
+    ps = -np.sort(-p, axis=1)
+    for k, t in [(2, 1.0), (8, 1.0), (8, 4.0), (5, 0.3)]:
+        A1 = oracle.soft_topk_reading(L, k, t, "A1")
+        assert np.allclose(A1, p * (1 + t * np.minimum(rank - 1, k)), rtol=1e-13)
+        assert np.allclose(A1.sum(axis=1), 1 + t * sum(1.0 - ps[:, :m].sum(axis=1) for m in range(1, k + 1)), rtol=1e-12)
+        B = oracle.soft_topk_reading(L, k, t, "B")
+        assert np.allclose(B, p * np.where(rank <= k, 1.0, 1 + t * (k - 1)), rtol=1e-13)
+        assert np.allclose(B.sum(axis=1), 1 + t * (k - 1) * (1.0 - ps[:, :k].sum(axis=1)), rtol=1e-12)
+        C = oracle.soft_topk_reading(L, k, t, "C")
+        assert np.allclose(C.sum(axis=1), 1 + t * (k - 1), rtol=1e-12)
+        w = np.zeros_like(p)                       # sum over the levels m = 2..min(rank, k) of 1 / (mass outside the m-1 largest)
+        for m in range(2, k + 1):
+            w += np.where(rank >= m, 1.0 / (1.0 - ps[:, :m - 1].sum(axis=1, keepdims=True)), 0.0)
+        assert np.allclose(C, p * (1 + t * w), rtol=1e-10)
+
+
+def test_softtopk_readings_hand_example():
+    """p = (0.8, 0.05, 0.05, 0.04, 0.03, 0.03), k = 2, t = 4 (the 0.8 / 0.05 pair of Section 3.1), worked by hand:
+    A lifts everything but the leader 5 times; A1 lifts the runner-up 5 times and the rest 9 times; B leaves the two
+    largest alone and lifts the rest 5 times; C gives the leader nothing and the others 1 + 4 / 0.2 = 21 times."""
+    p = np.array([[0.8, 0.05, 0.05, 0.04, 0.03, 0.03]])
+    L = np.log(p)
+    assert np.allclose(oracle.soft_topk_reading(L, 2, 4.0, "A")[0], [0.8, 0.25, 0.25, 0.2, 0.15, 0.15])
+    assert np.allclose(oracle.soft_topk_reading(L, 2, 4.0, "A1")[0], [0.8, 0.25, 0.45, 0.36, 0.27, 0.27])
+    assert np.allclose(oracle.soft_topk_reading(L, 2, 4.0, "B")[0], [0.8, 0.05, 0.25, 0.2, 0.15, 0.15])
+    assert np.allclose(oracle.soft_topk_reading(L, 2, 4.0, "C")[0], [0.8, 1.05, 1.05, 0.84, 0.63, 0.63])
+
+
 # ---- a3 quantise --------------------------------------------------------------------------------
 
 def test_quantise_half_even_and_scale():
