@@ -129,6 +129,20 @@ int32_t maxscore_router_logits(const void *x, const void *W, const float *bias, 
 int32_t maxscore_softtopk(const float *logits, int32_t T, int32_t E, int32_t k, float t,
                           int32_t quant_shift, float *scores, int32_t *q, void *stream);
 
+/* a2 + a3 under the other readings that the print of Eq. 6 admits (it has no base case, and its SE term does not
+ * depend on the recursion level).  Everything as maxscore_softtopk; `reading`:
+ *   MAXSCORE_SOFTTOPK_A   what maxscore_softtopk computes: level 1 is Softmax(a), level m = 2..k masks the m-1
+ *                         largest entries: p_i * (1 + t * (min(rank_i, k) - 1));
+ *   MAXSCORE_SOFTTOPK_A1  level 0 is Softmax(a), level m = 1..k masks the m largest: p_i * (1 + t * min(rank_i - 1, k));
+ *   MAXSCORE_SOFTTOPK_B   the mask as printed, the k largest entries at every level 2..k: p_i inside the top k,
+ *                         p_i * (1 + t * (k - 1)) outside;
+ *   MAXSCORE_SOFTTOPK_C   as A with SE renormalised over the entries it is added to (every level adds a
+ *                         distribution scaled by t, as the iterated operators of Table 2 do).
+ * The routing entry points use reading A. */
+enum { MAXSCORE_SOFTTOPK_A = 0, MAXSCORE_SOFTTOPK_A1 = 1, MAXSCORE_SOFTTOPK_B = 2, MAXSCORE_SOFTTOPK_C = 3 };
+int32_t maxscore_softtopk_reading(const float *logits, int32_t T, int32_t E, int32_t k, float t,
+                                  int32_t quant_shift, int32_t reading, float *scores, int32_t *q, void *stream);
+
 /* a4.  Exact assignment on integer rewards q[T,E] (Eq. 7-8, Table 1: maximum flow, then maximum score).
  *   assign[T,k] : expert ids per token, distinct, ascending slot order is arbitrary.  With more demand than
  *                 capacity (see above) a row holds fewer than k experts, first in the row, then -1; the prices

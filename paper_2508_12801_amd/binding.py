@@ -64,6 +64,9 @@ _SIGS = {
     "maxscore_softtopk": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.c_float, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                            ctypes.c_void_p]),
+    "maxscore_softtopk_reading": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                                   ctypes.c_float, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                                   ctypes.c_void_p, ctypes.c_void_p]),
     "maxscore_assign_i32": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                              ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
@@ -227,16 +230,25 @@ def router_logits(x, W, bias=None, use_workspace=True):
     return out
 
 
-def softtopk(logits, k: int, t: float, quant_shift: int = 20):
-    """a2 + a3: (scores fp32 [T,E], q int32 [T,E])."""
+READINGS = {"A": 0, "A1": 1, "B": 2, "C": 3}
+
+
+def softtopk(logits, k: int, t: float, quant_shift: int = 20, reading: str = None):
+    """a2 + a3: (scores fp32 [T,E], q int32 [T,E]).  reading: None (maxscore_softtopk) or one of READINGS
+    (maxscore_softtopk_reading: the other readings of Eq. 6)."""
     torch = _torch()
     T, E = logits.shape
     assert logits.dtype == torch.float32 and logits.is_contiguous()
     scores = torch.empty_like(logits)
     q = torch.empty((T, E), dtype=torch.int32, device=logits.device)
-    rc = load_library().maxscore_softtopk(_ptr(logits), T, E, k, float(t), quant_shift, _ptr(scores), _ptr(q),
-                                          _stream())
-    _check(rc, "maxscore_softtopk")
+    if reading is None:
+        rc = load_library().maxscore_softtopk(_ptr(logits), T, E, k, float(t), quant_shift, _ptr(scores), _ptr(q),
+                                              _stream())
+        _check(rc, "maxscore_softtopk")
+    else:
+        rc = load_library().maxscore_softtopk_reading(_ptr(logits), T, E, k, float(t), quant_shift, READINGS[reading],
+                                                      _ptr(scores), _ptr(q), _stream())
+        _check(rc, "maxscore_softtopk_reading")
     return scores, q
 
 

@@ -98,6 +98,16 @@ int32_t maxscore_softtopk(const float *logits, int32_t T, int32_t E, int32_t k, 
     return softtopk_run(logits, T, E, k, t, quant_shift, scores, q, (hipStream_t)stream);
 }
 
+int32_t maxscore_softtopk_reading(const float *logits, int32_t T, int32_t E, int32_t k, float t, int32_t quant_shift,
+                                  int32_t reading, float *scores, int32_t *q, void *stream)
+{
+    if (!logits || (!scores && !q)) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, k, 1) || quant_shift < 1 || quant_shift > 24 || !(t >= 0.f) || t > 64.f)
+        return MAXSCORE_ERR_SHAPE;
+    if (reading < MAXSCORE_SOFTTOPK_A || reading > MAXSCORE_SOFTTOPK_C) return MAXSCORE_ERR_SHAPE;
+    return softtopk_run(logits, T, E, k, t, quant_shift, scores, q, (hipStream_t)stream, reading);
+}
+
 int32_t maxscore_assign_i32(const int32_t *q, int32_t T, int32_t E, int32_t k, int32_t C,
                             const maxscore_opts *opts, int32_t *assign, int64_t *prices, int64_t *price_scale,
                             maxscore_stats *stats, void *workspace, size_t workspace_bytes, void *stream)

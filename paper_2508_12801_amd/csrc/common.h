@@ -121,7 +121,7 @@ int32_t oversub_run(const int32_t *q, int T, int E, int k, int Ce, const maxscor
                     hipStream_t s);
 // --- softtopk.hip
 int32_t softtopk_run(const float *logits, int T, int E, int k, float t, int shift, float *scores, int32_t *q,
-                     hipStream_t s);
+                     hipStream_t s, int reading = MAXSCORE_SOFTTOPK_A);
 int32_t quantise_run(const float *scores, int T, int E, int shift, int32_t *q, hipStream_t s);
 int32_t gates_run(const float *scores, const int32_t *assign, int T, int E, int k, float *gates, hipStream_t s);
 // --- dispatch.hip

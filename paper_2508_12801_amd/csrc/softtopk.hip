@@ -4,6 +4,15 @@
 // Eq. 6 is taken level by level: level 1 is Softmax(a); level m = 2..k adds t*Softmax(a)_i to the
 // entries that are not among the m-1 largest of a.  An entry of descending rank r (1-based, equal
 // logits ranked by lower index) therefore ends as p_i * (1 + t*(min(r,k) - 1)).
+//
+// Eq. 6 prints no base case and an SE term that does not depend on the level, so other readings exist; they are
+// kept behind an argument (MAXSCORE_SOFTTOPK_*).  All of them end as p_i * (1 + t * w) with a weight w that
+// depends on the rank r of the entry alone:
+//   A   (above)                                   w = min(r, k) - 1
+//   A1  level 0 is Softmax, level m = 1..k masks the m largest:      w = min(r - 1, k)
+//   B   the printed mask (the k largest) at every level 2..k:        w = 0 for r <= k, k - 1 otherwise
+//   C   A with SE renormalised over the entries it is added to:      w = sum over m = 2..min(r, k) of
+//                                                                        1 / (mass of p outside the m-1 largest)
 #include "common.h"
 
 namespace maxscore {
@@ -30,7 +39,7 @@ __device__ __forceinline__ unsigned ord_f32(float x)
 template <int G, int EPL, bool VEC>
 __global__ __launch_bounds__(256) void k_softtopk(const float *__restrict__ logits, int T, int E, int k, float t,
                                                   float qscale, float *__restrict__ scores,
-                                                  int32_t *__restrict__ q)
+                                                  int32_t *__restrict__ q, int reading)
 {
     const int tid = threadIdx.x, lane = tid & 63, lg = lane & (G - 1);
     const int grp = tid / G, ngrp = 256 / G;
@@ -65,13 +74,14 @@ __global__ __launch_bounds__(256) void k_softtopk(const float *__restrict__ logi
         for (int off = G / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
         const float inv = 1.0f / sum;
 
-        // ranks 1..k-1 by repeated arg-max (equal logits: lower column first); the rest has min(rank,k) = k
-        int rk[EPL];
-#pragma unroll
-        for (int m = 0; m < EPL; ++m) rk[m] = k;
+        // the largest entries one by one (equal logits: lower column first), each with the weight of its rank; the
+        // entries that are never picked share the weight of the ranks beyond
+        const int n_pick = (reading == MAXSCORE_SOFTTOPK_A1 || reading == MAXSCORE_SOFTTOPK_B) ? k : k - 1;
+        float wv[EPL];
+        float w_run = 0.f;                 // reading C: the weight of the rank being picked
         unsigned taken = 0;
         if (t != 0.f) {
-            for (int r = 1; r < k; ++r) {
+            for (int r = 1; r <= n_pick; ++r) {
                 unsigned bo = 0;
                 int bm = -1;
 #pragma unroll
@@ -92,19 +102,33 @@ __global__ __launch_bounds__(256) void k_softtopk(const float *__restrict__ logi
                 const bool mine = kVec ? (((e >> 2) & (G - 1)) == lg) : (e / EPL == lg);
                 if (mine) {
                     const int m = kVec ? ((e / (4 * G)) * 4 + (e & 3)) : (e % EPL);
+                    const float w = reading == MAXSCORE_SOFTTOPK_B ? 0.f
+                                  : reading == MAXSCORE_SOFTTOPK_C ? w_run : (float)(r - 1);
 #pragma unroll
                     for (int mm = 0; mm < EPL; ++mm)
-                        if (mm == m) rk[mm] = r;
+                        if (mm == m) wv[mm] = w;
                     taken |= 1u << m;
+                }
+                if (reading == MAXSCORE_SOFTTOPK_C) {
+                    // mass outside the r largest, summed over what is left (no cancellation on peaked rows)
+                    float rest = 0.f;
+#pragma unroll
+                    for (int m = 0; m < EPL; ++m) rest += ((taken >> m) & 1u) ? 0.f : ex[m];
+#pragma unroll
+                    for (int off = G / 2; off > 0; off >>= 1) rest += __shfl_xor(rest, off);
+                    w_run += rest > 0.f ? 1.0f / (rest * inv) : 0.f;      // (nothing left: the entries beyond are 0 anyway)
                 }
             }
         }
+        const float w_rest = reading == MAXSCORE_SOFTTOPK_A1 ? (float)k
+                           : reading == MAXSCORE_SOFTTOPK_C  ? w_run : (float)(k - 1);
         float sc[EPL];
         int qq[EPL];
 #pragma unroll
         for (int m = 0; m < EPL; ++m) {
             const float p = ex[m] * inv;
-            sc[m] = p * (1.0f + t * (float)(rk[m] - 1));
+            const float w = ((taken >> m) & 1u) ? wv[m] : w_rest;
+            sc[m] = p * (1.0f + t * w);
             qq[m] = __float2int_rn(sc[m] * qscale);
         }
         const size_t o0 = (size_t)row * E + lg * EPL;
@@ -157,7 +181,7 @@ __global__ __launch_bounds__(256) void k_gates(const float *__restrict__ scores,
 }  // namespace
 
 int32_t softtopk_run(const float *logits, int T, int E, int k, float t, int shift, float *scores, int32_t *q,
-                     hipStream_t s)
+                     hipStream_t s, int reading)
 {
     int G = 8, EPL = 1;
     while (G * 16 < E) G *= 2;
@@ -172,10 +196,10 @@ int32_t softtopk_run(const float *logits, int T, int E, int k, float t, int shif
     do {                                                                                                            \
         if (vec)                                                                                                    \
             hipLaunchKernelGGL((k_softtopk<GG, PP, true>), dim3(grid), dim3(256), 0, s, logits, T, E, k, t, qscale, \
-                               scores, q);                                                                          \
+                               scores, q, reading);                                                                 \
         else                                                                                                        \
             hipLaunchKernelGGL((k_softtopk<GG, PP, false>), dim3(grid), dim3(256), 0, s, logits, T, E, k, t,        \
-                               qscale, scores, q);                                                                  \
+                               qscale, scores, q, reading);                                                         \
     } while (0)
 #define MS_ST(GG)                    \
     do {                             \

@@ -35,7 +35,7 @@ int32_t kvec_check(const int32_t *, int, int, int, char *, long long *demand, hi
     *demand = 0;
     return MAXSCORE_OK;
 }
-int32_t softtopk_run(const float *, int, int, int, float, int, float *, int32_t *, hipStream_t) { return MAXSCORE_OK; }
+int32_t softtopk_run(const float *, int, int, int, float, int, float *, int32_t *, hipStream_t, int) { return MAXSCORE_OK; }
 int32_t quantise_run(const float *, int, int, int, int32_t *, hipStream_t) { return MAXSCORE_OK; }
 int32_t gates_run(const float *, const int32_t *, int, int, int, float *, hipStream_t) { return MAXSCORE_OK; }
 int32_t dispatch_run(const int32_t *, const float *, int, int, int, int32_t *, int32_t *, float *, int32_t *, char *,

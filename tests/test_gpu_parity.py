@@ -57,6 +57,29 @@ def test_softtopk(ms, T, E, k, t):
     assert np.all(np.abs(q - qo) <= np.maximum(2, 2e-5 * qo))       # element by element
 
 
+@pytest.mark.parametrize("reading", ["A", "A1", "B", "C"])
+@pytest.mark.parametrize("T,E,k,t", [(300, 16, 2, 1.0), (257, 64, 8, 1.0), (1000, 128, 8, 4.0), (77, 5, 3, 1.0),
+                                      (50, 100, 7, 0.5), (33, 200, 16, 1.0), (40, 12, 12, 2.0), (9, 8, 1, 1.0)])
+def test_softtopk_other_readings(ms, reading, T, E, k, t):
+    """The other readings of Eq. 6 (maxscore_softtopk_reading) against the checker's recursions, same bars as the
+    reading the path uses; reading A through this entry is bit-equal to maxscore_softtopk."""
+    print(f"softtopk reading {reading} T={T} E={E} k={k} t={t}", flush=True)
+    rng = np.random.default_rng(T * 1000 + E)
+    L = (rng.standard_normal((T, E)) * 1.5).astype(np.float32)
+    L[3] = L[2]
+    L[5, : E // 2] = L[5, 0]
+    scores, q = ms.softtopk(dev(L), k, t, reading=reading)
+    scores, q = scores.cpu().numpy(), q.cpu().numpy()
+    ref = oracle.soft_topk_reading(L.astype(np.float64), k, t, reading)
+    assert np.all(np.abs(scores - ref) <= 1e-5 * np.abs(ref) + 1e-12)
+    assert np.array_equal(q, np.rint(scores.astype(np.float64) * 2.0 ** 20).astype(np.int64))
+    qo = oracle.quantise(ref)
+    assert np.all(np.abs(q - qo) <= np.maximum(2, 2e-5 * qo))
+    if reading == "A":
+        s0, q0 = ms.softtopk(dev(L), k, t)
+        assert np.array_equal(s0.cpu().numpy(), scores) and np.array_equal(q0.cpu().numpy(), q)
+
+
 # ---- a4 -----------------------------------------------------------------------------------------
 
 def check_assignment(ms, q64, k, C, ref_total=None, **kw):
