@@ -120,6 +120,9 @@ def main():
     gemm_ms = timed(lambda: ms.router_logits(x, W, b))
     logits = out["logits"]
     soft_ms = timed(lambda: ms.softtopk(logits, k, r.t))
+    # a1..a3 as the whole path runs them where it can: one kernel, the scores come out of the projection's accumulators
+    fused_ms = timed(lambda: ms.router_softtopk(x, W, b, k, r.t))
+    fused_nolog_ms = timed(lambda: ms.router_softtopk(x, W, b, k, r.t, want_logits=False))
     gates_ms = timed(lambda: ms.gates(out["scores"], out["assign"]))
     disp_ms = timed(lambda: ms.dispatch(out["assign"], out["gates"], E, C))
     solve_ms = sorted(ms.assign_i32(out["q"], k, C)["stats"]["solver_ms"] for _ in range(5))[2]   # median, untimed launches
@@ -297,7 +300,11 @@ def main():
                      "copy_kernel_GBs": copy_gbs,
                      "note": "frac is below the 0.5 target: the passes are bound by launch and chain latency, "
                              "not by bytes (DESIGN.md section 8)"},
-        "stages_ms": {"router_gemm": gemm_ms, "softtopk_quantise": soft_ms, "assignment": solve_ms,
+        "stages_ms": {"router_gemm": gemm_ms, "softtopk_quantise": soft_ms,
+                      "router_gemm_softtopk_one_kernel": fused_ms,
+                      "router_gemm_softtopk_one_kernel_no_logits": fused_nolog_ms,
+                      "one_kernel_hbm_frac": (T * d * 2 + d * E * 2 + 3 * T * E * 4) / (fused_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      "assignment": solve_ms,
                       "gates_dispatch_in_route": gd_ms, "gates_entry": gates_ms, "dispatch_entry": disp_ms,
                       "gemm_hbm_frac": (T * d * 2 + d * E * 2 + T * E * 4) / (gemm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                       "gemm_tflops": 2.0 * T * d * E / (gemm_ms * 1e-3) / 1e12},

@@ -336,7 +336,19 @@ int32_t maxscore_route_scores(const float *scores, int32_t T, int32_t E, int32_t
                               int32_t *token_pos, int64_t *prices, maxscore_stats *stats, void *workspace,
                               size_t workspace_bytes, void *stream);
 
-/* a1..a6 from x and W_g.  logits_out[T,E] is required.  Synchronises `stream`. */
+/* a1 + a2 + a3: scores[T,E] and/or q[T,E] from x and W_g (Eq. 2, then Eq. 6 and the rounding), in one kernel where
+ * maxscore_route_xw can do so (same conditions, `workspace` as for maxscore_router_logits; logits_out may then be
+ * NULL), else by the two kernels of maxscore_router_logits and maxscore_softtopk through logits_out (required
+ * then).  Only enqueues work. */
+int32_t maxscore_router_softtopk(const void *x, const void *W, const float *bias, int32_t in_dtype, int32_t T,
+                                 int32_t d, int32_t E, int32_t k, float t, int32_t quant_shift, float *logits_out,
+                                 float *scores, int32_t *q, void *workspace, size_t workspace_bytes, void *stream);
+
+/* a1..a6 from x and W_g.  With bf16 inputs, E in {32, 64, 128}, d a multiple of 64 and the workspace of
+ * maxscore_workspace_bytes(T, d, ...) the projection computes the SoftTopk scores and the rewards in its own
+ * epilogue (a1..a3 in one kernel, Eq. 2 -> Eq. 6; scores and rewards bit-equal to the separate kernels'); then
+ * logits_out may be NULL and the logits are never written.  Otherwise logits_out[T,E] is required
+ * (MAXSCORE_ERR_NULL).  Synchronises `stream`. */
 int32_t maxscore_route_xw(const void *x, const void *W, const float *bias, int32_t in_dtype,
                           int32_t T, int32_t d, int32_t E, int32_t k, int32_t C,
                           const maxscore_opts *opts, float *logits_out, float *scores_out,

@@ -95,6 +95,10 @@ _SIGS = {
                                            ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                            ctypes.c_int32, ctypes.c_void_p] + [ctypes.c_void_p] * 12 +
                           [ctypes.c_size_t, ctypes.c_void_p]),
+    "maxscore_router_softtopk": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                                  ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                                  ctypes.c_float, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "maxscore_set_kernel_timing": (None, [ctypes.c_int32]),
     "maxscore_copy_bytes": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "maxscore_status_string": (ctypes.c_char_p, [ctypes.c_int32]),
@@ -228,6 +232,29 @@ def router_logits(x, W, bias=None, use_workspace=True):
                                                _ptr(ws), need, _stream())
     _check(rc, "maxscore_router_logits")
     return out
+
+
+def router_softtopk(x, W, bias, k: int, t: float, quant_shift: int = 20, want_logits: bool = True):
+    """a1 + a2 + a3: dict(logits or None, scores fp32 [T,E], q int32 [T,E]) from x and W_g; one kernel where the
+    library can fuse them (then the logits are optional), else the projection and the score kernel."""
+    torch = _torch()
+    T, d = x.shape
+    E = W.shape[1]
+    assert W.shape[0] == d and x.is_contiguous() and W.is_contiguous() and x.dtype == W.dtype
+    logits = torch.empty((T, E), dtype=torch.float32, device=x.device) if want_logits else None
+    scores = torch.empty((T, E), dtype=torch.float32, device=x.device)
+    q = torch.empty((T, E), dtype=torch.int32, device=x.device)
+    need = 2 * d * E
+    key = ("wt", str(x.device), torch.cuda.current_stream(x.device).cuda_stream)
+    ws = _WS.get(key)
+    if ws is None or ws.numel() < need:
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+        _WS[key] = ws
+    rc = load_library().maxscore_router_softtopk(_ptr(x), _ptr(W), _ptr(bias), _in_dtype(x), T, d, E, k, float(t),
+                                                 quant_shift, _ptr(logits), _ptr(scores), _ptr(q), _ptr(ws), need,
+                                                 _stream())
+    _check(rc, "maxscore_router_softtopk")
+    return dict(logits=logits, scores=scores, q=q)
 
 
 READINGS = {"A": 0, "A1": 1, "B": 2, "C": 3}
@@ -557,15 +584,16 @@ def route_scores(scores, k: int, C: int, quant_shift: int = 20, max_rounds: int 
 
 
 def route_xw(x, W, bias, k: int, C: int, t: float = 1.0, quant_shift: int = 20, max_rounds: int = 200000,
-             eps_div: int = 12, out: Optional[dict] = None, assignment: str = "exact"):
-    """a1..a6 from x and W_g."""
+             eps_div: int = 12, out: Optional[dict] = None, assignment: str = "exact", want_logits: bool = True):
+    """a1..a6 from x and W_g.  want_logits=False passes no logits buffer (accepted where the library computes the
+    scores inside the projection kernel; MaxScoreError -1 otherwise)."""
     torch = _torch()
     T, d = x.shape
     E = W.shape[1]
     assert W.shape[0] == d and x.is_contiguous() and W.is_contiguous() and x.dtype == W.dtype
     o = out if out is not None else _route_outputs(T, E, k, x.device)
     if "logits" not in o:
-        o["logits"] = torch.empty((T, E), dtype=torch.float32, device=x.device)
+        o["logits"] = torch.empty((T, E), dtype=torch.float32, device=x.device) if want_logits else None
     ws, need = _workspace(T, E, k, C, x.device, d)
     stats = Stats()
     opts = _opts(t, quant_shift, max_rounds, eps_div, assignment)

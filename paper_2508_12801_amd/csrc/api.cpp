@@ -59,6 +59,14 @@ static int32_t check_ws(const void *ws, size_t bytes, int T, int E, int k)
     return MAXSCORE_OK;
 }
 
+// The projection can compute the scores in its own epilogue (and skip the logits if the caller passes none).
+static bool fused_scores_ok(int dtype, int d, int E, const void *x, const void *wt, const float *logits,
+                            const float *scores, const int32_t *q)
+{
+    return gemm_softtopk_supported(dtype, d, E, x, wt) &&
+           ((((uintptr_t)logits) | ((uintptr_t)scores) | ((uintptr_t)q)) % 16) == 0;
+}
+
 }  // namespace maxscore
 
 using namespace maxscore;
@@ -416,24 +424,55 @@ int32_t maxscore_route_xw(const void *x, const void *W, const float *bias, int32
                           int64_t *prices, maxscore_stats *stats, void *workspace, size_t workspace_bytes,
                           void *stream)
 {
-    if (!x || !W || !logits_out) return MAXSCORE_ERR_NULL;
+    if (!x || !W) return MAXSCORE_ERR_NULL;
     if (d < 1) return MAXSCORE_ERR_SHAPE;
     if (in_dtype != MAXSCORE_DTYPE_BF16 && in_dtype != MAXSCORE_DTYPE_FP32) return MAXSCORE_ERR_DTYPE;
     if (!shape_ok(T, E, k, C)) return MAXSCORE_ERR_SHAPE;
     if (!scores_out || !q_out || !assign || !gates || !expert_offsets || !disp_token || !disp_gate || !token_pos)
         return MAXSCORE_ERR_NULL;
-    int32_t rc = route_check(T, E, k, C, resolve(opts), workspace, workspace_bytes);
+    const maxscore_opts o = resolve(opts);
+    int32_t rc = route_check(T, E, k, C, o, workspace, workspace_bytes);
     if (rc) return rc;
     void *wt = nullptr;
     {
         WorkspaceLayout L = workspace_layout(T, E, k, d);
         if (workspace_bytes >= L.total) wt = (char *)workspace + L.wt_off;
     }
-    rc = gemm_run(x, W, bias, in_dtype, T, d, E, logits_out, wt, (hipStream_t)stream);
+    hipStream_t s = (hipStream_t)stream;
+    if (fused_scores_ok(in_dtype, d, E, x, wt, logits_out, scores_out, q_out)) {
+        // a1..a3 in one kernel: the scores come straight out of the projection's accumulators
+        if (stats) std::memset(stats, 0, sizeof(*stats));
+        rc = gemm_softtopk_run(x, W, bias, in_dtype, T, d, E, k, o.t, o.quant_shift, logits_out, scores_out, q_out, wt,
+                               s);
+        if (rc) return rc;
+        return route_from_rewards(scores_out, q_out, T, E, k, C, o, assign, gates, expert_offsets, disp_token,
+                                  disp_gate, token_pos, prices, stats, (char *)workspace, workspace_bytes, s);
+    }
+    if (!logits_out) return MAXSCORE_ERR_NULL;          // the two-kernel form keeps the logits in the caller's buffer
+    rc = gemm_run(x, W, bias, in_dtype, T, d, E, logits_out, wt, s);
     if (rc) return rc;
     return maxscore_route_logits(logits_out, T, E, k, C, opts, scores_out, q_out, assign, gates, expert_offsets,
                                  disp_token, disp_gate, token_pos, prices, stats, workspace, workspace_bytes,
                                  stream);
+}
+
+int32_t maxscore_router_softtopk(const void *x, const void *W, const float *bias, int32_t in_dtype, int32_t T,
+                                 int32_t d, int32_t E, int32_t k, float t, int32_t quant_shift, float *logits_out,
+                                 float *scores, int32_t *q, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x || !W || (!scores && !q)) return MAXSCORE_ERR_NULL;
+    if (!shape_ok(T, E, k, 1) || d < 1 || quant_shift < 1 || quant_shift > 24 || !(t >= 0.f) || t > 64.f)
+        return MAXSCORE_ERR_SHAPE;
+    if (in_dtype != MAXSCORE_DTYPE_BF16 && in_dtype != MAXSCORE_DTYPE_FP32) return MAXSCORE_ERR_DTYPE;
+    void *wt = nullptr;     // optional scratch for the transposed weight: d*E 16-bit values, 256-byte aligned
+    if (workspace && ((uintptr_t)workspace % 256) == 0 && workspace_bytes >= (size_t)d * E * 2) wt = workspace;
+    hipStream_t s = (hipStream_t)stream;
+    if (fused_scores_ok(in_dtype, d, E, x, wt, logits_out, scores, q))
+        return gemm_softtopk_run(x, W, bias, in_dtype, T, d, E, k, t, quant_shift, logits_out, scores, q, wt, s);
+    if (!logits_out) return MAXSCORE_ERR_NULL;
+    int32_t rc = gemm_run(x, W, bias, in_dtype, T, d, E, logits_out, wt, s);
+    if (rc) return rc;
+    return softtopk_run(logits_out, T, E, k, t, quant_shift, scores, q, s);
 }
 
 void maxscore_set_kernel_timing(int32_t on) { g_kernel_timing = on ? 1 : 0; }

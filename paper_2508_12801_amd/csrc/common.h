@@ -171,6 +171,12 @@ int32_t combine_run(const void *buf, int dtype, const int32_t *assign, const int
 // --- gemm.hip
 int32_t gemm_run(const void *x, const void *W, const float *bias, int dtype, int T, int d, int E, float *logits,
                  void *wt_scratch, hipStream_t s);
+// a1 + a2 + a3 in one kernel (the scores come out of the projection's accumulators): bf16 inputs, E in {32, 64, 128},
+// d a multiple of 64, the transposed-weight scratch given.  logits may be null (then they are never written).
+bool gemm_softtopk_supported(int dtype, int d, int E, const void *x, const void *wt_scratch);
+int32_t gemm_softtopk_run(const void *x, const void *W, const float *bias, int dtype, int T, int d, int E, int k,
+                          float t, int shift, float *logits, float *scores, int32_t *q, void *wt_scratch,
+                          hipStream_t s);
 int32_t copy_run(const void *src, void *dst, size_t bytes, hipStream_t s);
 
 extern int g_kernel_timing;

@@ -7,6 +7,7 @@
 // kernel (k_gemm_bf16_wtc) reads x with whole-line loads and restores the operand layout through LDS.
 // fp32 inputs (the tiny configuration) use a plain FMA kernel.
 #include "common.h"
+#include "softtopk_row.h"
 
 namespace maxscore {
 namespace {
@@ -247,11 +248,18 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_wt(const unsigned short *__re
 // instruction then reads whole 128-byte lines (8 rows x 128 B, 8 lanes per row) instead of 32 rows x 32 B in the
 // MFMA operand layout, which is what the memory pipeline prefers; the operand layout is restored by the LDS
 // read.  Needs d to be a multiple of 64.
-template <int NT, int RB, int NS>
+//
+// FUSE: the workgroup holds whole rows (E = 32 * NT columns, one workgroup column), so the SoftTopk scores and the
+// integer rewards of Eq. 6 are computed here, from the accumulators, instead of writing the logits and reading
+// them back in a second kernel: every wavefront passes its 32 rows through LDS, 16 at a time, into the layout of
+// the score kernel (8 lanes per row, 16-byte pieces) and runs that kernel's row routine on them.  The logits are
+// written only if the caller wants them.
+template <int NT, int RB, int NS, bool FUSE>
 __global__ __launch_bounds__(256) void k_gemm_bf16_wtc(const unsigned short *__restrict__ x,
                                                        const unsigned short *__restrict__ wt,
                                                        const float *__restrict__ bias, int T, int d, int E,
-                                                       float *__restrict__ out)
+                                                       float *__restrict__ out, float *__restrict__ scores,
+                                                       int32_t *__restrict__ q, int k, float t, float qscale)
 {
     constexpr int BN = 32 * NT;
     constexpr int RW = 32 * RB;                  // rows per wavefront
@@ -346,6 +354,59 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_wtc(const unsigned short *__r
         for (int i = 0; i < NS; ++i)
             if (it + i < nslab) step(it + i, ra[i]);
     }
+    if constexpr (FUSE) {
+        static_assert(RB == 1, "the fused epilogue handles 32 rows per wavefront");
+        constexpr int EPLS = BN / 8;                 // values per lane with 8 lanes per row
+        constexpr int SP = BN + 4;                   // pitch of a staged row in floats
+        static_assert(4 * 16 * SP * sizeof(float) <= sizeof(sB), "the staged rows reuse the W tiles");
+        __syncthreads();                             // every wavefront is done with the W tiles
+        float *stage = (float *)&sB[0][0] + wave * (16 * SP);
+        float bvs[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) bvs[nt] = bias ? bias[nt * 32 + (lane & 31)] : 0.f;
+        const int lg = lane & 7, rl = lane >> 3;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        stage[(8 * jj + 4 * (lane >> 5) + i) * SP + nt * 32 + (lane & 31)] =
+                            acc[0][nt][4 * (2 * half + jj) + i] + bvs[nt];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+                const int r_local = 8 * pass + rl;
+                const int row = row0 + wave * RW + 16 * half + r_local;
+                float xv[EPLS];
+#pragma unroll
+                for (int m = 0; m < EPLS; m += 4) {
+                    const float4 v4 = *(const float4 *)&stage[r_local * SP + (m >> 2) * 32 + lg * 4];
+                    xv[m] = v4.x; xv[m + 1] = v4.y; xv[m + 2] = v4.z; xv[m + 3] = v4.w;
+                }
+                float sc[EPLS];
+                int qq[EPLS];
+                softtopk_row<8, EPLS, true>(xv, lg, E, k, t, qscale, MAXSCORE_SOFTTOPK_A, sc, qq);
+                if (row < T) {
+#pragma unroll
+                    for (int m = 0; m < EPLS; m += 4) {
+                        const size_t o = (size_t)row * E + (m >> 2) * 32 + lg * 4;
+                        if (out) *(float4 *)(out + o) = make_float4(xv[m], xv[m + 1], xv[m + 2], xv[m + 3]);
+                        if (scores) *(float4 *)(scores + o) = make_float4(sc[m], sc[m + 1], sc[m + 2], sc[m + 3]);
+                        if (q) *(int4 *)(q + o) = make_int4(qq[m], qq[m + 1], qq[m + 2], qq[m + 3]);
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();         // the next half overwrites the staged rows
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        return;
+    }
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int col = col0 + nt * 32 + (lane & 31);
@@ -403,8 +464,9 @@ int32_t gemm_run(const void *x, const void *W, const float *bias, int dtype, int
     if (wt_scratch && d % 8 == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)wt_scratch % 16) == 0) {
         unsigned short *wt = (unsigned short *)wt_scratch;
         hipLaunchKernelGGL(k_transpose_w, dim3((d + 31) / 32, (E + 31) / 32), dim3(256), 0, s, wb, wt, d, E);
-#define MS_GEMM3(NT_) \
-    hipLaunchKernelGGL((k_gemm_bf16_wtc<NT_, 1, 2>), grid, dim3(256), 0, s, xb, wt, bias, T, d, E, logits)
+#define MS_GEMM3(NT_)                                                                                          \
+    hipLaunchKernelGGL((k_gemm_bf16_wtc<NT_, 1, 2, false>), grid, dim3(256), 0, s, xb, wt, bias, T, d, E, logits, \
+                       (float *)nullptr, (int32_t *)nullptr, 0, 0.f, 0.f)
         if (d % BK == 0) {
             if (nt == 1) MS_GEMM3(1);
             else if (nt == 2) MS_GEMM3(2);
@@ -438,6 +500,34 @@ int32_t gemm_run(const void *x, const void *W, const float *bias, int dtype, int
         else MS_GEMM(4, false);
     }
 #undef MS_GEMM
+    MS_HIP(hipGetLastError());
+    return MAXSCORE_OK;
+}
+
+bool gemm_softtopk_supported(int dtype, int d, int E, const void *x, const void *wt_scratch)
+{
+    return dtype == MAXSCORE_DTYPE_BF16 && (E == 32 || E == 64 || E == 128) && d >= BK && d % BK == 0 && wt_scratch &&
+           ((uintptr_t)x % 16) == 0 && ((uintptr_t)wt_scratch % 16) == 0;
+}
+
+int32_t gemm_softtopk_run(const void *x, const void *W, const float *bias, int dtype, int T, int d, int E, int k,
+                          float t, int shift, float *logits, float *scores, int32_t *q, void *wt_scratch,
+                          hipStream_t s)
+{
+    if (!gemm_softtopk_supported(dtype, d, E, x, wt_scratch)) return MAXSCORE_ERR_SHAPE;
+    if (((((uintptr_t)logits) | ((uintptr_t)scores) | ((uintptr_t)q)) % 16) != 0) return MAXSCORE_ERR_SHAPE;
+    const unsigned short *xb = (const unsigned short *)x, *wb = (const unsigned short *)W;
+    unsigned short *wt = (unsigned short *)wt_scratch;
+    hipLaunchKernelGGL(k_transpose_w, dim3((d + 31) / 32, (E + 31) / 32), dim3(256), 0, s, wb, wt, d, E);
+    dim3 grid((T + BM - 1) / BM, 1);
+    const float qscale = (float)(1 << shift);
+#define MS_GEMMF(NT_)                                                                                         \
+    hipLaunchKernelGGL((k_gemm_bf16_wtc<NT_, 1, 2, true>), grid, dim3(256), 0, s, xb, wt, bias, T, d, E, logits, \
+                       scores, q, k, t, qscale)
+    if (E == 32) MS_GEMMF(1);
+    else if (E == 64) MS_GEMMF(2);
+    else MS_GEMMF(4);
+#undef MS_GEMMF
     MS_HIP(hipGetLastError());
     return MAXSCORE_OK;
 }

@@ -108,6 +108,15 @@ int32_t gemm_run(const void *, const void *, const float *, int, int, int, int, 
 {
     return MAXSCORE_OK;
 }
+bool gemm_softtopk_supported(int dtype, int d, int E, const void *, const void *wt)
+{
+    return dtype == MAXSCORE_DTYPE_BF16 && (E == 32 || E == 64 || E == 128) && d % 64 == 0 && wt;
+}
+int32_t gemm_softtopk_run(const void *, const void *, const float *, int, int, int, int, int, float, int, float *,
+                          float *, int32_t *, void *, hipStream_t)
+{
+    return MAXSCORE_OK;
+}
 int32_t copy_run(const void *, void *, size_t, hipStream_t) { return MAXSCORE_OK; }
 
 }  // namespace maxscore
