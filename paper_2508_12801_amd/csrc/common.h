@@ -107,10 +107,10 @@ size_t finish_area_bytes(int T);          // bytes of WorkspaceLayout::fin_off's
 // holds fin_tri_entries() of them (enough for every geometry the solver picks: rows * k <= 1024 per block).
 inline int fin_seg_cap(int rows, int k)
 {
-    const int c = rows * k / 8;
-    return c < 8 ? 8 : c;
+    const int c = rows * k / 4;
+    return c < 16 ? 16 : c;
 }
-inline size_t fin_tri_entries(int T, int k, int max_wg) { return ((size_t)T + 1024) * k / 8 + 8 * (size_t)max_wg + 8; }
+inline size_t fin_tri_entries(int T, int k, int max_wg) { return ((size_t)T + 1024) * k / 4 + 16 * (size_t)max_wg + 16; }
 // --- oversub.hip
 // Exact assignment with more demand than capacity (T*k > E*Ce): every expert ends full, the placed pairs have the
 // maximum score, rows come back with their experts first and -1 in the slots left empty.  Needs E + k <= kMaxE and
