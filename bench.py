@@ -157,6 +157,50 @@ def main():
     copy_gbs = 2 * src.numel() / (copy_ms * 1e-3) / 1e9
     del src, dst
 
+    # Several routing calls in flight: a call is bound by launch and chain latency and leaves most of the GPU idle, so
+    # independent batches routed at the same time (one host thread, stream, workspace and set of buffers each) share
+    # it well.  Reported beside `value`, which stays the one-call-at-a-time figure.
+    import threading
+    concurrent = {}
+    batches = [(x, W, b)]
+    for bi in range(1, 4):          # further batches of the same router: x ~ N(0,1) as in the recipe, drawn on the device
+        gen = torch.Generator(device=dev).manual_seed(1000 + bi)
+        xi_ = torch.randn(T, d, generator=gen, device=dev, dtype=torch.float32)
+        batches.append((xi_.to(torch.bfloat16) if r.dtype == "bf16" else xi_, W, b))
+        del xi_
+    for n_streams in (2, 4):
+        res = [None] * n_streams
+        gate = threading.Barrier(n_streams + 1)
+        n_calls = 10
+
+        def worker(i):
+            st_ = torch.cuda.Stream(device=dev)
+            xi, Wi, bi_ = batches[i]
+            with torch.cuda.stream(st_):
+                o = ms.route_xw(xi, Wi, bi_, k, C, t=r.t)
+                o = ms.route_xw(xi, Wi, bi_, k, C, t=r.t, out=o)
+                st_.synchronize()
+                gate.wait()
+                t_a = time.perf_counter()
+                for _ in range(n_calls):
+                    o = ms.route_xw(xi, Wi, bi_, k, C, t=r.t, out=o)
+                st_.synchronize()
+                res[i] = (time.perf_counter() - t_a, o["stats"]["status"], o["stats"]["flow_value"])
+
+        th = [threading.Thread(target=worker, args=(i,)) for i in range(n_streams)]
+        for t_ in th:
+            t_.start()
+        gate.wait()
+        t_a = time.perf_counter()
+        for t_ in th:
+            t_.join()
+        wall = time.perf_counter() - t_a
+        assert all(r_ is not None and r_[1] == 0 and r_[2] == min(T * k, E * min(C, T)) for r_ in res)
+        concurrent[str(n_streams)] = {"calls": n_streams * n_calls, "wall_ms": wall * 1e3,
+                                      "tokens_per_s": n_streams * n_calls * T / wall,
+                                      "latency_ms_per_call": sum(r_[0] for r_ in res) / n_streams / n_calls * 1e3}
+    del batches
+
     # the same solve with the auction running down to eps = 1 itself (no finisher), for comparison
     auction_only = ms.assign_i32(out["q"], k, C, finisher=False)["stats"]
     auction_only = {"solver_ms": sorted(ms.assign_i32(out["q"], k, C, finisher=False)["stats"]["solver_ms"]
@@ -308,6 +352,8 @@ def main():
                       "gates_dispatch_in_route": gd_ms, "gates_entry": gates_ms, "dispatch_entry": disp_ms,
                       "gemm_hbm_frac": (T * d * 2 + d * E * 2 + T * E * 4) / (gemm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                       "gemm_tflops": 2.0 * T * d * E / (gemm_ms * 1e-3) / 1e12},
+        "concurrent_calls": {"note": "independent batches routed at the same time, one host thread and stream each; "
+                                     "not part of `value`", "streams": concurrent},
         "tie_heavy_solve": tie,
         "auction_without_finisher": auction_only,
         "activation_movement": movement,
