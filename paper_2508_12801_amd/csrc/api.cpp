@@ -343,15 +343,30 @@ static int32_t route_from_rewards(const float *scores, const int32_t *q, int T, 
         // more demand than capacity: every expert ends full, rows come back with empty slots (-1) at their end
         src = oversub_run(q, T, E, k, Ce, o, assign, prices, nullptr, stats, ws, ws_bytes, s);
     } else {
-        SolverGeometry geom = {0, 0, 0};
-        src = solver_run(q, T, E, k, Ce, o, assign, prices, nullptr, stats, ws, s, nullptr, 0, nullptr, 0, &geom);
-        if (src == MAXSCORE_OK && geom.n_wg > 0) {
-            // converged: the final bid pass left every pair as a key, sorted by expert inside each block of rows
-            MS_HIP(hipEventRecord(ev_a, s));
-            int32_t rc = dispatch_from_keys(geom, scores, assign, T, E, k, gates, expert_offsets, disp_token,
-                                            disp_gate, token_pos, ws, s);
+        // After a converged solve the final bid pass has left every pair as a key, sorted by expert inside each block
+        // of rows: gates and dispatch come from there.  They are enqueued behind the solve before the call waits for
+        // it (the kernels stay inside their buffers on any state; if the solve did not converge the general kernels
+        // below overwrite what they wrote).
+        struct AfterCtx {
+            const float *scores; const int32_t *assign; int T, E, k; float *gates; int32_t *offsets, *disp_token;
+            float *disp_gate; int32_t *token_pos; char *ws; hipEvent_t ev_a, ev_b;
+        } ctx = {scores, assign, T, E, k, gates, expert_offsets, disp_token, disp_gate, token_pos, ws, ev_a, ev_b};
+        SolverAfter after = [](void *c, const SolverGeometry &g, hipStream_t st) -> int32_t {
+            AfterCtx *a = (AfterCtx *)c;
+            MS_HIP(hipEventRecord(a->ev_a, st));
+            int32_t rc = dispatch_from_keys(g, a->scores, a->assign, a->T, a->E, a->k, a->gates, a->offsets,
+                                            a->disp_token, a->disp_gate, a->token_pos, a->ws, st);
             if (rc) return rc;
-            return finish(src);
+            MS_HIP(hipEventRecord(a->ev_b, st));
+            return MAXSCORE_OK;
+        };
+        SolverGeometry geom = {0, 0, 0};
+        src = solver_run(q, T, E, k, Ce, o, assign, prices, nullptr, stats, ws, s, nullptr, 0, nullptr, 0, &geom, after,
+                         &ctx);
+        if (src == MAXSCORE_OK && geom.n_wg > 0) {
+            float t = 0.f;           // the solve has waited for the stream: both events are complete
+            if (stats && hipEventElapsedTime(&t, ev_a, ev_b) == hipSuccess) stats->gates_dispatch_ms = t;
+            return src;
         }
     }
     if (src != MAXSCORE_OK && src != MAXSCORE_ERR_NOT_CONVERGED) return src;

@@ -85,10 +85,16 @@ inline bool hip_ok(hipError_t e) { return e == hipSuccess; }
 // --- solver.hip
 // cap: optional device array of E per-expert capacities (each <= T) with sum `room`; NULL = Ce for all.
 // kvec: optional device array of T per-token k (each 0..k) with sum `demand`; NULL = k for all.
+// after: optional work the caller wants behind the solve on the same stream (the routing calls' gates and dispatch).
+// It is enqueued before the call waits for the stream, so the device goes from the solve straight into it; it
+// runs whatever the solve's status turns out to be and must therefore be safe on any state the solver can leave
+// (the caller redoes it another way when the status is not MAXSCORE_OK).
+typedef int32_t (*SolverAfter)(void *ctx, const SolverGeometry &g, hipStream_t s);
 int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore_opts &o, int32_t *assign,
                    int64_t *prices, int64_t *price_scale, maxscore_stats *stats, char *ws, hipStream_t s,
                    const int32_t *cap = nullptr, long long room = 0, const int32_t *kvec = nullptr,
-                   long long demand = 0, SolverGeometry *geom = nullptr);
+                   long long demand = 0, SolverGeometry *geom = nullptr, SolverAfter after = nullptr,
+                   void *after_ctx = nullptr);
 // Checks a device array of T per-token k (each 0..k) and returns its sum in *demand (synchronises the stream).
 int32_t kvec_check(const int32_t *kvec, int T, int E, int k, char *ws, long long *demand, hipStream_t s);
 // --- finish.hip

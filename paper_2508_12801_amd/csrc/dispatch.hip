@@ -246,6 +246,7 @@ __global__ __launch_bounds__(256) void k_keys_scatter(const long long *__restric
         const int e = s_e[idx];
         if (e < 0) continue;
         const int off = s_meta[e] >> 16, cnt = s_meta[e] & 0xffff;
+        if (off + cnt > nslots) continue;                  // never with the counts of this block's own bid pass
         const int tok = (int)(s_key[idx] & tmask);
         const int lr = tok - row0;
         if (lr < 0 || lr >= rows_here) continue;           // never with keys of this block

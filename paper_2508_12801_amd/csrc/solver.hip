@@ -1907,7 +1907,8 @@ static int32_t solver_host(SolverHost **out)
 
 int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore_opts &o, int32_t *assign,
                    int64_t *prices, int64_t *price_scale, maxscore_stats *stats, char *ws, hipStream_t s,
-                   const int32_t *cap, long long room, const int32_t *kvec, long long demand, SolverGeometry *geom)
+                   const int32_t *cap, long long room, const int32_t *kvec, long long demand, SolverGeometry *geom,
+                   SolverAfter after, void *after_ctx)
 {
     WorkspaceLayout L = workspace_layout(T, E, k);
     SolverState *st = (SolverState *)(ws + L.state_off);
@@ -2111,6 +2112,16 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     hipLaunchKernelGGL(k_finalize, dim3(kFinalBlocks), dim3(256), 0, s, q, assign, cand, T, E, k);   // lists are free again
     hipLaunchKernelGGL(k_finalize2, dim3(1), dim3(kFinalBlocks), 0, s, cand, theta, st + fpar, prices, price_scale, E);
     MS_HIP_SYNC(hipEventRecord(hs->ev1, s));
+    if (after) {
+        int tb = 1;                       // as k_setup computes it
+        while ((1 << tb) < T) ++tb;
+        const SolverGeometry g = {rows, n_wg, tb};
+        const int32_t arc = after(after_ctx, g, s);
+        if (arc != MAXSCORE_OK) {
+            (void)hipStreamSynchronize(s);
+            return arc;
+        }
+    }
     SolverState h;
     MS_HIP_SYNC(hipMemcpyAsync(&h, st + fpar, sizeof(h), hipMemcpyDeviceToHost, s));
     MS_HIP(hipStreamSynchronize(s));

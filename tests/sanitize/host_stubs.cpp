@@ -9,7 +9,7 @@ int g_kernel_timing = 0;
 
 int32_t solver_run(const int32_t *, int, int, int, int, const maxscore_opts &, int32_t *, int64_t *, int64_t *,
                    maxscore_stats *, char *, hipStream_t, const int32_t *, long long, const int32_t *, long long,
-                   SolverGeometry *)
+                   SolverGeometry *, SolverAfter, void *)
 {
     return MAXSCORE_OK;
 }
