@@ -102,12 +102,14 @@ int32_t kvec_check(const int32_t *kvec, int T, int E, int k, char *ws, long long
 // cycles of the expert graph until none is left and replaces the prices by exact ones.  One call enqueues the passes
 // first_pass .. first_pass + passes - 1 of total_passes, each a pair of (arc matrix, Bellman-Ford + cancelling) that
 // exits at once unless st->fin is 1, and a last kernel that reports to host_words[0..3]: {1 certified | 2 the auction
-// goes on | 3 not finished, passes left; cycles cancelled so far; st->fin; round}.  Supports E <= kFinMaxE.
+// goes on | 3 not finished, passes left; cycles cancelled so far; st->fin; round}.  retry: when the auction has to
+// go on it stops again one rung further down (the finisher can be enqueued anew, from pass 0) instead of running to
+// eps = 1.  Supports E <= kFinMaxE.
 constexpr int kFinMaxE = 128;
 constexpr int kFinMovedCap = 4096;        // tokens the finisher may move in one solve (more: the auction goes on)
 int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long long *theta2, const int *loads2,
                        const int *cap, int Ce, int T, int E, int k, char *ws, int rows, int n_wg, int first_pass,
-                       int passes, int total_passes, long long bound_mult, int *host_words, hipStream_t s);
+                       int passes, int total_passes, long long bound_mult, int *host_words, int retry, hipStream_t s);
 size_t finish_area_bytes(int T);          // bytes of WorkspaceLayout::fin_off's region
 // Arc lists of the finisher's first pass: key block w owns fin_seg_cap(rows, k) consecutive entries; the region
 // holds fin_tri_entries() of them (enough for every geometry the solver picks: rows * k <= 1024 per block).

@@ -864,9 +864,12 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
 
 // After a group of passes: the host learns where the finisher stands (word 0: 1 = certified, 2 = the auction goes
 // on, 3 = passes are left and the work is not finished).  After the last pass, or when the finisher gave up, an
-// optimum that is not certified sends the auction one step further down its ladder, to eps = 1, from the state the
-// finisher left (its exchanges only improved the assignment).
-__global__ void k_fin_end(SolverState *st, int T, int *host_words, int final)
+// optimum that is not certified sends the auction one step further down its ladder from the state the finisher
+// left (its exchanges only improved the assignment).  If attempts are left (retry), the auction stops again at
+// that next rung and the finisher takes over once more; otherwise it runs to eps = 1 itself.  Either way its phases
+// now run to quiescence: a phase that ends early leaves its longest chains to the next one, which is only sound
+// while the finisher is sure to take the last of them.
+__global__ void k_fin_end(SolverState *st, int T, int *host_words, int final, int retry)
 {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     int resumed = 0;
@@ -881,7 +884,8 @@ __global__ void k_fin_end(SolverState *st, int T, int *host_words, int final)
         st->eps_prev = st->eps;
         const long long ne = st->eps / st->eps_div;
         st->eps = ne > 1 ? ne : 1;
-        st->stop_eps = 1;
+        st->stop_eps = retry ? st->eps : 1;
+        st->early_off = 1;
         st->moves = T;
         st->phases += 1;
         st->phase_start = st->round;
@@ -903,7 +907,7 @@ size_t finish_area_bytes(int T)
 
 int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long long *theta2, const int *loads2,
                        const int *cap, int Ce, int T, int E, int k, char *ws, int rows, int n_wg, int first_pass,
-                       int passes, int total_passes, long long bound_mult, int *host_words, hipStream_t s)
+                       int passes, int total_passes, long long bound_mult, int *host_words, int retry, hipStream_t s)
 {
     if (E > kFinMaxE || passes < 1 || first_pass < 0 || first_pass + passes > total_passes || bound_mult < 1 ||
         rows * k > 1024 || n_wg < 1)
@@ -935,7 +939,7 @@ int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long 
                            Ce, T, E, k, pass == total_passes - 1 ? 1 : 0, q, tri_arc, tri_tok, tri_cnt, seg_cap, n_wg);
     }
     hipLaunchKernelGGL(k_fin_end, dim3(1), dim3(64), 0, s, st, T, host_words,
-                       first_pass + passes == total_passes ? 1 : 0);
+                       first_pass + passes == total_passes ? 1 : 0, retry);
     MS_HIP(hipGetLastError());
     return MAXSCORE_OK;
 }

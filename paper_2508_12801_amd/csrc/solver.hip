@@ -235,6 +235,7 @@ constexpr long long kMaxPriceIn = (long long)1 << 38;
 constexpr long long kFinPairBudget = 8000000;   // the finisher takes over at the first eps rung with pairs * eps (in reward units) under this
 constexpr int kFinPasses = 8;              // finisher passes per solve at most
 constexpr int kFinGroup = 4;               // passes enqueued at a time
+constexpr int kFinAttempts = 3;            // rungs of the ladder at which the finisher may try (after a try that fails the auction goes one rung down)
 constexpr int kFinFirstGroup = 2;          // ... the first time (the first pass usually certifies: it keeps its arc list complete)
 constexpr long long kFinBoundMult = 32;    // arcs with a reduced cost of 32 eps or more stay out of the finisher's arc matrix
 constexpr int kWarmPhaseCap = 48;          // rounds after which a phase started from given prices goes back up the ladder
@@ -2061,21 +2062,23 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         int32_t rc = run_rounds();
         if (rc != MAXSCORE_OK) return rc;
     }
-    int fin_cycles = 0, fin_state = 0;
-    if (fin_limit_q > 0) {
+    int fin_cycles = 0, fin_state = 0, fin_cycles_before = 0;
+    for (int attempt = 0; fin_limit_q > 0 && attempt < kFinAttempts; ++attempt) {
         // The auction has stopped at a coarse eps (or ended for another reason, then every finisher launch exits at
         // once).  A fixed number of finisher passes is enqueued; the last kernel reports through pinned memory
-        // whether the optimum is certified or the auction has been set going again (one step down its ladder).
+        // whether the optimum is certified or the auction has been set going again, one step down its ladder, where
+        // it stops again for the next attempt (after the last attempt it runs to eps = 1 itself).
         volatile int *words = (volatile int *)hs->flag;
         words[4] = 0;
         const int fp = launched & 1;
+        const int retry = attempt + 1 < kFinAttempts ? 1 : 0;
         // the passes are enqueued a few at a time (most solves are certified by the first pass, and a pass that
         // finds the work done still costs two launches)
         int32_t rc = MAXSCORE_OK;
         for (int p0 = 0, grp = kFinFirstGroup; p0 < fin_passes; p0 += grp, grp = kFinGroup) {
             grp = std::min(grp, fin_passes - p0);
             rc = finish_enqueue(q, assign, st + fp, theta, gcount, cap, Ce, T, E, k, ws, rows, n_wg, p0, grp, fin_passes,
-                                fin_bound_mult, hs->flag_dev + 4, s);
+                                fin_bound_mult, hs->flag_dev + 4, retry, s);
             if (rc != MAXSCORE_OK) {
                 (void)hipStreamSynchronize(s);
                 return rc;
@@ -2084,16 +2087,19 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             MS_HIP_SYNC(hipEventSynchronize(hs->evb[0]));
             if (words[4] != 3) break;
         }
-        fin_cycles = words[5];
+        fin_cycles = fin_cycles_before + words[5];
         fin_state = words[6];
         if (words[4] == 2) {
-            // not certified: the second copy of the state follows the first, and the rounds go on to eps = 1
+            // not certified: the second copy of the state follows the first, and the rounds go on
+            fin_cycles_before = fin_cycles;
             MS_HIP_SYNC(hipMemcpyAsync(st + (fp ^ 1), st + fp, sizeof(SolverState), hipMemcpyDeviceToDevice, s));
             words[0] = 0;
             launched = words[7];          // rounds done so far: thresholds and loads alternate with the round number
             rc = run_rounds();
             if (rc != MAXSCORE_OK) return rc;
-        } else if (fin_cycles > 0 && geom) {
+            continue;
+        }
+        if (words[5] > 0 && geom) {
             // the caller reads the key blocks of the last bid pass: one more pass rewrites them for the final
             // assignment (every hold is valid under the exact prices, so the pass moves nothing)
             const int par = launched & 1;
@@ -2106,6 +2112,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             else MS_BIDF(64);
 #undef MS_BIDF
         }
+        break;
     }
     const int fpar = launched & 1;       // every launch after the end copied the final state on: both copies hold it
     hipLaunchKernelGGL(k_trim, dim3(n_wg), dim3(256), 0, s, st + fpar, theta, klist, wcnt, assign, E, k, rows);
@@ -2247,7 +2254,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         stats->bid_launches = timed;
         stats->select_ms = select_ms;
         stats->finish_passes = h.fin_passes;
-        stats->finish_cycles = h.fin_cycles;
+        stats->finish_cycles = fin_cycles;        // over all attempts (finish_passes: the last attempt's)
     }
     return h.status;
 }

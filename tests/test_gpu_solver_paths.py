@@ -210,6 +210,25 @@ def test_finisher_certifies_in_one_pass_at_full_size(ms, name, seed):
     assert int(q[P.astype(bool)].sum()) == fin["stats"]["total_score_q"]
 
 
+@pytest.mark.parametrize("T,E,k,spread,seed", [(16384, 128, 2, 2.0, 0), (8192, 32, 4, 2.0, 1), (4096, 64, 8, 2.0, 2)])
+def test_finisher_that_cannot_take_over_at_its_first_rung(ms, T, E, k, spread, seed):
+    """Strongly skewed expert popularity: at the rung the finisher is first tried on, more arcs lie under its bound
+    than it can hold (or it runs out of room for moved tokens), so it hands back; the auction goes one rung down,
+    with phases that now run to quiescence, and the finisher tries again there.  The result is the checker's optimum
+    with prices that certify it, as on every other path."""
+    print(f"finisher retry T={T} E={E} k={k}", flush=True)
+    rng = np.random.default_rng(seed)
+    L = rng.normal(size=(T, E)) + spread * rng.normal(size=(1, E))
+    p = np.exp(L - L.max(axis=1, keepdims=True))
+    q = np.rint(p / p.sum(axis=1, keepdims=True) * ((1 << 20) - 1)).astype(np.int64)
+    C = -(-T * k // E)
+    out = solve_and_check(ms, q, k, C)
+    assert certified(q, out, k, C)
+    print("  ", out["stats"], flush=True)
+    auc = ms.assign_i32(dev(q.astype(np.int32)), k, C, finisher=False)
+    assert auc["stats"]["total_score_q"] == out["stats"]["total_score_q"]
+
+
 def test_finisher_with_k_vector_and_capacity_vector(ms):
     """Per-token k (with zeros) and unequal capacities through the finisher: checker's optimum, valid rows."""
     print("finisher kvec+caps", flush=True)
