@@ -31,9 +31,6 @@ constexpr long long kDistInf = (long long)1 << 60;
 constexpr int kFinThreads = 1024;
 constexpr int kFinMaxCyclesPerPass = 256;
 
-#ifdef MS_FIN_PROF
-__device__ int g_fin_triples[4];
-#endif
 
 __device__ __forceinline__ long long shfl_xor_i64(long long v, int off)
 {
@@ -142,9 +139,6 @@ __device__ __forceinline__ int token_arcs(const int32_t *__restrict__ q, const i
             const unsigned long long bal = __ballot(ok);
             if (ok) {
                 if (MIN) {
-#ifdef MS_FIN_PROF
-                    atomicAdd(&g_fin_triples[0], 1);
-#endif
                     const unsigned long long pk =
                         ((unsigned long long)(rc + kRcBias) << kTokBits) | (unsigned long long)u;
                     atomicMin(&M[(size_t)h * E + e], pk);
@@ -417,9 +411,6 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
         if (tid == 0) {
             sh.complete = complete ? 1 : 0;
             if (complete) sh.n_arcs = 2 * E + total;
-#ifdef MS_FIN_PROF
-            printf("[fin] arc list: %d arcs in %d segments of %d, complete %d\n", total, n_wg, seg_cap, (int)complete);
-#endif
         }
         __syncthreads();
     }
@@ -477,10 +468,6 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
             const int na = 2 * E + total;
             sh.n_arcs = na < kFinArcs ? na : kFinArcs;
             if (na > kFinArcs) sh.give_up = 1;          // more arcs than the list holds
-#ifdef MS_FIN_PROF
-            printf("[fin] arcs under the bound: %d (+ %d for Z); triples so far: %d (< B/2: %d, < B/4: %d, < B/8: %d)\n", total, 2 * E, g_fin_triples[0], g_fin_triples[1], g_fin_triples[2], g_fin_triples[3]);
-            g_fin_triples[0] = g_fin_triples[1] = g_fin_triples[2] = g_fin_triples[3] = 0;
-#endif
         }
     }
     __syncthreads();
@@ -501,18 +488,7 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
     bool converged = false, fresh = first_pass;     // fresh: the potentials started from zero and nothing was cancelled since
     int cur = 0;
     const int max_sweeps = 8 * (E + 2) + 16 * kFinMaxCyclesPerPass;
-#ifdef MS_FIN_PROF
-    long long c_t0 = wall_clock64(), c_sweep = 0, c_check = 0, c_cancel = 0;
-    const long long c_start = c_t0;
-    int n_sweeps = 0, n_checks = 0;
-#define MS_FP(var) { long long c_now = wall_clock64(); var += c_now - c_t0; c_t0 = c_now; }
-#else
-#define MS_FP(var)
-#endif
     for (int it = 0; it < max_sweeps && !sh.give_up; ++it) {
-#ifdef MS_FIN_PROF
-        ++n_sweeps;
-#endif
         // one sweep: labels are read from copy `cur` and lowered in the other copy (which starts equal to it)
         {
             const unsigned long long *kc = sh.key[cur];
@@ -555,7 +531,6 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
         if (tid == 0) sh.changed[(it + 1) % 3] = 0;      // last read before the previous barrier
         __syncthreads();
         cur ^= 1;
-        MS_FP(c_sweep)
         if (!sh.changed[it % 3]) {
             // Stopped relaxing.  If nothing was cancelled this pass can certify, provided the potentials spread
             // less than the bound; potentials carried over from earlier passes can spread more than needed, so
@@ -583,9 +558,6 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
             break;
         }
         if ((it & 7) != 7) continue;
-#ifdef MS_FIN_PROF
-        ++n_checks;
-#endif
         // cycles of the predecessor graph: follow the predecessors 256 steps by pointer doubling; a node that does
         // not end at the root has landed on a cycle.  Every node has one predecessor, so the cycles are disjoint;
         // each is named by its smallest node (wavefront 0, three nodes per lane; the others wait)
@@ -636,7 +608,6 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
             if (lane == 0) sh.n_found = n_found;
         }
         __syncthreads();
-        MS_FP(c_check)
         const int n_found = sh.n_found;
         if (n_found == 0) continue;
         bool stop = false;
@@ -790,13 +761,7 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
             load_arcs();
             fresh = false;
         }
-        MS_FP(c_cancel)
     }
-#ifdef MS_FIN_PROF
-    if (tid == 0)
-        printf("[fin] pass %d: arcs %d, %d sweeps %d checks %d cycles | ticks(10ns): sweeps %lld checks %lld cancels %lld total %lld\n",
-               st->fin_passes, n_arcs, n_sweeps, n_checks, sh.cycles, c_sweep, c_check, c_cancel, wall_clock64() - c_start);
-#endif
 
     // ---- end of the pass ----
     __syncthreads();
@@ -827,9 +792,6 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
             hi = b > hi ? b : hi;
         }
         const bool ok = hi - lo < B;
-#ifdef MS_FIN_PROF
-        if (tid == 0) printf("[fin] certificate: spread %lld = %.1f eps, bound %lld, ok %d\n", hi - lo, (double)(hi - lo) / (double)st->eps, B, (int)ok);
-#endif
         if (ok) {
             // exact prices: p_e - d_e + d_Z (>= 0 on every expert that holds a token, 0 where there is room)
             const long long dz = (long long)(kc[Z] >> kIdxBits) - kKeyBias;

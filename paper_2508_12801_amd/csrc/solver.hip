@@ -115,12 +115,6 @@ __device__ __forceinline__ unsigned long long group_max(unsigned long long v)
     return v;
 }
 
-#ifdef MS_BID_PROF
-// timing of the bid pass by round (100 MHz wall clock): earliest start and latest end over the workgroups, and
-// the sums over the workgroups of the time spent up to the first barrier, in the row loop, in the scan and in
-// the sort-and-store epilogue
-__device__ unsigned long long g_bidmin[256], g_bidmax[256], g_bidph[256][4];
-#endif
 
 // Maximum of a 32-bit value over the G lanes of a group, result in every lane of the group.  Groups of 8 and 16
 // lanes lie inside one 16-lane row, where data-parallel-primitive lane swaps do it without going through the LDS
@@ -159,13 +153,6 @@ __global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm,
         theta[i] = 0;
         gcount[i] = 0;
     }
-#ifdef MS_BID_PROF
-    if (i < 256) {
-        g_bidmin[i] = ~0ull;
-        g_bidmax[i] = 0;
-        for (int a = 0; a < 4; ++a) g_bidph[i][a] = 0;
-    }
-#endif
     if (i == 0) {
         qmm[0] = 0x7fffffff;
         qmm[1] = -0x7fffffff - 1;
@@ -383,9 +370,6 @@ __global__ __launch_bounds__(256, (G * EPL > 256 ? 3 : 4)) void k_bid(const int3
         if (KV) an = (lg < kvec[row]) ? an : -2;
     };
     auto load_row = [&](int row) { load_row_to(row, qn, an); };
-#ifdef MS_BID_PROF
-    const unsigned long long bp0 = wall_clock64();
-#endif
     // The first row of every group and the thresholds are requested before the state is looked at:
     // the exit test below then waits for the scalar loads of the state only, while the vector loads
     // are already on their way (rows and thresholds are valid memory whether or not the solve is over).
@@ -413,9 +397,6 @@ __global__ __launch_bounds__(256, (G * EPL > 256 ? 3 : 4)) void k_bid(const int3
         s_nq = 0;
     }
     __syncthreads();
-#ifdef MS_BID_PROF
-    const unsigned long long bp1 = wall_clock64();
-#endif
 
     // The prices of this lane's experts are read from the LDS copy of the thresholds where they are needed:
     // keeping the 64-bit values in registers through both kinds of pass costs more registers than a wavefront
@@ -643,9 +624,6 @@ __global__ __launch_bounds__(256, (G * EPL > 256 ? 3 : 4)) void k_bid(const int3
         }
     }
     __syncthreads();
-#ifdef MS_BID_PROF
-    const unsigned long long bp2 = wall_clock64();
-#endif
     // The keys of this workgroup are stored sorted by expert in one contiguous block of the key
     // buffer (block w starts at w*rows_per_wg*k), with (offset << 16 | count) per expert beside it:
     // full cache lines are written and no global atomics are needed.
@@ -674,9 +652,6 @@ __global__ __launch_bounds__(256, (G * EPL > 256 ? 3 : 4)) void k_bid(const int3
     }
     if (tid == 0) wmoves[blockIdx.x] = s_moves;
     __syncthreads();
-#ifdef MS_BID_PROF
-    const unsigned long long bp3 = wall_clock64();
-#endif
     int rows_here = T - row0;
     rows_here = rows_here < rows_per_wg ? rows_here : rows_per_wg;
     const int nslots = rows_here * k;
@@ -689,19 +664,6 @@ __global__ __launch_bounds__(256, (G * EPL > 256 ? 3 : 4)) void k_bid(const int3
     }
     __syncthreads();
     for (int idx = tid; idx < nslots; idx += 256) blk[idx] = s_sorted[idx];
-#ifdef MS_BID_PROF
-    __syncthreads();
-    if (tid == 0) {
-        const unsigned long long bp4 = wall_clock64();
-        const int r = st->round & 255;
-        atomicMin(&g_bidmin[r], bp0);
-        atomicMax(&g_bidmax[r], bp4);
-        atomicAdd(&g_bidph[r][0], bp1 - bp0);
-        atomicAdd(&g_bidph[r][1], bp2 - bp1);
-        atomicAdd(&g_bidph[r][2], bp3 - bp2);
-        atomicAdd(&g_bidph[r][3], bp4 - bp3);
-    }
-#endif
 }
 
 // Tail pass: when a bid pass moved only a few slots, one workgroup continues the same auction on the
@@ -714,9 +676,6 @@ __global__ __launch_bounds__(256, (G * EPL > 256 ? 3 : 4)) void k_bid(const int3
 // stops when nothing is over capacity, when a list runs out or after max_iters rounds; the next bid
 // pass re-validates every token, so this pass only has to make valid moves, not complete ones.
 constexpr int kTailThreads = 1024;
-#ifdef MS_TAIL_PROF
-__device__ int g_tailstat[8];
-#endif
 #ifdef MAXSCORE_DEBUG_ENV
 __device__ int g_tailtrace[256 * 8];      // per tail run: round, iterations, victims, stop1, stop2, over_last, wall ticks
 __device__ int g_tailruns;
@@ -852,12 +811,6 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
     }
     __syncthreads();
 
-#ifdef MS_TAIL_PROF
-    long long c_p1 = 0, c_p2 = 0, c_p3 = 0, c_t0 = clock64(), c_init = 0, c_x = 0, c_y = 0, c_e[5] = {0, 0, 0, 0, 0};
-#define MS_TP(var) { long long c_now = clock64(); var += c_now - c_t0; c_t0 = c_now; }
-#else
-#define MS_TP(var)
-#endif
 #ifdef MAXSCORE_DEBUG_ENV
     int dbg_vict = 0;
     const long long dbg_t0 = wall_clock64();
@@ -907,7 +860,6 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             }
         }
-        MS_TP(c_p3)
         // 1. every over-full expert drops its lowest candidates and raises its threshold (expert e: lane e/16 of
         //    wavefront e mod 16)
         // (the words of an expert are asked for together, and the list entries together with the slot reservation:
@@ -951,7 +903,6 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
             }
         }
         __syncthreads();
-        MS_TP(c_p1)
         // the counters of the other parity were last read in step 0 above; the next iteration starts from zero
         // (by the last wavefront: the first ones are the ones that evaluate, and this pass is bound by what they have to issue)
         if (tid == kTailThreads - 1) { s_nv2[pi ^ 1] = 0; s_ni2[pi ^ 1] = 0; s_over2[pi ^ 1] = 0; }
@@ -985,9 +936,6 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
             if (twins & ((1ull << vi) - 1)) continue;
             const int ve = __builtin_amdgcn_readlane(vexp_l, vi);
             const long long theta_ve = s_theta[ve];
-#ifdef MS_TAIL_PROF
-            long long c_a = clock64();
-#endif
             long long v[TEPL];
             unsigned validm = 0, heldm = 0;
 #pragma unroll
@@ -1001,9 +949,6 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                     }
                 }
             }
-#ifdef MS_TAIL_PROF
-            long long c_b = clock64();
-#endif
             {
                 // which of this lane's experts the token holds: the slot lanes mark their expert in a byte map of the
                 // wavefront, every lane reads its own bytes, the marks are taken back (three LDS instructions where a
@@ -1020,9 +965,6 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                 if (my_e >= 0) hm[my_e] = 0;
             }
-#ifdef MS_TAIL_PROF
-            long long c_h = clock64();
-#endif
             // equal values are ranked by expert id XOR a per-token mask (a bijection below 1024), so that
             // identical rows spread over the experts
             const int r0 = tok & 1023;
@@ -1057,9 +999,6 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 }
             };
             unsigned long long pk = best_unheld();
-#ifdef MS_TAIL_PROF
-            long long c_r1 = clock64(), c_r2 = c_r1, c_r3 = c_r1;
-#endif
             if (!twins) {
                 // The usual case: one hold (tok, ve) is challenged.  Every other hold of the token is
                 // still valid (its listed key was not popped and true keys only rise), so only this
@@ -1075,9 +1014,6 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                     const long long key = key_of(reward_of(ve), pk);
                     if (key >= theta_ve) {
                         if (lane == 0) request(ve, key, s_bound[ve]);   // survives: back on the list with its true key
-#ifdef MS_TAIL_PROF
-                        if (lane == 0) atomicAdd(&g_tailstat[nv == 1 ? 0 : 2], 1);
-#endif
                     } else {
                         // falls below the threshold: the best expert not held takes the slot (ve itself
                         // cannot be it: its value is now at least eps under that best one)
@@ -1088,13 +1024,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                             const long long bound_e1 = s_bound[e1];     // on its way while the next best is found
                             if ((ve & 63) == lane) heldm &= ~(1u << (ve >> 6));
                             if ((e1 & 63) == lane) heldm |= 1u << (e1 >> 6);
-#ifdef MS_TAIL_PROF
-                            c_r2 = clock64();
-#endif
                             const unsigned long long pk2 = best_unheld();
-#ifdef MS_TAIL_PROF
-                            c_r3 = clock64();
-#endif
                             const long long key1 = key_of(reward_of(e1), pk2);
                             if (my_e == ve)
                                 __hip_atomic_store(&assign[(size_t)tok * k + lane], e1, __ATOMIC_RELAXED,
@@ -1108,20 +1038,10 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                             }
                             if (lane == 0) {
                                 request(e1, key1, bound_e1);
-#ifdef MS_TAIL_PROF
-                                atomicAdd(&g_tailstat[nv == 1 ? 1 : 3], 1);
-#endif
                             }
                         }
                     }
                 }
-#ifdef MS_TAIL_PROF
-                if (wv == 0) {
-                    long long c_c = clock64();
-                    c_init += c_b - c_a; c_x += c_c - c_b;
-                    c_e[0] += c_h - c_b; c_e[1] += c_r1 - c_h; c_e[2] += c_r2 - c_r1; c_e[3] += c_r3 - c_r2; c_e[4] += c_c - c_r3;
-                }
-#endif
                 continue;
             }
             // several holds of the token are challenged at once: the bid pass's general evaluation
@@ -1191,14 +1111,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
             }
             __builtin_amdgcn_wave_barrier();
         }
-#ifdef MS_TAIL_PROF
-        long long c_d = clock64();
-#endif
         __syncthreads();
-#ifdef MS_TAIL_PROF
-        c_y += clock64() - c_d;
-#endif
-        MS_TP(c_p2)
         if (s_stop2) break;
     }
     for (int e = tid; e < E; e += kTailThreads) {
@@ -1233,12 +1146,6 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
 #endif
         st->tail_runs += 1;
         st->tail_iters += it;
-#ifdef MS_TAIL_PROF
-        st->phase_round[20] += (int)(c_init >> 6); st->phase_round[21] += (int)(c_p1 >> 6);
-        st->phase_round[22] += (int)(c_p2 >> 6); st->phase_round[23] += (int)(c_p3 >> 6);
-        st->phase_round[24] += (int)(c_x >> 6); st->phase_round[25] += (int)(c_y >> 6);
-        for (int a = 0; a < 5; ++a) st->phase_round[14 + a] += (int)(c_e[a] >> 6);
-#endif
     }
 }
 
@@ -1248,14 +1155,6 @@ constexpr int kSelThreads = 1024;
 constexpr int kSelCache = 6144;
 constexpr int kSelDirect = 256;           // at most this many keys are ranked against each other directly
 
-#ifdef MS_SEL_PROF
-__device__ long long g_selprof[kMaxE * 8];
-__device__ long long g_selwall[2];
-__device__ unsigned long long g_selround[1024];
-#define MS_SP(slot) { if (tid == 0 && !is_tail) { long long c_now = clock64(); g_selprof[j * 8 + slot] += c_now - c_sp; c_sp = c_now; } }
-#else
-#define MS_SP(slot)
-#endif
 
 static_assert(kSelThreads == kTailThreads, "the tail pass runs in a workgroup of the select pass");
 
@@ -1320,10 +1219,6 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     // per-workgroup counts, with an exclusive scan that places each thread's keys in the LDS copy),
     // the moves of this bid pass, and the over-capacity / unfilled-but-priced experts after the
     // previous round.  All loads are issued before the single barrier.
-#ifdef MS_SEL_PROF
-    long long c_sp = clock64();
-    const long long c_w0 = wall_clock64(), c_c0 = c_sp;
-#endif
     int ct = mt0 & 0xffff, ov = 0, vi = 0;
     for (int w = tid + kSelThreads; w < n_wg; w += kSelThreads) {
         ct += meta(w) & 0xffff;
@@ -1367,7 +1262,6 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
         moves += s_mvw[w];
     }
     if (tid == 0 && !is_tail) gcur[j] = n;
-    MS_SP(0)
 
     // the decision every thread of every block takes identically: nothing moved in this bid pass and
     // no expert was above capacity after the previous one  =>  the phase is quiescent
@@ -1535,7 +1429,6 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             }
             __syncthreads();
         }
-        MS_SP(1)
         // visit every key of this expert (LDS copy when it fits, else the global segments)
         auto for_keys = [&](auto fn) {
             if (cached) {
@@ -1560,7 +1453,6 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                 atomicAdd(&s_hist[0][u ? 64 - __clzll((long long)u) : 0], 1);
             });
             __syncthreads();
-            MS_SP(2)
             auto scan_find = [&](int h) {       // finds the bin holding `rank`; call from all threads
                 if (wv == 0) {
                     const int4 b4 = *(const int4 *)&s_hist[h][lane * 4];
@@ -1582,7 +1474,6 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                 __syncthreads();
             };
             scan_find(0);
-            MS_SP(3)
             const int bl = s_d;                  // bit length of the wanted u
             if (bl <= 1) return base + (long long)bl;     // u = 0 or u = 1
             rank = s_rank;
@@ -1604,7 +1495,6 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
                 rank = s_rank;
                 m = s_m;
             }
-            MS_SP(4)
             if (shift == 0) return base + (long long)prefix;
             for_keys([&](long long kv) {
                 const unsigned long long u = (unsigned long long)(kv - base);
@@ -1632,7 +1522,6 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             const unsigned long long res = s_res;
             __syncthreads();
             if (tid == 0) s_nsm = 0;
-            MS_SP(5)
             return base + (long long)res;
         };
         if (need_select) {
@@ -1676,12 +1565,6 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             atomicAdd(ready, 1);
         }
     }
-    MS_SP(6)
-#ifdef MS_SEL_PROF
-    if (tid == 0) g_selprof[j * 8 + 7] += 1;
-    if (tid == 0 && j == 0) { g_selwall[0] += wall_clock64() - c_w0; g_selwall[1] += clock64() - c_c0; }
-    if (tid == 0) atomicMax(&g_selround[cur_round & 1023], ((unsigned long long)(clock64() - c_c0) << 32) | ((unsigned)n << 8) | (need_select ? 1 : 0) | (need_cand ? 2 : 0));
-#endif
 }
 
 // Total score and flow of the final assignment: per-workgroup partial sums (no contended atomics), then
@@ -2169,47 +2052,6 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             }
         }
     }
-#ifdef MS_SEL_PROF
-    {
-        static long long hp[kMaxE * 8];
-        (void)hipMemcpyFromSymbol(hp, HIP_SYMBOL(g_selprof), sizeof(hp));
-        long long sum[8] = {0}, mx[8] = {0};
-        for (int e = 0; e < E; ++e)
-            for (int a = 0; a < 8; ++a) {
-                sum[a] += hp[e * 8 + a];
-                mx[a] = hp[e * 8 + a] > mx[a] ? hp[e * 8 + a] : mx[a];
-            }
-        fprintf(stderr, "[selprof] cumulative cycles, mean over experts (max): ");
-        const char *nm[8] = {"prologue", "gather", "bitlen-hist", "scan0", "digits", "direct", "rest", "launches"};
-        for (int a = 0; a < 8; ++a) fprintf(stderr, "%s %lld (%lld)  ", nm[a], sum[a] / E, mx[a]);
-        fprintf(stderr, "\n");
-        long long hw[2];
-        (void)hipMemcpyFromSymbol(hw, HIP_SYMBOL(g_selwall), sizeof(hw));
-        static unsigned long long hr[1024];
-        (void)hipMemcpyFromSymbol(hr, HIP_SYMBOL(g_selround), sizeof(hr));
-        for (int a = 0; a < 90; ++a) fprintf(stderr, "[selround] %d cyc %llu n %llu fl %llu\n", a, hr[a] >> 32, (hr[a] >> 8) & 0xffffff, hr[a] & 3);
-        fprintf(stderr, "[selprof] block 0: wall ticks (100 MHz) %lld, clock64 ticks %lld\n", hw[0], hw[1]);
-    }
-#endif
-#ifdef MS_BID_PROF
-    {
-        static unsigned long long hmin[256], hmax[256], hph[256][4];
-        (void)hipMemcpyFromSymbol(hmin, HIP_SYMBOL(g_bidmin), sizeof(hmin));
-        (void)hipMemcpyFromSymbol(hmax, HIP_SYMBOL(g_bidmax), sizeof(hmax));
-        (void)hipMemcpyFromSymbol(hph, HIP_SYMBOL(g_bidph), sizeof(hph));
-        for (int r = 0; r < h.round && r < 256; ++r)
-            fprintf(stderr, "[bidprof] round %d span %.2f us; mean per workgroup: to first barrier %.2f, rows %.2f, scan %.2f, store %.2f us\n",
-                    r, (hmax[r] - hmin[r]) * 0.01, hph[r][0] * 0.01 / n_wg, hph[r][1] * 0.01 / n_wg,
-                    hph[r][2] * 0.01 / n_wg, hph[r][3] * 0.01 / n_wg);
-    }
-#endif
-#ifdef MS_TAIL_PROF
-    {
-        int hs[8];
-        (void)hipMemcpyFromSymbol(hs, HIP_SYMBOL(g_tailstat), sizeof(hs));
-        fprintf(stderr, "[tailstat] cumulative: single-victim iterations survive %d drop %d; multi-victim survive %d drop %d\n", hs[0], hs[1], hs[2], hs[3]);
-    }
-#endif
 #ifdef MAXSCORE_DEBUG_ENV
     if (getenv("MAXSCORE_DEBUG"))
         fprintf(stderr, "[maxscore] finisher: stop_eps %lld state %d passes %d cycles %d (host saw state %d cycles %d)\n",
