@@ -136,6 +136,16 @@ def test_reward_range_too_wide_is_an_error(ms):
     with pytest.raises(ms.MaxScoreError) as e:
         ms.assign_i32(dev(q.astype(np.int32)), 2, 64)
     assert e.value.code == -7
+    # through a routing entry the gates and dispatch kernels are already queued behind the solve when the error is
+    # known: they must stay inside their buffers on a state that holds no keys at all, and the call reports the error
+    # (the second call finds the workspace as another shape's solve left it)
+    scores = np.full((64, 1000), 1e-3, dtype=np.float32)
+    scores[0, 0] = 600.0                              # 600 * 2^20 > 2^29
+    for _ in range(2):
+        with pytest.raises(ms.MaxScoreError) as e:
+            ms.route_scores(dev(scores), 2, 64)
+        assert e.value.code == -7
+        solve_and_check(ms, skewed_rewards(np.random.default_rng(3), 64, 1000, 16), 2, 64)
 
 
 def test_tail_pass_switch_gives_the_same_optimum(ms):
