@@ -61,7 +61,7 @@ struct SolverState {
 
 struct WorkspaceLayout {
     size_t state_off, theta_off, gcount_off, klist_off, wcnt_off, wmoves_off, cand_off, tiles_off, cap_off, aux_off,
-        wt_off, dbase_off, fin_off, tri_off, total;
+        wt_off, dbase_off, fin_off, finm_off, tri_off, total;
     int n_tiles, max_wg;
 };
 
@@ -105,7 +105,7 @@ int32_t kvec_check(const int32_t *kvec, int T, int E, int k, char *ws, long long
 // goes on | 3 not finished, passes left; cycles cancelled so far; st->fin; round}.  retry: when the auction has to
 // go on it stops again one rung further down (the finisher can be enqueued anew, from pass 0) instead of running to
 // eps = 1.  Supports E <= kFinMaxE.
-constexpr int kFinMaxE = 128;
+constexpr int kFinMaxE = 256;
 constexpr int kFinMovedCap = 4096;        // tokens the finisher may move in one solve (more: the auction goes on)
 int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long long *theta2, const int *loads2,
                        const int *cap, int Ce, int T, int E, int k, char *ws, int rows, int n_wg, int first_pass,

@@ -11,7 +11,7 @@
 //   k_fin_arcs    streams the rewards once and builds the arc matrix (smallest loss and its token per expert pair)
 //                 in reduced form, loss - price_a + price_b, keeping only arcs under a bound (the others cannot lie
 //                 on a negative cycle; this is verified at the end from the distances found);
-//   k_fin_cycles  one workgroup: Bellman-Ford over the <= 129 nodes, cycles of the predecessor graph are negative
+//   k_fin_cycles  one workgroup: Bellman-Ford over the <= kFinMaxE + 1 nodes, cycles of the predecessor graph are negative
 //                 cycles and are cancelled at once (the tokens on their arcs move, arcs of moved tokens leave the
 //                 matrix), until the distances converge.  If anything was cancelled the matrix is incomplete and
 //                 another pass follows; if nothing was, the optimum is certified and the prices are replaced.
@@ -95,15 +95,15 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_begin(SolverState *st, unsi
 // expert e it does not hold, the loss of moving it there in reduced form; arcs under the bound count.  With MIN they
 // go into the matrix (smallest loss wins, then the lower token id); with an output list they are also written there
 // in a fixed order (slot of the hold, then expert), the j-th of them at out_base + j while that is below out_end.
-// Returns their number (the same in every lane).  One wavefront; lane l owns experts l and l + 64.  The assignment
+// Returns their number (the same in every lane).  One wavefront; lane l owns experts l, l + 64, ... (TEPL of them).  The assignment
 // row is read at device scope: the Bellman-Ford workgroup calls this for tokens it has just moved.
 __device__ __forceinline__ unsigned long long arc_pack(int cost, int a, int b)
 {
-    return ((unsigned long long)(unsigned)cost << 32) | (unsigned)((a << 8) | b);
+    return ((unsigned long long)(unsigned)cost << 32) | (unsigned)((a << 16) | b);
 }
 __device__ __forceinline__ int arc_cost(unsigned long long w) { return (int)(unsigned)(w >> 32); }
-__device__ __forceinline__ int arc_from(unsigned long long w) { return (int)((w >> 8) & 255); }
-__device__ __forceinline__ int arc_to(unsigned long long w) { return (int)(w & 255); }
+__device__ __forceinline__ int arc_from(unsigned long long w) { return (int)((w >> 16) & 0xffff); }
+__device__ __forceinline__ int arc_to(unsigned long long w) { return (int)(w & 0xffff); }
 
 template <int TEPL, bool MIN>
 __device__ __forceinline__ int token_arcs(const int32_t *__restrict__ q, const int32_t *assign,
@@ -129,7 +129,9 @@ __device__ __forceinline__ int token_arcs(const int32_t *__restrict__ q, const i
     for (int s = 0; s < k; ++s) {
         const int h = __builtin_amdgcn_readlane(a, s);
         if (h < 0 || (only >= 0 && h != only)) continue;
-        const long long x = (TEPL > 1 && (h >> 6)) ? v[TEPL - 1] : v[0];
+        long long x = v[0];
+#pragma unroll
+        for (int m = 1; m < TEPL; ++m) x = (h >> 6) == m ? v[m] : x;
         const long long vh = readlane_i64(x, h & 63);
 #pragma unroll
         for (int m = 0; m < TEPL; ++m) {
@@ -275,7 +277,8 @@ __global__ __launch_bounds__(256) void k_fin_arcs(const int32_t *__restrict__ q,
         (void)token_arcs<TEPL, true>(q, assign, p, sb, fa.list[i], -1, B, M, E, k, lane, nullptr, nullptr, 0, 0);
 }
 
-constexpr int kFinArcs = 12288;               // arcs the Bellman-Ford workgroup can hold (more: the auction goes on)
+constexpr int kFinArcs = 11264;               // arcs the Bellman-Ford workgroup can hold (more: the auction goes on)
+constexpr int kFinChunkGroup = 16;            // chunks of the arc matrix whose loads are in flight together
 constexpr long long kKeyBias = (long long)1 << 48;   // potentials stay far inside (-2^48, 2^48)
 constexpr int kIdxBits = 14;
 constexpr unsigned kIdxRoot = (1u << kIdxBits) - 1;  // "no predecessor arc"
@@ -283,8 +286,8 @@ constexpr long long kZCostMax = (long long)1 << 30;  // prices must stay under t
 
 
 struct FinShared {
-    // arc i: reduced cost (signed, kCostInf = slot empty or arc withdrawn) in the high word, from << 8 | to in the
-    // low one (nodes 0..E-1 experts, E = Z)
+    // arc i: reduced cost (signed, kCostInf = slot empty or arc withdrawn) in the high word, from << 16 | to in the
+    // low one (16 bits each; nodes 0..E-1 experts, E = Z)
     unsigned long long arc[kFinArcs];
     int atok[kFinArcs];                       // token that realises arc i (-1 for the arcs of Z)
     // node labels: (potential + bias) << 14 | index of the arc that last lowered it; two copies (a sweep reads
@@ -306,8 +309,10 @@ struct FinShared {
     int complete;         // the arc list holds EVERY arc under the bound (kept so while tokens move): one pass can certify
     long long cyc_sum;
 };
+static_assert(sizeof(FinShared) <= 160 * 1024, "the Bellman-Ford workgroup keeps everything in one compute unit's LDS");
+static_assert(kFinMaxE * kFinMaxE / kFinThreads * (kFinThreads / 64) <= kFinThreads, "one count per thread in the prefix");
 
-// Bellman-Ford with cancelling.  One workgroup of kFinThreads threads, E <= kFinMaxE.
+// Bellman-Ford with cancelling.  One workgroup of kFinThreads threads, E <= 64 * TEPL <= kFinMaxE.
 //
 // The arcs under the bound are few (a few thousand of the E*E pairs), so they are kept as a list.  Node potentials
 // (0 at the start) are lowered sweep by sweep, every thread relaxing its arcs, until no arc a -> b has
@@ -316,6 +321,7 @@ struct FinShared {
 // on it must hold the expert it leaves and not the one it goes to) and cancelled.  The potentials are kept across
 // a cancellation: any potentials that stop relaxing certify the arcs that are left, and a negative cycle keeps
 // them relaxing.
+template <int TEPL>
 __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, unsigned long long *M, int32_t *assign,
                                                             long long *theta2, const int *__restrict__ loads2,
                                                             char *fin_base, const int *__restrict__ cap, int Ce,
@@ -415,53 +421,62 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
         __syncthreads();
     }
     if (!sh.complete) {
-        // the matrix is read in chunks of kFinThreads consecutive entries (all loads are issued at once); an arc's
-        // place in the list follows from the number of arcs before it in matrix order
+        // The matrix is read in chunks of kFinThreads consecutive entries, kFinChunkGroup chunks' loads in flight at
+        // a time; an arc's place in the list follows from the number of arcs before it in matrix order.  Two
+        // readings: the first counts, the second places.
         const int n = E * E;
-        constexpr int kChunks = kFinMaxE * kFinMaxE / kFinThreads;       // 16
-        unsigned long long pk[kChunks];
+        const int n_chunks = (n + kFinThreads - 1) / kFinThreads;
+        const int n_flat = n_chunks * (kFinThreads / 64);                 // counts in (chunk, wavefront) order
+        const int n_sw = (n_flat + 63) / 64;                              // wavefronts that scan them
+        for (int g0 = 0; g0 < n_chunks; g0 += kFinChunkGroup) {
+            unsigned long long pk[kFinChunkGroup];
 #pragma unroll
-        for (int c = 0; c < kChunks; ++c) {
-            const int i = c * kFinThreads + tid;
-            pk[c] = i < n ? M[i] : kArcNone;
-        }
-        int before[kChunks];
+            for (int c = 0; c < kFinChunkGroup; ++c) {
+                const int i = (g0 + c) * kFinThreads + tid;
+                pk[c] = (g0 + c < n_chunks && i < n) ? M[i] : kArcNone;
+            }
 #pragma unroll
-        for (int c = 0; c < kChunks; ++c) {
-            const unsigned long long bal = __ballot(pk[c] != kArcNone);
-            before[c] = __popcll(bal & ((1ull << lane) - 1));
-            if (lane == 0) sh.scan[c][wv] = __popcll(bal);
+            for (int c = 0; c < kFinChunkGroup; ++c) {
+                const unsigned long long bal = __ballot(pk[c] != kArcNone);
+                if (lane == 0 && g0 + c < n_chunks) sh.scan[g0 + c][wv] = __popcll(bal);
+            }
         }
         __syncthreads();
-        if (tid < kChunks * (kFinThreads / 64)) {                         // 256 counts in (chunk, wavefront) order
-            // exclusive prefix over the 256 counts, four per lane of wavefronts 0..3
-            int *flat = &sh.scan[0][0];
-            const int v = flat[tid];
+        int *flat = &sh.scan[0][0];
+        if (wv < n_sw) {
+            // exclusive prefix inside every wavefront of counts, the wavefront totals beside it
+            const int v = tid < n_flat ? flat[tid] : 0;
             int inc = v;
             for (int off = 1; off < 64; off <<= 1) {
                 const int o = __shfl_up(inc, off);
                 if (lane >= off) inc += o;
             }
-            flat[tid] = inc - v;                                          // exclusive inside its wavefront
-            if (lane == 63) sh.cyc[wv] = inc;                             // wavefront totals (4 of them)
+            if (tid < n_flat) flat[tid] = inc - v;
+            if (lane == 63) sh.cyc[wv] = inc;
         }
         __syncthreads();
         int total = 0;
-        {
-            const int nw = kChunks * (kFinThreads / 64) / 64;             // 4
-            for (int w4 = 0; w4 < nw; ++w4) total += sh.cyc[w4];
-        }
+        for (int w4 = 0; w4 < n_sw; ++w4) total += sh.cyc[w4];
+        for (int g0 = 0; g0 < n_chunks; g0 += kFinChunkGroup) {
+            unsigned long long pk[kFinChunkGroup];
 #pragma unroll
-        for (int c = 0; c < kChunks; ++c) {
-            if (pk[c] == kArcNone) continue;
-            const int flat_i = c * (kFinThreads / 64) + wv;
-            int base = 2 * E + sh.scan[c][wv] + before[c];
-            for (int w4 = 0; w4 < flat_i / 64; ++w4) base += sh.cyc[w4];
-            if (base < kFinArcs) {
-                const int i = c * kFinThreads + tid;
-                const int a = i / E, b = i - a * E;
-                sh.arc[base] = arc_pack((int)((long long)(pk[c] >> kTokBits) - kRcBias), a, b);
-                sh.atok[base] = (int)(pk[c] & ((1u << kTokBits) - 1));
+            for (int c = 0; c < kFinChunkGroup; ++c) {
+                const int i = (g0 + c) * kFinThreads + tid;
+                pk[c] = (g0 + c < n_chunks && i < n) ? M[i] : kArcNone;
+            }
+#pragma unroll
+            for (int c = 0; c < kFinChunkGroup; ++c) {
+                const unsigned long long bal = __ballot(pk[c] != kArcNone);
+                if (pk[c] == kArcNone) continue;
+                const int flat_i = (g0 + c) * (kFinThreads / 64) + wv;
+                int base = 2 * E + flat[flat_i] + __popcll(bal & ((1ull << lane) - 1));
+                for (int w4 = 0; w4 < flat_i / 64; ++w4) base += sh.cyc[w4];
+                if (base < kFinArcs) {
+                    const int i = (g0 + c) * kFinThreads + tid;
+                    const int a = i / E, b = i - a * E;
+                    sh.arc[base] = arc_pack((int)((long long)(pk[c] >> kTokBits) - kRcBias), a, b);
+                    sh.atok[base] = (int)(pk[c] & ((1u << kTokBits) - 1));
+                }
             }
         }
         if (tid == 0) {
@@ -560,7 +575,7 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
         if ((it & 7) != 7) continue;
         // cycles of the predecessor graph: follow the predecessors 256 steps by pointer doubling; a node that does
         // not end at the root has landed on a cycle.  Every node has one predecessor, so the cycles are disjoint;
-        // each is named by its smallest node (wavefront 0, three nodes per lane; the others wait)
+        // each is named by its smallest node (wavefront 0, a few nodes per lane; the others wait)
         if (wv == 0) {
             for (int v = lane; v <= R; v += 64) {
                 int pv = R;
@@ -711,16 +726,16 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
                 // ... and, with a complete list, the arcs the moved tokens offer from where they are now join it
                 // (counted first, then written behind the list in the order of the cycle), so the list stays complete
                 const int nm = sh.n_moved;
-                long long pp[2];
-                pp[0] = lane < E ? sh.p[lane] : 0;
-                pp[1] = lane + 64 < E ? sh.p[lane + 64] : 0;
+                long long pp[TEPL];
+#pragma unroll
+                for (int m = 0; m < TEPL; ++m) pp[m] = lane + 64 * m < E ? sh.p[lane + 64 * m] : 0;
                 const int sbq = st->sbits;
                 for (int i = wv; i < nm; i += kFinThreads / 64) {
                     const int u = sh.moved[i];
                     bool skip = u < 0;
                     for (int j = 0; j < i; ++j) skip |= sh.moved[j] == u;      // a token on two arcs is taken once
                     const int c = skip ? 0
-                                       : token_arcs<2, false>(q, assign, pp, sbq, u, -1, B, M, E, k, lane, nullptr,
+                                       : token_arcs<TEPL, false>(q, assign, pp, sbq, u, -1, B, M, E, k, lane, nullptr,
                                                               nullptr, 0, 0);
                     if (lane == 0) sh.newcnt[i] = skip ? -1 : c;
                 }
@@ -739,7 +754,7 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
                 if (sh.complete) {
                     for (int i = wv; i < nm; i += kFinThreads / 64)
                         if (sh.newcnt[i] >= 0)
-                            (void)token_arcs<2, false>(q, assign, pp, sbq, sh.moved[i], -1, B, M, E, k, lane, sh.arc,
+                            (void)token_arcs<TEPL, false>(q, assign, pp, sbq, sh.moved[i], -1, B, M, E, k, lane, sh.arc,
                                                        sh.atok, sh.newcnt[i], kFinArcs);
                     n_arcs = sh.n_arcs;
                 }
@@ -875,9 +890,7 @@ int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long 
         rows * k > 1024 || n_wg < 1)
         return MAXSCORE_ERR_SHAPE;
     WorkspaceLayout L = workspace_layout(T, E, k);
-    unsigned long long *M = (unsigned long long *)(ws + L.cand_off);      // E*E*8 <= 128 KB of the 278 KB there
-    static_assert(sizeof(unsigned long long) * kFinMaxE * kFinMaxE <= sizeof(long long) * (size_t)kMaxE * (kCand + 2),
-                  "the finisher's arc matrix lives in the candidate-list region");
+    unsigned long long *M = (unsigned long long *)(ws + L.finm_off);      // E*E entries of the kFinMaxE^2 there
     char *fin_base = ws + L.fin_off;
     if (finish_area_bytes(T) > L.wt_off - L.fin_off) return MAXSCORE_ERR_WORKSPACE;      // layout and area must agree
     const long long *klist = (const long long *)(ws + L.klist_off);
@@ -894,11 +907,19 @@ int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long 
         if (E <= 64)
             hipLaunchKernelGGL(k_fin_arcs<1>, dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
                                fin_base, T, E, k, rows, tri_arc, tri_tok, tri_cnt, seg_cap);
-        else
+        else if (E <= 128)
             hipLaunchKernelGGL(k_fin_arcs<2>, dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
                                fin_base, T, E, k, rows, tri_arc, tri_tok, tri_cnt, seg_cap);
-        hipLaunchKernelGGL(k_fin_cycles, dim3(1), dim3(kFinThreads), 0, s, st, M, assign, theta2, loads2, fin_base, cap,
-                           Ce, T, E, k, pass == total_passes - 1 ? 1 : 0, q, tri_arc, tri_tok, tri_cnt, seg_cap, n_wg);
+        else
+            hipLaunchKernelGGL(k_fin_arcs<4>, dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
+                               fin_base, T, E, k, rows, tri_arc, tri_tok, tri_cnt, seg_cap);
+        const int last = pass == total_passes - 1 ? 1 : 0;
+        if (E <= 128)
+            hipLaunchKernelGGL(k_fin_cycles<2>, dim3(1), dim3(kFinThreads), 0, s, st, M, assign, theta2, loads2, fin_base,
+                               cap, Ce, T, E, k, last, q, tri_arc, tri_tok, tri_cnt, seg_cap, n_wg);
+        else
+            hipLaunchKernelGGL(k_fin_cycles<4>, dim3(1), dim3(kFinThreads), 0, s, st, M, assign, theta2, loads2, fin_base,
+                               cap, Ce, T, E, k, last, q, tri_arc, tri_tok, tri_cnt, seg_cap, n_wg);
     }
     hipLaunchKernelGGL(k_fin_end, dim3(1), dim3(64), 0, s, st, T, host_words,
                        first_pass + passes == total_passes ? 1 : 0, retry);

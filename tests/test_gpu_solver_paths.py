@@ -239,6 +239,46 @@ def test_finisher_that_cannot_take_over_at_its_first_rung(ms, T, E, k, spread, s
     assert auc["stats"]["total_score_q"] == out["stats"]["total_score_q"]
 
 
+@pytest.mark.parametrize("T,E,k,slack", [(4096, 160, 5, 0), (3072, 200, 8, 3), (4096, 256, 4, 0), (2048, 256, 8, 0)])
+def test_finisher_beyond_128_experts(ms, T, E, k, slack):
+    """Up to 256 experts the finisher takes over from the auction (four experts per lane in its arc kernels, an arc
+    matrix of E*E entries in a workspace region of its own): the checker's optimum, prices that certify it, and the
+    finisher did run."""
+    print(f"finisher E={E} T={T} k={k} slack={slack}", flush=True)
+    C = -(-T * k // E) + slack
+    q = skewed_rewards(np.random.default_rng(E + 7 * k), T, E, 20)
+    out = solve_and_check(ms, q, k, C)
+    assert certified(q, out, k, C)
+    assert out["stats"]["finish_passes"] >= 1, out["stats"]
+    auc = solve_and_check(ms, q, k, C, finisher=False)
+    assert auc["stats"]["finish_passes"] == 0 and out["stats"]["rounds"] <= auc["stats"]["rounds"]
+
+
+def test_finisher_at_256_experts_full_batch(ms):
+    """T = 65536, E = 256, k = 8 (tight capacity, Zipf-biased experts): one finisher pass certifies; the total equals
+    the auction's own and the returned prices certify it."""
+    print("finisher E=256 full batch", flush=True)
+    T, E, k = 65536, 256, 8
+    rng = np.random.default_rng(5)
+    z = np.arange(1, E + 1, dtype=np.float64) ** -1.2
+    z = (z - z.min()) / (z.max() - z.min()) * 2.0
+    rng.shuffle(z)
+    L = (rng.standard_normal((T, E)) + z[None, :]).astype(np.float32)
+    q = oracle.quantise(oracle.soft_topk(L, k, 1.0))
+    C = T * k // E
+    qd = dev(q.astype(np.int32))
+    fin = ms.assign_i32(qd, k, C)
+    auc = ms.assign_i32(qd, k, C, finisher=False)
+    print("  ", fin["stats"], flush=True)
+    assert fin["stats"]["status"] == 0 and fin["stats"]["total_score_q"] == auc["stats"]["total_score_q"]
+    assert certified(q, fin, k, C)
+    assert fin["stats"]["finish_passes"] >= 1 and fin["stats"]["rounds"] < auc["stats"]["rounds"]
+    P = oracle.assignment_matrix(fin["assign"].cpu().numpy(), E)
+    ok, why = oracle.check_feasible(P, k, C)
+    assert ok, why
+    assert int(q[P.astype(bool)].sum()) == fin["stats"]["total_score_q"]
+
+
 def test_finisher_with_k_vector_and_capacity_vector(ms):
     """Per-token k (with zeros) and unequal capacities through the finisher: checker's optimum, valid rows."""
     print("finisher kvec+caps", flush=True)
