@@ -277,6 +277,35 @@ def test_route_scores_end_to_end(ms, name, T):
     assert np.array_equal(out["token_pos"].cpu().numpy(), d["token_pos"])
 
 
+def test_route_scores_with_256_experts(ms):
+    """a3..a6 with E = 256, k = 8 (the fine-grained shape): the solve ends in the cycle-cancelling finisher and the
+    gates and dispatch lists are built from its key blocks; everything equal to the checker's."""
+    print("route_scores E=256", flush=True)
+    rng = np.random.default_rng(77)
+    T, E, k = 3072, 256, 8
+    L = (rng.standard_normal((T, E)) + 1.2 * rng.standard_normal((1, E))).astype(np.float32)
+    C = T * k // E
+    A32 = oracle.soft_topk(L.astype(np.float64), k, 1.0).astype(np.float32)
+    out = ms.route_scores(dev(A32), k, C)
+    q = out["q"].cpu().numpy().astype(np.int64)
+    assert np.array_equal(q, oracle.quantise(A32))
+    assign = out["assign"].cpu().numpy()
+    P = oracle.assignment_matrix(assign, E)
+    ok, why = oracle.check_feasible(P, k, C)
+    assert ok, why
+    ref = oracle.max_score_assignment(q, k, C)
+    assert int(P.sum()) == ref["flow"] == out["stats"]["flow_value"]
+    assert int(q[P.astype(bool)].sum()) == ref["total"] == out["stats"]["total_score_q"]
+    assert out["stats"]["finish_passes"] >= 1, out["stats"]
+    g = out["gates"].cpu().numpy()
+    assert np.array_equal(g.astype(np.float64), oracle.gates(A32.astype(np.float64), assign))
+    d = oracle.dispatch(assign, g, E)
+    assert np.array_equal(out["expert_offsets"].cpu().numpy(), d["expert_offsets"])
+    assert np.array_equal(out["disp_token"].cpu().numpy(), d["disp_token"])
+    assert np.array_equal(out["disp_gate"].cpu().numpy(), d["disp_gate"].astype(np.float32))
+    assert np.array_equal(out["token_pos"].cpu().numpy(), d["token_pos"])
+
+
 def test_route_with_token_dropping_when_capacity_is_short(ms):
     """T*k > E*C: iterative rerouting routes with holes (Section 2.3, Figure 1(b)/(c)) and matches the checker
     element by element (the exact solver's answer to the same case is in test_gpu_oversubscribed.py)."""

@@ -279,14 +279,14 @@ def test_finisher_at_256_experts_full_batch(ms):
     assert int(q[P.astype(bool)].sum()) == fin["stats"]["total_score_q"]
 
 
-def test_finisher_with_k_vector_and_capacity_vector(ms):
+@pytest.mark.parametrize("T,E,k,cap_lo,cap_hi", [(3000, 48, 6, 200, 500), (3000, 192, 6, 50, 125)])
+def test_finisher_with_k_vector_and_capacity_vector(ms, T, E, k, cap_lo, cap_hi):
     """Per-token k (with zeros) and unequal capacities through the finisher: checker's optimum, valid rows."""
-    print("finisher kvec+caps", flush=True)
+    print(f"finisher kvec+caps E={E}", flush=True)
     rng = np.random.default_rng(31)
-    T, E, k = 3000, 48, 6
     q = skewed_rewards(rng, T, E, 20)
     kvec = rng.integers(0, k + 1, T).astype(np.int32)
-    caps = rng.integers(200, 500, E).astype(np.int32)
+    caps = rng.integers(cap_lo, cap_hi, E).astype(np.int32)
     caps[3] = 0
     assert caps.sum() >= kvec.sum()
     out = ms.assign_kvec_i32(dev(q.astype(np.int32)), k, dev(kvec), caps=list(caps))
