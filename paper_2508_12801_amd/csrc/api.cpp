@@ -351,11 +351,11 @@ static int32_t route_from_rewards(const float *scores, const int32_t *q, int T, 
         // below overwrite what they wrote).
         struct AfterCtx {
             const float *scores; const int32_t *assign; int T, E, k; float *gates; int32_t *offsets, *disp_token;
-            float *disp_gate; int32_t *token_pos; char *ws; hipEvent_t ev_a, ev_b;
-        } ctx = {scores, assign, T, E, k, gates, expert_offsets, disp_token, disp_gate, token_pos, ws, ev_a, ev_b};
-        SolverAfter after = [](void *c, const SolverGeometry &g, hipStream_t st) -> int32_t {
+            float *disp_gate; int32_t *token_pos; char *ws; hipEvent_t ev_start, ev_b;
+        } ctx = {scores, assign, T, E, k, gates, expert_offsets, disp_token, disp_gate, token_pos, ws, nullptr, ev_b};
+        SolverAfter after = [](void *c, const SolverGeometry &g, hipStream_t st, hipEvent_t solve_end) -> int32_t {
             AfterCtx *a = (AfterCtx *)c;
-            MS_HIP(hipEventRecord(a->ev_a, st));
+            a->ev_start = solve_end;         // gates and dispatch are timed from the end of the solve (no event of their own)
             int32_t rc = dispatch_from_keys(g, a->scores, a->assign, a->T, a->E, a->k, a->gates, a->offsets,
                                             a->disp_token, a->disp_gate, a->token_pos, a->ws, st);
             if (rc) return rc;
@@ -367,7 +367,8 @@ static int32_t route_from_rewards(const float *scores, const int32_t *q, int T, 
                          &ctx);
         if (src == MAXSCORE_OK && geom.n_wg > 0) {
             float t = 0.f;           // the solve has waited for the stream: both events are complete
-            if (stats && hipEventElapsedTime(&t, ev_a, ev_b) == hipSuccess) stats->gates_dispatch_ms = t;
+            if (stats && ctx.ev_start && hipEventElapsedTime(&t, ctx.ev_start, ev_b) == hipSuccess)
+                stats->gates_dispatch_ms = t;
             return src;
         }
     }

@@ -89,7 +89,9 @@ inline bool hip_ok(hipError_t e) { return e == hipSuccess; }
 // It is enqueued before the call waits for the stream, so the device goes from the solve straight into it; it
 // runs whatever the solve's status turns out to be and must therefore be safe on any state the solver can leave
 // (the caller redoes it another way when the status is not MAXSCORE_OK).
-typedef int32_t (*SolverAfter)(void *ctx, const SolverGeometry &g, hipStream_t s);
+// solve_end: the event the solver has just recorded behind its last kernel (it stays valid until the calling thread
+// solves again on this device); work timed from there needs no start event of its own.
+typedef int32_t (*SolverAfter)(void *ctx, const SolverGeometry &g, hipStream_t s, hipEvent_t solve_end);
 int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore_opts &o, int32_t *assign,
                    int64_t *prices, int64_t *price_scale, maxscore_stats *stats, char *ws, hipStream_t s,
                    const int32_t *cap = nullptr, long long room = 0, const int32_t *kvec = nullptr,

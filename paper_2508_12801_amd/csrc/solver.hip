@@ -383,7 +383,9 @@ __global__ __launch_bounds__(256, (G * EPL > 256 ? 3 : 4)) void k_bid(const int3
     const int over = st->done;
     const long long eps = st->eps, qmin = st->qmin;
     const int sb = st->sbits, tb = st->tbits;
-    if (over && !force) return;       // (force: one more pass after the end, which only rewrites the key blocks)
+    // force: one more pass after the end, which only rewrites the key blocks (1: always; 2: if the finisher has
+    // certified the optimum after moving tokens, which the host does not know yet when it enqueues this pass)
+    if (force == 2 ? !(st->fin == 2 && st->fin_cycles > 0) : (over && !force)) return;
 #pragma unroll
     for (int i = 0; i < (EP + 255) / 256; ++i) {
         const int e = tid + i * 256;
@@ -680,6 +682,7 @@ constexpr int kTailThreads = 1024;
 __device__ int g_tailtrace[256 * 8];      // per tail run: round, iterations, victims, stop1, stop2, over_last, wall ticks
 __device__ int g_tailruns;
 #endif
+constexpr int kHostRoundWord = 8;       // word of the pinned host block that carries the number of rounds done
 constexpr int kTailMoves = 16;            // hand over to the tail pass when a bid pass moved this few slots
 constexpr int kEarlyMoves = 16;           // a phase before the last one ends when a bid pass moved this few slots
 constexpr long long kKeyInf = (long long)1 << 62;
@@ -1352,7 +1355,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
         ns.after_tail = 0;
         ns.tail_block = 0;
         *st_out = ns;
-        // the host polls this word (pinned host memory) instead of copying the state
+        // the host polls these words (pinned host memory) instead of copying the state or waiting for events: the
+        // number of rounds done so far, by which it paces its launches, and the end of the solve
+        __hip_atomic_store(host_done + kHostRoundWord, round, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         if (ns.done) __hip_atomic_store(host_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
     if (is_tail) {
@@ -1747,9 +1752,10 @@ int32_t kvec_check(const int32_t *kvec, int T, int E, int k, char *ws, long long
 // Per-host-thread objects of the solver that outlive a call: the pinned flag the select pass writes `done` into,
 // and the events (created once, reused by every solve of the thread, never destroyed: a few handles per thread).
 struct SolverHost {
-    int *flag = nullptr;        // pinned and mapped
-    int *flag_dev = nullptr;    // the same word as the device sees it
-    hipEvent_t ev0 = nullptr, ev1 = nullptr, evb[2] = {nullptr, nullptr};
+    // pinned and mapped, 16 words: [0] the solve has ended, [4..7] the finisher's report, [kHostRoundWord] rounds done
+    int *flag = nullptr;
+    int *flag_dev = nullptr;    // the same words as the device sees them
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
     std::vector<hipEvent_t> tev;      // pool of per-launch timing events (kernel timing only)
     int device = -1;
 };
@@ -1771,8 +1777,6 @@ static int32_t solver_host(SolverHost **out)
         MS_HIP(hipHostGetDevicePointer((void **)&h->flag_dev, h->flag, 0));
         MS_HIP(hipEventCreate(&h->ev0));
         MS_HIP(hipEventCreate(&h->ev1));
-        MS_HIP(hipEventCreateWithFlags(&h->evb[0], hipEventDisableTiming));
-        MS_HIP(hipEventCreateWithFlags(&h->evb[1], hipEventDisableTiming));
         h->device = dev;
     }
     *out = h;
@@ -1880,14 +1884,37 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
                            eps0_shift, theta, o.prices_in, (long long)o.eps_start, fin_limit_q);
     }
 
-    // Rounds are enqueued in batches; the select pass writes `done` straight into pinned host memory.
-    // The next batch is always enqueued BEFORE the host waits for the flag of the current one, so the
-    // device never idles during the host round trip; once the solve is over the rounds still in the
-    // queue exit at once.
-    *(volatile int *)hs->flag = 0;
+    // Rounds are enqueued in batches; the select pass writes the number of rounds done and `done` straight into
+    // pinned host memory, and the host paces itself by polling those words (an event per batch would cost the
+    // device a pipeline drain of several microseconds each).  The next batch is always enqueued BEFORE the host
+    // waits for the current one to end, so the device never idles during the host round trip; once the solve is
+    // over the rounds still in the queue exit at once.
+    volatile int *hw = (volatile int *)hs->flag;
+    hw[0] = 0;
+    hw[kHostRoundWord] = 0;
+    // Waits until `word` reaches `target` or the solve has ended.  The stream is looked at now and then: an error
+    // ends the wait, and so does a stream that has drained (everything enqueued has run; the caller's own limits
+    // then decide how to go on).
+    auto wait_word = [&](int word, int target, bool or_done) -> int32_t {
+        for (unsigned spin = 1;; ++spin) {
+            if ((or_done && hw[0]) || hw[word] >= target) return MAXSCORE_OK;
+            if ((spin & 2047) == 0) {
+                const hipError_t e = hipStreamQuery(s);
+                if (e == hipSuccess) return MAXSCORE_OK;
+                if (e != hipErrorNotReady) {
+                    (void)hipStreamSynchronize(s);
+                    return MAXSCORE_ERR_HIP;
+                }
+            }
+            __builtin_ia32_pause();
+        }
+    };
     std::vector<hipEvent_t> &tev = hs->tev;
     size_t tev_used = 0;
-    const int batch = 4;
+    int batch = 2;      // two to four rounds in flight: each round still queued when the solve ends costs an empty launch pair
+#ifdef MAXSCORE_DEBUG_ENV
+    if (const char *ev = getenv("MAXSCORE_BATCH")) batch = std::max(1, std::min(atoi(ev), 64));
+#endif
     int launched = 0;
     auto enqueue_batch = [&](int slot) -> int32_t {
         for (int b = 0; b < batch; ++b) {
@@ -1923,7 +1950,6 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             }
             ++launched;
         }
-        MS_HIP(hipEventRecord(hs->evb[slot], s));
         return MAXSCORE_OK;
     };
     auto run_rounds = [&]() -> int32_t {
@@ -1934,8 +1960,9 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             const int launched_cur = launched;
             rc = enqueue_batch(cur ^ 1);
             if (rc != MAXSCORE_OK) break;
-            MS_HIP_SYNC(hipEventSynchronize(hs->evb[cur]));
-            if (*(volatile int *)hs->flag || launched_cur - launched0 > o.max_rounds + 64) break;
+            rc = wait_word(kHostRoundWord, launched_cur, true);      // the batch before the one just enqueued has run
+            if (rc != MAXSCORE_OK) return rc;
+            if (hw[0] || launched_cur - launched0 > o.max_rounds + 64) break;
             cur ^= 1;
         }
         if (rc != MAXSCORE_OK) (void)hipStreamSynchronize(s);
@@ -1945,7 +1972,38 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         int32_t rc = run_rounds();
         if (rc != MAXSCORE_OK) return rc;
     }
+    // What follows the solve on the stream: the pass that rewrites the key blocks for the caller (if asked for),
+    // the trim at the round cap, totals and prices, the end-of-solve event and the caller's own work.
+    auto enqueue_end = [&](int bid_force) -> int32_t {
+        const int par = launched & 1;    // every launch after the end copied the final state on: both copies hold it
+        if (bid_force && geom) {
+#define MS_BIDF(GG) \
+    launch_bid_g<GG>(EPL, vec, q, assign, theta + par * kMaxE, st + par, klist, wcnt, wmoves, qmm + 2, T, E, k, rows, \
+                     kvec, bid_force, s)
+            if (G == 8) MS_BIDF(8);
+            else if (G == 16) MS_BIDF(16);
+            else if (G == 32) MS_BIDF(32);
+            else MS_BIDF(64);
+#undef MS_BIDF
+        }
+        hipLaunchKernelGGL(k_trim, dim3(n_wg), dim3(256), 0, s, st + par, theta, klist, wcnt, assign, E, k, rows);
+        hipLaunchKernelGGL(k_finalize, dim3(kFinalBlocks), dim3(256), 0, s, q, assign, cand, T, E, k);   // lists are free again
+        hipLaunchKernelGGL(k_finalize2, dim3(1), dim3(kFinalBlocks), 0, s, cand, theta, st + par, prices, price_scale, E);
+        MS_HIP_SYNC(hipEventRecord(hs->ev1, s));
+        if (after) {
+            int tb = 1;                       // as k_setup computes it
+            while ((1 << tb) < T) ++tb;
+            const SolverGeometry g = {rows, n_wg, tb};
+            const int32_t arc = after(after_ctx, g, s, hs->ev1);
+            if (arc != MAXSCORE_OK) {
+                (void)hipStreamSynchronize(s);
+                return arc;
+            }
+        }
+        return MAXSCORE_OK;
+    };
     int fin_cycles = 0, fin_state = 0, fin_cycles_before = 0;
+    bool end_enqueued = false;
     for (int attempt = 0; fin_limit_q > 0 && attempt < kFinAttempts; ++attempt) {
         // The auction has stopped at a coarse eps (or ended for another reason, then every finisher launch exits at
         // once).  A fixed number of finisher passes is enqueued; the last kernel reports through pinned memory
@@ -1960,14 +2018,29 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         int32_t rc = MAXSCORE_OK;
         for (int p0 = 0, grp = kFinFirstGroup; p0 < fin_passes; p0 += grp, grp = kFinGroup) {
             grp = std::min(grp, fin_passes - p0);
+            words[4] = 0;                         // (the previous group's report has been read)
             rc = finish_enqueue(q, assign, st + fp, theta, gcount, cap, Ce, T, E, k, ws, rows, n_wg, p0, grp, fin_passes,
                                 fin_bound_mult, hs->flag_dev + 4, retry, s);
             if (rc != MAXSCORE_OK) {
                 (void)hipStreamSynchronize(s);
                 return rc;
             }
-            MS_HIP_SYNC(hipEventRecord(hs->evb[0], s));
-            MS_HIP_SYNC(hipEventSynchronize(hs->evb[0]));
+            // The first group of the first attempt usually certifies.  What follows a certified solve is therefore
+            // enqueued before the host learns how the group ended, so the device goes straight on (the key-block
+            // pass decides on the device whether it is needed); if the group did not certify, these launches ran
+            // on a state that is not final, which is harmless, and they are enqueued again at the real end.
+            const bool ahead = attempt == 0 && p0 == 0;
+            if (ahead) {
+                rc = enqueue_end(2);
+                if (rc != MAXSCORE_OK) return rc;
+            }
+            rc = wait_word(4, 1, false);          // the group's last kernel has reported
+            if (rc != MAXSCORE_OK) return rc;
+            if (words[4] == 0) {                  // (the stream drained without a report: cannot happen)
+                (void)hipStreamSynchronize(s);
+                return MAXSCORE_ERR_HIP;
+            }
+            if (ahead && words[4] == 1) end_enqueued = true;
             if (words[4] != 3) break;
         }
         fin_cycles = fin_cycles_before + words[5];
@@ -1982,36 +2055,20 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             if (rc != MAXSCORE_OK) return rc;
             continue;
         }
-        if (words[5] > 0 && geom) {
-            // the caller reads the key blocks of the last bid pass: one more pass rewrites them for the final
-            // assignment (every hold is valid under the exact prices, so the pass moves nothing)
-            const int par = launched & 1;
-#define MS_BIDF(GG) \
-    launch_bid_g<GG>(EPL, vec, q, assign, theta + par * kMaxE, st + par, klist, wcnt, wmoves, qmm + 2, T, E, k, rows, \
-                     kvec, 1, s)
-            if (G == 8) MS_BIDF(8);
-            else if (G == 16) MS_BIDF(16);
-            else if (G == 32) MS_BIDF(32);
-            else MS_BIDF(64);
-#undef MS_BIDF
+        if (!end_enqueued) {
+            // the caller reads the key blocks of the last bid pass: if tokens were moved, one more pass rewrites them
+            // for the final assignment (every hold is valid under the exact prices, so the pass moves nothing)
+            rc = enqueue_end(words[5] > 0 ? 1 : 0);
+            if (rc != MAXSCORE_OK) return rc;
+            end_enqueued = true;
         }
         break;
     }
-    const int fpar = launched & 1;       // every launch after the end copied the final state on: both copies hold it
-    hipLaunchKernelGGL(k_trim, dim3(n_wg), dim3(256), 0, s, st + fpar, theta, klist, wcnt, assign, E, k, rows);
-    hipLaunchKernelGGL(k_finalize, dim3(kFinalBlocks), dim3(256), 0, s, q, assign, cand, T, E, k);   // lists are free again
-    hipLaunchKernelGGL(k_finalize2, dim3(1), dim3(kFinalBlocks), 0, s, cand, theta, st + fpar, prices, price_scale, E);
-    MS_HIP_SYNC(hipEventRecord(hs->ev1, s));
-    if (after) {
-        int tb = 1;                       // as k_setup computes it
-        while ((1 << tb) < T) ++tb;
-        const SolverGeometry g = {rows, n_wg, tb};
-        const int32_t arc = after(after_ctx, g, s);
-        if (arc != MAXSCORE_OK) {
-            (void)hipStreamSynchronize(s);
-            return arc;
-        }
+    if (!end_enqueued) {
+        const int32_t rc = enqueue_end(0);
+        if (rc != MAXSCORE_OK) return rc;
     }
+    const int fpar = launched & 1;
     SolverState h;
     MS_HIP_SYNC(hipMemcpyAsync(&h, st + fpar, sizeof(h), hipMemcpyDeviceToHost, s));
     MS_HIP(hipStreamSynchronize(s));
