@@ -18,6 +18,8 @@
 //
 // Everything is integer and deterministic (ties between tokens go to the lower token id).  When the finisher cannot
 // certify (bound check fails, pass limit) the auction simply continues down its eps ladder from the state left here.
+#include <algorithm>
+
 #include "common.h"
 
 namespace maxscore {
@@ -895,9 +897,11 @@ int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long 
     if (finish_area_bytes(T) > L.wt_off - L.fin_off) return MAXSCORE_ERR_WORKSPACE;      // layout and area must agree
     const long long *klist = (const long long *)(ws + L.klist_off);
     const int *wcnt = (const int *)(ws + L.wcnt_off);
-    const int seg_cap = fin_seg_cap(rows, k);
     const size_t tri_n = fin_tri_entries(T, k, L.max_wg);
-    if ((size_t)n_wg * seg_cap > tri_n || n_wg > L.max_wg) return MAXSCORE_ERR_WORKSPACE;
+    if ((size_t)n_wg * fin_seg_cap(rows, k) > tri_n || n_wg > L.max_wg) return MAXSCORE_ERR_WORKSPACE;
+    // every key block gets an equal share of the region (at least fin_seg_cap(rows, k) entries: with few blocks
+    // much more, so that the short key blocks of a small batch do not run over)
+    const int seg_cap = (int)std::min<size_t>(tri_n / (size_t)n_wg, 4096);
     unsigned long long *tri_arc = (unsigned long long *)(ws + L.tri_off);
     int *tri_tok = (int *)(ws + L.tri_off + 8 * tri_n);
     int *tri_cnt = tri_tok + tri_n;

@@ -1756,6 +1756,9 @@ struct SolverHost {
     int *flag = nullptr;
     int *flag_dev = nullptr;    // the same words as the device sees them
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    // whether the first finisher group of the last solve of this shape certified (what follows a certified solve is
+    // enqueued ahead of the group's report only while that keeps happening)
+    int ahead_T = 0, ahead_E = 0, ahead_k = 0, ahead_ok = 1;
     std::vector<hipEvent_t> tev;      // pool of per-launch timing events (kernel timing only)
     int device = -1;
 };
@@ -2029,7 +2032,8 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             // enqueued before the host learns how the group ended, so the device goes straight on (the key-block
             // pass decides on the device whether it is needed); if the group did not certify, these launches ran
             // on a state that is not final, which is harmless, and they are enqueued again at the real end.
-            const bool ahead = attempt == 0 && p0 == 0;
+            const bool same_shape = hs->ahead_T == T && hs->ahead_E == E && hs->ahead_k == k;
+            const bool ahead = attempt == 0 && p0 == 0 && (!same_shape || hs->ahead_ok);
             if (ahead) {
                 rc = enqueue_end(2);
                 if (rc != MAXSCORE_OK) return rc;
@@ -2041,6 +2045,10 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
                 return MAXSCORE_ERR_HIP;
             }
             if (ahead && words[4] == 1) end_enqueued = true;
+            if (attempt == 0 && p0 == 0) {
+                hs->ahead_T = T; hs->ahead_E = E; hs->ahead_k = k;
+                hs->ahead_ok = words[4] == 1 ? 1 : 0;
+            }
             if (words[4] != 3) break;
         }
         fin_cycles = fin_cycles_before + words[5];

@@ -198,7 +198,7 @@ def test_finisher_and_auction_reach_the_same_optimum(ms, name, T, seed):
         assert torch.equal(again["assign"], fin["assign"]) and torch.equal(again["prices"], fin["prices"])
 
 
-@pytest.mark.parametrize("name,seed", [("cfg5", 0), ("cfg5", 1), ("cfg3", 1)])
+@pytest.mark.parametrize("name,seed", [("cfg5", 0), ("cfg5", 1), ("cfg3", 1), ("cfg2", 0), ("cfg2", 3)])
 def test_finisher_certifies_in_one_pass_at_full_size(ms, name, seed):
     """At the benchmark's sizes the first finisher pass holds every arc under its bound and keeps that list complete
     while it moves tokens (the arcs of a moved token are replaced on the spot), so it cancels all cycles and
@@ -212,7 +212,8 @@ def test_finisher_certifies_in_one_pass_at_full_size(ms, name, seed):
     auc = ms.assign_i32(qd, k, C, finisher=False)
     assert fin["stats"]["status"] == 0 and fin["stats"]["total_score_q"] == auc["stats"]["total_score_q"]
     assert certified(q, fin, k, C)
-    assert fin["stats"]["finish_cycles"] > 0 and fin["stats"]["finish_passes"] == 1, fin["stats"]
+    assert fin["stats"]["finish_passes"] == 1, fin["stats"]
+    assert fin["stats"]["finish_cycles"] > 0 or name == "cfg2", fin["stats"]     # (the small batch may leave no cycle)
     a = fin["assign"].cpu().numpy()
     P = oracle.assignment_matrix(a, E)
     ok, why = oracle.check_feasible(P, k, C)
