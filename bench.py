@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-concurrent", action="store_true",
+                    help="skip the extra section that routes several batches at the same time (for profiler runs: "
+                         "every launch in the trace then belongs to a call that had the GPU to itself)")
     ap.add_argument("--cpu-sample", type=int, default=65536)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -163,12 +166,12 @@ def main():
     import threading
     concurrent = {}
     batches = [(x, W, b)]
-    for bi in range(1, 4):          # further batches of the same router: x ~ N(0,1) as in the recipe, drawn on the device
+    for bi in (() if args.no_concurrent else range(1, 4)):          # further batches of the same router: x ~ N(0,1) as in the recipe, drawn on the device
         gen = torch.Generator(device=dev).manual_seed(1000 + bi)
         xi_ = torch.randn(T, d, generator=gen, device=dev, dtype=torch.float32)
         batches.append((xi_.to(torch.bfloat16) if r.dtype == "bf16" else xi_, W, b))
         del xi_
-    for n_streams in (2, 4):
+    for n_streams in (() if args.no_concurrent else (2, 4)):
         res = [None] * n_streams
         gate = threading.Barrier(n_streams + 1)
         n_calls = 10
@@ -343,7 +346,7 @@ def main():
                                             "frac": gd_bytes / (gd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}},
                      "copy_kernel_GBs": copy_gbs,
                      "note": "frac is below the 0.5 target: the passes are bound by launch and chain latency, "
-                             "not by bytes (DESIGN.md section 8)"},
+                             "not by bytes"},
         "stages_ms": {"router_gemm": gemm_ms, "softtopk_quantise": soft_ms,
                       "router_gemm_softtopk_one_kernel": fused_ms,
                       "router_gemm_softtopk_one_kernel_no_logits": fused_nolog_ms,

@@ -113,6 +113,9 @@ int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long 
                        const int *cap, int Ce, int T, int E, int k, char *ws, int rows, int n_wg, int first_pass,
                        int passes, int total_passes, long long bound_mult, int *host_words, int retry, hipStream_t s);
 size_t finish_area_bytes(int T);          // bytes of WorkspaceLayout::fin_off's region
+// One bit per token, set for the tokens the finisher has moved since its first pass of this attempt (the region's
+// first (T + 31) / 32 + 1 words).
+inline const unsigned *finish_moved_bits(const char *ws, const WorkspaceLayout &L) { return (const unsigned *)(ws + L.fin_off); }
 // Arc lists of the finisher's first pass: key block w owns a segment of consecutive entries, an equal share of a
 // region of fin_tri_entries() entries; the region is sized so that a share is never smaller than fin_seg_cap(rows, k)
 // for any geometry the solver picks (rows * k <= 1024 per block).

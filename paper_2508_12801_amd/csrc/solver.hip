@@ -311,7 +311,8 @@ __global__ __launch_bounds__(256, (G * EPL > 256 ? 3 : 4)) void k_bid(const int3
                                              const long long *__restrict__ theta, const SolverState *__restrict__ st,
                                              long long *__restrict__ klist, int *__restrict__ wcnt,
                                              int *__restrict__ wmoves, int *__restrict__ errflag, int T, int E, int k,
-                                             int rows_per_wg, const int32_t *__restrict__ kvec, int force)
+                                             int rows_per_wg, const int32_t *__restrict__ kvec, int force,
+                                             const unsigned *__restrict__ moved_bits)
 {
     constexpr int EP = G * EPL;
     constexpr int NG = 256 / G;
@@ -386,6 +387,19 @@ __global__ __launch_bounds__(256, (G * EPL > 256 ? 3 : 4)) void k_bid(const int3
     // force: one more pass after the end, which only rewrites the key blocks (1: always; 2: if the finisher has
     // certified the optimum after moving tokens, which the host does not know yet when it enqueues this pass)
     if (force == 2 ? !(st->fin == 2 && st->fin_cycles > 0) : (over && !force)) return;
+    if (force && moved_bits) {
+        // only the key blocks that hold a token the finisher has moved change (the dispatch reads which pairs a
+        // block holds, not the key values): the other workgroups leave theirs as they are
+        const int r1 = (row0 + rows_per_wg < T ? row0 + rows_per_wg : T) - 1;
+        unsigned any = 0;
+        for (int wd = row0 >> 5; wd <= (r1 >> 5); ++wd) {
+            unsigned m = moved_bits[wd];
+            if (wd == (row0 >> 5)) m &= ~0u << (row0 & 31);
+            if (wd == (r1 >> 5)) m &= ~0u >> (31 - (r1 & 31));
+            any |= m;
+        }
+        if (!any) return;
+    }
 #pragma unroll
     for (int i = 0; i < (EP + 255) / 256; ++i) {
         const int e = tid + i * 256;
@@ -1698,12 +1712,12 @@ __global__ __launch_bounds__(256) void k_kvec_check(const int32_t *__restrict__ 
 template <int G, int EPL>
 void launch_bid(bool vec, const int32_t *q, int32_t *assign, const long long *theta, const SolverState *st,
                 long long *klist, int *wcnt, int *wmoves, int *errflag, int T, int E, int k, int rows_per_wg,
-                const int32_t *kvec, int force, hipStream_t s)
+                const int32_t *kvec, int force, const unsigned *moved_bits, hipStream_t s)
 {
     int grid = (T + rows_per_wg - 1) / rows_per_wg;
 #define MS_BK(VV, KK)                                                                                        \
     hipLaunchKernelGGL((k_bid<G, EPL, VV, KK>), dim3(grid), dim3(256), 0, s, q, assign, theta, st, klist, wcnt, \
-                       wmoves, errflag, T, E, k, rows_per_wg, kvec, force)
+                       wmoves, errflag, T, E, k, rows_per_wg, kvec, force, moved_bits)
     if (kvec) {
         if (vec) MS_BK(true, true);
         else MS_BK(false, true);
@@ -1717,9 +1731,10 @@ void launch_bid(bool vec, const int32_t *q, int32_t *assign, const long long *th
 template <int G>
 void launch_bid_g(int EPL, bool vec, const int32_t *q, int32_t *assign, const long long *theta,
                   const SolverState *st, long long *klist, int *wcnt, int *wmoves, int *errflag, int T, int E, int k,
-                  int rows_per_wg, const int32_t *kvec, int force, hipStream_t s)
+                  int rows_per_wg, const int32_t *kvec, int force, const unsigned *moved_bits, hipStream_t s)
 {
-#define MS_B(PP) launch_bid<G, PP>(vec, q, assign, theta, st, klist, wcnt, wmoves, errflag, T, E, k, rows_per_wg, kvec, force, s)
+#define MS_B(PP) \
+    launch_bid<G, PP>(vec, q, assign, theta, st, klist, wcnt, wmoves, errflag, T, E, k, rows_per_wg, kvec, force, moved_bits, s)
     if (EPL == 1) MS_B(1);
     else if (EPL == 2) MS_B(2);
     else if (EPL == 4) MS_B(4);
@@ -1932,7 +1947,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             }
 #define MS_BID(GG)                                                                                   \
     launch_bid_g<GG>(EPL, vec, q, assign, theta + par * kMaxE, st + par, klist, wcnt, wmoves, qmm + 2, T, E, k, \
-                     rows, kvec, 0, s)
+                     rows, kvec, 0, nullptr, s)
             if (G == 8) MS_BID(8);
             else if (G == 16) MS_BID(16);
             else if (G == 32) MS_BID(32);
@@ -1982,7 +1997,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         if (bid_force && geom) {
 #define MS_BIDF(GG) \
     launch_bid_g<GG>(EPL, vec, q, assign, theta + par * kMaxE, st + par, klist, wcnt, wmoves, qmm + 2, T, E, k, rows, \
-                     kvec, bid_force, s)
+                     kvec, bid_force, finish_moved_bits(ws, L), s)
             if (G == 8) MS_BIDF(8);
             else if (G == 16) MS_BIDF(16);
             else if (G == 32) MS_BIDF(32);
