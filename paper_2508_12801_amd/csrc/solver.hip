@@ -1649,7 +1649,8 @@ __global__ __launch_bounds__(256) void k_trim(const SolverState *__restrict__ st
 
 __global__ __launch_bounds__(kFinalBlocks) void k_finalize2(const long long *__restrict__ part,
                                                            const long long *__restrict__ theta2, SolverState *st,
-                                                           int64_t *prices, int64_t *price_scale, int E)
+                                                           int64_t *prices, int64_t *price_scale, int E,
+                                                           SolverState *host_state)
 {
     const long long *theta = theta2 + (st->round & 1) * kMaxE;      // what the last select pass wrote
     __shared__ long long s_sum[kFinalBlocks / 64], s_cnt[kFinalBlocks / 64];
@@ -1672,6 +1673,8 @@ __global__ __launch_bounds__(kFinalBlocks) void k_finalize2(const long long *__r
         st->total = ts;
         st->flow = (int)tc;
         if (price_scale) *price_scale = (int64_t)1 << st->sbits;
+        // the host reads the final state from pinned memory once the stream has drained (no copy in the stream)
+        *host_state = *st;
     }
     const int tb = st->tbits;
     if (prices)
@@ -1770,6 +1773,7 @@ struct SolverHost {
     // pinned and mapped, 16 words: [0] the solve has ended, [4..7] the finisher's report, [kHostRoundWord] rounds done
     int *flag = nullptr;
     int *flag_dev = nullptr;    // the same words as the device sees them
+    SolverState *state = nullptr, *state_dev = nullptr;      // pinned and mapped: the final state of the last solve
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     // whether the first finisher group of the last solve of this shape certified (what follows a certified solve is
     // enqueued ahead of the group's report only while that keeps happening)
@@ -1793,6 +1797,8 @@ static int32_t solver_host(SolverHost **out)
     if (h->device < 0) {
         MS_HIP(hipHostMalloc((void **)&h->flag, 64, hipHostMallocMapped));
         MS_HIP(hipHostGetDevicePointer((void **)&h->flag_dev, h->flag, 0));
+        MS_HIP(hipHostMalloc((void **)&h->state, sizeof(SolverState), hipHostMallocMapped));
+        MS_HIP(hipHostGetDevicePointer((void **)&h->state_dev, h->state, 0));
         MS_HIP(hipEventCreate(&h->ev0));
         MS_HIP(hipEventCreate(&h->ev1));
         h->device = dev;
@@ -2006,7 +2012,8 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         }
         hipLaunchKernelGGL(k_trim, dim3(n_wg), dim3(256), 0, s, st + par, theta, klist, wcnt, assign, E, k, rows);
         hipLaunchKernelGGL(k_finalize, dim3(kFinalBlocks), dim3(256), 0, s, q, assign, cand, T, E, k);   // lists are free again
-        hipLaunchKernelGGL(k_finalize2, dim3(1), dim3(kFinalBlocks), 0, s, cand, theta, st + par, prices, price_scale, E);
+        hipLaunchKernelGGL(k_finalize2, dim3(1), dim3(kFinalBlocks), 0, s, cand, theta, st + par, prices, price_scale, E,
+                           hs->state_dev);
         MS_HIP_SYNC(hipEventRecord(hs->ev1, s));
         if (after) {
             int tb = 1;                       // as k_setup computes it
@@ -2091,11 +2098,9 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         const int32_t rc = enqueue_end(0);
         if (rc != MAXSCORE_OK) return rc;
     }
-    const int fpar = launched & 1;
-    SolverState h;
-    MS_HIP_SYNC(hipMemcpyAsync(&h, st + fpar, sizeof(h), hipMemcpyDeviceToHost, s));
     MS_HIP(hipStreamSynchronize(s));
     MS_HIP(hipGetLastError());
+    const SolverState h = *hs->state;     // what the last k_finalize2 wrote
     float ms = 0.f, bid_ms = 0.f, select_ms = 0.f;
     (void)hipEventElapsedTime(&ms, hs->ev0, hs->ev1);
     int timed = 0;
