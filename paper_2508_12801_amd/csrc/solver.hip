@@ -2041,7 +2041,9 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
         // the passes are enqueued a few at a time (most solves are certified by the first pass, and a pass that
         // finds the work done still costs two launches)
         int32_t rc = MAXSCORE_OK;
-        for (int p0 = 0, grp = kFinFirstGroup; p0 < fin_passes; p0 += grp, grp = kFinGroup) {
+        // (one pass alone the first time if that was enough for the previous solve of the same shape)
+        const bool one_sufficed = hs->ahead_T == T && hs->ahead_E == E && hs->ahead_k == k && hs->ahead_ok == 2;
+        for (int p0 = 0, grp = one_sufficed ? 1 : kFinFirstGroup; p0 < fin_passes; p0 += grp, grp = kFinGroup) {
             grp = std::min(grp, fin_passes - p0);
             words[4] = 0;                         // (the previous group's report has been read)
             rc = finish_enqueue(q, assign, st + fp, theta, gcount, cap, Ce, T, E, k, ws, rows, n_wg, p0, grp, fin_passes,
@@ -2055,7 +2057,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             // pass decides on the device whether it is needed); if the group did not certify, these launches ran
             // on a state that is not final, which is harmless, and they are enqueued again at the real end.
             const bool same_shape = hs->ahead_T == T && hs->ahead_E == E && hs->ahead_k == k;
-            const bool ahead = attempt == 0 && p0 == 0 && (!same_shape || hs->ahead_ok);
+            const bool ahead = attempt == 0 && p0 == 0 && (!same_shape || hs->ahead_ok > 0);
             if (ahead) {
                 rc = enqueue_end(2);
                 if (rc != MAXSCORE_OK) return rc;
@@ -2069,6 +2071,7 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             if (ahead && words[4] == 1) end_enqueued = true;
             if (attempt == 0 && p0 == 0) {
                 hs->ahead_T = T; hs->ahead_E = E; hs->ahead_k = k;
+                // 1: certified by the group (2 once the final state shows that one pass did it); 0: not certified
                 hs->ahead_ok = words[4] == 1 ? 1 : 0;
             }
             if (words[4] != 3) break;
@@ -2101,6 +2104,9 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     MS_HIP(hipStreamSynchronize(s));
     MS_HIP(hipGetLastError());
     const SolverState h = *hs->state;     // what the last k_finalize2 wrote
+    if (fin_limit_q > 0 && hs->ahead_T == T && hs->ahead_E == E && hs->ahead_k == k && hs->ahead_ok == 1 &&
+        h.fin == 2 && h.fin_passes <= 1)
+        hs->ahead_ok = 2;
     float ms = 0.f, bid_ms = 0.f, select_ms = 0.f;
     (void)hipEventElapsedTime(&ms, hs->ev0, hs->ev1);
     int timed = 0;
