@@ -25,11 +25,12 @@
  *     aligned.  Two calls may overlap only if they use different workspaces.
  *   - Return value: MAXSCORE_OK or a negative MAXSCORE_ERR_* code.  Argument errors are found on
  *     the host before anything is launched.  No entry point throws or allocates device memory.
- *   - Entry points that contain the assignment step (a4) poll a convergence flag and therefore
- *     SYNCHRONISE `stream` before returning; the others only enqueue work.  The flag lives in 64 bytes
- *     of pinned host memory that the first such call of a host thread allocates and keeps until the
- *     process ends (one solve at a time per host thread; different threads may solve concurrently on
- *     different streams with different workspaces).
+ *   - Entry points that contain the assignment step (a4) pace their launches by the solver's progress and
+ *     therefore SYNCHRONISE `stream` before returning; the others only enqueue work.  The progress words (rounds
+ *     done, end of the solve, the finisher's report) and the final solver state live in two small blocks of pinned
+ *     host memory (under 1 KiB together) that the first such call of a host thread allocates per device and keeps
+ *     until the process ends; the calling thread polls them while the solve runs (one solve at a time per host
+ *     thread; different threads may solve concurrently on different streams with different workspaces).
  *   - Supported sizes: 1 <= k <= E <= 1024, k <= 64, 1 <= T <= 2^21, C >= 1 (C > T acts as T).
  *   - More demand than capacity, T*k > E*min(C,T) (never with a capacity c' = c_f*k*n/e, c_f >= 1, of Section 2.3):
  *     Eq. 7's equalities cannot all hold then; with the capacities of Table 1 the problem is still a flow problem
