@@ -143,12 +143,22 @@ __device__ __forceinline__ int group_max_i32(int v)
     return v;
 }
 
-__global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm, int32_t *assign, int T, int E,
-                       int k, int eps_div, int max_rounds, int slack, long long stop_eps)
+// Start of a solve: empty assignment, zero thresholds and counters, the control block.  Runs as the first part of
+// k_init_minmax (any grid of 256-thread workgroups with at least 2 * kMaxE threads in all).
+__device__ __forceinline__ void init_solve(SolverState *st, long long *theta, int *gcount, int *qmm, int32_t *assign,
+                                           int T, int E, int k, int eps_div, int max_rounds, int slack,
+                                           long long stop_eps)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t n = (size_t)T * k;
-    for (size_t a = i; a < n; a += (size_t)gridDim.x * blockDim.x) assign[a] = -1;
+    if ((((uintptr_t)assign) & 15) == 0) {
+        int4 *a4 = (int4 *)assign;
+        const size_t n4 = n / 4;
+        for (size_t a = i; a < n4; a += (size_t)gridDim.x * blockDim.x) a4[a] = make_int4(-1, -1, -1, -1);
+        for (size_t a = n4 * 4 + i; a < n; a += (size_t)gridDim.x * blockDim.x) assign[a] = -1;
+    } else {
+        for (size_t a = i; a < n; a += (size_t)gridDim.x * blockDim.x) assign[a] = -1;
+    }
     if (i < (size_t)2 * kMaxE) {
         theta[i] = 0;
         gcount[i] = 0;
@@ -175,8 +185,12 @@ __global__ void k_init(SolverState *st, long long *theta, int *gcount, int *qmm,
 // a thousand workgroups updating one word cost more than reading the matrix), k_setup reduces them.
 constexpr int kMinmaxBlocks = 512;
 
-__global__ __launch_bounds__(256) void k_minmax(const int32_t *__restrict__ q, size_t n, int *__restrict__ part)
+__global__ __launch_bounds__(256) void k_init_minmax(const int32_t *__restrict__ q, size_t n, int *__restrict__ part,
+                                                     SolverState *st, long long *theta, int *gcount, int *qmm,
+                                                     int32_t *assign, int T, int E, int k, int eps_div,
+                                                     int max_rounds, int slack, long long stop_eps)
 {
+    init_solve(st, theta, gcount, qmm, assign, T, E, k, eps_div, max_rounds, slack, stop_eps);
     __shared__ int s_lo[4], s_hi[4];
     int lo = 0x7fffffff, hi = -0x7fffffff - 1;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -1892,18 +1906,15 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
     const int slack = ((cap ? room : (long long)E * Ce) - want) > 0 ? 1 : 0;
     MS_HIP(hipEventRecord(hs->ev0, s));
     {
-        size_t n = (size_t)T * k;
-        int grid = (int)((n + 255) / 256);
-        if (grid < 4) grid = 4;
-        if (grid > 4096) grid = 4096;
-        hipLaunchKernelGGL(k_init, dim3(grid), dim3(256), 0, s, st, theta, gcount, qmm, assign, T, E, k,
-                           o.eps_div, o.max_rounds, slack, stop_eps);
+        // one launch: the start state of the solve and the reward range, per-workgroup partial results of which
+        // k_setup reduces (at least 2 * kMaxE threads: the init part clears that many thresholds and counters)
         size_t nq = (size_t)T * E;
         int g2 = (int)((nq + 256 * 16 - 1) / (256 * 16));
         if (g2 > kMinmaxBlocks) g2 = kMinmaxBlocks;
-        if (g2 < 1) g2 = 1;
+        if (g2 < 2 * kMaxE / 256) g2 = 2 * kMaxE / 256;
         int *part = (int *)cand;                 // the candidate lists are not in use yet
-        hipLaunchKernelGGL(k_minmax, dim3(g2), dim3(256), 0, s, q, nq, part);
+        hipLaunchKernelGGL(k_init_minmax, dim3(g2), dim3(256), 0, s, q, nq, part, st, theta, gcount, qmm, assign, T, E,
+                           k, o.eps_div, o.max_rounds, slack, stop_eps);
         hipLaunchKernelGGL(k_setup, dim3(1), dim3(kMinmaxBlocks), 0, s, st, part, g2, T, E, k == E ? 1 : 0,
                            eps0_shift, theta, o.prices_in, (long long)o.eps_start, fin_limit_q);
     }
