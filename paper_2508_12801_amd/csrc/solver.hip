@@ -2021,7 +2021,9 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             else MS_BIDF(64);
 #undef MS_BIDF
         }
-        hipLaunchKernelGGL(k_trim, dim3(n_wg), dim3(256), 0, s, st + par, theta, klist, wcnt, assign, E, k, rows);
+        // (the trim only has work when the solve ended at the round cap, which takes that many rounds)
+        if (launched >= o.max_rounds)
+            hipLaunchKernelGGL(k_trim, dim3(n_wg), dim3(256), 0, s, st + par, theta, klist, wcnt, assign, E, k, rows);
         hipLaunchKernelGGL(k_finalize, dim3(kFinalBlocks), dim3(256), 0, s, q, assign, cand, T, E, k);   // lists are free again
         hipLaunchKernelGGL(k_finalize2, dim3(1), dim3(kFinalBlocks), 0, s, cand, theta, st + par, prices, price_scale, E,
                            hs->state_dev);
