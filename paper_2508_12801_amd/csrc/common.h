@@ -16,8 +16,8 @@ constexpr int kDispTile = MS_DISP_TILE;   // slots of the pair list owned by one
 constexpr int kMaxK = 64;
 constexpr int kMaxTBits = 21;
 constexpr int64_t kBidBig = (int64_t)1 << 40;   // bid of a token that has no alternative left
-constexpr int kCand = 32;          // lowest keys per expert handed to the tail pass
-constexpr int kTailMaxE = 256;     // the tail pass keeps all candidate lists in LDS
+constexpr int kCand = 32;          // lowest keys per expert handed to the tail pass (half as many beyond 256 experts)
+constexpr int kTailMaxE = 512;     // the tail pass keeps all candidate lists in LDS
 
 // Device-resident control block of one assignment solve.
 struct SolverState {

@@ -718,7 +718,6 @@ constexpr int kTailSpinMax = 1 << 20;     // polls of the tail workgroup for the
 constexpr int kTailVict = 64;             // dropped tokens per iteration (the list is read back one entry per lane)
 static_assert(kTailVict == 64, "the victim list is read with one entry per lane");
 constexpr int kTailIns = 256;
-constexpr int kTailEPL = kTailMaxE / 64;
 
 // maximum over the 64 lanes with DPP row operations (the result is wavefront-uniform)
 __device__ __forceinline__ unsigned wave_max_u32(unsigned v)
@@ -754,32 +753,44 @@ __device__ __forceinline__ int *opaque_counter(int *p)
     return (int *)(lds_int *)(unsigned long)off;
 }
 
+// Sizes of the tail pass by expert slots per lane.  Up to 256 experts every candidate list holds kCand keys; up to
+// 512 experts half as many (all lists, the per-wavefront row copies and the select pass's own key cache share one
+// compute unit's LDS), and the select pass caches fewer keys.
+template <int TEPL> struct TailCfg {
+    static constexpr int MaxE = 256, KC = kCand, SelCache = 6144;
+};
+template <> struct TailCfg<8> {
+    static constexpr int MaxE = 512, KC = kCand / 2, SelCache = 3072;
+};
+
 // Runs in the extra workgroup of the select pass (all kTailThreads threads), after the other
 // workgroups have published their candidate lists.
 // LDS of the tail pass, in a function of its own so that the instantiations of tail_pass share one copy.
-struct TailShared {
+template <int MAXE, int KC>
+struct TailSharedT {
     // candidate lists are kept in DESCENDING order: the lowest keys sit at the end and leave by
     // shortening the list
-    long long cand[kTailMaxE * kCand];
-    long long theta[kTailMaxE];
-    long long bound[kTailMaxE];
+    long long cand[MAXE * KC];
+    long long theta[MAXE];
+    long long bound[MAXE];
     long long ikey[kTailIns];
-    int n[kTailMaxE];
-    int capv[kTailMaxE];     // capacity of every expert (uniform Ce unless a vector was given)
-    int cn[kTailMaxE];
+    int n[MAXE];
+    int capv[MAXE];     // capacity of every expert (uniform Ce unless a vector was given)
+    int cn[MAXE];
     int vtok[kTailVict], vexp[kTailVict];
     int iexp[kTailIns];
-    int qrow[kTailThreads / 64][kTailMaxE];
-    unsigned char hmark[kTailThreads / 64][kTailMaxE];   // per wavefront: 1 on the experts the token under evaluation holds
+    int qrow[kTailThreads / 64][MAXE];
+    unsigned char hmark[kTailThreads / 64][MAXE];   // per wavefront: 1 on the experts the token under evaluation holds
     int nv2[2], ni2[2], over2[2];     // per-iteration counters, double-buffered by iteration parity
     // stop requests: stop1 is written in step 1 and read after the barrier that ends it, stop2 likewise for
     // step 2, so a flag is never written between a barrier and the reads that follow that barrier
     int stop1, stop2, moves, changed;
 };
 
-__device__ __forceinline__ TailShared *tail_shared()
+template <int MAXE, int KC>
+__device__ __forceinline__ TailSharedT<MAXE, KC> *tail_shared()
 {
-    __shared__ TailShared s;
+    __shared__ TailSharedT<MAXE, KC> s;
     return &s;
 }
 
@@ -794,7 +805,8 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
     SolverState *st = st2 + (par ^ 1);          // the state the next bid pass will read
     long long *theta = theta2 + (par ^ 1) * kMaxE;
     int *gcur = gcount2 + par * kMaxE;
-    TailShared &sh = *tail_shared();
+    constexpr int KC = TailCfg<TEPL>::KC;       // keys per candidate list
+    TailSharedT<TailCfg<TEPL>::MaxE, KC> &sh = *tail_shared<TailCfg<TEPL>::MaxE, KC>();
     auto &s_cand = sh.cand;
     auto &s_theta = sh.theta;
     auto &s_bound = sh.bound;
@@ -822,7 +834,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         const long long val = cand[i];
         const int cn = (int)cand[(size_t)e * (kCand + 2) + kCand];
         if (c < kCand) {
-            if (c < cn) s_cand[e * kCand + (cn - 1 - c)] = val;     // ascending in memory -> descending here
+            if (c < cn && cn <= KC) s_cand[e * KC + (cn - 1 - c)] = val;     // ascending in memory -> descending here
         } else if (c == kCand) {
             s_cn[e] = (int)val;
         } else {
@@ -834,8 +846,8 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         s_n[e] = gcur[e];
         s_capv[e] = cap ? cap[e] : Ce;
     }
-    static_assert(sizeof(sh.hmark) == 4 * kTailThreads, "one word of marks per thread");
-    ((int *)&s_hmark[0][0])[tid] = 0;
+    static_assert(sizeof(sh.hmark) % (4 * kTailThreads) == 0, "whole words of marks per thread");
+    for (int i = tid; i < (int)(sizeof(sh.hmark) / 4); i += kTailThreads) ((int *)&s_hmark[0][0])[i] = 0;
     if (tid == 0) {
         s_stop1 = 0; s_stop2 = 0; s_moves = 0; s_changed = 0;
         s_nv2[0] = s_nv2[1] = 0; s_ni2[0] = s_ni2[1] = 0; s_over2[0] = s_over2[1] = 0;
@@ -852,7 +864,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
         const int pi = it & 1;
         int &s_nv = s_nv2[pi], &s_ni = s_ni2[pi], &s_over = s_over2[pi];
         // 0. the keys requested in the previous iteration enter the lists in request order; wavefront w serves
-        //    the experts e with e mod 16 = w (its first kCand lanes hold one list entry each) and, right after,
+        //    the experts e with e mod 16 = w (its first KC lanes hold one list entry each) and, right after,
         //    runs step 1 for the same experts, so no workgroup barrier is needed between the two
         if (it > 0) {
             const int ni_prev = s_ni2[pi ^ 1];
@@ -861,11 +873,11 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 const int e = __builtin_amdgcn_readfirstlane(s_iexp[r]);
                 if ((e & (kTailThreads / 64 - 1)) != wv) continue;
                 const long long key = s_ikey[r];
-                long long *ce = s_cand + e * kCand;
+                long long *ce = s_cand + e * KC;
                 int cn = s_cn[e];
-                long long val = (lane < cn && lane < kCand) ? ce[lane] : -1;
+                long long val = (lane < cn && lane < KC) ? ce[lane] : -1;
                 bool skip = false;
-                if (cn == kCand) {
+                if (cn == KC) {
                     const long long top = ce[0];                 // largest listed key
                     if (key > top) {
                         if (lane == 0 && key < s_bound[e]) s_bound[e] = key;   // stays off the list
@@ -907,7 +919,7 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 if (cn < m) {
                     s_stop1 = 1;                       // list exhausted: the select pass has to rebuild it
                 } else {
-                    const long long *ce = s_cand + e * kCand;
+                    const long long *ce = s_cand + e * KC;
                     const long long low0 = ce[cn - 1];                       // the first key to go
                     const long long next_key = cn > m ? ce[cn - 1 - m] : bound_e;
                     const long long last_out = ce[cn - m];                   // the highest key that goes
@@ -1183,7 +1195,6 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
 // Select pass: one workgroup per expert; exact (n-Ce+1)-th smallest key by radix select (Ce = the expert's
 // capacity: cap[e] when a capacity vector is given, else the same Ce for all).
 constexpr int kSelThreads = 1024;
-constexpr int kSelCache = 6144;
 constexpr int kSelDirect = 256;           // at most this many keys are ranked against each other directly
 
 
@@ -1230,6 +1241,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
     long long *theta_out = theta2 + (par ^ 1) * kMaxE;
     const int *gprev = gcount2 + (par ^ 1) * kMaxE;   // loads after the previous round
     int *gcur = gcount2 + par * kMaxE;
+    constexpr int kSelCache = TailCfg<TEPL>::SelCache;       // keys of an expert that are copied to LDS
+    constexpr int KC = TailCfg<TEPL>::KC;                    // keys per candidate list of the tail pass
     __shared__ long long s_keys[kSelCache];
     __shared__ __attribute__((aligned(16))) int s_hist[2][256];
     __shared__ unsigned long long s_small[kSelDirect];
@@ -1563,14 +1576,14 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const long long *__restr
             const int rank = Cj > 0 ? n - Cj : n - 1;
             new_theta = nth_by_narrowing(rank) + (Cj > 0 ? 0 : 1);
         } else {
-            // candidate list for the tail pass: the kCand smallest keys in ascending order, their
+            // candidate list for the tail pass: the KC smallest keys in ascending order, their
             // count, and a bound no other key of this expert lies under
-            const long long bound = n > kCand ? nth_by_narrowing(kCand) : kKeyInf;
+            const long long bound = n > KC ? nth_by_narrowing(KC) : kKeyInf;
             for_keys([&](long long kv) {
                 if (kv < bound) s_cl[atomicAdd(&s_ncl, 1)] = kv;
             });
             __syncthreads();
-            const int nc = s_ncl;            // = min(n, kCand): keys are distinct
+            const int nc = s_ncl;            // = min(n, KC): keys are distinct
             long long *cj_out = cand + (size_t)j * (kCand + 2);
             if (tid < nc) {
                 const long long mine = s_cl[tid];
@@ -1977,7 +1990,8 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
                        tail_moves, early_moves, tail_iters, kvec)
             if (E <= 64) MS_SEL(1);
             else if (E <= 128) MS_SEL(2);
-            else MS_SEL(kTailEPL);
+            else if (E <= 256) MS_SEL(4);
+            else MS_SEL(8);
 #undef MS_SEL
             if (g_kernel_timing) {
                 MS_HIP(hipEventRecord(tev[tev_used + 2], s));
