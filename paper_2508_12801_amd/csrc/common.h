@@ -106,8 +106,9 @@ int32_t kvec_check(const int32_t *kvec, int T, int E, int k, char *ws, long long
 // exits at once unless st->fin is 1, and a last kernel that reports to host_words[0..3]: {1 certified | 2 the auction
 // goes on | 3 not finished, passes left; cycles cancelled so far; st->fin; round}.  retry: when the auction has to
 // go on it stops again one rung further down (the finisher can be enqueued anew, from pass 0) instead of running to
-// eps = 1.  Supports E <= kFinMaxE.
-constexpr int kFinMaxE = 256;
+// eps = 1.  Supports E <= kFinMaxE (beyond 256 experts without the arc matrix: a first pass whose arc list is not
+// complete hands back to the auction).
+constexpr int kFinMaxE = 512;
 constexpr int kFinMovedCap = 4096;        // tokens the finisher may move in one solve (more: the auction goes on)
 int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long long *theta2, const int *loads2,
                        const int *cap, int Ce, int T, int E, int k, char *ws, int rows, int n_wg, int first_pass,

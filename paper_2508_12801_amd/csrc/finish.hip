@@ -171,7 +171,7 @@ __device__ __forceinline__ int token_arcs(const int32_t *__restrict__ q, const i
 // key block, then by expert), with their number in tri_cnt[w] (-1: the segment is too small).  With the complete
 // list the Bellman-Ford workgroup can keep the arcs up to date itself while it moves tokens, so one pass is enough.
 // Grid: one workgroup per key block (n_wg), 256 threads.
-template <int TEPL>
+template <int TEPL, bool MIN>
 __global__ __launch_bounds__(256) void k_fin_arcs(const int32_t *__restrict__ q, const int32_t *assign,
                                                   const long long *__restrict__ theta2,
                                                   const SolverState *__restrict__ st,
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(256) void k_fin_arcs(const int32_t *__restrict__ q,
     for (int i = wv; i < n; i += 4) {
         const int idx = s_list[i];
         const int u = (int)(blk[idx] & tmask);
-        const int c = token_arcs<TEPL, true>(q, assign, p, sb, u, s_e[idx], B, M, E, k, lane, nullptr, nullptr, 0, 0);
+        const int c = token_arcs<TEPL, MIN>(q, assign, p, sb, u, s_e[idx], B, M, E, k, lane, nullptr, nullptr, 0, 0);
         if (lane == 0) s_cnt[i] = c;
     }
     if (want_list) {
@@ -273,13 +273,23 @@ __global__ __launch_bounds__(256) void k_fin_arcs(const int32_t *__restrict__ q,
             }
         }
     }
-    // the moved tokens, spread over all wavefronts of the grid
-    const int nm = fa.n_moved[0] < kFinMovedCap ? fa.n_moved[0] : kFinMovedCap;
-    for (int i = w * 4 + wv; i < nm; i += gridDim.x * 4)
-        (void)token_arcs<TEPL, true>(q, assign, p, sb, fa.list[i], -1, B, M, E, k, lane, nullptr, nullptr, 0, 0);
+    // the moved tokens, spread over all wavefronts of the grid (their arcs only matter to the matrix)
+    if (MIN) {
+        const int nm = fa.n_moved[0] < kFinMovedCap ? fa.n_moved[0] : kFinMovedCap;
+        for (int i = w * 4 + wv; i < nm; i += gridDim.x * 4)
+            (void)token_arcs<TEPL, true>(q, assign, p, sb, fa.list[i], -1, B, M, E, k, lane, nullptr, nullptr, 0, 0);
+    }
 }
 
-constexpr int kFinArcs = 11264;               // arcs the Bellman-Ford workgroup can hold (more: the auction goes on)
+constexpr int kFinMatrixMaxE = 256;           // the arc matrix (one token per expert pair) serves up to this many experts
+// Sizes of the Bellman-Ford workgroup by expert slots per lane: nodes it has tables for and arcs its list can hold
+// (more arcs: the auction goes on).  Beyond kFinMatrixMaxE experts only the complete arc list is used.
+template <int TEPL> struct FinCfg {
+    static constexpr int MaxE = 256, Arcs = 11264;
+};
+template <> struct FinCfg<8> {
+    static constexpr int MaxE = 512, Arcs = 9984;
+};
 constexpr int kFinChunkGroup = 16;            // chunks of the arc matrix whose loads are in flight together
 constexpr long long kKeyBias = (long long)1 << 48;   // potentials stay far inside (-2^48, 2^48)
 constexpr int kIdxBits = 14;
@@ -287,7 +297,8 @@ constexpr unsigned kIdxRoot = (1u << kIdxBits) - 1;  // "no predecessor arc"
 constexpr long long kZCostMax = (long long)1 << 30;  // prices must stay under this for the spare-capacity arcs
 
 
-struct FinShared {
+template <int kFinMaxE, int kFinArcs>
+struct FinSharedT {
     // arc i: reduced cost (signed, kCostInf = slot empty or arc withdrawn) in the high word, from << 16 | to in the
     // low one (16 bits each; nodes 0..E-1 experts, E = Z)
     unsigned long long arc[kFinArcs];
@@ -302,7 +313,7 @@ struct FinShared {
     int pred[kFinMaxE + 2];                   // predecessor of every node at the last check
     int cycflag[kFinMaxE + 2], cyclist[kFinMaxE + 2];     // smallest node of every cycle found by the check
     int moved[kFinMaxE + 2];
-    int scan[kFinMaxE * kFinMaxE / kFinThreads][kFinThreads / 64];           // arcs per (chunk of the matrix, wavefront) while the list is built
+    int scan[kFinMatrixMaxE * kFinMatrixMaxE / kFinThreads][kFinThreads / 64];     // arcs per (chunk of the matrix, wavefront) while the list is built
     int moved_all[kFinMovedCap / 8];          // tokens moved in this pass, for the list in memory
     int changed[3];       // one flag per sweep, three in rotation (a flag is cleared two sweeps after its last read)
     int newcnt[kFinMaxE + 2];                 // arcs that every token moved by the current cycle offers anew
@@ -311,10 +322,13 @@ struct FinShared {
     int complete;         // the arc list holds EVERY arc under the bound (kept so while tokens move): one pass can certify
     long long cyc_sum;
 };
-static_assert(sizeof(FinShared) <= 160 * 1024, "the Bellman-Ford workgroup keeps everything in one compute unit's LDS");
-static_assert(kFinMaxE * kFinMaxE / kFinThreads * (kFinThreads / 64) <= kFinThreads, "one count per thread in the prefix");
+static_assert(sizeof(FinSharedT<FinCfg<4>::MaxE, FinCfg<4>::Arcs>) <= 160 * 1024 &&
+                  sizeof(FinSharedT<FinCfg<8>::MaxE, FinCfg<8>::Arcs>) <= 160 * 1024,
+              "the Bellman-Ford workgroup keeps everything in one compute unit's LDS");
+static_assert(kFinMatrixMaxE * kFinMatrixMaxE / kFinThreads * (kFinThreads / 64) <= kFinThreads, "one count per thread in the prefix");
+static_assert(FinCfg<8>::MaxE == kFinMaxE, "tables for every expert count the finisher accepts");
 
-// Bellman-Ford with cancelling.  One workgroup of kFinThreads threads, E <= 64 * TEPL <= kFinMaxE.
+// Bellman-Ford with cancelling.  One workgroup of kFinThreads threads, E <= 64 * TEPL <= FinCfg<TEPL>::MaxE.
 //
 // The arcs under the bound are few (a few thousand of the E*E pairs), so they are kept as a list.  Node potentials
 // (0 at the start) are lowered sweep by sweep, every thread relaxing its arcs, until no arc a -> b has
@@ -334,7 +348,8 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
                                                             const int *__restrict__ tri_cnt, int seg_cap, int n_wg)
 {
     if (st->fin != 1) return;
-    __shared__ FinShared sh;
+    constexpr int kNodes = FinCfg<TEPL>::MaxE, kFinArcs = FinCfg<TEPL>::Arcs;
+    __shared__ FinSharedT<kNodes, kFinArcs> sh;
     const FinArea fa = fin_area(fin_base, T);
     int *fin_loads = fa.loads;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -357,7 +372,7 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
         sh.load[e] = first_pass ? loads[e] : fin_loads[e];      // later passes carry their own count
         sh.capv[e] = cap ? cap[e] : Ce;
     }
-    for (int v = tid; v < kFinMaxE + 2; v += kFinThreads) {
+    for (int v = tid; v < kNodes + 2; v += kFinThreads) {
         // potentials: 0 in the first pass, then what the previous pass ended with (any start is valid: potentials
         // only have to stop relaxing; a good start saves sweeps)
         const long long d0 = (first_pass || v > E) ? 0 : fa.pot[v];
@@ -422,7 +437,13 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
         }
         __syncthreads();
     }
-    if (!sh.complete) {
+    if (!sh.complete && E > kFinMatrixMaxE) {
+        // no arc matrix for this many experts: the auction goes on
+        if (tid == 0) {
+            sh.n_arcs = 2 * E;
+            sh.give_up = 1;
+        }
+    } else if (!sh.complete) {
         // The matrix is read in chunks of kFinThreads consecutive entries, kFinChunkGroup chunks' loads in flight at
         // a time; an arc's place in the list follows from the number of arcs before it in matrix order.  Two
         // readings: the first counts, the second places.
@@ -561,7 +582,7 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
                 }
                 if (hi - lo >= B) {            // the same for every thread
                     __syncthreads();
-                    for (int v = tid; v < kFinMaxE + 2; v += kFinThreads) {
+                    for (int v = tid; v < kNodes + 2; v += kFinThreads) {
                         const unsigned long long k0 = ((unsigned long long)kKeyBias << kIdxBits) | kIdxRoot;
                         sh.key[0][v] = k0;
                         sh.key[1][v] = k0;
@@ -909,20 +930,26 @@ int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long 
         hipLaunchKernelGGL(k_fin_begin, dim3(1), dim3(kFinThreads), 0, s, st, M, fin_base, T, E, bound_mult);
     for (int pass = first_pass; pass < first_pass + passes; ++pass) {
         if (E <= 64)
-            hipLaunchKernelGGL(k_fin_arcs<1>, dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
+            hipLaunchKernelGGL((k_fin_arcs<1, true>), dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
                                fin_base, T, E, k, rows, tri_arc, tri_tok, tri_cnt, seg_cap);
         else if (E <= 128)
-            hipLaunchKernelGGL(k_fin_arcs<2>, dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
+            hipLaunchKernelGGL((k_fin_arcs<2, true>), dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
+                               fin_base, T, E, k, rows, tri_arc, tri_tok, tri_cnt, seg_cap);
+        else if (E <= 256)
+            hipLaunchKernelGGL((k_fin_arcs<4, true>), dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
                                fin_base, T, E, k, rows, tri_arc, tri_tok, tri_cnt, seg_cap);
         else
-            hipLaunchKernelGGL(k_fin_arcs<4>, dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
+            hipLaunchKernelGGL((k_fin_arcs<8, false>), dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
                                fin_base, T, E, k, rows, tri_arc, tri_tok, tri_cnt, seg_cap);
         const int last = pass == total_passes - 1 ? 1 : 0;
         if (E <= 128)
             hipLaunchKernelGGL(k_fin_cycles<2>, dim3(1), dim3(kFinThreads), 0, s, st, M, assign, theta2, loads2, fin_base,
                                cap, Ce, T, E, k, last, q, tri_arc, tri_tok, tri_cnt, seg_cap, n_wg);
-        else
+        else if (E <= 256)
             hipLaunchKernelGGL(k_fin_cycles<4>, dim3(1), dim3(kFinThreads), 0, s, st, M, assign, theta2, loads2, fin_base,
+                               cap, Ce, T, E, k, last, q, tri_arc, tri_tok, tri_cnt, seg_cap, n_wg);
+        else
+            hipLaunchKernelGGL(k_fin_cycles<8>, dim3(1), dim3(kFinThreads), 0, s, st, M, assign, theta2, loads2, fin_base,
                                cap, Ce, T, E, k, last, q, tri_arc, tri_tok, tri_cnt, seg_cap, n_wg);
     }
     hipLaunchKernelGGL(k_fin_end, dim3(1), dim3(64), 0, s, st, T, host_words,
