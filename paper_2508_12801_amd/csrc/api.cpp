@@ -28,7 +28,7 @@ WorkspaceLayout workspace_layout(int T, int E, int k, int d)
     // finisher scratch: a bit per token, the moved-token list, loads and potentials (same layout as fin_area())
     L.fin_off = off; off = align_up(off + sizeof(unsigned) * (((size_t)T + 31) / 32 + 1) + 16 + sizeof(int) * (4 + kFinMovedCap + kFinMaxE) + 16 + sizeof(long long) * (kFinMaxE + 2), 256);
     // finisher arc matrix: smallest loss (and its token) per expert pair
-    L.finm_off = off; off = align_up(off + sizeof(unsigned long long) * (size_t)kFinMaxE * kFinMaxE, 256);
+    L.finm_off = off; off = align_up(off + sizeof(unsigned long long) * (size_t)kFinMatrixMaxE * kFinMatrixMaxE, 256);
     // finisher arc lists: one segment per key block (fin_seg_cap(rows, k) arcs of 12 bytes each) and a count per block
     L.tri_off = off; off = align_up(off + 12 * fin_tri_entries(T, k, L.max_wg) + sizeof(int) * ((size_t)L.max_wg + 1), 256);
     L.wt_off = off; off = align_up(off + sizeof(unsigned short) * (size_t)E * (d > 0 ? d : 0), 256);

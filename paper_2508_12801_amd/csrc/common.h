@@ -16,8 +16,8 @@ constexpr int kDispTile = MS_DISP_TILE;   // slots of the pair list owned by one
 constexpr int kMaxK = 64;
 constexpr int kMaxTBits = 21;
 constexpr int64_t kBidBig = (int64_t)1 << 40;   // bid of a token that has no alternative left
-constexpr int kCand = 32;          // lowest keys per expert handed to the tail pass (half as many beyond 256 experts)
-constexpr int kTailMaxE = 512;     // the tail pass keeps all candidate lists in LDS
+constexpr int kCand = 32;          // lowest keys per expert handed to the tail pass (16 beyond 256 experts, 8 beyond 512)
+constexpr int kTailMaxE = 1024;    // the tail pass keeps all candidate lists in LDS (= kMaxE: it always runs)
 
 // Device-resident control block of one assignment solve.
 struct SolverState {
@@ -108,7 +108,8 @@ int32_t kvec_check(const int32_t *kvec, int T, int E, int k, char *ws, long long
 // go on it stops again one rung further down (the finisher can be enqueued anew, from pass 0) instead of running to
 // eps = 1.  Supports E <= kFinMaxE (beyond 256 experts without the arc matrix: a first pass whose arc list is not
 // complete hands back to the auction).
-constexpr int kFinMaxE = 512;
+constexpr int kFinMaxE = 1024;
+constexpr int kFinMatrixMaxE = 256;       // its arc matrix (one token per expert pair) serves up to this many experts
 constexpr int kFinMovedCap = 4096;        // tokens the finisher may move in one solve (more: the auction goes on)
 int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long long *theta2, const int *loads2,
                        const int *cap, int Ce, int T, int E, int k, char *ws, int rows, int n_wg, int first_pass,

@@ -80,7 +80,8 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_begin(SolverState *st, unsi
 {
     if (st->fin != 1) return;
     FinArea fa = fin_area(fin_base, T);
-    for (int i = threadIdx.x; i < E * E; i += kFinThreads) M[i] = kArcNone;
+    if (E <= kFinMatrixMaxE)
+        for (int i = threadIdx.x; i < E * E; i += kFinThreads) M[i] = kArcNone;
     for (int i = threadIdx.x; i < (T + 31) / 32 + 1; i += kFinThreads) fa.bits[i] = 0u;
     if (threadIdx.x == 0) {
         long long b = bound_mult * st->eps;
@@ -281,7 +282,6 @@ __global__ __launch_bounds__(256) void k_fin_arcs(const int32_t *__restrict__ q,
     }
 }
 
-constexpr int kFinMatrixMaxE = 256;           // the arc matrix (one token per expert pair) serves up to this many experts
 // Sizes of the Bellman-Ford workgroup by expert slots per lane: nodes it has tables for and arcs its list can hold
 // (more arcs: the auction goes on).  Beyond kFinMatrixMaxE experts only the complete arc list is used.
 template <int TEPL> struct FinCfg {
@@ -289,6 +289,9 @@ template <int TEPL> struct FinCfg {
 };
 template <> struct FinCfg<8> {
     static constexpr int MaxE = 512, Arcs = 9984;
+};
+template <> struct FinCfg<16> {
+    static constexpr int MaxE = 1024, Arcs = 7168;
 };
 constexpr int kFinChunkGroup = 16;            // chunks of the arc matrix whose loads are in flight together
 constexpr long long kKeyBias = (long long)1 << 48;   // potentials stay far inside (-2^48, 2^48)
@@ -323,10 +326,11 @@ struct FinSharedT {
     long long cyc_sum;
 };
 static_assert(sizeof(FinSharedT<FinCfg<4>::MaxE, FinCfg<4>::Arcs>) <= 160 * 1024 &&
-                  sizeof(FinSharedT<FinCfg<8>::MaxE, FinCfg<8>::Arcs>) <= 160 * 1024,
+                  sizeof(FinSharedT<FinCfg<8>::MaxE, FinCfg<8>::Arcs>) <= 160 * 1024 &&
+                  sizeof(FinSharedT<FinCfg<16>::MaxE, FinCfg<16>::Arcs>) <= 160 * 1024,
               "the Bellman-Ford workgroup keeps everything in one compute unit's LDS");
 static_assert(kFinMatrixMaxE * kFinMatrixMaxE / kFinThreads * (kFinThreads / 64) <= kFinThreads, "one count per thread in the prefix");
-static_assert(FinCfg<8>::MaxE == kFinMaxE, "tables for every expert count the finisher accepts");
+static_assert(FinCfg<16>::MaxE == kFinMaxE, "tables for every expert count the finisher accepts");
 
 // Bellman-Ford with cancelling.  One workgroup of kFinThreads threads, E <= 64 * TEPL <= FinCfg<TEPL>::MaxE.
 //
@@ -843,7 +847,7 @@ __global__ __launch_bounds__(kFinThreads) void k_fin_cycles(SolverState *st, uns
         if (tid == 0) st->fin = ok ? 2 : 3;
     }
     // the next pass starts from an empty matrix; the loads go with it
-    if (!sh.give_up && sh.dirty > 0) {
+    if (!sh.give_up && sh.dirty > 0 && E <= kFinMatrixMaxE) {
         for (int i = tid; i < E * E; i += kFinThreads) M[i] = kArcNone;
     }
     for (int e = tid; e < E; e += kFinThreads) fin_loads[e] = sh.load[e];
@@ -913,7 +917,7 @@ int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long 
         rows * k > 1024 || n_wg < 1)
         return MAXSCORE_ERR_SHAPE;
     WorkspaceLayout L = workspace_layout(T, E, k);
-    unsigned long long *M = (unsigned long long *)(ws + L.finm_off);      // E*E entries of the kFinMaxE^2 there
+    unsigned long long *M = (unsigned long long *)(ws + L.finm_off);      // E*E entries of the kFinMatrixMaxE^2 there (not used beyond that)
     char *fin_base = ws + L.fin_off;
     if (finish_area_bytes(T) > L.wt_off - L.fin_off) return MAXSCORE_ERR_WORKSPACE;      // layout and area must agree
     const long long *klist = (const long long *)(ws + L.klist_off);
@@ -938,8 +942,11 @@ int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long 
         else if (E <= 256)
             hipLaunchKernelGGL((k_fin_arcs<4, true>), dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
                                fin_base, T, E, k, rows, tri_arc, tri_tok, tri_cnt, seg_cap);
-        else
+        else if (E <= 512)
             hipLaunchKernelGGL((k_fin_arcs<8, false>), dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
+                               fin_base, T, E, k, rows, tri_arc, tri_tok, tri_cnt, seg_cap);
+        else
+            hipLaunchKernelGGL((k_fin_arcs<16, false>), dim3(n_wg), dim3(256), 0, s, q, assign, theta2, st, klist, wcnt, M,
                                fin_base, T, E, k, rows, tri_arc, tri_tok, tri_cnt, seg_cap);
         const int last = pass == total_passes - 1 ? 1 : 0;
         if (E <= 128)
@@ -948,8 +955,11 @@ int32_t finish_enqueue(const int32_t *q, int32_t *assign, SolverState *st, long 
         else if (E <= 256)
             hipLaunchKernelGGL(k_fin_cycles<4>, dim3(1), dim3(kFinThreads), 0, s, st, M, assign, theta2, loads2, fin_base,
                                cap, Ce, T, E, k, last, q, tri_arc, tri_tok, tri_cnt, seg_cap, n_wg);
-        else
+        else if (E <= 512)
             hipLaunchKernelGGL(k_fin_cycles<8>, dim3(1), dim3(kFinThreads), 0, s, st, M, assign, theta2, loads2, fin_base,
+                               cap, Ce, T, E, k, last, q, tri_arc, tri_tok, tri_cnt, seg_cap, n_wg);
+        else
+            hipLaunchKernelGGL(k_fin_cycles<16>, dim3(1), dim3(kFinThreads), 0, s, st, M, assign, theta2, loads2, fin_base,
                                cap, Ce, T, E, k, last, q, tri_arc, tri_tok, tri_cnt, seg_cap, n_wg);
     }
     hipLaunchKernelGGL(k_fin_end, dim3(1), dim3(64), 0, s, st, T, host_words,

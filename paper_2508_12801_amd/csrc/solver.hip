@@ -754,19 +754,23 @@ __device__ __forceinline__ int *opaque_counter(int *p)
 }
 
 // Sizes of the tail pass by expert slots per lane.  Up to 256 experts every candidate list holds kCand keys; up to
-// 512 experts half as many (all lists, the per-wavefront row copies and the select pass's own key cache share one
-// compute unit's LDS), and the select pass caches fewer keys.
+// 512 experts half as many and up to 1024 a quarter (all lists, the per-wavefront row copies and the select pass's
+// own key cache share one compute unit's LDS), and the select pass caches fewer keys.  With 1024 experts there is no
+// room for the row copies: the rare evaluation that needs one reads the row from memory again.
 template <int TEPL> struct TailCfg {
-    static constexpr int MaxE = 256, KC = kCand, SelCache = 6144;
+    static constexpr int MaxE = 256, KC = kCand, SelCache = 6144, RowCopy = 256;
 };
 template <> struct TailCfg<8> {
-    static constexpr int MaxE = 512, KC = kCand / 2, SelCache = 3072;
+    static constexpr int MaxE = 512, KC = kCand / 2, SelCache = 3072, RowCopy = 512;
+};
+template <> struct TailCfg<16> {
+    static constexpr int MaxE = 1024, KC = kCand / 4, SelCache = 3072, RowCopy = 1;
 };
 
 // Runs in the extra workgroup of the select pass (all kTailThreads threads), after the other
 // workgroups have published their candidate lists.
 // LDS of the tail pass, in a function of its own so that the instantiations of tail_pass share one copy.
-template <int MAXE, int KC>
+template <int MAXE, int KC, int ROWCOPY>
 struct TailSharedT {
     // candidate lists are kept in DESCENDING order: the lowest keys sit at the end and leave by
     // shortening the list
@@ -779,7 +783,7 @@ struct TailSharedT {
     int cn[MAXE];
     int vtok[kTailVict], vexp[kTailVict];
     int iexp[kTailIns];
-    int qrow[kTailThreads / 64][MAXE];
+    int qrow[kTailThreads / 64][ROWCOPY];       // per wavefront: the row under evaluation (ROWCOPY = MAXE, or 1: not kept)
     unsigned char hmark[kTailThreads / 64][MAXE];   // per wavefront: 1 on the experts the token under evaluation holds
     int nv2[2], ni2[2], over2[2];     // per-iteration counters, double-buffered by iteration parity
     // stop requests: stop1 is written in step 1 and read after the barrier that ends it, stop2 likewise for
@@ -787,10 +791,10 @@ struct TailSharedT {
     int stop1, stop2, moves, changed;
 };
 
-template <int MAXE, int KC>
-__device__ __forceinline__ TailSharedT<MAXE, KC> *tail_shared()
+template <int MAXE, int KC, int ROWCOPY>
+__device__ __forceinline__ TailSharedT<MAXE, KC, ROWCOPY> *tail_shared()
 {
-    __shared__ TailSharedT<MAXE, KC> s;
+    __shared__ TailSharedT<MAXE, KC, ROWCOPY> s;
     return &s;
 }
 
@@ -806,7 +810,8 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
     long long *theta = theta2 + (par ^ 1) * kMaxE;
     int *gcur = gcount2 + par * kMaxE;
     constexpr int KC = TailCfg<TEPL>::KC;       // keys per candidate list
-    TailSharedT<TailCfg<TEPL>::MaxE, KC> &sh = *tail_shared<TailCfg<TEPL>::MaxE, KC>();
+    constexpr bool kRowCopy = TailCfg<TEPL>::RowCopy > 1;
+    auto &sh = *tail_shared<TailCfg<TEPL>::MaxE, KC, TailCfg<TEPL>::RowCopy>();
     auto &s_cand = sh.cand;
     auto &s_theta = sh.theta;
     auto &s_bound = sh.bound;
@@ -1088,13 +1093,17 @@ __device__ __forceinline__ void tail_pass(const int32_t *__restrict__ q, int32_t
                 continue;
             }
             // several holds of the token are challenged at once: the bid pass's general evaluation
-            int *qrow = s_qrow[wv];
+            // (the slot lanes need the reward of their own expert: from a copy of the row in LDS, or from memory)
+            const int *qrow = kRowCopy ? s_qrow[wv] : qr;
+            if (kRowCopy) {
+                int *qw = s_qrow[wv];
 #pragma unroll
-            for (int m = 0; m < TEPL; ++m)
-                if (m < eplt && lane + 64 * m < E) qrow[lane + 64 * m] = qv[m];
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                for (int m = 0; m < TEPL; ++m)
+                    if (m < eplt && lane + 64 * m < E) qw[lane + 64 * m] = qv[m];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
             long long my_sq = 0;
             bool dropped = false;
             if (my_e >= 0) {
@@ -1991,7 +2000,8 @@ int32_t solver_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore
             if (E <= 64) MS_SEL(1);
             else if (E <= 128) MS_SEL(2);
             else if (E <= 256) MS_SEL(4);
-            else MS_SEL(8);
+            else if (E <= 512) MS_SEL(8);
+            else MS_SEL(16);
 #undef MS_SEL
             if (g_kernel_timing) {
                 MS_HIP(hipEventRecord(tev[tev_used + 2], s));
