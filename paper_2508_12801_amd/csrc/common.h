@@ -17,6 +17,7 @@ constexpr int kMaxK = 64;
 constexpr int kMaxTBits = 21;
 constexpr int64_t kBidBig = (int64_t)1 << 40;   // bid of a token that has no alternative left
 constexpr int kCand = 32;          // lowest keys per expert handed to the tail pass (16 beyond 256 experts, 8 beyond 512)
+constexpr int kEps0Shift = 8;      // the auction's first phase runs at eps0 <= S * (reward range) / 2^8
 constexpr int kTailMaxE = 1024;    // the tail pass keeps all candidate lists in LDS (= kMaxE: it always runs)
 
 // Device-resident control block of one assignment solve.

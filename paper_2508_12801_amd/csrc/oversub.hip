@@ -12,6 +12,15 @@
 // (capacity suffices), the optimum of the padded problem uses as few padding pairs as possible (that is the
 // maximum flow), and what it pays for the real pairs is the maximum score at that flow.  A hold on a padding expert
 // is an empty slot: the rows come back with the real experts first and -1 after them.
+//
+// Where the auction starts.  Every real expert ends full and its last token is indifferent between it and a padding
+// expert, so its price ends at S * (q - PAD) >= S * (lo - PAD) for some reward q of its own (S the solver's scale
+// factor, lo the smallest real reward).  From zero prices the auction would climb that height, E + k + 1 times
+// the reward range, in steps of eps, through thousands of rounds; it is started instead with S * (lo - PAD) on
+// every real expert and 0 on the padding experts (never full: their price stays 0), at the eps a problem with the
+// real reward range starts from.  Net of these prices a real expert is worth S * (q - lo) >= 0 to a token and a
+// padding expert 0, and the auction only has to resolve differences inside the real range.  (Starting prices do not
+// change the optimum the solver returns, only its rounds.)
 #include <vector>
 
 #include "common.h"
@@ -50,11 +59,14 @@ __global__ __launch_bounds__(256) void k_os_minmax(const int32_t *__restrict__ q
     }
 }
 
-// q2[T, E + k]: the rewards, then k columns of PAD
+// q2[T, E + k]: the rewards, then k columns of PAD; start[E + k]: the starting prices
 __global__ __launch_bounds__(256) void k_os_pad(const int32_t *__restrict__ q, int32_t *__restrict__ q2, int T, int E,
-                                                int E2, int pad, int *holes)
+                                                int E2, int pad, int *holes, int64_t *__restrict__ start,
+                                                long long start_real)
 {
     if (blockIdx.x == 0 && threadIdx.x == 0) holes[0] = 0;
+    if (blockIdx.x == 0)
+        for (int e = threadIdx.x; e < E2; e += 256) start[e] = e < E ? start_real : 0;
     const size_t n = (size_t)T * E2;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
         const size_t row = i / E2;
@@ -92,7 +104,7 @@ size_t oversub_workspace_bytes(int T, int E, int k)
     const int E2 = E + k;
     if (E2 > kMaxE) return 0;
     return up256(workspace_layout(T, E2, k).total) + up256(sizeof(int32_t) * (size_t)T * E2) +
-           up256(sizeof(int64_t) * E2) + 256;
+           2 * up256(sizeof(int64_t) * E2) + 256;
 }
 
 int32_t oversub_run(const int32_t *q, int T, int E, int k, int Ce, const maxscore_opts &o, int32_t *assign,
@@ -105,7 +117,8 @@ int32_t oversub_run(const int32_t *q, int T, int E, int k, int Ce, const maxscor
     const size_t solver_bytes = up256(workspace_layout(T, E2, k).total);
     int32_t *q2 = (int32_t *)(ws + solver_bytes);
     int64_t *prices2 = (int64_t *)(ws + solver_bytes + up256(sizeof(int32_t) * (size_t)T * E2));
-    int *holes_dev = (int *)((char *)prices2 + up256(sizeof(int64_t) * E2));
+    int64_t *start = (int64_t *)((char *)prices2 + up256(sizeof(int64_t) * E2));
+    int *holes_dev = (int *)((char *)start + up256(sizeof(int64_t) * E2));
 
     // reward range (the partial results use the head of the region the padded rewards will fill)
     const size_t n = (size_t)T * E;
@@ -123,13 +136,22 @@ int32_t oversub_run(const int32_t *q, int T, int E, int k, int Ce, const maxscor
     }
     const long long pad = lo - (long long)(E2 + 1) * (hi - lo + 1);
     if (pad < -((long long)1 << 30)) return MAXSCORE_ERR_RANGE;  // the padded rewards must stay 32-bit values
+    long long start_real = 0, eps_start = 1;
 
     {
         const size_t n2 = (size_t)T * E2;
         int grid = (int)((n2 + 256 * 8 - 1) / (256 * 8));
         grid = grid < 1 ? 1 : (grid > 8192 ? 8192 : grid);
-        hipLaunchKernelGGL(k_os_pad, dim3(grid), dim3(256), 0, s, q, q2, T, E, E2, (int)pad, holes_dev);
+        int sb = 0;                      // the solver's scale factor for E2 experts: S = 2^sb > E2
+        while ((1 << sb) < E2 + 1) ++sb;
+        start_real = (lo - pad) << sb;
+        eps_start = ((hi - lo) << sb) >> kEps0Shift;
+        hipLaunchKernelGGL(k_os_pad, dim3(grid), dim3(256), 0, s, q, q2, T, E, E2, (int)pad, holes_dev, start,
+                           start_real);
     }
+    maxscore_opts o2 = o;                // (prices the caller may have given refer to another problem: not used)
+    o2.prices_in = start;
+    o2.eps_start = eps_start > 1 ? eps_start : 1;
     std::vector<int32_t> caps(E2);
     for (int e = 0; e < E2; ++e) caps[e] = e < E ? Ce : T;
     const int32_t *cap_dev = nullptr;
@@ -139,7 +161,7 @@ int32_t oversub_run(const int32_t *q, int T, int E, int k, int Ce, const maxscor
     if (rc) return rc;
     maxscore_stats st2;
     st2 = maxscore_stats();
-    rc = solver_run(q2, T, E2, k, cmax, o, assign, prices2, price_scale, &st2, ws, s, cap_dev, room);
+    rc = solver_run(q2, T, E2, k, cmax, o2, assign, prices2, price_scale, &st2, ws, s, cap_dev, room);
     if (rc != MAXSCORE_OK && rc != MAXSCORE_ERR_NOT_CONVERGED) return rc;
     hipLaunchKernelGGL(k_os_unpad, dim3((T + 255) / 256), dim3(256), 0, s, assign, T, E, k, holes_dev);
     int holes = 0;

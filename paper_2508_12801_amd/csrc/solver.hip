@@ -47,7 +47,6 @@ int g_kernel_timing = 0;
 namespace {
 
 constexpr unsigned long long kVB = 1ull << 52;  // bias that makes packed values unsigned
-constexpr int kEps0Shift = 8;              // the first phase runs at eps0 <= S * range / 2^8
 constexpr long long kNarrowPrice = (long long)1 << 29;   // prices below this (and a reward range below 2^28/S) fit 32-bit values
 
 __device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int off)
