@@ -219,6 +219,20 @@ def main():
         runs = [ms.assign_i32(q4, c4["k"], c4["C"])["stats"] for _ in range(3)]
         tie[nm] = {"solver_ms": sorted(s_["solver_ms"] for s_ in runs)[1], "rounds": runs[0]["rounds"]}
         del q4
+    # the same variant through the projection: x rows that differ by 1e-3 before the bf16 rounding give rows of rewards
+    # that are all distinct but closer to each other than the auction's first eps (harder than the logits-level noise above)
+    from workloads import make_inputs as _mk
+    r4 = _mk("cfg4b_near", seed=0)
+    if r4.dtype == "bf16":
+        x4 = torch.from_numpy(r4.x_bits.view(np.int16)).to(dev).view(torch.bfloat16)
+        W4 = torch.from_numpy(r4.W_bits.view(np.int16)).to(dev).view(torch.bfloat16)
+        q4 = ms.router_softtopk(x4, W4, None, r4.k, r4.t, want_logits=False)["q"]
+        ms.assign_i32(q4, r4.k, r4.C)
+        runs = [ms.assign_i32(q4, r4.k, r4.C)["stats"] for _ in range(3)]
+        tie["cfg4b_near_through_projection"] = {"solver_ms": sorted(s_["solver_ms"] for s_ in runs)[1],
+                                                "rounds": runs[0]["rounds"], "finisher_passes": runs[0]["finish_passes"]}
+        del x4, W4, q4
+    del r4
 
     # the step after the routing path (measured beside it, not part of `value`): activation rows into the
     # expert input buffers and the gate-weighted combine back, at the same configuration
