@@ -287,7 +287,8 @@ def test_finisher_with_many_experts_full_batch(ms, T, E, k):
     assert int(q[P.astype(bool)].sum()) == fin["stats"]["total_score_q"]
 
 
-@pytest.mark.parametrize("T,E,k,cap_lo,cap_hi", [(3000, 48, 6, 200, 500), (3000, 192, 6, 50, 125)])
+@pytest.mark.parametrize("T,E,k,cap_lo,cap_hi", [(3000, 48, 6, 200, 500), (3000, 192, 6, 50, 125), (2500, 257, 6, 31, 80),
+                                                 (2000, 513, 4, 9, 24), (1500, 1024, 8, 7, 18)])
 def test_finisher_with_k_vector_and_capacity_vector(ms, T, E, k, cap_lo, cap_hi):
     """Per-token k (with zeros) and unequal capacities through the finisher: checker's optimum, valid rows."""
     print(f"finisher kvec+caps E={E}", flush=True)
